@@ -1,0 +1,593 @@
+"""CPU oracle for the semantic-parallel MoE layer (Sem-MoE, arxiv 2503.04398).
+
+TEST INFRASTRUCTURE ONLY.  This file is the plain, slow reference that the HIP
+library is checked against.  Only the tests, the smoke check and the
+`cpu_baseline` leg of the benchmark may import it; the product path never does.
+It shares no code, tables or helpers with the HIP path.
+
+Floating point is fp64 (inputs are taken as given, e.g. bf16-rounded values held
+in float32) except where a decision must be taken in the kernel's precision:
+the top-k selection works on fp32 logits, and the sigmoid score is an fp32
+recipe fixed operation by operation (see `sigmoid_f32`).  Integers are int64.
+
+Notation follows the paper: T tokens, d hidden, E experts (the paper's N),
+k experts per token, D logical EP ranks (the paper's E / G / Q), m = E/D.
+Pair index p = i*k + j (token i, slot j).
+
+Which passage each function follows
+  route_logits / select_topk   gating function G(h) = top-k(softmax(W_g h + b_g))  (Sec. 3.2)
+  coact_hist                   token->expert activation counts (Sec. 3.2) in their
+                               key-free form; expert-expert affinity of Alg. 1
+  place                        Alg. 1 `expert_place` (+ App. B text), request term dropped
+  reshuffle                    Alg. 3 `rebatch_tokens` (argsort, group, align, concat)
+  reshuffle_exact              the ILP's communication term (Sec. 3.3) solved exactly
+                               for fixed placement: min-cost flow
+  dispatch / combine           the two all2all of expert parallelism (Sec. 1) as
+                               single-device permutations; `resume_tokens` of Alg. 3
+  expert_ffn                   the expert FFN (Sec. 2), SwiGLU form
+  moe_definition               the plain MoE layer: what the whole path must equal
+                               ("losslessly", Sec. 5)
+  remote volume                alpha*k*B*S/G all2all volume model (Sec. 3.1)
+
+Pins (tests/test_oracle_*.py): brute force on tiny inputs, closed forms,
+library argsort / matmul special cases, the 1/D local-activation rate of
+class-free routing (the ~25 % baseline of Tables 3-4 at D = 4), planted-cluster
+recovery.  Parity unpinned (the paper gives nothing to check against): the
+values of alpha, gamma, ft_steps; the behaviour of `align`; Fig. 3's example.
+"""
+from __future__ import annotations
+
+import itertools
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+# --------------------------------------------------------------------------------------------
+# a1  route
+# --------------------------------------------------------------------------------------------
+
+
+def route_logits(X, W_r, b_g=None, token_class=None, class_bias=None) -> np.ndarray:
+    """logits[i,e] = sum_c X[i,c] W_r[e,c] + b_g[e] + class_bias[token_class[i], e], in fp64,
+    rounded once to fp32 (gating function, Sec. 3.2; the class term is the synthetic
+    context-independent token->expert affinity).  token_class = -1 adds nothing."""
+    L = np.asarray(X, dtype=np.float64) @ np.asarray(W_r, dtype=np.float64).T
+    if b_g is not None:
+        L = L + np.asarray(b_g, dtype=np.float64)[None, :]
+    if token_class is not None and class_bias is not None:
+        tc = np.asarray(token_class)
+        cb = np.asarray(class_bias, dtype=np.float64)
+        has = tc >= 0
+        L[has] += cb[tc[has]]
+    return L.astype(np.float32)
+
+
+# fp32 constants of the sigmoid recipe (each literal is rounded to fp32 once)
+_LOG2E = np.float32(1.4426950408889634)
+_EXP2_COEF = [np.float32(c) for c in (
+    1.0,
+    0.6931471805599453,      # ln2
+    0.2402265069591007,      # ln2^2/2
+    0.05550410866482158,     # ln2^3/6
+    0.009618129107628477,    # ln2^4/24
+    0.0013333558146428443,   # ln2^5/120
+    0.00015403530393381608,  # ln2^6/720
+)]
+
+
+def sigmoid_f32(x: np.ndarray) -> np.ndarray:
+    """Sigmoid as a fixed sequence of individually rounded fp32 operations (no fused
+    multiply-add), so that a kernel executing the same sequence gets the same bits:
+        x <- clamp(x, -30, 30);  t = (-x) * log2(e);  n = rint(t);  f = t - n
+        p = c6;  p = p*f + c_i  for i = 5..0   (multiply, round, add, round)
+        z = p * 2^n (exact);  s = 1 / (1 + z)  (correctly rounded add and divide)
+    with c_i = ln(2)^i / i! rounded to fp32.  Accuracy: a few ulp."""
+    x = np.asarray(x, dtype=np.float32)
+    x = np.minimum(np.maximum(x, np.float32(-30.0)), np.float32(30.0))
+    t = (-x) * _LOG2E
+    n = np.rint(t)
+    f = t - n
+    p = np.full_like(f, _EXP2_COEF[6])
+    for i in range(5, -1, -1):
+        p = p * f
+        p = p + _EXP2_COEF[i]
+    z = np.ldexp(p, n.astype(np.int32)).astype(np.float32)
+    s = np.float32(1.0) / (np.float32(1.0) + z)
+    assert s.dtype == np.float32
+    return s
+
+
+def _topk_desc_lowidx(v: np.ndarray, k: int) -> np.ndarray:
+    """indices of the k largest entries of a 1-D array, descending value, ties -> lower index"""
+    order = sorted(range(len(v)), key=lambda e: (-v[e], e))
+    return np.array(order[:k], dtype=np.int64)
+
+
+def select_topk(logits, k: int, score: str = "softmax", renorm: bool = False, n_group: int = 1,
+                topk_group: int = 1, routed_scale: float = 1.0, sel_bias=None):
+    """Top-k expert ids and combine weights from fp32 logits (gating function, Sec. 3.2).
+
+    softmax: choose the k largest logits (softmax is monotone), descending, ties -> lower
+      expert id; weight = softmax over all E experts (fp64, max-subtracted) at the chosen ids,
+      divided by their sum when `renorm`.
+    sigmoid (group-limited, the DeepSeek-V3-style router named by the workload, not by the
+      paper): s = sigmoid_f32(logit); s' = s + sel_bias (fp32); experts form n_group contiguous
+      groups; group score = sum (fp32) of the group's two largest s'; keep the topk_group best
+      groups (ties -> lower group); choose the k largest s' among their experts; weight =
+      s[id] / sum_j s[id_j] * routed_scale (fp64) when `renorm`, else s[id] * routed_scale.
+    Returns (ids[T,k] int32, w[T,k] float64)."""
+    L = np.asarray(logits)
+    assert L.dtype == np.float32, "selection is defined on fp32 logits"
+    assert np.isfinite(L).all()
+    T, E = L.shape
+    assert 1 <= k <= E
+    ids = np.zeros((T, k), dtype=np.int32)
+    w = np.zeros((T, k), dtype=np.float64)
+    if score == "softmax":
+        for i in range(T):
+            sel = _topk_desc_lowidx(L[i], k)
+            z = L[i].astype(np.float64)
+            z = np.exp(z - z.max())
+            p = z / z.sum()
+            wi = p[sel]
+            if renorm:
+                wi = wi / wi.sum()
+            ids[i], w[i] = sel, wi
+        return ids, w
+    assert score == "sigmoid"
+    assert E % n_group == 0 and 1 <= topk_group <= n_group
+    gs = E // n_group
+    assert k <= topk_group * gs
+    s = sigmoid_f32(L)
+    sb = np.zeros(E, dtype=np.float32) if sel_bias is None else np.asarray(sel_bias, dtype=np.float32)
+    sp = s + sb[None, :]
+    assert sp.dtype == np.float32
+    for i in range(T):
+        if n_group > 1:
+            gscore = np.zeros(n_group, dtype=np.float32)
+            for g in range(n_group):
+                seg = sp[i, g * gs:(g + 1) * gs]
+                if gs >= 2:
+                    top2 = _topk_desc_lowidx(seg, 2)
+                    gscore[g] = np.float32(seg[top2[0]]) + np.float32(seg[top2[1]])
+                else:
+                    gscore[g] = seg[0]
+            keep = _topk_desc_lowidx(gscore, topk_group)
+            allowed = np.zeros(E, dtype=bool)
+            for g in keep:
+                allowed[g * gs:(g + 1) * gs] = True
+        else:
+            allowed = np.ones(E, dtype=bool)
+        cand = [e for e in range(E) if allowed[e]]
+        cand.sort(key=lambda e: (-sp[i, e], e))
+        sel = np.array(cand[:k], dtype=np.int64)
+        wi = s[i, sel].astype(np.float64)
+        if renorm:
+            wi = wi / wi.sum()
+        ids[i], w[i] = sel, wi * float(routed_scale)
+    return ids, w
+
+
+# --------------------------------------------------------------------------------------------
+# a2  coact_hist
+# --------------------------------------------------------------------------------------------
+
+
+def coact_hist(ids, E: int, load=None, coact=None):
+    """load[e] = #{(i,j): ids[i,j] = e};  coact[a,b] = #{i: a in ids[i] and b in ids[i]} for all
+    ordered (a,b), a = b included (activation counts of Sec. 3.2 summed over token ids; the
+    expert-expert affinity Alg. 1 consumes).  Accumulates into `load`/`coact` when given."""
+    ids = np.asarray(ids)
+    load = np.zeros(E, dtype=np.int64) if load is None else load
+    coact = np.zeros((E, E), dtype=np.int64) if coact is None else coact
+    for row in ids:
+        for a in row:
+            load[a] += 1
+            for b in row:
+                coact[a, b] += 1
+    return load, coact
+
+
+# --------------------------------------------------------------------------------------------
+# a3  place  (Alg. 1 expert_place)
+# --------------------------------------------------------------------------------------------
+
+
+def place(load, coact, D: int, alpha: int = 1, gamma: int = 0, ft_passes: int = 8):
+    """Balanced expert -> rank placement (Alg. 1 `expert_place`, request-affinity term dropped
+    because this path has no requests).
+
+    Greedy pass: experts in order of load, hottest first (ties -> lower id).  For expert e and
+    every rank c that is not full:  EAfE[e,c] = sum of coact[e,e'] over experts e' already on c;
+    score = alpha*EAfE[e,c] - gamma*loads_cls[c].  e goes to the arg-max rank (ties -> smaller
+    loads_cls, then smaller c); a rank holding E/D experts is masked.
+    Fine-tuning: the algorithm's random pair swaps "kept if the affinity gain is positive" are
+    taken as deterministic first-improvement sweeps over pairs e1 < e2 on different ranks, at
+    most `ft_passes` sweeps, stopping after a sweep without a swap.  gain = change of the
+    intra-rank co-activation mass W = sum_c sum_{a<b on c} coact[a,b].
+    Physical order: rank-major, ascending original id inside a rank.
+    Returns (expert_to_rank[E], phys_of_expert[E], expert_of_phys[E]) int32."""
+    load = np.asarray(load, dtype=np.int64)
+    A = np.asarray(coact, dtype=np.int64)
+    E = load.shape[0]
+    assert A.shape == (E, E) and E % D == 0
+    m = E // D
+    order = sorted(range(E), key=lambda e: (-int(load[e]), e))
+    rank_of = [-1] * E
+    members = [[] for _ in range(D)]
+    loads_cls = [0] * D
+    for e in order:
+        best = None
+        for c in range(D):
+            if len(members[c]) >= m:       # masked
+                continue
+            eafe = sum(int(A[e, e2]) for e2 in members[c])
+            score = alpha * eafe - gamma * loads_cls[c]
+            key = (-score, loads_cls[c], c)
+            if best is None or key < best[0]:
+                best = (key, c)
+        c = best[1]
+        rank_of[e] = c
+        members[c].append(e)
+        loads_cls[c] += int(load[e])
+
+    def aff(e, c, excl):
+        """A(e, S) with S = experts on rank c other than e and `excl`"""
+        on_c = np.array(rank_of) == c
+        on_c[e] = False
+        on_c[excl] = False
+        return int(A[e][on_c].sum())
+
+    for _ in range(ft_passes):
+        swapped = False
+        for e1 in range(E):
+            for e2 in range(e1 + 1, E):
+                c1, c2 = rank_of[e1], rank_of[e2]
+                if c1 == c2:
+                    continue
+                gain = aff(e1, c2, e2) + aff(e2, c1, e1) - aff(e1, c1, e1) - aff(e2, c2, e2)
+                if gain > 0:
+                    rank_of[e1], rank_of[e2] = c2, c1
+                    swapped = True
+        if not swapped:
+            break
+    expert_to_rank = np.array(rank_of, dtype=np.int32)
+    phys = np.zeros(E, dtype=np.int32)
+    seen = [0] * D
+    for e in range(E):
+        c = rank_of[e]
+        phys[e] = c * m + seen[c]
+        seen[c] += 1
+    inv = np.zeros(E, dtype=np.int32)
+    inv[phys] = np.arange(E, dtype=np.int32)
+    return expert_to_rank, phys, inv
+
+
+def vanilla_placement(E: int, D: int):
+    """the original placement: expert e on rank e div m (the comparison baseline of Sec. 4.6)"""
+    m = E // D
+    e = np.arange(E, dtype=np.int32)
+    return (e // m).astype(np.int32), e.copy(), e.copy()
+
+
+def intra_rank_mass(coact, expert_to_rank) -> int:
+    """W = sum over ranks of sum_{a<b on the rank} coact[a,b]"""
+    A = np.asarray(coact, dtype=np.int64)
+    r = np.asarray(expert_to_rank)
+    E = len(r)
+    return int(sum(int(A[a, b]) for a in range(E) for b in range(a + 1, E) if r[a] == r[b]))
+
+
+# --------------------------------------------------------------------------------------------
+# a4  reshuffle  (Alg. 3 rebatch_tokens)
+# --------------------------------------------------------------------------------------------
+
+
+def home_rank(T: int, D: int) -> np.ndarray:
+    """the contiguous shard a plain reduce-scatter gives token i: i div ceil(T/D)"""
+    per = -(-T // D)
+    return (np.arange(T) // per).astype(np.int32)
+
+
+def gain_matrix(ids, expert_to_rank, D: int) -> np.ndarray:
+    """g[i,r] = #{j: expert_to_rank[ids[i,j]] = r}"""
+    ids = np.asarray(ids)
+    T, k = ids.shape
+    g = np.zeros((T, D), dtype=np.int64)
+    for i in range(T):
+        for j in range(k):
+            g[i, expert_to_rank[ids[i, j]]] += 1
+    return g
+
+
+def reshuffle(ids, expert_to_rank, D: int, cap: int):
+    """Capacity-bounded token -> rank assignment and the shuffle permutation
+    (Alg. 3 `rebatch_tokens`: device ids, argsort, group_by_key, align, concat).
+
+    The per-token device id comes from the token's actual top-k against the placement (the
+    perfect-predictor limit of the paper's lookup tables).  `align` is read as the capacity
+    bound that makes all shards equal: at most `cap` tokens per rank, cap*D >= T.
+      1. g[i,r]; pref(i) = argmax_r g[i,r], ties -> home(i) if it is a maximiser, else the
+         smallest maximiser; conf(i) = g[i,pref(i)].
+      2. keep: per rank the candidates {i: pref(i) = r} ordered by (conf desc, i asc); the first
+         min(n_r, cap) stay on r.
+      3. spill: the s-th spilled token (ascending i) takes the s-th free slot, free slots
+         enumerated rank by rank in ascending rank order.
+      4. shf = token indices stably sorted by token_rank (new position -> token);
+         inv_shf[shf[q]] = q (`resume_tokens`).
+    Returns (token_rank[T], shf[T], inv_shf[T], rank_count[D]) int32."""
+    ids = np.asarray(ids)
+    T, k = ids.shape
+    assert cap * D >= T
+    g = gain_matrix(ids, expert_to_rank, D)
+    home = home_rank(T, D)
+    pref = np.zeros(T, dtype=np.int64)
+    conf = np.zeros(T, dtype=np.int64)
+    for i in range(T):
+        mx = g[i].max()
+        if g[i, home[i]] == mx:
+            pref[i] = home[i]
+        else:
+            pref[i] = int(np.flatnonzero(g[i] == mx)[0])
+        conf[i] = mx
+    token_rank = np.full(T, -1, dtype=np.int64)
+    kept = np.zeros(D, dtype=np.int64)
+    for r in range(D):
+        cand = [i for i in range(T) if pref[i] == r]
+        cand.sort(key=lambda i: (-conf[i], i))
+        for i in cand[:cap]:
+            token_rank[i] = r
+        kept[r] = min(len(cand), cap)
+    free_slots = [r for r in range(D) for _ in range(int(cap - kept[r]))]
+    spilled = [i for i in range(T) if token_rank[i] < 0]
+    for s, i in enumerate(spilled):
+        token_rank[i] = free_slots[s]
+    shf = np.argsort(token_rank, kind="stable")
+    inv_shf = np.zeros(T, dtype=np.int64)
+    inv_shf[shf] = np.arange(T)
+    rank_count = np.bincount(token_rank, minlength=D)
+    return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
+            rank_count.astype(np.int32))
+
+
+def home_assignment(T: int, D: int):
+    """no reshuffle: tokens stay on their home rank; identity permutation"""
+    tr = home_rank(T, D)
+    idt = np.arange(T, dtype=np.int32)
+    return tr, idt.copy(), idt.copy(), np.bincount(tr, minlength=D).astype(np.int32)
+
+
+def local_pairs(ids, expert_to_rank, token_rank) -> int:
+    """sum_i g[i, token_rank[i]]: pairs whose expert sits on the token's rank"""
+    ids = np.asarray(ids)
+    e2r = np.asarray(expert_to_rank)
+    return int((e2r[ids] == np.asarray(token_rank)[:, None]).sum())
+
+
+def reshuffle_bruteforce(ids, expert_to_rank, D: int, cap: int) -> int:
+    """max over all capacity-feasible assignments of the local pair count (tiny inputs only)"""
+    ids = np.asarray(ids)
+    T = ids.shape[0]
+    g = gain_matrix(ids, expert_to_rank, D)
+    best = -1
+    for assign in itertools.product(range(D), repeat=T):
+        cnt = [0] * D
+        ok = True
+        for r in assign:
+            cnt[r] += 1
+            if cnt[r] > cap:
+                ok = False
+                break
+        if ok:
+            best = max(best, sum(int(g[i, assign[i]]) for i in range(T)))
+    return best
+
+
+def reshuffle_exact(ids, expert_to_rank, D: int, cap: int):
+    """The assignment maximising local pairs under the capacity bound (the communication term of
+    the Sec. 3.3 objective for a fixed placement), by min-cost flow: source -> token (cap 1) ->
+    rank (cost -g[i,r]) -> sink (cap `cap`), successive shortest augmenting paths found with
+    Bellman-Ford.  Returns (token_rank[T] int32, local_pair_count)."""
+    ids = np.asarray(ids)
+    T = ids.shape[0]
+    assert cap * D >= T
+    g = gain_matrix(ids, expert_to_rank, D)
+    S, Z = T + D, T + D + 1
+    n = T + D + 2
+    # edge lists
+    to, capa, cost, adj = [], [], [], [[] for _ in range(n)]
+
+    def add(u, v, c, w):
+        adj[u].append(len(to)); to.append(v); capa.append(c); cost.append(w)
+        adj[v].append(len(to)); to.append(u); capa.append(0); cost.append(-w)
+
+    for i in range(T):
+        add(S, i, 1, 0)
+        for r in range(D):
+            add(i, T + r, 1, -int(g[i, r]))
+    for r in range(D):
+        add(T + r, Z, cap, 0)
+    INF = 1 << 60
+    total = 0
+    for _ in range(T):
+        dist = [INF] * n
+        prev_e = [-1] * n
+        dist[S] = 0
+        inq = [False] * n
+        queue = [S]
+        inq[S] = True
+        while queue:
+            u = queue.pop(0)
+            inq[u] = False
+            for ei in adj[u]:
+                if capa[ei] > 0 and dist[u] + cost[ei] < dist[to[ei]]:
+                    dist[to[ei]] = dist[u] + cost[ei]
+                    prev_e[to[ei]] = ei
+                    if not inq[to[ei]]:
+                        queue.append(to[ei]); inq[to[ei]] = True
+        assert dist[Z] < INF
+        v = Z
+        while v != S:
+            ei = prev_e[v]
+            capa[ei] -= 1
+            capa[ei ^ 1] += 1
+            v = to[ei ^ 1]
+        total += dist[Z]
+    token_rank = np.zeros(T, dtype=np.int32)
+    for i in range(T):
+        for ei in adj[i]:
+            if to[ei] >= T and to[ei] < T + D and ei % 2 == 0 and capa[ei] == 0:
+                token_rank[i] = to[ei] - T
+    return token_rank, -total
+
+
+# --------------------------------------------------------------------------------------------
+# a5  dispatch
+# --------------------------------------------------------------------------------------------
+
+
+def dispatch(X, ids, token_rank, inv_shf, phys_of_expert, D: int) -> Dict[str, np.ndarray]:
+    """Dispatch half of expert parallelism (Sec. 1) on one device: order the P = T*k
+    (token, expert) pairs by physical expert, pairs of one expert in arrival order of a
+    rank-ordered all2all, i.e. by shuffled pair index p' = inv_shf[i]*k + j.
+      slot                = position of (q, p') in the sort by q = phys_of_expert[ids[i,j]], then p'
+      slot_of_pair[i*k+j] = slot;  pair_of_slot[slot] = i*k+j
+      expert_offsets[q]   = first slot of physical expert q ([E] = P)
+      rank_offsets[r]     = expert_offsets[r*m]
+      X_perm[slot]        = X[i]
+      send_matrix[s,r]    = #{(i,j): token_rank[i] = s and rank of ids[i,j] = r}
+      remote_pairs        = sum_{s != r} send_matrix[s,r]   (dispatch direction only; the
+                            all2all volume model alpha*k*B*S/G of Sec. 3.1 has
+                            alpha = remote_pairs / P)"""
+    ids = np.asarray(ids)
+    T, k = ids.shape
+    P = T * k
+    phys = np.asarray(phys_of_expert, dtype=np.int64)
+    E = phys.shape[0]
+    m = E // D
+    q = phys[ids].reshape(P)                                             # key of pair p
+    pprime = (np.asarray(inv_shf, dtype=np.int64)[:, None] * k + np.arange(k)[None, :]).reshape(P)
+    order = sorted(range(P), key=lambda p: (int(q[p]), int(pprime[p])))   # slot -> pair
+    pair_of_slot = np.array(order, dtype=np.int64)
+    slot_of_pair = np.zeros(P, dtype=np.int64)
+    slot_of_pair[pair_of_slot] = np.arange(P)
+    counts = np.bincount(q, minlength=E)
+    expert_offsets = np.concatenate([[0], np.cumsum(counts)])
+    rank_offsets = expert_offsets[::m].copy()
+    send = np.zeros((D, D), dtype=np.int64)
+    tr = np.asarray(token_rank, dtype=np.int64)
+    for p in range(P):
+        send[tr[p // k], q[p] // m] += 1
+    remote = int(send.sum() - np.trace(send))
+    out = dict(slot_of_pair=slot_of_pair.astype(np.int32), pair_of_slot=pair_of_slot.astype(np.int32),
+               expert_offsets=expert_offsets.astype(np.int32), rank_offsets=rank_offsets.astype(np.int32),
+               send_matrix=send.astype(np.uint32), remote_pairs=np.uint64(remote))
+    if X is not None:
+        out["X_perm"] = np.asarray(X)[pair_of_slot // k]
+    return out
+
+
+# --------------------------------------------------------------------------------------------
+# a6  expert_ffn
+# --------------------------------------------------------------------------------------------
+
+
+def swiglu_ffn(x, W_gu, W_down) -> np.ndarray:
+    """y = W_down ( silu(W_gate x) * (W_up x) ) for rows x[n,d]; W_gu[2F,d] = [gate; up],
+    W_down[d,F]; fp64, no intermediate rounding."""
+    x = np.asarray(x, dtype=np.float64)
+    W_gu = np.asarray(W_gu, dtype=np.float64)
+    F = W_gu.shape[0] // 2
+    gate = x @ W_gu[:F].T
+    up = x @ W_gu[F:].T
+    h = gate / (1.0 + np.exp(-gate)) * up
+    return h @ np.asarray(W_down, dtype=np.float64).T
+
+
+def expert_ffn(X_perm, expert_offsets, expert_of_phys, weight_of, D: int, rank: int = -1, Y=None):
+    """Grouped expert FFN (Sec. 2 "experts ... typically FFNs"; SwiGLU): for every physical
+    expert q of `rank` (all ranks when -1), rows expert_offsets[q] .. expert_offsets[q+1] of
+    X_perm go through the FFN of original expert expert_of_phys[q].  `weight_of(e)` returns
+    (W_gu[e], W_down[e]).  Rows of other ranks are left as they are in Y."""
+    Xp = np.asarray(X_perm)
+    off = np.asarray(expert_offsets, dtype=np.int64)
+    E = off.shape[0] - 1
+    m = E // D
+    Y = np.zeros(Xp.shape, dtype=np.float64) if Y is None else Y
+    qs = range(E) if rank < 0 else range(rank * m, (rank + 1) * m)
+    for q in qs:
+        lo, hi = off[q], off[q + 1]
+        if hi > lo:
+            wgu, wdn = weight_of(int(expert_of_phys[q]))
+            Y[lo:hi] = swiglu_ffn(Xp[lo:hi], wgu, wdn)
+    return Y
+
+
+# --------------------------------------------------------------------------------------------
+# a7  combine
+# --------------------------------------------------------------------------------------------
+
+
+def combine(Y, slot_of_pair, topk_w, Y_shared=None) -> np.ndarray:
+    """Out[i] = sum_j topk_w[i,j] * Y[slot_of_pair[i*k+j]] (+ Y_shared[i]); the combine all2all
+    (Sec. 1) plus the un-permutation (`resume_tokens`, Alg. 3); fp64."""
+    w = np.asarray(topk_w, dtype=np.float64)
+    T, k = w.shape
+    Y = np.asarray(Y, dtype=np.float64)
+    s = np.asarray(slot_of_pair, dtype=np.int64).reshape(T, k)
+    out = np.zeros((T, Y.shape[1]), dtype=np.float64)
+    for j in range(k):
+        out += w[:, j:j + 1] * Y[s[:, j]]
+    if Y_shared is not None:
+        out += np.asarray(Y_shared, dtype=np.float64)
+    return out
+
+
+# --------------------------------------------------------------------------------------------
+# the plain definition the whole path must equal
+# --------------------------------------------------------------------------------------------
+
+
+def moe_definition(X, ids, topk_w, weight_of, shared=None, tokens=None) -> np.ndarray:
+    """Out[i] = sum_j topk_w[i,j] * FFN_{ids[i,j]}(X[i]) (+ FFN_shared(X[i])), token by token from
+    the definition, with no placement, shuffle or permutation.  `tokens` restricts to a sample."""
+    X = np.asarray(X)
+    ids = np.asarray(ids)
+    w = np.asarray(topk_w, dtype=np.float64)
+    toks = np.arange(X.shape[0]) if tokens is None else np.asarray(tokens)
+    out = np.zeros((len(toks), X.shape[1]), dtype=np.float64)
+    cache = {}
+    for n, i in enumerate(toks):
+        for j in range(ids.shape[1]):
+            e = int(ids[i, j])
+            if e not in cache:
+                cache[e] = weight_of(e)
+            out[n] += w[i, j] * swiglu_ffn(X[i:i + 1], *cache[e])[0]
+        if shared is not None:
+            out[n] += swiglu_ffn(X[i:i + 1], *shared)[0]
+    return out
+
+
+# --------------------------------------------------------------------------------------------
+# reported quantities
+# --------------------------------------------------------------------------------------------
+
+
+def remote_fraction(ids, expert_to_rank, token_rank) -> float:
+    """alpha = remote pairs / (T*k); local activation rate LAR = 1 - alpha (Sec. 4.5)"""
+    ids = np.asarray(ids)
+    return 1.0 - local_pairs(ids, expert_to_rank, token_rank) / ids.size
+
+
+def load_imbalance(send_matrix) -> float:
+    """maximum rank load / median rank load over the pairs each rank computes (Sec. 4.6)"""
+    col = np.asarray(send_matrix, dtype=np.float64).sum(axis=0)
+    return float(col.max() / np.median(col))
+
+
+def max_rel_err(a, b) -> float:
+    """max|a-b| / max|b|: the tolerance measure for floating-point outputs"""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.abs(b).max()
+    return float(np.abs(a - b).max() / den) if den > 0 else float(np.abs(a - b).max())
