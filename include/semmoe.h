@@ -1,0 +1,193 @@
+/*
+ * semmoe.h - C ABI of the semantic-parallel MoE layer hot path for AMD MI355X (gfx950).
+ *
+ * One MoE layer of Sem-MoE ("Semantic Parallelism", arxiv 2503.04398) on one GPU, with the
+ * expert-parallel ranks simulated as D expert-placement groups:
+ *
+ *   route -> [coact_hist -> place : offline] -> reshuffle -> dispatch -> expert_ffn -> combine
+ *
+ * Conventions
+ *   - Every function returns a status: SEMMOE_OK or a negative SEMMOE_E* code.  Arguments are
+ *     validated before anything is launched, so argument errors need no GPU.
+ *   - "dev" pointers are device memory, "host" pointers host memory.  The caller owns every
+ *     buffer; the library allocates nothing and keeps no state between calls.  Scratch comes
+ *     from the caller's workspace `ws` of at least semmoe_workspace_bytes() bytes, 256-byte
+ *     aligned; calls on one stream may share it.
+ *   - Device calls enqueue on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and return without synchronising.  Calls that share a workspace must not overlap.
+ *   - Activations and weights ("act" type) are fp32 or bf16 as cfg->dtype says, row-major,
+ *     rows 16-byte aligned (d % 8 == 0 and F % 8 == 0).  Index arrays are int32.
+ *   - Notation: T tokens, d hidden width, E routed experts, k experts per token, F expert FFN
+ *     width, D logical ranks, m = E/D experts per rank, P = T*k (token, expert) pairs;
+ *     pair index p = i*k + j (token i, choice j).  "Physical" expert q = position of an expert
+ *     after placement (rank-major: rank of q is q / m).
+ */
+#ifndef SEMMOE_H
+#define SEMMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SEMMOE_OK 0
+#define SEMMOE_EINVAL (-1)       /* null / negative / misaligned argument */
+#define SEMMOE_ESHAPE (-2)       /* inconsistent shapes: E % D, k > E, cap*D < T, d % 8, groups ... */
+#define SEMMOE_EWORKSPACE (-3)   /* workspace missing or too small */
+#define SEMMOE_EHIP (-4)         /* a HIP call failed; see semmoe_last_hip_error() */
+#define SEMMOE_EUNSUPPORTED (-5) /* dtype / score mode / size outside what the kernels cover */
+
+#define SEMMOE_FP32 0
+#define SEMMOE_BF16 1
+#define SEMMOE_SOFTMAX 0
+#define SEMMOE_SIGMOID 1
+
+/* Limits of the kernels (validated): */
+#define SEMMOE_MAX_E 512 /* experts */
+#define SEMMOE_MAX_K 16  /* experts per token */
+#define SEMMOE_MAX_D 64  /* logical ranks */
+
+typedef struct semmoe_config {
+  int32_t T, d, E, k, F, D;
+  int32_t dtype;       /* SEMMOE_FP32 | SEMMOE_BF16 */
+  int32_t score;       /* SEMMOE_SOFTMAX | SEMMOE_SIGMOID */
+  int32_t renorm;      /* divide the k weights by their sum */
+  int32_t n_group;     /* sigmoid mode: expert groups (1 = no group limit); E % n_group == 0 */
+  int32_t topk_group;  /* sigmoid mode: groups kept */
+  float routed_scale;  /* sigmoid mode: factor on the weights */
+  int32_t cap;         /* reshuffle: tokens per rank at most; cap * D >= T */
+  int32_t num_classes; /* rows of class_bias (0 when unused) */
+} semmoe_config;
+
+int32_t semmoe_version(void);
+/* hipError_t of the last failed HIP call on this thread (0 if none). */
+int32_t semmoe_last_hip_error(void);
+/* Workspace size that covers every device call below for this config. */
+int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*host*/);
+
+/*
+ * route - the gating function G(h) = top-k(softmax(W_g h + b_g)) of Sec. 3.2.
+ *   logits[i,e] = sum_c X[i,c] W_r[e,c] + b_g[e] + class_bias[token_class[i], e]   (fp32 accumulate;
+ *   token_class[i] < 0 adds nothing; the class term is the synthetic token->expert affinity).
+ *   Selection and weights: see semmoe_route_from_logits.
+ * dev in : X[T,d] act; W_r[E,d] act (one row per expert); b_g[E] f32 or NULL; token_class[T] i32
+ *          and class_bias[num_classes,E] f32, both or neither; sel_bias[E] f32 or NULL.
+ * dev out: logits_out[T,E] f32 or NULL (then the logits live in the workspace only);
+ *          topk_ids[T,k] i32; topk_w[T,k] f32.
+ */
+int32_t semmoe_route(const semmoe_config* cfg, void* stream, const void* X, const void* W_r, const float* b_g,
+                     const int32_t* token_class, const float* class_bias, const float* sel_bias,
+                     float* logits_out, int32_t* topk_ids, float* topk_w, void* ws, size_t ws_bytes);
+
+/*
+ * route_from_logits - the selection half of the gating function (Sec. 3.2) on given fp32 logits.
+ *   softmax: the k largest logits, descending, equal logits -> lower expert id; weight = softmax over
+ *     all E at the chosen ids, divided by their sum if cfg->renorm.
+ *   sigmoid: s = sigmoid(logit) evaluated as the fixed fp32 sequence  x=clamp(logit,-30,30);
+ *     t=(-x)*log2e; n=rint(t); f=t-n; p=c6; p=p*f+c_i (i=5..0, product and sum rounded separately,
+ *     c_i = ln2^i/i!); z=p*2^n; s=1/(1+z).  s' = s + sel_bias.  Experts form n_group contiguous groups;
+ *     group score = sum of its two largest s'; the topk_group best groups are kept (equal -> lower
+ *     group); the k largest s' among their experts are chosen (equal -> lower id); weight =
+ *     s[id] (/ sum of the k if cfg->renorm) * routed_scale.
+ * dev in : logits[T,E] f32 (finite); sel_bias[E] f32 or NULL.   dev out: topk_ids[T,k], topk_w[T,k].
+ */
+int32_t semmoe_route_from_logits(const semmoe_config* cfg, void* stream, const float* logits,
+                                 const float* sel_bias, int32_t* topk_ids, float* topk_w);
+
+/*
+ * coact_hist - token->expert activation counts of Sec. 3.2 in key-free form, and the expert-expert
+ * affinity that Alg. 1 consumes:  load[e] += #{(i,j): ids[i,j]=e};
+ * coact[a,b] += #{i: a in ids[i] and b in ids[i]} for all ordered (a,b), a=b included.
+ * ACCUMULATES: the caller zeroes load/coact before the first batch of a profile.
+ * dev in : topk_ids[T_batch,k] (ids of one token distinct, in [0,E)).  dev in/out: load[E] u32, coact[E,E] u32.
+ * cfg->T is ignored; T_batch >= 0 is the batch length.
+ */
+int32_t semmoe_coact_hist(const semmoe_config* cfg, void* stream, const int32_t* topk_ids, int32_t T_batch,
+                          uint32_t* load, uint32_t* coact);
+
+/*
+ * place - Alg. 1 `expert_place` (App. B), request-affinity term dropped; HOST function, synchronous.
+ *   Experts by load descending (equal -> lower id); expert e goes to the not-yet-full rank c maximising
+ *   alpha*sum_{e' on c} coact[e,e'] - gamma*loads_cls[c] (equal -> smaller loads_cls, then smaller c);
+ *   a rank is full at E/D experts.  Then at most ft_passes first-improvement sweeps over pairs e1<e2 on
+ *   different ranks, swapping when the intra-rank co-activation mass rises; stops after a sweep with no swap.
+ *   Physical order: rank-major, ascending original id inside a rank (the transparent gate-column shuffle
+ *   of Sec. 3.3 "Model scheduling" is phys_of_expert).
+ * host in : load[E] u64, coact[E*E] u64 (symmetric).  host out: expert_to_rank[E], phys_of_expert[E],
+ *           expert_of_phys[E] i32.
+ */
+int32_t semmoe_place(const semmoe_config* cfg, const uint64_t* load, const uint64_t* coact, int64_t alpha,
+                     int64_t gamma, int32_t ft_passes, int32_t* expert_to_rank, int32_t* phys_of_expert,
+                     int32_t* expert_of_phys);
+
+/*
+ * reshuffle - Alg. 3 `rebatch_tokens` (device ids, argsort, group_by_key, align, concat) with the
+ * device id taken from the token's actual top-k:  g[i,r] = #{j: expert_to_rank[ids[i,j]] = r};
+ * pref(i) = argmax_r g[i,r] (equal -> home(i) = i / ceil(T/D) if it is a maximiser, else the smallest);
+ * conf(i) = g[i,pref(i)].  Keep: per rank the candidates ordered by (conf desc, i asc), the first cap stay.
+ * Spill ("align"): the s-th spilled token (ascending i) takes the s-th free slot, ranks ascending.
+ * shf = tokens stably sorted by token_rank (new position -> token); inv_shf[shf[q]] = q (`resume_tokens`).
+ * dev in : topk_ids[T,k], expert_to_rank[E].  dev out: token_rank[T], shf[T], inv_shf[T], rank_count[D].
+ */
+int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                         const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf, int32_t* inv_shf,
+                         int32_t* rank_count, void* ws, size_t ws_bytes);
+
+/*
+ * dispatch - the dispatch all2all of expert parallelism (Sec. 1) as a single-device permutation.
+ *   Pairs are ordered by physical expert q = phys_of_expert[ids[i,j]], pairs of one expert by shuffled
+ *   pair index p' = inv_shf[i]*k + j (arrival order of a rank-ordered all2all).  slot = that position.
+ *   slot_of_pair[i*k+j] = slot; pair_of_slot[slot] = i*k+j; expert_offsets[q] = first slot of q
+ *   ([E] = P); rank_offsets[r] = expert_offsets[r*m]; X_perm[slot,:] = X[i,:] (bit copy);
+ *   send_matrix[s,r] = #{(i,j): token_rank[i]=s, rank of ids[i,j] = r};
+ *   remote_pairs = sum_{s != r} send_matrix[s,r]  (alpha of the volume model alpha*k*B*S/G, Sec. 3.1, is
+ *   remote_pairs / P).
+ * dev in : X[T,d] act or NULL (then no rows are moved and X_perm may be NULL); topk_ids[T,k];
+ *          token_rank[T]; shf[T] (a permutation; inv_shf is its inverse, not needed here);
+ *          phys_of_expert[E].
+ * dev out: X_perm[P,d] act; slot_of_pair[P]; pair_of_slot[P]; expert_offsets[E+1]; rank_offsets[D+1];
+ *          send_matrix[D,D] u32; remote_pairs[1] u64.
+ */
+int32_t semmoe_dispatch(const semmoe_config* cfg, void* stream, const void* X, const int32_t* topk_ids,
+                        const int32_t* token_rank, const int32_t* shf, const int32_t* phys_of_expert,
+                        void* X_perm, int32_t* slot_of_pair, int32_t* pair_of_slot, int32_t* expert_offsets,
+                        int32_t* rank_offsets, uint32_t* send_matrix, uint64_t* remote_pairs, void* ws,
+                        size_t ws_bytes);
+
+/*
+ * expert_ffn - the expert FFN (Sec. 2) in SwiGLU form, grouped over one rank's experts:
+ *   for every physical expert q of `rank` (rank = -1: all), for slots s in [expert_offsets[q],
+ *   expert_offsets[q+1]):  Y[s] = W_down[e] ( silu(W_gate[e] x_s) * (W_up[e] x_s) ),  e = expert_of_phys[q],
+ *   W_gate[e] = W_gu[e, 0:F, :], W_up[e] = W_gu[e, F:2F, :].  fp32 accumulate; the hidden activation is
+ *   rounded to the act type once.  Rows of other ranks in Y are not written.
+ * dev in : X_perm[P,d] act; expert_offsets[E+1]; expert_of_phys[E]; W_gu[E,2F,d] act; W_down[E,d,F] act
+ *          (both indexed by ORIGINAL expert id).   dev out: Y[P,d] act.
+ */
+int32_t semmoe_expert_ffn(const semmoe_config* cfg, void* stream, int32_t rank, const void* X_perm,
+                          const int32_t* expert_offsets, const int32_t* expert_of_phys, const void* W_gu,
+                          const void* W_down, void* Y, void* ws, size_t ws_bytes);
+
+/*
+ * shared_ffn - the same FFN with one set of weights applied to n_tokens rows (the always-active shared
+ * expert of DeepSeek-style layers).  dev in: X[n_tokens,d]; W_gu_sh[2F,d]; W_down_sh[d,F].  dev out:
+ * Y_shared[n_tokens,d].  n_tokens <= T*k.
+ */
+int32_t semmoe_shared_ffn(const semmoe_config* cfg, void* stream, const void* X, int32_t n_tokens,
+                          const void* W_gu_sh, const void* W_down_sh, void* Y_shared, void* ws,
+                          size_t ws_bytes);
+
+/*
+ * combine - the combine all2all (Sec. 1) plus `resume_tokens` (Alg. 3):
+ *   Out[i] = sum_{j<k} topk_w[i,j] * Y[slot_of_pair[i*k+j]] (+ Y_shared[i]), accumulated in fp32 in
+ *   ascending j, rounded once to the act type.
+ * dev in : Y[P,d] act; slot_of_pair[P]; topk_w[T,k] f32; Y_shared[T,d] act or NULL.  dev out: Out[T,d] act.
+ */
+int32_t semmoe_combine(const semmoe_config* cfg, void* stream, const void* Y, const int32_t* slot_of_pair,
+                       const float* topk_w, const void* Y_shared, void* Out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEMMOE_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of libsemmoe.so: argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; this module turns torch tensors into
+raw pointers, passes torch's current stream, and raises on a non-zero status.  torch is used for
+device memory and streams, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+STATUS_NAMES = {0: "OK", -1: "EINVAL", -2: "ESHAPE", -3: "EWORKSPACE", -4: "EHIP", -5: "EUNSUPPORTED"}
+FP32, BF16 = 0, 1
+SOFTMAX, SIGMOID = 0, 1
+
+
+class SemMoEError(RuntimeError):
+    def __init__(self, call: str, status: int, hip_error: int = 0):
+        self.call, self.status, self.hip_error = call, status, hip_error
+        msg = "%s failed: %s (%d)" % (call, STATUS_NAMES.get(status, "?"), status)
+        if status == -4:
+            msg += ", hipError_t %d" % hip_error
+        super().__init__(msg)
+
+
+class _CConfig(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("E", C.c_int32), ("k", C.c_int32), ("F", C.c_int32),
+                ("D", C.c_int32), ("dtype", C.c_int32), ("score", C.c_int32), ("renorm", C.c_int32),
+                ("n_group", C.c_int32), ("topk_group", C.c_int32), ("routed_scale", C.c_float),
+                ("cap", C.c_int32), ("num_classes", C.c_int32)]
+
+
+@dataclass
+class Config:
+    T: int
+    d: int
+    E: int
+    k: int
+    F: int
+    D: int
+    dtype: int = BF16
+    score: int = SOFTMAX
+    renorm: bool = True
+    n_group: int = 1
+    topk_group: int = 1
+    routed_scale: float = 1.0
+    cap: int = 0
+    num_classes: int = 0
+
+    def c(self) -> _CConfig:
+        return _CConfig(self.T, self.d, self.E, self.k, self.F, self.D, self.dtype, self.score, int(self.renorm),
+                        self.n_group, self.topk_group, self.routed_scale, self.cap, self.num_classes)
+
+    @staticmethod
+    def from_workload(w, cap: Optional[int] = None, T: Optional[int] = None) -> "Config":
+        return Config(T=w.T if T is None else T, d=w.d, E=w.E, k=w.k, F=w.F, D=w.D,
+                      dtype=BF16 if w.dtype == "bf16" else FP32,
+                      score=SIGMOID if w.score == "sigmoid" else SOFTMAX, renorm=bool(w.renorm),
+                      n_group=w.n_group, topk_group=w.topk_group, routed_scale=w.routed_scale,
+                      cap=w.cap if cap is None else cap, num_classes=w.C)
+
+
+def lib_path() -> str:
+    return os.environ.get("SEMMOE_LIB", os.path.join(HERE, "lib", "libsemmoe.so"))
+
+
+_LIB = None
+_P = C.c_void_p
+_SIGS = {
+    "semmoe_version": ([], C.c_int32),
+    "semmoe_last_hip_error": ([], C.c_int32),
+    "semmoe_workspace_bytes": ([_P, C.POINTER(C.c_size_t)], C.c_int32),
+    "semmoe_route": ([_P] * 12 + [C.c_size_t], C.c_int32),
+    "semmoe_route_from_logits": ([_P] * 6, C.c_int32),
+    "semmoe_coact_hist": ([_P, _P, _P, C.c_int32, _P, _P], C.c_int32),
+    "semmoe_place": ([_P, _P, _P, C.c_int64, C.c_int64, C.c_int32, _P, _P, _P], C.c_int32),
+    "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
+    "semmoe_dispatch": ([_P] * 15 + [C.c_size_t], C.c_int32),
+    "semmoe_expert_ffn": ([_P, _P, C.c_int32] + [_P] * 7 + [C.c_size_t], C.c_int32),
+    "semmoe_shared_ffn": ([_P, _P, _P, C.c_int32, _P, _P, _P, _P, C.c_size_t], C.c_int32),
+    "semmoe_combine": ([_P] * 7, C.c_int32),
+}
+EXPORTS = tuple(_SIGS)
+
+
+def load_library():
+    """Load libsemmoe.so (built by `python -m paper_2503_04398_amd.build`).  No fallback."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise SemMoEError("load_library: %s is missing; build it with "
+                              "`python -m paper_2503_04398_amd.build`" % path, -1)
+        lib = C.CDLL(path)
+        for name, (args, res) in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.argtypes, fn.restype = args, res
+        _LIB = lib
+    return _LIB
+
+
+def _ptr(t):
+    """device (or host) pointer of a torch tensor / numpy array / None / int"""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        assert t.is_contiguous(), "tensors must be contiguous"
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+
+
+class SemMoE:
+    """One config + one workspace; methods mirror the C entry points one to one."""
+
+    def __init__(self, cfg: Config, device="cuda:0", allocate_workspace: bool = True):
+        self.lib = load_library()
+        self.cfg = cfg
+        self.device = device
+        self.ws = None
+        self.ws_bytes = 0
+        if allocate_workspace:
+            import torch
+            self.ws_bytes = self.workspace_bytes()
+            self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    # -- helpers
+    def _check(self, name: str, st: int):
+        if st != 0:
+            raise SemMoEError(name, st, self.lib.semmoe_last_hip_error())
+
+    def _cfg(self, **over):
+        c = self.cfg.c()
+        for k_, v in over.items():
+            setattr(c, k_, v)
+        return c
+
+    def workspace_bytes(self) -> int:
+        n = C.c_size_t(0)
+        c = self._cfg()
+        self._check("semmoe_workspace_bytes", self.lib.semmoe_workspace_bytes(C.byref(c), C.byref(n)))
+        return int(n.value)
+
+    # -- entry points
+    def route(self, X, W_r, topk_ids, topk_w, b_g=None, token_class=None, class_bias=None, sel_bias=None,
+              logits_out=None, T=None):
+        c = self._cfg(**({"T": T} if T is not None else {}))
+        self._check("semmoe_route", self.lib.semmoe_route(
+            C.byref(c), _stream(), _ptr(X), _ptr(W_r), _ptr(b_g), _ptr(token_class), _ptr(class_bias),
+            _ptr(sel_bias), _ptr(logits_out), _ptr(topk_ids), _ptr(topk_w), _ptr(self.ws), self.ws_bytes))
+
+    def route_from_logits(self, logits, topk_ids, topk_w, sel_bias=None, T=None):
+        c = self._cfg(**({"T": T} if T is not None else {}))
+        self._check("semmoe_route_from_logits", self.lib.semmoe_route_from_logits(
+            C.byref(c), _stream(), _ptr(logits), _ptr(sel_bias), _ptr(topk_ids), _ptr(topk_w)))
+
+    def coact_hist(self, topk_ids, T_batch, load, coact):
+        c = self._cfg()
+        self._check("semmoe_coact_hist", self.lib.semmoe_coact_hist(
+            C.byref(c), _stream(), _ptr(topk_ids), int(T_batch), _ptr(load), _ptr(coact)))
+
+    def place(self, load_u64, coact_u64, alpha=1, gamma=0, ft_passes=8):
+        """host call: numpy uint64 in, three numpy int32 arrays out"""
+        import numpy as np
+        load_u64 = np.ascontiguousarray(load_u64, dtype=np.uint64)
+        coact_u64 = np.ascontiguousarray(coact_u64, dtype=np.uint64)
+        E = self.cfg.E
+        e2r, phys, inv = (np.zeros(E, dtype=np.int32) for _ in range(3))
+        c = self._cfg()
+        self._check("semmoe_place", self.lib.semmoe_place(
+            C.byref(c), _ptr(load_u64), _ptr(coact_u64), int(alpha), int(gamma), int(ft_passes), _ptr(e2r),
+            _ptr(phys), _ptr(inv)))
+        return e2r, phys, inv
+
+    def reshuffle(self, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count, cap=None):
+        c = self._cfg(**({"cap": cap} if cap is not None else {}))
+        self._check("semmoe_reshuffle", self.lib.semmoe_reshuffle(
+            C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), _ptr(token_rank), _ptr(shf),
+            _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def dispatch(self, X, topk_ids, token_rank, shf, phys_of_expert, X_perm, slot_of_pair, pair_of_slot,
+                 expert_offsets, rank_offsets, send_matrix, remote_pairs):
+        c = self._cfg()
+        self._check("semmoe_dispatch", self.lib.semmoe_dispatch(
+            C.byref(c), _stream(), _ptr(X), _ptr(topk_ids), _ptr(token_rank), _ptr(shf), _ptr(phys_of_expert),
+            _ptr(X_perm), _ptr(slot_of_pair), _ptr(pair_of_slot), _ptr(expert_offsets), _ptr(rank_offsets),
+            _ptr(send_matrix), _ptr(remote_pairs), _ptr(self.ws), self.ws_bytes))
+
+    def expert_ffn(self, rank, X_perm, expert_offsets, expert_of_phys, W_gu, W_down, Y):
+        c = self._cfg()
+        self._check("semmoe_expert_ffn", self.lib.semmoe_expert_ffn(
+            C.byref(c), _stream(), int(rank), _ptr(X_perm), _ptr(expert_offsets), _ptr(expert_of_phys),
+            _ptr(W_gu), _ptr(W_down), _ptr(Y), _ptr(self.ws), self.ws_bytes))
+
+    def shared_ffn(self, X, n_tokens, W_gu_sh, W_down_sh, Y_shared):
+        c = self._cfg()
+        self._check("semmoe_shared_ffn", self.lib.semmoe_shared_ffn(
+            C.byref(c), _stream(), _ptr(X), int(n_tokens), _ptr(W_gu_sh), _ptr(W_down_sh), _ptr(Y_shared),
+            _ptr(self.ws), self.ws_bytes))
+
+    def combine(self, Y, slot_of_pair, topk_w, Out, Y_shared=None):
+        c = self._cfg()
+        self._check("semmoe_combine", self.lib.semmoe_combine(
+            C.byref(c), _stream(), _ptr(Y), _ptr(slot_of_pair), _ptr(topk_w), _ptr(Y_shared), _ptr(Out)))

@@ -1,0 +1,254 @@
+// dispatch: the dispatch all2all of expert parallelism (Sec. 1) as a single-device permutation.
+// Index half: a stable counting sort of the P = T*k (token, expert) pairs by physical expert, pairs
+// taken in shuffled-token order.  A token's k experts are distinct, so inside a 256-token workgroup the
+// rank of a pair among equal keys is the popcount of the key's token bitmap below that token; across
+// workgroups an exclusive scan over (expert, workgroup).  Row half: each token row is read once and
+// written to its k slots with 16-byte accesses.
+#include "common.hpp"
+
+namespace semmoe {
+
+constexpr int kWords = kTokBlock / 32;
+
+struct DispatchWs {
+  int32_t* cnt;        // [NB][E]    per-block pair counts per physical expert -> base slot after the scan
+  uint32_t* send_part; // [NB][D*D]  per-block send matrices
+};
+
+__device__ __forceinline__ int bitmap_rank(const uint32_t* words, int t) {
+  int r = 0;
+  const int w = t >> 5;
+  for (int x = 0; x < w; ++x) r += __popc(words[x]);
+  r += __popc(words[w] & ((1u << (t & 31)) - 1u));
+  return r;
+}
+
+// fill the [E][kWords] bitmaps of this block's 256 shuffled positions; returns the thread's token (or -1)
+__device__ __forceinline__ int fill_bitmaps(int T, int k, int E, const int32_t* __restrict__ ids,
+                                            const int32_t* __restrict__ shf, const int32_t* __restrict__ phys,
+                                            uint32_t* bm, int* q_out) {
+  for (int x = threadIdx.x; x < E * kWords; x += blockDim.x) bm[x] = 0;
+  __syncthreads();
+  const int t = threadIdx.x;
+  const int pos = blockIdx.x * kTokBlock + t;
+  int tok = -1;
+  if (pos < T) {
+    tok = shf[pos];
+    if ((unsigned)tok >= (unsigned)T) tok = -1;
+  }
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+    q_out[j] = -1;
+    if (j < k && tok >= 0) {
+      const int e = ids[size_t(tok) * k + j];
+      if ((unsigned)e < (unsigned)E) {
+        const int q = phys[e];
+        if ((unsigned)q < (unsigned)E) {
+          q_out[j] = q;
+          atomicOr(&bm[q * kWords + (t >> 5)], 1u << (t & 31));
+        }
+      }
+    }
+  }
+  __syncthreads();
+  return tok;
+}
+
+// D1: per-block counts per physical expert and per-block send matrix
+__global__ __launch_bounds__(kTokBlock) void dp_count_kernel(int T, int k, int E, int D,
+                                                             const int32_t* __restrict__ ids,
+                                                             const int32_t* __restrict__ token_rank,
+                                                             const int32_t* __restrict__ shf,
+                                                             const int32_t* __restrict__ phys, DispatchWs w) {
+  extern __shared__ uint32_t lds[];  // [E][kWords] bitmaps, [D*D] send counts
+  uint32_t* bm = lds;
+  uint32_t* send = lds + E * kWords;
+  for (int x = threadIdx.x; x < D * D; x += blockDim.x) send[x] = 0;
+  int q[SEMMOE_MAX_K];
+  const int tok = fill_bitmaps(T, k, E, ids, shf, phys, bm, q);
+  if (tok >= 0) {
+    const int s = token_rank[tok];
+    const int m = E / D;
+    if ((unsigned)s < (unsigned)D) {
+#pragma unroll
+      for (int j = 0; j < SEMMOE_MAX_K; ++j)
+        if (q[j] >= 0) atomicAdd(&send[s * D + q[j] / m], 1u);
+    }
+  }
+  for (int x = threadIdx.x; x < E; x += blockDim.x) {
+    int c = 0;
+#pragma unroll
+    for (int y = 0; y < kWords; ++y) c += __popc(bm[x * kWords + y]);
+    w.cnt[size_t(blockIdx.x) * E + x] = c;
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < D * D; x += blockDim.x) w.send_part[size_t(blockIdx.x) * D * D + x] = send[x];
+}
+
+// D2: expert_offsets, rank_offsets, base slot of (block, expert), send_matrix, remote_pairs (one workgroup)
+__global__ __launch_bounds__(1024) void dp_scan_kernel(int NB, int E, int D, int32_t* __restrict__ expert_offsets,
+                                                       int32_t* __restrict__ rank_offsets,
+                                                       uint32_t* __restrict__ send_matrix,
+                                                       unsigned long long* __restrict__ remote_pairs,
+                                                       DispatchWs w) {
+  __shared__ int32_t tot[SEMMOE_MAX_E + 1];
+  __shared__ unsigned long long remote_sh;
+  const int tid = threadIdx.x;
+  if (tid == 0) remote_sh = 0ull;
+  for (int q = tid; q < E; q += blockDim.x) {
+    int s = 0;
+    for (int b = 0; b < NB; ++b) s += w.cnt[size_t(b) * E + q];
+    tot[q] = s;
+  }
+  __syncthreads();
+  if (tid < 64) {  // exclusive scan over experts by one wave
+    const int per = (E + 63) / 64;
+    const int lo = min(tid * per, E), hi = min(lo + per, E);
+    int s = 0;
+    for (int q = lo; q < hi; ++q) s += tot[q];
+    int incl = s;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off);
+      if (tid >= off) incl += v;
+    }
+    int run = incl - s;
+    for (int q = lo; q < hi; ++q) {
+      const int c = tot[q];
+      tot[q] = run;
+      run += c;
+    }
+    if (tid == 63) tot[E] = incl;
+  }
+  __syncthreads();
+  const int m = E / D;
+  for (int q = tid; q <= E; q += blockDim.x) {
+    expert_offsets[q] = tot[q];
+    if (q % m == 0) rank_offsets[q / m] = tot[q];
+  }
+  for (int q = tid; q < E; q += blockDim.x) {
+    int run = tot[q];
+    for (int b = 0; b < NB; ++b) {
+      const int c = w.cnt[size_t(b) * E + q];
+      w.cnt[size_t(b) * E + q] = run;
+      run += c;
+    }
+  }
+  unsigned long long remote = 0;
+  for (int x = tid; x < D * D; x += blockDim.x) {
+    uint32_t s = 0;
+    for (int b = 0; b < NB; ++b) s += w.send_part[size_t(b) * D * D + x];
+    send_matrix[x] = s;
+    if (x / D != x % D) remote += s;
+  }
+  if (remote) atomicAdd(&remote_sh, remote);
+  __syncthreads();
+  if (tid == 0) *remote_pairs = remote_sh;
+}
+
+// D3: slot of every pair and its inverse
+__global__ __launch_bounds__(kTokBlock) void dp_slot_kernel(int T, int k, int E, const int32_t* __restrict__ ids,
+                                                            const int32_t* __restrict__ shf,
+                                                            const int32_t* __restrict__ phys,
+                                                            int32_t* __restrict__ slot_of_pair,
+                                                            int32_t* __restrict__ pair_of_slot, DispatchWs w) {
+  extern __shared__ uint32_t lds[];  // [E][kWords]
+  int q[SEMMOE_MAX_K];
+  const int tok = fill_bitmaps(T, k, E, ids, shf, phys, lds, q);
+  if (tok < 0) return;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+    if (q[j] < 0) continue;
+    const int slot = w.cnt[size_t(blockIdx.x) * E + q[j]] + bitmap_rank(lds + q[j] * kWords, t);
+    const int pair = tok * k + j;
+    slot_of_pair[pair] = slot;
+    pair_of_slot[slot] = pair;
+  }
+}
+
+// D4: move rows.  One workgroup per token; each thread owns 16-byte chunks of the row.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+template <int K_UNROLL>
+__global__ __launch_bounds__(256) void dp_rows_kernel(int k, int row_chunks, int P, const u32x4_t* __restrict__ X,
+                                                      const int32_t* __restrict__ slot_of_pair,
+                                                      u32x4_t* __restrict__ X_perm) {
+  const int tok = blockIdx.x;
+  const int32_t* sl = slot_of_pair + size_t(tok) * k;
+  for (int c = threadIdx.x; c < row_chunks; c += blockDim.x) {
+    const u32x4_t v = X[size_t(tok) * row_chunks + c];
+    if constexpr (K_UNROLL > 0) {
+#pragma unroll
+      for (int j = 0; j < K_UNROLL; ++j) {
+        const int s = sl[j];
+        if ((unsigned)s < (unsigned)P) __builtin_nontemporal_store(v, &X_perm[size_t(s) * row_chunks + c]);
+      }
+    } else {
+      for (int j = 0; j < k; ++j) {
+        const int s = sl[j];
+        if ((unsigned)s < (unsigned)P) __builtin_nontemporal_store(v, &X_perm[size_t(s) * row_chunks + c]);
+      }
+    }
+  }
+}
+
+static bool carve_dispatch(const semmoe_config* cfg, void* ws, size_t bytes, DispatchWs* w) {
+  const size_t NB = cdiv(cfg->T, kTokBlock);
+  Carver c(ws, bytes);
+  w->cnt = c.take<int32_t>(NB * cfg->E);
+  w->send_part = c.take<uint32_t>(NB * cfg->D * cfg->D);
+  return c.ok;
+}
+
+size_t ws_dispatch(const semmoe_config* cfg) {
+  const size_t NB = cdiv(cfg->T, kTokBlock);
+  return align_up(NB * cfg->E * 4, 256) + align_up(NB * cfg->D * cfg->D * 4, 256) + 512;
+}
+
+}  // namespace semmoe
+
+using namespace semmoe;
+
+extern "C" int32_t semmoe_dispatch(const semmoe_config* cfg, void* stream, const void* X, const int32_t* topk_ids,
+                                   const int32_t* token_rank, const int32_t* shf, const int32_t* phys_of_expert,
+                                   void* X_perm, int32_t* slot_of_pair, int32_t* pair_of_slot,
+                                   int32_t* expert_offsets, int32_t* rank_offsets, uint32_t* send_matrix,
+                                   uint64_t* remote_pairs, void* ws, size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, X != nullptr, false);
+  if (st != SEMMOE_OK) return st;
+  if (!topk_ids || !token_rank || !shf || !phys_of_expert || !slot_of_pair || !pair_of_slot || !expert_offsets ||
+      !rank_offsets || !send_matrix || !remote_pairs)
+    return SEMMOE_EINVAL;
+  if (X && (!X_perm || !aligned16(X) || !aligned16(X_perm))) return SEMMOE_EINVAL;
+  DispatchWs w;
+  if (!carve_dispatch(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int T = cfg->T, k = cfg->k, E = cfg->E, D = cfg->D;
+  const int NB = cdiv(T, kTokBlock);
+  if (NB > 0) {
+    hipLaunchKernelGGL(dp_count_kernel, dim3(NB), dim3(kTokBlock), (E * kWords + D * D) * 4, s, T, k, E, D, topk_ids,
+                       token_rank, shf, phys_of_expert, w);
+  }
+  hipLaunchKernelGGL(dp_scan_kernel, dim3(1), dim3(1024), 0, s, NB, E, D, expert_offsets, rank_offsets, send_matrix,
+                     reinterpret_cast<unsigned long long*>(remote_pairs), w);
+  if (NB > 0) {
+    hipLaunchKernelGGL(dp_slot_kernel, dim3(NB), dim3(kTokBlock), E * kWords * 4, s, T, k, E, topk_ids, shf,
+                       phys_of_expert, slot_of_pair, pair_of_slot, w);
+    if (X) {
+      const int row_chunks = int(size_t(cfg->d) * act_bytes(cfg) / 16);
+      const u32x4_t* Xv = static_cast<const u32x4_t*>(X);
+      u32x4_t* Xp = static_cast<u32x4_t*>(X_perm);
+      const int P = T * k;
+      switch (k) {
+        case 1: hipLaunchKernelGGL(dp_rows_kernel<1>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+        case 2: hipLaunchKernelGGL(dp_rows_kernel<2>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+        case 4: hipLaunchKernelGGL(dp_rows_kernel<4>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+        case 8: hipLaunchKernelGGL(dp_rows_kernel<8>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+        default: hipLaunchKernelGGL(dp_rows_kernel<0>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+      }
+    }
+  }
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}

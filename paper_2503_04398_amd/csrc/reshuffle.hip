@@ -1,0 +1,329 @@
+// reshuffle: Alg. 3 `rebatch_tokens` on one device.  Per-token device id from the token's top-k and
+// the placement, capacity-bounded keep / spill ("align"), then the shuffle permutation and its
+// inverse (`resume_tokens`).  Everything is integer and order-independent: stable ranks inside a
+// 256-token workgroup come from LDS bitmaps (rank = popcount of the key's bits below the token),
+// ranks across workgroups from small exclusive scans; no atomic's ordering reaches an output.
+#include "common.hpp"
+
+namespace semmoe {
+
+constexpr int kWords = kTokBlock / 32;  // bitmap words per key
+
+struct ReshuffleWs {
+  int32_t* pc;          // [T]   pref | conf << 8
+  int32_t* cnt;         // [NB][D*(k+1)]  per-block (pref, conf) counts
+  int32_t* thr;         // [D]   borderline confidence c* per rank (-1: every candidate is kept)
+  int32_t* quota;       // [D]   borderline candidates kept
+  int32_t* free_pre;    // [D+1] exclusive prefix of free slots
+  int32_t* border_pre;  // [NB][D] borderline candidates of rank r in earlier blocks
+  int32_t* spill_cnt;   // [NB]  -> exclusive prefix after the scan
+  int32_t* rank_hist;   // [NB][D] -> base position after the scan
+};
+
+__device__ __forceinline__ int bitmap_rank(const uint32_t* words, int t) {
+  int r = 0;
+  const int w = t >> 5;
+  for (int x = 0; x < w; ++x) r += __popc(words[x]);
+  r += __popc(words[w] & ((1u << (t & 31)) - 1u));
+  return r;
+}
+
+// K1: pref / conf per token, per-block (pref, conf) histogram
+__global__ __launch_bounds__(kTokBlock) void rs_pref_kernel(int T, int k, int D, int E, int per_home,
+                                                            const int32_t* __restrict__ ids,
+                                                            const int32_t* __restrict__ e2r, ReshuffleWs w) {
+  extern __shared__ int32_t hist[];  // D*(k+1)
+  const int nkeys = D * (k + 1);
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) hist[x] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  if (i < T) {
+    int r[SEMMOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      r[j] = -1;
+      if (j < k) {
+        const int e = ids[size_t(i) * k + j];
+        if ((unsigned)e < (unsigned)E) {
+          const int rr = e2r[e];
+          if ((unsigned)rr < (unsigned)D) r[j] = rr;
+        }
+      }
+    }
+    const int home = i / per_home;
+    int best_r = home, best_c = 0;  // g[i, home] first: it wins every tie
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) best_c += (r[j] == home);
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      if (r[j] < 0) continue;
+      int c = 0;
+#pragma unroll
+      for (int j2 = 0; j2 < SEMMOE_MAX_K; ++j2) c += (r[j2] == r[j]);
+      // larger gain wins; among equal gains home stays, otherwise the smallest rank
+      if (c > best_c || (c == best_c && best_r != home && r[j] < best_r)) {
+        best_c = c;
+        best_r = r[j];
+      }
+    }
+    w.pc[i] = best_r | (best_c << 8);
+    atomicAdd(&hist[best_r * (k + 1) + best_c], 1);
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) w.cnt[size_t(blockIdx.x) * nkeys + x] = hist[x];
+}
+
+// K2: thresholds per rank, free-slot prefix, borderline prefix over blocks (one workgroup)
+__global__ __launch_bounds__(1024) void rs_threshold_kernel(int NB, int k, int D, int cap, ReshuffleWs w) {
+  extern __shared__ int32_t tot[];  // D*(k+1) totals, then D free counts
+  const int nkeys = D * (k + 1);
+  int32_t* free_cnt = tot + nkeys;
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) {
+    int s = 0;
+    for (int b = 0; b < NB; ++b) s += w.cnt[size_t(b) * nkeys + x];
+    tot[x] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < D) {
+    const int r = threadIdx.x;
+    // walk the confidence levels from the top: the level at which the candidates overflow `cap` is the
+    // borderline level c*; `quota` of its candidates (lowest token index first) are kept.  -1: all kept.
+    int cum = 0, thr = -1, quota = 0;
+    for (int c = k; c >= 0; --c) {
+      const int n = tot[r * (k + 1) + c];
+      if (cum + n > cap) {
+        thr = c;
+        quota = cap - cum;
+        cum = cap;
+        break;
+      }
+      cum += n;
+    }
+    w.thr[r] = thr;
+    w.quota[r] = quota;
+    free_cnt[r] = cap - cum;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int s = 0;
+    for (int r = 0; r < D; ++r) {
+      w.free_pre[r] = s;
+      s += free_cnt[r];
+    }
+    w.free_pre[D] = s;
+  }
+  if (threadIdx.x < D) {
+    const int r = threadIdx.x;
+    const int thr = w.thr[r];
+    int s = 0;
+    for (int b = 0; b < NB; ++b) {
+      w.border_pre[size_t(b) * D + r] = s;
+      if (thr >= 0) s += w.cnt[size_t(b) * nkeys + r * (k + 1) + thr];
+    }
+  }
+}
+
+// K3: keep phase.  token_rank[i] = pref if kept, -1 if spilled; spill count per block
+__global__ __launch_bounds__(kTokBlock) void rs_keep_kernel(int T, int D, int32_t* __restrict__ token_rank,
+                                                            ReshuffleWs w) {
+  extern __shared__ uint32_t bm[];  // [D][kWords] borderline bitmaps, then 1 counter
+  uint32_t* spill_total = bm + D * kWords;
+  for (int x = threadIdx.x; x < D * kWords + 1; x += blockDim.x) bm[x] = 0;
+  __syncthreads();
+  const int t = threadIdx.x;
+  const int i = blockIdx.x * kTokBlock + t;
+  int pref = 0, conf = 0, thr = -1;
+  bool border = false;
+  if (i < T) {
+    const int pc = w.pc[i];
+    pref = pc & 0xff;
+    conf = pc >> 8;
+    thr = w.thr[pref];
+    border = (thr >= 0 && conf == thr);
+    if (border) atomicOr(&bm[pref * kWords + (t >> 5)], 1u << (t & 31));
+  }
+  __syncthreads();
+  bool spilled = false;
+  if (i < T) {
+    bool kept;
+    if (thr < 0 || conf > thr) kept = true;
+    else if (conf < thr) kept = false;
+    else {
+      const int idx = w.border_pre[size_t(blockIdx.x) * D + pref] + bitmap_rank(bm + pref * kWords, t);
+      kept = idx < w.quota[pref];
+    }
+    spilled = !kept;
+    token_rank[i] = kept ? pref : -1;
+  }
+  const unsigned long long bal = __ballot(spilled);
+  if ((t & 63) == 0 && bal) atomicAdd(spill_total, (uint32_t)__popcll(bal));
+  __syncthreads();
+  if (t == 0) w.spill_cnt[blockIdx.x] = (int32_t)*spill_total;
+}
+
+// generic single-workgroup exclusive scan of n ints in place (n small); total goes to *total if given
+__global__ __launch_bounds__(1024) void rs_scan_kernel(int n, int32_t* __restrict__ v) {
+  __shared__ int32_t part[1024];
+  const int per = (n + 1023) / 1024;
+  const int lo = min((int)threadIdx.x * per, n), hi = min(lo + per, n);
+  int s = 0;
+  for (int x = lo; x < hi; ++x) s += v[x];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    int add = (threadIdx.x >= off) ? part[threadIdx.x - off] : 0;
+    __syncthreads();
+    part[threadIdx.x] += add;
+    __syncthreads();
+  }
+  int run = part[threadIdx.x] - s;
+  for (int x = lo; x < hi; ++x) {
+    const int c = v[x];
+    v[x] = run;
+    run += c;
+  }
+}
+
+// K5: spilled tokens take the free slots in rank order; per-block histogram of the final ranks
+__global__ __launch_bounds__(kTokBlock) void rs_assign_kernel(int T, int D, int32_t* __restrict__ token_rank,
+                                                              ReshuffleWs w) {
+  extern __shared__ uint32_t sm[];  // [kWords] spilled bitmap, [D] rank histogram
+  uint32_t* spbm = sm;
+  int32_t* hist = reinterpret_cast<int32_t*>(sm + kWords);
+  for (int x = threadIdx.x; x < kWords + D; x += blockDim.x) sm[x] = 0;
+  __syncthreads();
+  const int t = threadIdx.x;
+  const int i = blockIdx.x * kTokBlock + t;
+  int rank = -1;
+  if (i < T) {
+    rank = token_rank[i];
+    if (rank < 0) atomicOr(&spbm[t >> 5], 1u << (t & 31));
+  }
+  __syncthreads();
+  if (i < T) {
+    if (rank < 0) {
+      const int s = w.spill_cnt[blockIdx.x] + bitmap_rank(spbm, t);
+      int r = 0;
+      while (r + 1 < D && w.free_pre[r + 1] <= s) ++r;  // free_pre[r] <= s < free_pre[r+1]
+      rank = r;
+      token_rank[i] = rank;
+    }
+    atomicAdd(&hist[rank], 1);
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < D; x += blockDim.x) w.rank_hist[size_t(blockIdx.x) * D + x] = hist[x];
+}
+
+// K6: rank_count, and base position of (block, rank) in the shuffled order (one workgroup)
+__global__ __launch_bounds__(64) void rs_rank_scan_kernel(int NB, int D, int32_t* __restrict__ rank_count,
+                                                          ReshuffleWs w) {
+  __shared__ int32_t total[SEMMOE_MAX_D];
+  const int r = threadIdx.x;
+  if (r < D) {
+    int s = 0;
+    for (int b = 0; b < NB; ++b) s += w.rank_hist[size_t(b) * D + r];
+    total[r] = s;
+    rank_count[r] = s;
+  }
+  __syncthreads();
+  if (r < D) {
+    int start = 0;
+    for (int x = 0; x < r; ++x) start += total[x];
+    int run = start;
+    for (int b = 0; b < NB; ++b) {
+      const int c = w.rank_hist[size_t(b) * D + r];
+      w.rank_hist[size_t(b) * D + r] = run;
+      run += c;
+    }
+  }
+}
+
+// K7: stable scatter: shf (new position -> token) and inv_shf
+__global__ __launch_bounds__(kTokBlock) void rs_scatter_kernel(int T, int D, const int32_t* __restrict__ token_rank,
+                                                               int32_t* __restrict__ shf,
+                                                               int32_t* __restrict__ inv_shf, ReshuffleWs w) {
+  extern __shared__ uint32_t bm[];  // [D][kWords]
+  for (int x = threadIdx.x; x < D * kWords; x += blockDim.x) bm[x] = 0;
+  __syncthreads();
+  const int t = threadIdx.x;
+  const int i = blockIdx.x * kTokBlock + t;
+  int rank = 0;
+  if (i < T) {
+    rank = token_rank[i];
+    atomicOr(&bm[rank * kWords + (t >> 5)], 1u << (t & 31));
+  }
+  __syncthreads();
+  if (i < T) {
+    const int pos = w.rank_hist[size_t(blockIdx.x) * D + rank] + bitmap_rank(bm + rank * kWords, t);
+    inv_shf[i] = pos;
+    shf[pos] = i;
+  }
+}
+
+__global__ void rs_zero_kernel(int n, int32_t* __restrict__ v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) v[i] = 0;
+}
+
+static bool carve_reshuffle(const semmoe_config* cfg, void* ws, size_t bytes, ReshuffleWs* w) {
+  const size_t NB = cdiv(cfg->T, kTokBlock);
+  const size_t nkeys = size_t(cfg->D) * (cfg->k + 1);
+  Carver c(ws, bytes);
+  w->pc = c.take<int32_t>(cfg->T);
+  w->cnt = c.take<int32_t>(NB * nkeys);
+  w->thr = c.take<int32_t>(cfg->D);
+  w->quota = c.take<int32_t>(cfg->D);
+  w->free_pre = c.take<int32_t>(cfg->D + 1);
+  w->border_pre = c.take<int32_t>(NB * cfg->D);
+  w->spill_cnt = c.take<int32_t>(NB);
+  w->rank_hist = c.take<int32_t>(NB * cfg->D);
+  return c.ok;
+}
+
+size_t ws_reshuffle(const semmoe_config* cfg) {
+  const size_t NB = cdiv(cfg->T, kTokBlock);
+  const size_t nkeys = size_t(cfg->D) * (cfg->k + 1);
+  const size_t counts[8] = {size_t(cfg->T), NB * nkeys, size_t(cfg->D), size_t(cfg->D), size_t(cfg->D) + 1,
+                            NB * cfg->D, NB, NB * cfg->D};
+  size_t b = 0;
+  for (size_t n : counts) b = align_up(b, 256) + n * 4;
+  return b + 256;
+}
+
+}  // namespace semmoe
+
+using namespace semmoe;
+
+extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                    const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf,
+                                    int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, false, false);
+  if (st != SEMMOE_OK) return st;
+  if (!topk_ids || !expert_to_rank || !token_rank || !shf || !inv_shf || !rank_count) return SEMMOE_EINVAL;
+  if (cfg->cap < 0) return SEMMOE_EINVAL;
+  if ((long long)cfg->cap * cfg->D < cfg->T) return SEMMOE_ESHAPE;
+  if (cfg->k >= 128) return SEMMOE_EUNSUPPORTED;
+  ReshuffleWs w;
+  if (!carve_reshuffle(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int T = cfg->T, D = cfg->D, k = cfg->k;
+  const int NB = cdiv(T, kTokBlock);
+  if (T == 0) {
+    hipLaunchKernelGGL(rs_zero_kernel, dim3(1), dim3(64), 0, s, D, rank_count);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  const int per_home = cdiv(T, D);
+  const int nkeys = D * (k + 1);
+  hipLaunchKernelGGL(rs_pref_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, cfg->E, per_home, topk_ids,
+                     expert_to_rank, w);
+  hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(1024), (nkeys + D) * 4, s, NB, k, D, cfg->cap, w);
+  hipLaunchKernelGGL(rs_keep_kernel, dim3(NB), dim3(kTokBlock), (D * kWords + 1) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_scan_kernel, dim3(1), dim3(1024), 0, s, NB, w.spill_cnt);
+  hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(64), 0, s, NB, D, rank_count, w);
+  hipLaunchKernelGGL(rs_scatter_kernel, dim3(NB), dim3(kTokBlock), D * kWords * 4, s, T, D, token_rank, shf, inv_shf,
+                     w);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}

@@ -1,0 +1,325 @@
+"""GPU parity: every step of the HIP path against the CPU oracle, through the C ABI.
+
+Integer and index outputs are compared bit for bit; floats with max|a-b|/max|b| <= 1e-5 (fp32) or
+2e-2 (bf16).  Sizes here are the ones the oracle finishes in seconds; they span several tiles and
+ragged tails.  Full-size configurations are in test_gpu_configs.py.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import semmoe_oracle as O
+import paper_2503_04398_amd as S
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------------------------------- route
+@pytest.mark.parametrize("E,k,T,renorm", [(16, 2, 100, False), (128, 8, 300, True), (256, 8, 77, True),
+                                           (64, 1, 65, True), (200, 5, 33, False), (512, 16, 40, True)])
+def test_route_from_logits_softmax(E, k, T, renorm):
+    _say("route_from_logits softmax", E, k, T, renorm)
+    r = np.random.default_rng(E + k)
+    L = (2 * r.standard_normal((T, E))).astype(np.float32)
+    L[0, :] = 0.25                       # a full tie row: lowest ids win
+    L[1, E // 2:] = L[1, :E - E // 2]    # pairwise ties
+    L[2] = np.round(L[2])                # many ties
+    cfg = S.Config(T=T, d=8, E=E, k=k, F=8, D=1, renorm=renorm, cap=T)
+    m = S.SemMoE(cfg, allocate_workspace=False)
+    ids = torch.empty(T, k, dtype=torch.int32, device=H.DEV)
+    w = torch.empty(T, k, dtype=torch.float32, device=H.DEV)
+    m.route_from_logits(H.to_dev(L), ids, w)
+    torch.cuda.synchronize()
+    want_ids, want_w = O.select_topk(L, k, "softmax", renorm)
+    assert (H.to_np(ids) == want_ids).all()
+    assert O.max_rel_err(H.to_np(w), want_w) <= 1e-5
+
+
+@pytest.mark.parametrize("E,k,T,ng,tg,scale,bias", [(256, 8, 200, 8, 4, 2.5, True), (64, 6, 90, 4, 2, 1.0, False),
+                                                     (32, 4, 70, 1, 1, 1.0, True), (128, 8, 50, 16, 3, 1.0, True),
+                                                     (16, 2, 40, 16, 4, 1.0, False)])
+def test_route_from_logits_sigmoid_group_limited(E, k, T, ng, tg, scale, bias):
+    _say("route_from_logits sigmoid", E, k, T, ng, tg)
+    r = np.random.default_rng(E * 3 + k)
+    L = (1.7 * r.standard_normal((T, E))).astype(np.float32)
+    L[0, :] = 0.0
+    L[1] = np.round(L[1])
+    L[2, 0] = 40.0                       # beyond the clamp
+    L[2, 1] = -40.0
+    sb = (0.05 * r.standard_normal(E)).astype(np.float32) if bias else None
+    cfg = S.Config(T=T, d=8, E=E, k=k, F=8, D=1, score=S.binding.SIGMOID, renorm=True, n_group=ng, topk_group=tg,
+                   routed_scale=scale, cap=T)
+    m = S.SemMoE(cfg, allocate_workspace=False)
+    ids = torch.empty(T, k, dtype=torch.int32, device=H.DEV)
+    w = torch.empty(T, k, dtype=torch.float32, device=H.DEV)
+    m.route_from_logits(H.to_dev(L), ids, w, sel_bias=None if sb is None else H.to_dev(sb))
+    torch.cuda.synchronize()
+    want_ids, want_w = O.select_topk(L, k, "sigmoid", True, ng, tg, scale, sb)
+    got = H.to_np(ids)
+    assert (got == want_ids).all(), np.argwhere(got != want_ids)[:5]
+    assert O.max_rel_err(H.to_np(w), want_w) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k", [("fp32", 200, 72, 16, 2), ("bf16", 333, 200, 128, 8),
+                                           ("bf16", 130, 64, 24, 3), ("fp32", 64, 512, 16, 2)])
+def test_route_gemm_and_selection(dtype, T, d, E, k):
+    _say("route", dtype, T, d, E, k)
+    w = WL.small(T=T, d=d, E=E, k=k, D=1, C=4, dtype=dtype)
+    inp = H.make_inputs(w)
+    lay = H.Layer(w)
+    b_g = (0.1 * np.random.default_rng(1).standard_normal(E)).astype(np.float32)
+    logits, ids, tw = lay.route(inp, b_g=b_g)
+    want_logits = O.route_logits(inp.X, inp.W_r, b_g, inp.token_class, inp.class_bias)
+    err = O.max_rel_err(logits, want_logits)
+    assert err <= 1e-5, err              # inputs are exact in both; only fp32 accumulation order differs
+    want_ids, want_w = H.oracle_select(w, logits)
+    assert (ids == want_ids).all()
+    assert O.max_rel_err(tw, want_w) <= 1e-5
+    _say("  logits err %.2e, ids that differ from the oracle-logits selection: %.4f" %
+         (err, (want_ids != H.oracle_select(w, want_logits)[0]).any(axis=1).mean()))
+
+
+# ------------------------------------------------------------------------------------------- coact_hist
+@pytest.mark.parametrize("T,E,k", [(1000, 16, 2), (5000, 128, 8), (777, 256, 8), (300, 512, 16), (64, 8, 1)])
+def test_coact_hist_bit_exact_and_accumulating(T, E, k):
+    _say("coact_hist", T, E, k)
+    ids = WL.uniform_random_ids(T, E, k, seed=T)
+    m = S.SemMoE(S.Config(T=T, d=8, E=E, k=k, F=8, D=1, cap=T), allocate_workspace=False)
+    load = torch.zeros(E, dtype=torch.int32, device=H.DEV)
+    co = torch.zeros(E, E, dtype=torch.int32, device=H.DEV)
+    ids_d = H.to_dev(ids)
+    half = T // 3
+    m.coact_hist(ids_d[:half].contiguous(), half, load, co)
+    m.coact_hist(ids_d[half:].contiguous(), T - half, load, co)
+    torch.cuda.synchronize()
+    wl, wc = O.coact_hist(ids, E)
+    assert (H.to_np(load) == wl).all() and (H.to_np(co) == wc).all()
+
+
+# ------------------------------------------------------------------------------------------- reshuffle
+def _planted(T, E, D, k, seed, noise):
+    r = np.random.default_rng(seed)
+    m = E // D
+    e2r = r.permutation(np.repeat(np.arange(D), m)).astype(np.int32)
+    members = [np.flatnonzero(e2r == c) for c in range(D)]
+    p = (np.arange(D) + 1.0) ** -1.2
+    p /= p.sum()
+    ids = np.zeros((T, k), dtype=np.int32)
+    for i in range(T):
+        if r.random() < noise or k > m:
+            ids[i] = r.choice(E, k, replace=False)
+        else:
+            c = r.choice(D, p=p)                      # skewed: capacity binds on the popular ranks
+            ids[i] = r.choice(members[c], k, replace=False)
+    return ids, e2r
+
+
+@pytest.mark.parametrize("T,E,D,k,cf,noise", [
+    (256, 16, 4, 2, 1.0, 0.2), (1000, 128, 8, 8, 1.0, 0.5), (777, 64, 16, 4, 1.0, 0.3), (300, 32, 32, 2, 1.0, 0.5),
+    (513, 16, 4, 4, 1.25, 0.4), (100, 8, 1, 2, 1.0, 0.5), (2049, 64, 64, 1, 1.0, 0.0), (64, 16, 8, 2, 8.0, 0.3),
+    (5, 16, 4, 2, 1.0, 0.5), (4000, 256, 32, 8, 1.0, 0.6)])
+def test_reshuffle_bit_exact(T, E, D, k, cf, noise):
+    _say("reshuffle", T, E, D, k, cf)
+    ids, e2r = _planted(T, E, D, k, seed=T + D, noise=noise)
+    cap = int(math.ceil(cf * T / D))
+    w = WL.small(T=T, E=E, D=D, k=k)
+    lay = H.Layer(w, cap=cap)
+    lay.set_routing(ids)
+    lay.e2r = H.to_dev(e2r)
+    got = lay.reshuffle()
+    want = O.reshuffle(ids, e2r, D, cap)
+    for g, w_, name in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == w_).all(), name
+    assert (got[3] <= cap).all()
+
+
+# ------------------------------------------------------------------------------------------- dispatch
+@pytest.mark.parametrize("dtype,T,E,D,k,d", [("bf16", 700, 128, 8, 8, 64), ("fp32", 256, 16, 4, 2, 40),
+                                              ("bf16", 1030, 256, 32, 8, 136), ("bf16", 90, 8, 2, 1, 8),
+                                              ("fp32", 300, 24, 3, 3, 16), ("bf16", 513, 512, 64, 16, 24)])
+def test_dispatch_bit_exact(dtype, T, E, D, k, d):
+    _say("dispatch", dtype, T, E, D, k, d)
+    w = WL.small(T=T, E=E, D=D, k=k, d=d, dtype=dtype)
+    ids, e2r = _planted(T, E, D, k, seed=T, noise=0.4)
+    m = E // D
+    phys = np.zeros(E, dtype=np.int32)
+    seen = [0] * D
+    for e in range(E):
+        phys[e] = e2r[e] * m + seen[e2r[e]]
+        seen[e2r[e]] += 1
+    inv = np.argsort(phys).astype(np.int32)
+    tr, shf, ishf, rc = O.reshuffle(ids, e2r, D, w.cap)
+    lay = H.Layer(w)
+    lay.X = H.to_dev(WL.hidden(w), w)
+    lay.set_routing(ids)
+    lay.set_placement(e2r, phys, inv)
+    lay.set_assignment(tr, shf, ishf)
+    got = lay.dispatch()
+    want = O.dispatch(WL.hidden(w), ids, tr, ishf, phys, D)
+    for name in ("slot_of_pair", "pair_of_slot", "expert_offsets", "rank_offsets", "send_matrix"):
+        assert (got[name] == want[name]).all(), name
+    assert int(got["remote_pairs"]) == int(want["remote_pairs"])
+    assert (H.to_np(lay.X_perm) == want["X_perm"]).all()          # rows are bit copies
+    assert sorted(got["slot_of_pair"]) == list(range(T * k))      # every pair dispatched exactly once
+
+
+# ------------------------------------------------------------------------------------------- FFN + combine + whole path
+def _run_path(w, placed=True, shuffle=True, cf=1.0, rank=-1, shared=False):
+    inp = H.make_inputs(w)
+    cap = int(math.ceil(cf * w.T / w.D))
+    lay = H.Layer(w, cap=cap)
+    logits, ids, tw = lay.route(inp)
+    want_ids, want_w = H.oracle_select(w, logits)
+    assert (ids == want_ids).all()
+    # placement from a separate profiling batch, through coact_hist + the host solver
+    if placed:
+        pinp = H.make_inputs(w, profile=True)
+        play = H.Layer(w, T=pinp.X.shape[0])
+        plog, pids, _ = play.route(pinp)
+        load, co, (e2r, phys, inv) = play.profile_placement(play.ids)
+        ol, oc = O.coact_hist(pids, w.E)
+        assert (load == ol).all() and (co == oc).all()
+        oe2r, ophys, oinv = O.place(ol, oc, w.D)
+        assert (e2r == oe2r).all() and (phys == ophys).all() and (inv == oinv).all()
+    else:
+        e2r, phys, inv = O.vanilla_placement(w.E, w.D)
+    lay.set_placement(e2r, phys, inv)
+    if shuffle:
+        got = lay.reshuffle()
+        want = O.reshuffle(ids, e2r, w.D, cap)
+        for g, w_ in zip(got, want):
+            assert (g == w_).all()
+        tr, shf, ishf, rc = want
+    else:
+        tr, shf, ishf, rc = O.home_assignment(w.T, w.D)
+        lay.set_assignment(tr, shf, ishf)
+    dg = lay.dispatch()
+    dw = O.dispatch(inp.X, ids, tr, ishf, phys, w.D)
+    for name in ("slot_of_pair", "pair_of_slot", "expert_offsets", "rank_offsets", "send_matrix"):
+        assert (dg[name] == dw[name]).all(), name
+    assert (H.to_np(lay.X_perm) == dw["X_perm"]).all()
+    weights = {e: WL.expert_weight(w, e) for e in range(w.E)}
+    lay.load_experts(range(w.E))
+    Y = H.to_np(lay.expert_ffn(rank, poison=512.0))
+    Yo = O.expert_ffn(dw["X_perm"], dw["expert_offsets"], inv, lambda e: weights[e], w.D, rank=rank,
+                      Y=np.full(Y.shape, 512.0))
+    return lay, inp, ids, want_w, dw, Y, Yo, weights
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k,F,D,rank", [
+    ("bf16", 200, 64, 16, 2, 96, 4, -1), ("bf16", 700, 200, 32, 4, 72, 4, 1), ("fp32", 150, 72, 16, 2, 40, 4, -1),
+    ("bf16", 1300, 136, 8, 2, 264, 2, 0), ("fp32", 300, 64, 8, 3, 104, 2, 1), ("bf16", 64, 128, 64, 8, 128, 8, -1)])
+def test_expert_ffn_and_combine(dtype, T, d, E, k, F, D, rank):
+    _say("ffn+combine", dtype, T, d, E, k, F, D, rank)
+    w = WL.small(T=T, d=d, E=E, k=k, F=F, D=D, dtype=dtype, C=D)
+    lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, rank=rank)
+    lo, hi = (0, T * k) if rank < 0 else (dw["rank_offsets"][rank], dw["rank_offsets"][rank + 1])
+    assert (Y[:lo] == 512.0).all() and (Y[hi:] == 512.0).all()          # other ranks' rows untouched
+    if hi > lo:
+        H.assert_close(Y[lo:hi], Yo[lo:hi], dtype, "Y")
+    if rank < 0:
+        out = lay.combine()
+        H.assert_close(out, O.combine(Yo, dw["slot_of_pair"], want_w), dtype, "Out (oracle chain)")
+        ref = O.moe_definition(inp.X, ids, want_w, lambda e: weights[e])
+        H.assert_close(out, ref, dtype, "Out vs plain MoE definition")
+
+
+@pytest.mark.parametrize("placed,shuffle,cf", [(False, False, 1.0), (True, False, 1.0), (True, True, 1.0),
+                                               (True, True, 1.5)])
+def test_layer_output_is_independent_of_placement_and_shuffle(placed, shuffle, cf):
+    """lossless (Sec. 5): all variants equal the plain MoE definition"""
+    _say("lossless", placed, shuffle, cf)
+    w = WL.small(T=300, d=64, E=16, k=2, F=64, D=4, dtype="bf16", n_shared=1)
+    lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, placed, shuffle, cf)
+    ysh = lay.shared_ffn()
+    out = lay.combine(Y_shared=ysh)
+    shared = WL.shared_weight(w)
+    H.assert_close(H.to_np(ysh), O.swiglu_ffn(inp.X, *shared), "bf16", "Y_shared")
+    ref = O.moe_definition(inp.X, ids, want_w, lambda e: weights[e], shared)
+    H.assert_close(out, ref, "bf16", "Out")
+
+
+@pytest.mark.parametrize("dtype,k", [("bf16", 1), ("bf16", 2), ("bf16", 4), ("bf16", 8), ("fp32", 1), ("fp32", 2),
+                                     ("bf16", 3)])
+def test_combine_after_dispatch_is_identity_for_unit_weights(dtype, k):
+    _say("combine identity", dtype, k)
+    T, E, D, d = 500, 16, 4, 72
+    w = WL.small(T=T, E=E, D=D, k=k, d=d, dtype=dtype)
+    ids, e2r = _planted(T, E, D, k, seed=k, noise=0.5)
+    phys = np.argsort(np.argsort(e2r, kind="stable"), kind="stable").astype(np.int32)
+    tr, shf, ishf, rc = O.reshuffle(ids, e2r, D, w.cap)
+    lay = H.Layer(w)
+    X = WL.hidden(w)
+    lay.X = H.to_dev(X, w)
+    lay.set_routing(ids, np.ones((T, k), dtype=np.float32))
+    lay.set_placement(e2r, phys, np.argsort(phys).astype(np.int32))
+    lay.set_assignment(tr, shf, ishf)
+    lay.dispatch()
+    out = lay.combine(Y=lay.X_perm)
+    if k in (1, 2, 4, 8):
+        assert (out == k * X).all()                   # exact: power-of-two scaling
+    else:
+        H.assert_close(out, k * X.astype(np.float64), dtype, "k*X")
+    onehot = np.zeros((T, k), dtype=np.float32)
+    onehot[:, k - 1] = 1
+    lay.set_routing(ids, onehot)
+    assert (lay.combine(Y=lay.X_perm) == X).all()
+
+
+def test_combine_weights_and_shared_term():
+    _say("combine weights")
+    T, k, d = 260, 4, 136
+    w = WL.small(T=T, k=k, d=d, dtype="bf16")
+    r = np.random.default_rng(0)
+    Y = WL.round_to_bf16(r.standard_normal((T * k, d)).astype(np.float32))
+    Ysh = WL.round_to_bf16(r.standard_normal((T, d)).astype(np.float32))
+    slot = r.permutation(T * k).astype(np.int32)
+    tw = r.random((T, k)).astype(np.float32)
+    lay = H.Layer(w)
+    lay.slot_of_pair.copy_(torch.from_numpy(slot))
+    lay.tw.copy_(torch.from_numpy(tw))
+    out = lay.combine(Y=H.to_dev(Y, w), Y_shared=H.to_dev(Ysh, w))
+    H.assert_close(out, O.combine(Y, slot, tw, Ysh), "bf16", "Out")
+
+
+def test_empty_and_degenerate_inputs():
+    _say("empty inputs")
+    # T = 0: every call is a no-op that still returns OK
+    w = WL.small(T=0, E=16, D=4, k=2)
+    lay = H.Layer(w, cap=0)
+    lay.e2r = H.to_dev(np.zeros(16, dtype=np.int32))
+    lay.phys = H.to_dev(np.arange(16, dtype=np.int32))
+    lay.inv = H.to_dev(np.arange(16, dtype=np.int32))
+    tr, shf, ishf, rc = lay.reshuffle()
+    assert (rc == 0).all()
+    lay.X = torch.empty(0, w.d, dtype=torch.bfloat16, device=H.DEV)
+    got = lay.dispatch()
+    assert (got["expert_offsets"] == 0).all() and (got["rank_offsets"] == 0).all() and int(got["remote_pairs"]) == 0
+    # an expert with zero rows writes nothing; all tokens on one expert pair
+    w = WL.small(T=130, E=8, D=2, k=2, d=64, F=64)
+    ids = np.tile(np.array([[3, 5]], dtype=np.int32), (130, 1))
+    e2r, phys, inv = O.vanilla_placement(8, 2)
+    lay = H.Layer(w)
+    lay.X = H.to_dev(WL.hidden(w), w)
+    lay.set_routing(ids, np.full((130, 2), 0.5, dtype=np.float32))
+    lay.set_placement(e2r, phys, inv)
+    got = lay.reshuffle()
+    want = O.reshuffle(ids, e2r, 2, w.cap)
+    for g, w_ in zip(got, want):
+        assert (g == w_).all()
+    dg = lay.dispatch()
+    assert list(np.diff(dg["expert_offsets"])) == [0, 0, 0, 130, 0, 130, 0, 0]
+    lay.load_experts([3, 5])
+    Y = H.to_np(lay.expert_ffn(-1, poison=1.0))
+    weights = {e: WL.expert_weight(w, e) for e in (3, 5)}
+    dw = O.dispatch(WL.hidden(w), ids, want[0], want[2], phys, 2)
+    Yo = O.expert_ffn(dw["X_perm"], dw["expert_offsets"], inv, lambda e: weights[e], 2)
+    H.assert_close(Y, Yo, "bf16", "Y")
