@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the semantic-parallel MoE layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2_qwen3_30b]
+
+A step = one pass of the online hot path over one batch of seeded synthetic input that is already
+resident in HBM:  route -> reshuffle -> dispatch (index + rows) -> expert_ffn (rank 0's experts) ->
+combine.  The offline part (coact_hist on a profiling batch -> place on the host) runs once before and
+is timed separately.  Prints ONE JSON line: MoE-layer tokens/s, per-stage times from HIP events, the
+roofline of the dominant stage, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def cpu_baseline(w, n_tokens):
+    """the oracle as it stands on a bounded sample: the first n_tokens of the batch, rank 0's FFN"""
+    import numpy as np
+    import workloads as WL
+    from oracle import semmoe_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    X = WL.hidden(w)[:n_tokens]
+    W_r, cb = WL.router_weight(w), WL.class_bias(w)
+    tc = WL.token_class(w)[:n_tokens]
+    # offline, untimed: placement from a profiling sample
+    Lp = O.route_logits(WL.hidden(w, True, n_tokens), W_r, None, WL.token_class(w, True, n_tokens), cb)
+    idp, _ = O.select_topk(Lp, w.k, w.score, w.renorm, w.n_group, w.topk_group, w.routed_scale)
+    e2r, phys, inv = O.place(*O.coact_hist(idp, w.E), w.D)
+    weights = {int(inv[q]): WL.expert_weight(w, int(inv[q])) for q in range(w.m)}   # rank 0's experts
+    cap = -(-n_tokens // w.D)
+    t0 = time.perf_counter()
+    L = O.route_logits(X, W_r, None, tc, cb)
+    ids, tw = O.select_topk(L, w.k, w.score, w.renorm, w.n_group, w.topk_group, w.routed_scale)
+    tr, shf, ishf, rc = O.reshuffle(ids, e2r, w.D, cap)
+    dsp = O.dispatch(X, ids, tr, ishf, phys, w.D)
+    Y = O.expert_ffn(dsp["X_perm"], dsp["expert_offsets"], inv, lambda e: weights[e], w.D, rank=0)
+    out = O.combine(Y, dsp["slot_of_pair"], tw)
+    dt = time.perf_counter() - t0
+    assert out.shape == (n_tokens, w.d)
+    return {"value": n_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "first %d tokens of the batch through the whole oracle chain (fp64 numpy; route, select, "
+                      "reshuffle, dispatch, rank-0 expert FFN, combine), %.1f s" % (n_tokens, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c2_qwen3_30b")
+    ap.add_argument("--cpu-sample", type=int, default=8192)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--all-ranks", action="store_true", help="FFN over every rank's experts instead of rank 0")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a one-GPU hot path (logical ranks are simulated on one device); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as WL
+    import paper_2503_04398_amd as S
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = WL.CONFIGS[args.config]
+    adt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    b = 2 if w.dtype == "bf16" else 4
+    T, d, E, k, F, D, P = w.T, w.d, w.E, w.k, w.F, w.D, w.P
+
+    def up(x, act=False):
+        t = torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+        return t.to(adt) if act else t
+
+    # ---------------- inputs, resident in HBM before anything is timed
+    X = up(WL.hidden(w), True)
+    W_r = up(WL.router_weight(w), True)
+    tc = up(WL.token_class(w))
+    cb = up(WL.class_bias(w))
+    W_gu = torch.empty(E, 2 * F, d, dtype=adt, device=dev)
+    W_down = torch.empty(E, d, F, dtype=adt, device=dev)
+    for e in range(E):
+        wgu, wdn = WL.expert_weight(w, e)
+        W_gu[e].copy_(up(wgu, True))
+        W_down[e].copy_(up(wdn, True))
+    m = S.SemMoE(S.Config.from_workload(w), device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    ids = torch.empty(T, k, **i32)
+    tw = torch.empty(T, k, dtype=torch.float32, device=dev)
+    token_rank, shf, inv_shf = (torch.empty(T, **i32) for _ in range(3))
+    rank_count = torch.empty(D, **i32)
+    slot_of_pair, pair_of_slot = torch.empty(P, **i32), torch.empty(P, **i32)
+    expert_offsets, rank_offsets = torch.empty(E + 1, **i32), torch.empty(D + 1, **i32)
+    send_matrix = torch.empty(D, D, **i32)
+    remote_pairs = torch.empty(1, dtype=torch.int64, device=dev)
+    X_perm = torch.empty(P, d, dtype=adt, device=dev)
+    Y = torch.zeros(P, d, dtype=adt, device=dev)
+    Out = torch.empty(T, d, dtype=adt, device=dev)
+
+    # ---------------- offline: profile batch -> co-activation histogram -> placement (host)
+    Tp = w.profile_tokens
+    mp = S.SemMoE(S.Config.from_workload(w, T=Tp, cap=-(-Tp // D)), device=dev)
+    Xp = up(WL.hidden(w, profile=True), True)
+    tcp = up(WL.token_class(w, profile=True))
+    idp = torch.empty(Tp, k, **i32)
+    twp = torch.empty(Tp, k, dtype=torch.float32, device=dev)
+    load = torch.zeros(E, **i32)
+    coact = torch.zeros(E, E, **i32)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    mp.route(Xp, W_r, idp, twp, token_class=tcp, class_bias=cb)
+    mp.coact_hist(idp, Tp, load, coact)
+    torch.cuda.synchronize()
+    t_hist = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    e2r_h, phys_h, inv_h = m.place(load.cpu().numpy().astype(np.uint64), coact.cpu().numpy().astype(np.uint64))
+    t_place = time.perf_counter() - t0
+    e2r, phys, inv = up(e2r_h), up(phys_h), up(inv_h)
+    del Xp, mp
+
+    ffn_rank = -1 if args.all_ranks else 0
+    stages = ["route", "reshuffle", "dispatch_index", "dispatch_rows", "expert_ffn", "combine"]
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        m.route(X, W_r, ids, tw, token_class=tc, class_bias=cb)
+        if ev: ev[1].record()
+        m.reshuffle(ids, e2r, token_rank, shf, inv_shf, rank_count)
+        if ev: ev[2].record()
+        m.dispatch_index(ids, token_rank, shf, phys, slot_of_pair, pair_of_slot, expert_offsets, rank_offsets,
+                         send_matrix, remote_pairs)
+        if ev: ev[3].record()
+        m.dispatch_rows(X, slot_of_pair, X_perm)
+        if ev: ev[4].record()
+        m.expert_ffn(ffn_rank, X_perm, expert_offsets, inv, W_gu, W_down, Y)
+        if ev: ev[5].record()
+        m.combine(Y, slot_of_pair, tw, Out)
+        if ev: ev[6].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    stage_ms = {name: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps
+                for i, name in enumerate(stages)}
+    # the same loop without events between the calls, for reference
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t0) / args.steps * 1e3
+
+    # ---------------- what the batch looked like
+    ro = rank_offsets.cpu().numpy()
+    rows_ffn = int(ro[D] - ro[0]) if args.all_ranks else int(ro[1] - ro[0])
+    remote = int(remote_pairs.item())
+    send = send_matrix.cpu().numpy().astype(np.int64)
+    col = send.sum(axis=0)
+    # remote fraction of the same routing under vanilla placement + home ranks (index pass only)
+    van = torch.arange(E, **i32)
+    home = (torch.arange(T, device=dev) // (-(-T // D))).to(torch.int32)
+    ident = torch.arange(T, **i32)
+    rp2 = torch.empty(1, dtype=torch.int64, device=dev)
+    tmp = [torch.empty_like(slot_of_pair) for _ in range(2)]
+    m.dispatch_index(ids, home, ident, van, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                     torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rp2)
+    rp3 = torch.empty(1, dtype=torch.int64, device=dev)
+    m.dispatch_index(ids, home, ident, phys, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                     torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rp3)
+    torch.cuda.synchronize()
+
+    # ---------------- algorithmic bytes / flops per launch
+    alg = {
+        "route": ("hbm", T * d * b + E * d * b + T * k * 8 + 2 * 4 * T * E),
+        "reshuffle": ("hbm", T * k * 4 + E * 4 + 3 * T * 4),
+        "dispatch_index": ("hbm", 2 * T * k * 4 + 2 * T * 4 + 2 * P * 4),
+        "dispatch_rows": ("hbm", (T + P) * d * b + P * 4),
+        "expert_ffn": ("mfma" if w.dtype == "bf16" else "alu", 6.0 * d * F * rows_ffn),
+        "combine": ("hbm", (P + T) * d * b + P * 8),
+    }
+    roof = {}
+    for name in stages:
+        bound, work = alg[name]
+        sec = stage_ms[name] * 1e-3
+        if bound == "hbm":
+            ach, peak, unit = work / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, unit = work / sec / 1e12, "TFLOP/s"
+            peak = MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else FP32_VECTOR_PEAK_TFLOPS
+        roof[name] = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+                      "frac": round(ach / peak, 4), "ms": round(stage_ms[name], 4)}
+    dominant = max(stages, key=lambda n: stage_ms[n])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.config, {}).get(dominant)
+        except Exception:
+            traffic = None
+    roofline = dict(roof[dominant])
+    roofline.pop("ms")
+    roofline.update({"kernel": dominant, "traffic": traffic})
+
+    out = {
+        "metric": "MoE-layer tokens/s on 1 MI355X",
+        "value": round(T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: T=%d d=%d E=%d k=%d F=%d D=%d %s %s top-%d, semantic classes C=%d, "
+                               "expert FFN for %s" % (w.name, T, d, E, k, F, D, w.dtype, w.score, k, w.C,
+                                                      "all ranks" if args.all_ranks else "rank 0's experts"),
+                   "cap": w.cap, "ffn_rows": rows_ffn},
+        "roofline": roofline,
+        "stages": roof,
+        "ms_per_step_without_events": round(ms_plain, 4),
+        "remote_pair_fraction": {"vanilla_placement_home_ranks": round(int(rp2.item()) / P, 4),
+                                 "semmoe_placement_home_ranks": round(int(rp3.item()) / P, 4),
+                                 "semmoe_placement_reshuffle": round(remote / P, 4)},
+        "load_imbalance_max_over_median": round(float(col.max() / max(np.median(col), 1)), 4),
+        "offline_ms": {"route+coact_hist(profile batch of %d)" % Tp: round(t_hist * 1e3, 3),
+                       "place(host)": round(t_place * 1e3, 3)},
+        "device": torch.cuda.get_device_name(0),
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_sample, T))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

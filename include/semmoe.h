@@ -157,6 +157,20 @@ int32_t semmoe_dispatch(const semmoe_config* cfg, void* stream, const void* X, c
                         size_t ws_bytes);
 
 /*
+ * dispatch_index / dispatch_rows - the two halves of semmoe_dispatch as separate calls (same passages:
+ * Sec. 1 dispatch all2all, Sec. 3.1 volume model): the index half computes every output of semmoe_dispatch
+ * except X_perm; the row half moves rows, X_perm[slot_of_pair[i*k+j],:] = X[i,:].  One index pass can serve
+ * several row tensors, and the halves can be timed apart.  Arguments as in semmoe_dispatch.
+ */
+int32_t semmoe_dispatch_index(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                              const int32_t* token_rank, const int32_t* shf, const int32_t* phys_of_expert,
+                              int32_t* slot_of_pair, int32_t* pair_of_slot, int32_t* expert_offsets,
+                              int32_t* rank_offsets, uint32_t* send_matrix, uint64_t* remote_pairs, void* ws,
+                              size_t ws_bytes);
+int32_t semmoe_dispatch_rows(const semmoe_config* cfg, void* stream, const void* X, const int32_t* slot_of_pair,
+                             void* X_perm);
+
+/*
  * expert_ffn - the expert FFN (Sec. 2) in SwiGLU form, grouped over one rank's experts:
  *   for every physical expert q of `rank` (rank = -1: all), for slots s in [expert_offsets[q],
  *   expert_offsets[q+1]):  Y[s] = W_down[e] ( silu(W_gate[e] x_s) * (W_up[e] x_s) ),  e = expert_of_phys[q],

@@ -80,6 +80,8 @@ _SIGS = {
     "semmoe_place": ([_P, _P, _P, C.c_int64, C.c_int64, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch": ([_P] * 15 + [C.c_size_t], C.c_int32),
+    "semmoe_dispatch_index": ([_P] * 13 + [C.c_size_t], C.c_int32),
+    "semmoe_dispatch_rows": ([_P] * 5, C.c_int32),
     "semmoe_expert_ffn": ([_P, _P, C.c_int32] + [_P] * 7 + [C.c_size_t], C.c_int32),
     "semmoe_shared_ffn": ([_P, _P, _P, C.c_int32, _P, _P, _P, _P, C.c_size_t], C.c_int32),
     "semmoe_combine": ([_P] * 7, C.c_int32),
@@ -195,6 +197,19 @@ class SemMoE:
             C.byref(c), _stream(), _ptr(X), _ptr(topk_ids), _ptr(token_rank), _ptr(shf), _ptr(phys_of_expert),
             _ptr(X_perm), _ptr(slot_of_pair), _ptr(pair_of_slot), _ptr(expert_offsets), _ptr(rank_offsets),
             _ptr(send_matrix), _ptr(remote_pairs), _ptr(self.ws), self.ws_bytes))
+
+    def dispatch_index(self, topk_ids, token_rank, shf, phys_of_expert, slot_of_pair, pair_of_slot, expert_offsets,
+                       rank_offsets, send_matrix, remote_pairs):
+        c = self._cfg()
+        self._check("semmoe_dispatch_index", self.lib.semmoe_dispatch_index(
+            C.byref(c), _stream(), _ptr(topk_ids), _ptr(token_rank), _ptr(shf), _ptr(phys_of_expert),
+            _ptr(slot_of_pair), _ptr(pair_of_slot), _ptr(expert_offsets), _ptr(rank_offsets), _ptr(send_matrix),
+            _ptr(remote_pairs), _ptr(self.ws), self.ws_bytes))
+
+    def dispatch_rows(self, X, slot_of_pair, X_perm):
+        c = self._cfg()
+        self._check("semmoe_dispatch_rows", self.lib.semmoe_dispatch_rows(
+            C.byref(c), _stream(), _ptr(X), _ptr(slot_of_pair), _ptr(X_perm)))
 
     def expert_ffn(self, rank, X_perm, expert_offsets, expert_of_phys, W_gu, W_down, Y):
         c = self._cfg()

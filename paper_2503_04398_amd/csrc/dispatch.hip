@@ -210,20 +210,16 @@ size_t ws_dispatch(const semmoe_config* cfg) {
 
 using namespace semmoe;
 
-extern "C" int32_t semmoe_dispatch(const semmoe_config* cfg, void* stream, const void* X, const int32_t* topk_ids,
+static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, const int32_t* topk_ids,
                                    const int32_t* token_rank, const int32_t* shf, const int32_t* phys_of_expert,
-                                   void* X_perm, int32_t* slot_of_pair, int32_t* pair_of_slot,
-                                   int32_t* expert_offsets, int32_t* rank_offsets, uint32_t* send_matrix,
-                                   uint64_t* remote_pairs, void* ws, size_t ws_bytes) {
-  int32_t st = validate_config(cfg, true, X != nullptr, false);
-  if (st != SEMMOE_OK) return st;
+                                   int32_t* slot_of_pair, int32_t* pair_of_slot, int32_t* expert_offsets,
+                                   int32_t* rank_offsets, uint32_t* send_matrix, uint64_t* remote_pairs, void* ws,
+                                   size_t ws_bytes) {
   if (!topk_ids || !token_rank || !shf || !phys_of_expert || !slot_of_pair || !pair_of_slot || !expert_offsets ||
       !rank_offsets || !send_matrix || !remote_pairs)
     return SEMMOE_EINVAL;
-  if (X && (!X_perm || !aligned16(X) || !aligned16(X_perm))) return SEMMOE_EINVAL;
   DispatchWs w;
   if (!carve_dispatch(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
-  hipStream_t s = static_cast<hipStream_t>(stream);
   const int T = cfg->T, k = cfg->k, E = cfg->E, D = cfg->D;
   const int NB = cdiv(T, kTokBlock);
   if (NB > 0) {
@@ -235,20 +231,61 @@ extern "C" int32_t semmoe_dispatch(const semmoe_config* cfg, void* stream, const
   if (NB > 0) {
     hipLaunchKernelGGL(dp_slot_kernel, dim3(NB), dim3(kTokBlock), E * kWords * 4, s, T, k, E, topk_ids, shf,
                        phys_of_expert, slot_of_pair, pair_of_slot, w);
-    if (X) {
-      const int row_chunks = int(size_t(cfg->d) * act_bytes(cfg) / 16);
-      const u32x4_t* Xv = static_cast<const u32x4_t*>(X);
-      u32x4_t* Xp = static_cast<u32x4_t*>(X_perm);
-      const int P = T * k;
-      switch (k) {
-        case 1: hipLaunchKernelGGL(dp_rows_kernel<1>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-        case 2: hipLaunchKernelGGL(dp_rows_kernel<2>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-        case 4: hipLaunchKernelGGL(dp_rows_kernel<4>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-        case 8: hipLaunchKernelGGL(dp_rows_kernel<8>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-        default: hipLaunchKernelGGL(dp_rows_kernel<0>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-      }
-    }
   }
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
+}
+
+static int32_t dispatch_rows_impl(const semmoe_config* cfg, hipStream_t s, const void* X,
+                                  const int32_t* slot_of_pair, void* X_perm) {
+  if (!X || !X_perm || !slot_of_pair || !aligned16(X) || !aligned16(X_perm)) return SEMMOE_EINVAL;
+  const int T = cfg->T, k = cfg->k;
+  if (T == 0) return SEMMOE_OK;
+  const int row_chunks = int(size_t(cfg->d) * act_bytes(cfg) / 16);
+  const u32x4_t* Xv = static_cast<const u32x4_t*>(X);
+  u32x4_t* Xp = static_cast<u32x4_t*>(X_perm);
+  const int P = T * k;
+  switch (k) {
+    case 1: hipLaunchKernelGGL(dp_rows_kernel<1>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 2: hipLaunchKernelGGL(dp_rows_kernel<2>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 4: hipLaunchKernelGGL(dp_rows_kernel<4>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 8: hipLaunchKernelGGL(dp_rows_kernel<8>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    default: hipLaunchKernelGGL(dp_rows_kernel<0>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+  }
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_dispatch_index(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                         const int32_t* token_rank, const int32_t* shf,
+                                         const int32_t* phys_of_expert, int32_t* slot_of_pair, int32_t* pair_of_slot,
+                                         int32_t* expert_offsets, int32_t* rank_offsets, uint32_t* send_matrix,
+                                         uint64_t* remote_pairs, void* ws, size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, false, false);
+  if (st != SEMMOE_OK) return st;
+  return dispatch_index_impl(cfg, static_cast<hipStream_t>(stream), topk_ids, token_rank, shf, phys_of_expert,
+                             slot_of_pair, pair_of_slot, expert_offsets, rank_offsets, send_matrix, remote_pairs, ws,
+                             ws_bytes);
+}
+
+extern "C" int32_t semmoe_dispatch_rows(const semmoe_config* cfg, void* stream, const void* X,
+                                        const int32_t* slot_of_pair, void* X_perm) {
+  int32_t st = validate_config(cfg, true, true, false);
+  if (st != SEMMOE_OK) return st;
+  return dispatch_rows_impl(cfg, static_cast<hipStream_t>(stream), X, slot_of_pair, X_perm);
+}
+
+extern "C" int32_t semmoe_dispatch(const semmoe_config* cfg, void* stream, const void* X, const int32_t* topk_ids,
+                                   const int32_t* token_rank, const int32_t* shf, const int32_t* phys_of_expert,
+                                   void* X_perm, int32_t* slot_of_pair, int32_t* pair_of_slot,
+                                   int32_t* expert_offsets, int32_t* rank_offsets, uint32_t* send_matrix,
+                                   uint64_t* remote_pairs, void* ws, size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, X != nullptr, false);
+  if (st != SEMMOE_OK) return st;
+  if (X && (!X_perm || !aligned16(X) || !aligned16(X_perm))) return SEMMOE_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  st = dispatch_index_impl(cfg, s, topk_ids, token_rank, shf, phys_of_expert, slot_of_pair, pair_of_slot,
+                           expert_offsets, rank_offsets, send_matrix, remote_pairs, ws, ws_bytes);
+  if (st != SEMMOE_OK || !X) return st;
+  return dispatch_rows_impl(cfg, s, X, slot_of_pair, X_perm);
 }

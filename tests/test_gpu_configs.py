@@ -1,0 +1,119 @@
+"""GPU parity at the five full workload sizes, in the launch configuration the benchmark times.
+
+Integer stages are compared in full, bit for bit.  Floating-point stages are compared on sampled
+outputs the oracle can compute one by one: logits in full, X_perm rows and FFN rows on sampled slots of
+one rank, and the layer output on sampled tokens against the plain MoE definition (the experts those
+tokens use are the only ones whose weights are generated; all others are zero on the device).
+"""
+import math
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import semmoe_oracle as O
+import paper_2503_04398_amd as S
+from tests import harness as H
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1100)]
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _full_config(name, n_tok_sample, n_slot_sample, rank):
+    w = WL.CONFIGS[name]
+    t0 = time.time()
+    inp = H.make_inputs(w)
+    lay = H.Layer(w)
+    # ---- route
+    logits, ids, tw = lay.route(inp)
+    want_logits = O.route_logits(inp.X, inp.W_r, None, inp.token_class, inp.class_bias)
+    err = O.max_rel_err(logits, want_logits)
+    _say("  [%5.1fs] logits err %.2e" % (time.time() - t0, err))
+    assert err <= 1e-5
+    want_ids, want_w = H.oracle_select(w, logits)
+    assert (ids == want_ids).all()
+    assert O.max_rel_err(tw, want_w) <= 1e-5
+    flips = (want_ids != H.oracle_select(w, want_logits)[0]).any(axis=1).mean()
+    _say("  [%5.1fs] ids bit-exact on the GPU's logits; tokens whose ids differ under oracle logits: %.4f"
+         % (time.time() - t0, flips))
+    # ---- offline: profile batch -> histogram -> placement
+    pinp = H.make_inputs(w, profile=True)
+    play = H.Layer(w, T=pinp.X.shape[0])
+    plog, pids, _ = play.route(pinp)
+    assert (pids == H.oracle_select(w, plog)[0]).all()
+    load, co, (e2r, phys, inv) = play.profile_placement(play.ids)
+    ol, oc = O.coact_hist(pids, w.E)
+    assert (load == ol).all() and (co == oc).all()
+    oe2r, ophys, oinv = O.place(ol, oc, w.D)
+    assert (e2r == oe2r).all() and (phys == ophys).all() and (inv == oinv).all()
+    del play, pinp
+    _say("  [%5.1fs] coact_hist and place bit-exact" % (time.time() - t0))
+    # ---- reshuffle, dispatch
+    lay.set_placement(e2r, phys, inv)
+    got = lay.reshuffle()
+    want = O.reshuffle(ids, e2r, w.D, w.cap)
+    for g, x, nm in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == x).all(), nm
+    tr, shf, ishf, rc = want
+    dg = lay.dispatch()
+    dw = O.dispatch(None, ids, tr, ishf, phys, w.D)
+    for nm in ("slot_of_pair", "pair_of_slot", "expert_offsets", "rank_offsets", "send_matrix"):
+        assert (dg[nm] == dw[nm]).all(), nm
+    assert int(dg["remote_pairs"]) == int(dw["remote_pairs"])
+    P = w.P
+    rs = np.random.default_rng(7)
+    slots = np.sort(rs.choice(P, min(4096, P), replace=False))
+    xp = H.to_np(lay.X_perm[torch.from_numpy(slots).to(H.DEV)])
+    assert (xp == inp.X[dw["pair_of_slot"][slots] // w.k]).all()
+    v_e2r, _, _ = O.vanilla_placement(w.E, w.D)
+    home = O.home_rank(w.T, w.D)
+    _say("  [%5.1fs] reshuffle/dispatch bit-exact; remote-pair fraction vanilla %.4f, placed %.4f, placed+reshuffle %.4f"
+         % (time.time() - t0, O.remote_fraction(ids, v_e2r, home), O.remote_fraction(ids, e2r, home),
+            int(dw["remote_pairs"]) / P))
+    # ---- FFN + combine on samples
+    toks = np.sort(rs.choice(w.T, n_tok_sample, replace=False))
+    lo, hi = int(dw["rank_offsets"][rank]), int(dw["rank_offsets"][rank + 1])
+    sl = np.sort(rs.choice(np.arange(lo, hi), min(n_slot_sample, hi - lo), replace=False)) if hi > lo else []
+    need = set(int(e) for e in ids[toks].reshape(-1)) | set(int(ids.reshape(-1)[dw["pair_of_slot"][s]]) for s in sl)
+    weights = {e: WL.expert_weight(w, e) for e in sorted(need)}
+    lay.W_gu = torch.zeros(w.E, 2 * w.F, w.d, dtype=H.act_dtype(w), device=H.DEV)
+    lay.W_down = torch.zeros(w.E, w.d, w.F, dtype=H.act_dtype(w), device=H.DEV)
+    lay._loaded = set()
+    for e in sorted(need):
+        lay.W_gu[e].copy_(H.to_dev(weights[e][0], w))
+        lay.W_down[e].copy_(H.to_dev(weights[e][1], w))
+    _say("  [%5.1fs] %d experts' weights generated" % (time.time() - t0, len(need)))
+    Y = lay.expert_ffn(-1)
+    if len(sl):
+        ys = H.to_np(Y[torch.from_numpy(sl).to(H.DEV)])
+        yo = np.stack([O.swiglu_ffn(inp.X[dw["pair_of_slot"][s] // w.k][None],
+                                    *weights[int(ids.reshape(-1)[dw["pair_of_slot"][s]])])[0] for s in sl])
+        H.assert_close(ys, yo, w.dtype, "Y rows of rank %d" % rank)
+    shared = None
+    ysh = None
+    if w.n_shared:
+        ysh = lay.shared_ffn()
+        shared = WL.shared_weight(w)
+        H.assert_close(H.to_np(ysh[torch.from_numpy(toks).to(H.DEV)]), O.swiglu_ffn(inp.X[toks], *shared), w.dtype,
+                       "Y_shared")
+    out = lay.combine(Y_shared=ysh)
+    ref = O.moe_definition(inp.X, ids, want_w, lambda e: weights[e], shared, tokens=toks)
+    e2 = H.assert_close(out[toks], ref, w.dtype, "Out vs plain MoE definition")
+    _say("  [%5.1fs] FFN rows and layer output within tolerance (Out err %.2e)" % (time.time() - t0, e2))
+
+
+@pytest.mark.parametrize("name,n_tok,n_slot,rank", [
+    ("c1_tiny_fp32", 256, 128, 0),
+    ("c2_qwen3_30b", 24, 64, 0),
+    ("c5_qwen3_235b_decode", 8, 32, 0),
+    ("c4_gpt_oss_120b", 8, 32, 0),
+    ("c3_deepseek_v3", 3, 16, 0),
+])
+def test_full_config(name, n_tok, n_slot, rank):
+    _say("full config", name)
+    _full_config(name, n_tok, n_slot, rank)
