@@ -68,6 +68,18 @@ int32_t semmoe_last_hip_error(void);
 int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*host*/);
 
 /*
+ * Tuning knobs for benchmarks (process-wide, not thread-safe).  value < 0 restores the default, which the
+ * library picks per shape.  Results never depend on them beyond fp32 summation order inside a GEMM tile.
+ *   SEMMOE_TUNE_GATEUP_TILE / SEMMOE_TUNE_DOWN_TILE: tile-shape id of the bf16 grouped GEMMs
+ *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny tiles for decode)
+ *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs
+ */
+#define SEMMOE_TUNE_GATEUP_TILE 0
+#define SEMMOE_TUNE_DOWN_TILE 1
+#define SEMMOE_TUNE_BLOCKS_PER_CU 2
+int32_t semmoe_set_tuning(int32_t key, int32_t value);
+
+/*
  * route - the gating function G(h) = top-k(softmax(W_g h + b_g)) of Sec. 3.2.
  *   logits[i,e] = sum_c X[i,c] W_r[e,c] + b_g[e] + class_bias[token_class[i], e]   (fp32 accumulate;
  *   token_class[i] < 0 adds nothing; the class term is the synthetic token->expert affinity).

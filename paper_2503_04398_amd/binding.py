@@ -74,6 +74,7 @@ _SIGS = {
     "semmoe_version": ([], C.c_int32),
     "semmoe_last_hip_error": ([], C.c_int32),
     "semmoe_workspace_bytes": ([_P, C.POINTER(C.c_size_t)], C.c_int32),
+    "semmoe_set_tuning": ([C.c_int32, C.c_int32], C.c_int32),
     "semmoe_route": ([_P] * 12 + [C.c_size_t], C.c_int32),
     "semmoe_route_from_logits": ([_P] * 6, C.c_int32),
     "semmoe_coact_hist": ([_P, _P, _P, C.c_int32, _P, _P], C.c_int32),
@@ -152,6 +153,9 @@ class SemMoE:
         c = self._cfg()
         self._check("semmoe_workspace_bytes", self.lib.semmoe_workspace_bytes(C.byref(c), C.byref(n)))
         return int(n.value)
+
+    def set_tuning(self, key: int, value: int):
+        self._check("semmoe_set_tuning", self.lib.semmoe_set_tuning(int(key), int(value)))
 
     # -- entry points
     def route(self, X, W_r, topk_ids, topk_w, b_g=None, token_class=None, class_bias=None, sel_bias=None,

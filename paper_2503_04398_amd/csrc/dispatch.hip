@@ -5,6 +5,7 @@
 // workgroups an exclusive scan over (expert, workgroup).  Row half: each token row is read once and
 // written to its k slots with 16-byte accesses.
 #include "common.hpp"
+#include "scan_util.hpp"
 
 namespace semmoe {
 
@@ -85,61 +86,33 @@ __global__ __launch_bounds__(kTokBlock) void dp_count_kernel(int T, int k, int E
   for (int x = threadIdx.x; x < D * D; x += blockDim.x) w.send_part[size_t(blockIdx.x) * D * D + x] = send[x];
 }
 
-// D2: expert_offsets, rank_offsets, base slot of (block, expert), send_matrix, remote_pairs (one workgroup)
-__global__ __launch_bounds__(1024) void dp_scan_kernel(int NB, int E, int D, int32_t* __restrict__ expert_offsets,
-                                                       int32_t* __restrict__ rank_offsets,
-                                                       uint32_t* __restrict__ send_matrix,
-                                                       unsigned long long* __restrict__ remote_pairs,
-                                                       DispatchWs w) {
+// D2: expert_offsets, rank_offsets, slot base of (block, expert) relative to the expert's first slot,
+// send_matrix, remote_pairs (one workgroup, all threads busy: see column_prefix)
+__global__ __launch_bounds__(kScanThreads) void dp_scan_kernel(int NB, int E, int D,
+                                                                int32_t* __restrict__ expert_offsets,
+                                                                int32_t* __restrict__ rank_offsets,
+                                                                uint32_t* __restrict__ send_matrix,
+                                                                unsigned long long* __restrict__ remote_pairs,
+                                                                DispatchWs w) {
   __shared__ int32_t tot[SEMMOE_MAX_E + 1];
+  __shared__ int32_t send_tot[SEMMOE_MAX_D * SEMMOE_MAX_D];
+  __shared__ int32_t scratch[kScanThreads];
   __shared__ unsigned long long remote_sh;
   const int tid = threadIdx.x;
   if (tid == 0) remote_sh = 0ull;
-  for (int q = tid; q < E; q += blockDim.x) {
-    int s = 0;
-    for (int b = 0; b < NB; ++b) s += w.cnt[size_t(b) * E + q];
-    tot[q] = s;
-  }
-  __syncthreads();
-  if (tid < 64) {  // exclusive scan over experts by one wave
-    const int per = (E + 63) / 64;
-    const int lo = min(tid * per, E), hi = min(lo + per, E);
-    int s = 0;
-    for (int q = lo; q < hi; ++q) s += tot[q];
-    int incl = s;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int v = __shfl_up(incl, off);
-      if (tid >= off) incl += v;
-    }
-    int run = incl - s;
-    for (int q = lo; q < hi; ++q) {
-      const int c = tot[q];
-      tot[q] = run;
-      run += c;
-    }
-    if (tid == 63) tot[E] = incl;
-  }
-  __syncthreads();
+  column_prefix(w.cnt, E, [](int c) { return c; }, E, NB, w.cnt, E, tot, scratch);
+  wave_exclusive_scan_lds(tot, E);
   const int m = E / D;
   for (int q = tid; q <= E; q += blockDim.x) {
     expert_offsets[q] = tot[q];
     if (q % m == 0) rank_offsets[q / m] = tot[q];
   }
-  for (int q = tid; q < E; q += blockDim.x) {
-    int run = tot[q];
-    for (int b = 0; b < NB; ++b) {
-      const int c = w.cnt[size_t(b) * E + q];
-      w.cnt[size_t(b) * E + q] = run;
-      run += c;
-    }
-  }
+  column_prefix(reinterpret_cast<const int32_t*>(w.send_part), D * D, [](int c) { return c; }, D * D, NB,
+                static_cast<int32_t*>(nullptr), 0, send_tot, scratch);
   unsigned long long remote = 0;
   for (int x = tid; x < D * D; x += blockDim.x) {
-    uint32_t s = 0;
-    for (int b = 0; b < NB; ++b) s += w.send_part[size_t(b) * D * D + x];
-    send_matrix[x] = s;
-    if (x / D != x % D) remote += s;
+    send_matrix[x] = (uint32_t)send_tot[x];
+    if (x / D != x % D) remote += (uint32_t)send_tot[x];
   }
   if (remote) atomicAdd(&remote_sh, remote);
   __syncthreads();
@@ -151,7 +124,8 @@ __global__ __launch_bounds__(kTokBlock) void dp_slot_kernel(int T, int k, int E,
                                                             const int32_t* __restrict__ shf,
                                                             const int32_t* __restrict__ phys,
                                                             int32_t* __restrict__ slot_of_pair,
-                                                            int32_t* __restrict__ pair_of_slot, DispatchWs w) {
+                                                            int32_t* __restrict__ pair_of_slot,
+                                                            const int32_t* __restrict__ expert_offsets, DispatchWs w) {
   extern __shared__ uint32_t lds[];  // [E][kWords]
   int q[SEMMOE_MAX_K];
   const int tok = fill_bitmaps(T, k, E, ids, shf, phys, lds, q);
@@ -160,7 +134,7 @@ __global__ __launch_bounds__(kTokBlock) void dp_slot_kernel(int T, int k, int E,
 #pragma unroll
   for (int j = 0; j < SEMMOE_MAX_K; ++j) {
     if (q[j] < 0) continue;
-    const int slot = w.cnt[size_t(blockIdx.x) * E + q[j]] + bitmap_rank(lds + q[j] * kWords, t);
+    const int slot = expert_offsets[q[j]] + w.cnt[size_t(blockIdx.x) * E + q[j]] + bitmap_rank(lds + q[j] * kWords, t);
     const int pair = tok * k + j;
     slot_of_pair[pair] = slot;
     pair_of_slot[slot] = pair;
@@ -226,11 +200,11 @@ static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, cons
     hipLaunchKernelGGL(dp_count_kernel, dim3(NB), dim3(kTokBlock), (E * kWords + D * D) * 4, s, T, k, E, D, topk_ids,
                        token_rank, shf, phys_of_expert, w);
   }
-  hipLaunchKernelGGL(dp_scan_kernel, dim3(1), dim3(1024), 0, s, NB, E, D, expert_offsets, rank_offsets, send_matrix,
+  hipLaunchKernelGGL(dp_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, E, D, expert_offsets, rank_offsets, send_matrix,
                      reinterpret_cast<unsigned long long*>(remote_pairs), w);
   if (NB > 0) {
     hipLaunchKernelGGL(dp_slot_kernel, dim3(NB), dim3(kTokBlock), E * kWords * 4, s, T, k, E, topk_ids, shf,
-                       phys_of_expert, slot_of_pair, pair_of_slot, w);
+                       phys_of_expert, slot_of_pair, pair_of_slot, expert_offsets, w);
   }
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;

@@ -5,7 +5,7 @@
 namespace semmoe {
 
 static int32_t run_ffn(const semmoe_config* cfg, hipStream_t s, const void* X, const int32_t* offsets, int q_lo,
-                       int nq, int n_rows_single, int max_rows, const int32_t* group_to_weight, const void* W_gu,
+                       int nq, int n_rows_single, int max_rows, int est_rows, const int32_t* group_to_weight, const void* W_gu,
                        const void* W_down, void* Y, void* H) {
   GemmArgs a{};
   a.X = X; a.ldx = cfg->d;
@@ -14,14 +14,14 @@ static int32_t run_ffn(const semmoe_config* cfg, hipStream_t s, const void* X, c
   a.offsets = offsets; a.q_lo = q_lo; a.nq = nq; a.n_rows_single = n_rows_single;
   a.group_to_weight = group_to_weight;
   a.out = H; a.ldo = cfg->F;
-  int32_t st = launch_gemm(kModeSwiglu, cfg->dtype, a, max_rows, s);
+  int32_t st = launch_gemm(kModeSwiglu, cfg->dtype, a, max_rows, est_rows, s);
   if (st != SEMMOE_OK) return st;
   GemmArgs b = a;
   b.X = H; b.ldx = cfg->F;
   b.W = W_down; b.w_group_stride = size_t(cfg->d) * cfg->F; b.ldw = cfg->F;
   b.N = cfg->d; b.K = cfg->F;
   b.out = Y; b.ldo = cfg->d;
-  return launch_gemm(kModeStore, cfg->dtype, b, max_rows, s);
+  return launch_gemm(kModeStore, cfg->dtype, b, max_rows, est_rows, s);
 }
 
 size_t ws_ffn(const semmoe_config* cfg) {
@@ -47,7 +47,7 @@ extern "C" int32_t semmoe_expert_ffn(const semmoe_config* cfg, void* stream, int
   const int q_lo = rank < 0 ? 0 : rank * m;
   const int nq = rank < 0 ? cfg->E : m;
   return run_ffn(cfg, static_cast<hipStream_t>(stream), X_perm, expert_offsets, q_lo, nq, 0, cfg->T * cfg->k,
-                 expert_of_phys, W_gu, W_down, Y, H);
+                 cfg->T * cfg->k / cfg->E, expert_of_phys, W_gu, W_down, Y, H);
 }
 
 extern "C" int32_t semmoe_shared_ffn(const semmoe_config* cfg, void* stream, const void* X, int32_t n_tokens,
@@ -62,6 +62,6 @@ extern "C" int32_t semmoe_shared_ffn(const semmoe_config* cfg, void* stream, con
   void* H = c.take<char>(size_t(n_tokens) * cfg->F * act_bytes(cfg));
   if (!c.ok) return SEMMOE_EWORKSPACE;
   if (n_tokens == 0) return SEMMOE_OK;
-  return run_ffn(cfg, static_cast<hipStream_t>(stream), X, nullptr, 0, 1, n_tokens, n_tokens, nullptr, W_gu_sh,
+  return run_ffn(cfg, static_cast<hipStream_t>(stream), X, nullptr, 0, 1, n_tokens, n_tokens, n_tokens, nullptr, W_gu_sh,
                  W_down_sh, Y_shared, H);
 }

@@ -4,26 +4,65 @@
 namespace semmoe {
 
 static int g_num_cu = 0;
+static int g_max_lds = 0;
+static int g_tune[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
 
 static int num_cu() {
   if (g_num_cu == 0) {
-    int dev = 0, n = 0;
+    int dev = 0, n = 0, l = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 256;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    if (hipDeviceGetAttribute(&l, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || l <= 0) l = 65536;
     g_num_cu = n;
+    g_max_lds = l;
   }
   return g_num_cu;
 }
 
-template <int MODE, int NWF, int NWT, int TF, int TT>
-static int32_t launch_bf16(const GemmArgs& a, int max_rows, hipStream_t stream) {
-  using C = Bf16Cfg<MODE, NWF, NWT, TF, TT>;
+int tuning_value(int key) { return (key >= 0 && key < 8) ? g_tune[key] : -1; }
+
+template <int MODE, int NWF, int NWT, int TF, int TT, int BK, int MINW = 1>
+static int32_t launch_bf16(const GemmArgs& a, int max_rows, int blocks_per_cu, hipStream_t stream) {
+  using C = Bf16Cfg<MODE, NWF, NWT, TF, TT, BK>;
   const int n_ftiles = cdiv(a.N, C::FEAT);
   const long long bound = (long long)(max_rows / C::BT + a.nq) * n_ftiles;
   if (bound <= 0) return SEMMOE_OK;
-  const int grid = (int)(bound < (long long)num_cu() * 2 ? bound : (long long)num_cu() * 2);
-  hipLaunchKernelGGL((gemm_bf16_kernel<MODE, NWF, NWT, TF, TT>), dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream,
-                     a);
+  const long long cap = (long long)num_cu() * blocks_per_cu;
+  const int grid = (int)(bound < cap ? bound : cap);
+  auto kern = gemm_bf16_kernel<MODE, NWF, NWT, TF, TT, BK, MINW>;
+  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > 48 * 1024) {
+    static bool attr_set = false;  // one flag per instantiation
+    if (!attr_set) {
+      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     int(C::kLdsBytes)));
+      attr_set = true;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+template <int MODE, int NWF, int NWT, int TF, int TT, int BK, int NSTAGE, int MINW = 1>
+static int32_t launch_dma(const GemmArgs& a, int max_rows, int blocks_per_cu, hipStream_t stream) {
+  using C = DmaCfg<MODE, NWF, NWT, TF, TT, BK, NSTAGE>;
+  const int n_ftiles = cdiv(a.N, C::FEAT);
+  const long long bound = (long long)(max_rows / C::BT + a.nq) * n_ftiles;
+  if (bound <= 0) return SEMMOE_OK;
+  const long long cap = (long long)num_cu() * blocks_per_cu;
+  const int grid = (int)(bound < cap ? bound : cap);
+  auto kern = gemm_bf16_dma_kernel<MODE, NWF, NWT, TF, TT, BK, NSTAGE, MINW>;
+  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > 48 * 1024) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     int(C::kLdsBytes)));
+      attr_set = true;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
 }
@@ -41,14 +80,53 @@ static int32_t launch_f32(const GemmArgs& a, int max_rows, hipStream_t stream) {
   return SEMMOE_OK;
 }
 
-int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, hipStream_t stream) {
+// tile shapes: id -> (waves along weight rows, waves along tokens, MFMA tiles per wave, K slice)
+template <int MODE>
+static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc, hipStream_t s) {
+  switch (id) {
+    case 0: return launch_bf16<MODE, 2, 2, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);  // 128 x 128, 4 waves
+    case 3: return launch_bf16<MODE, 2, 4, 4, 2, 64>(a, max_rows, bpc > 0 ? bpc : 1, s);  // 256 x 256, 8 waves
+    case 4: return launch_bf16<MODE, 4, 2, 2, 4, 64>(a, max_rows, bpc > 0 ? bpc : 1, s);  // 256 x 256, 8 waves
+    case 6: return launch_bf16<MODE, 2, 4, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 1, s);  // 128 x 256, 8 waves
+    case 11: return launch_dma<MODE, 2, 4, 4, 2, 32, 4>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 256, 8 waves
+    case 12: return launch_dma<MODE, 4, 2, 2, 4, 32, 4>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 256, 8 waves
+    case 14: return launch_dma<MODE, 2, 4, 2, 2, 32, 4>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 128 x 256, 8 waves
+    case 15: return launch_dma<MODE, 2, 4, 4, 2, 32, 3>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 256, ring of 3
+    case 16: return launch_dma<MODE, 2, 4, 4, 2, 64, 2>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 256, K 64 x 2
+    case 17: return launch_bf16<MODE, 4, 1, 2, 1, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 32 (decode)
+    case 18: return launch_bf16<MODE, 4, 1, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 64
+    default: return SEMMOE_EINVAL;
+  }
+}
+
+// Default tile shape from the mean rows per group the caller expects (the true, ragged row counts live on
+// the device): big direct-to-LDS tiles when groups fill them, small register-staged tiles otherwise.
+static int default_tile(int est_rows_per_group) {
+  if (est_rows_per_group >= 192) return 16;
+  if (est_rows_per_group >= 96) return 0;
+  if (est_rows_per_group >= 48) return 18;
+  return 17;
+}
+
+int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int est_rows_per_group,
+                    hipStream_t stream) {
   if (a.nq <= 0 || max_rows <= 0) return SEMMOE_OK;
   if (a.nq > 512) return SEMMOE_EUNSUPPORTED;
+  num_cu();
   if (dtype == SEMMOE_BF16) {
+    const int bpc = g_tune[SEMMOE_TUNE_BLOCKS_PER_CU];
     switch (mode) {
-      case kModeLogits: return launch_bf16<kModeLogits, 2, 2, 2, 1>(a, max_rows, stream);  // 128 experts x 64 tokens
-      case kModeSwiglu: return launch_bf16<kModeSwiglu, 2, 2, 2, 2>(a, max_rows, stream);
-      default: return launch_bf16<kModeStore, 2, 2, 2, 2>(a, max_rows, stream);
+      case kModeLogits: return launch_bf16<kModeLogits, 2, 2, 2, 1, 64>(a, max_rows, 2, stream);  // 128 experts x 64 tokens
+      case kModeSwiglu: {
+        const int id = g_tune[SEMMOE_TUNE_GATEUP_TILE] >= 0 ? g_tune[SEMMOE_TUNE_GATEUP_TILE]
+                                                            : default_tile(est_rows_per_group);
+        return launch_bf16_tile<kModeSwiglu>(id, a, max_rows, bpc, stream);
+      }
+      default: {
+        const int id = g_tune[SEMMOE_TUNE_DOWN_TILE] >= 0 ? g_tune[SEMMOE_TUNE_DOWN_TILE]
+                                                          : default_tile(est_rows_per_group);
+        return launch_bf16_tile<kModeStore>(id, a, max_rows, bpc, stream);
+      }
     }
   }
   switch (mode) {
@@ -59,3 +137,9 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, hipStr
 }
 
 }  // namespace semmoe
+
+extern "C" int32_t semmoe_set_tuning(int32_t key, int32_t value) {
+  if (key < 0 || key >= 8) return SEMMOE_EINVAL;
+  semmoe::g_tune[key] = value;
+  return SEMMOE_OK;
+}

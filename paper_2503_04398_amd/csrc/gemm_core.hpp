@@ -79,31 +79,126 @@ __device__ __forceinline__ int find_group(const int* pre, int nq, int t) {
   return lo;
 }
 
+// Workgroups are handed to the 8 XCDs round-robin by workgroup id, and each XCD has its own L2.  Worker
+// index = the position of this workgroup in an order where the workgroups of one XCD are consecutive, so
+// that at any time one XCD works on a contiguous run of the tile list.
+__device__ __forceinline__ int xcd_worker_index() {
+  const int g = gridDim.x, b = blockIdx.x;
+  if (g % 8 != 0) return b;
+  return (b & 7) * (g >> 3) + (b >> 3);
+}
+
+// Inside a group the tile list walks blocks of kFeatBlock feature tiles x all token tiles of the group
+// (feature tile fastest inside a block): a run of consecutive tiles shares few weight panels and few
+// token panels, which is what the L2 of one XCD can keep.
+constexpr int kFeatBlock = 8;
+__device__ __forceinline__ void decode_tile(int local, int n_ttiles, int n_ftiles, int* tt, int* ft) {
+  const int full = (n_ftiles / kFeatBlock) * kFeatBlock;
+  const int per_block = n_ttiles * kFeatBlock;
+  if (local < (n_ftiles / kFeatBlock) * per_block) {
+    const int fb = local / per_block, rem = local - fb * per_block;
+    *tt = rem / kFeatBlock;
+    *ft = fb * kFeatBlock + rem % kFeatBlock;
+  } else {
+    const int rest = n_ftiles - full;
+    const int l2 = local - (n_ftiles / kFeatBlock) * per_block;
+    *tt = l2 / rest;
+    *ft = full + l2 % rest;
+  }
+}
+
+// Output tile of a bf16 GEMM: accumulators -> LDS (bf16, 16-byte chunks swizzled by the row so that the 32
+// lanes of a half-wave, which hold 32 different rows, spread over the banks) -> coalesced 16-byte global
+// stores, one row segment per group of consecutive lanes.  acc[i][j][r] belongs to weight row
+// 8*(r/4) + 4*(lane/32) + r%4 of MFMA tile i and token lane%32 of token tile j.
+// The caller guarantees that no wave still reads the LDS region and puts a barrier after the call.
+template <int MODE, int NWF, int NWT, int TF, int TT>
+__device__ __forceinline__ void store_tile_via_lds(f32x16_t (&acc)[TF][TT], unsigned char* lds, const GemmArgs& a,
+                                                   int row_lo, int n_tok, int f0, int wf, int wt) {
+  constexpr int BT = NWT * TT * 32;
+  constexpr int FEAT = (MODE == kModeSwiglu) ? NWF * TF * 16 : NWF * TF * 32;
+  constexpr int CPR = FEAT / 8;                   // 16-byte chunks per output row
+  constexpr int MASK = (CPR < 32 ? CPR : 32) - 1; // swizzle range
+  constexpr int RB = FEAT * 2;
+  constexpr int kThreads = 64 * NWF * NWT;
+  const int lane = threadIdx.x & 63;
+  const int tok_in = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < TT; ++j) {
+    const int t = (wt * TT + j) * 32 + tok_in;
+    unsigned char* rowp = lds + t * RB + half * 8;
+    if constexpr (MODE == kModeSwiglu) {
+#pragma unroll
+      for (int i = 0; i < TF; i += 2) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int chunk = (wf * (TF / 2) + i / 2) * 4 + g4;
+          const float h0 = silu_mul(acc[i][j][g4 * 4 + 0], acc[i + 1][j][g4 * 4 + 0]);
+          const float h1 = silu_mul(acc[i][j][g4 * 4 + 1], acc[i + 1][j][g4 * 4 + 1]);
+          const float h2 = silu_mul(acc[i][j][g4 * 4 + 2], acc[i + 1][j][g4 * 4 + 2]);
+          const float h3 = silu_mul(acc[i][j][g4 * 4 + 3], acc[i + 1][j][g4 * 4 + 3]);
+          *reinterpret_cast<uint2*>(rowp + ((chunk ^ (t & MASK)) * 16)) =
+              make_uint2(pack_bf16x2(h0, h1), pack_bf16x2(h2, h3));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TF; ++i) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int chunk = (wf * TF + i) * 4 + g4;
+          *reinterpret_cast<uint2*>(rowp + ((chunk ^ (t & MASK)) * 16)) =
+              make_uint2(pack_bf16x2(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1]),
+                         pack_bf16x2(acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]));
+        }
+      }
+    }
+  }
+  __syncthreads();
+  bf16_t* out = static_cast<bf16_t*>(a.out);
+  for (int idx = threadIdx.x; idx < BT * CPR; idx += kThreads) {
+    const int row = idx / CPR, c = idx % CPR;
+    const int feat = f0 + c * 8;
+    if (row < n_tok && feat < a.N) {
+      const uint4 v = *reinterpret_cast<const uint4*>(lds + row * RB + ((c ^ (row & MASK)) * 16));
+      *reinterpret_cast<uint4*>(out + (size_t(row_lo) + row) * a.ldo + feat) = v;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
+//   NWF x NWT waves (along weight rows x along tokens), each wave TF x TT MFMA tiles of 32x32.
+//   K is consumed in BK slices through a two-stage LDS ring: while slice `it` is multiplied out of one
+//   stage, slice it+1 (already in registers) is written to the other stage and slice it+2 is requested
+//   from global memory; one barrier per slice.
 // ------------------------------------------------------------------------------------------------
-template <int MODE, int NWF, int NWT, int TF, int TT>
+template <int MODE, int NWF, int NWT, int TF, int TT, int BK>
 struct Bf16Cfg {
   static constexpr int kThreads = 64 * NWF * NWT;
   static constexpr int BW = NWF * TF * 32;  // weight rows per tile
   static constexpr int BT = NWT * TT * 32;  // token rows per tile
-  static constexpr int BK = 64;
-  static constexpr int LDK = BK + 8;        // LDS row stride in elements (144 B: conflict-free b128 reads)
+  static constexpr int LDK = BK + 8;        // LDS row stride in elements: conflict-free 16-byte reads
+  static constexpr int CPR = BK / 8;        // 16-byte chunks per tile row
   static constexpr int FEAT = (MODE == kModeSwiglu) ? BW / 2 : BW;  // output features per tile
-  static constexpr int W_CHUNKS = BW * (BK / 8) / kThreads;
-  static constexpr int X_CHUNKS = BT * (BK / 8) / kThreads;
-  static constexpr size_t kLdsBytes = size_t(BW + BT) * LDK * 2 + 520 * 4;
+  static constexpr int W_CHUNKS = BW * CPR / kThreads;
+  static constexpr int X_CHUNKS = BT * CPR / kThreads;
+  static constexpr int kStageElems = (BW + BT) * LDK;
+  static constexpr size_t kRingBytes = size_t(2) * kStageElems * 2;
+  static constexpr size_t kOutBytes = size_t(BT) * FEAT * 2;  // the output tile is staged in the ring's place
+  static constexpr size_t kTileBytes = kRingBytes > kOutBytes ? kRingBytes : kOutBytes;
+  static constexpr size_t kLdsBytes = kTileBytes + 520 * 4;
   static_assert(MODE != kModeSwiglu || TF % 2 == 0, "gate/up tiles come in pairs");
-  static_assert(BW * (BK / 8) % kThreads == 0 && BT * (BK / 8) % kThreads == 0, "loader shape");
+  static_assert((BW * CPR) % kThreads == 0 && (BT * CPR) % kThreads == 0, "loader shape");
+  static_assert(BK % 16 == 0, "k-steps of 16");
 };
 
-template <int MODE, int NWF, int NWT, int TF, int TT>
-__global__ __launch_bounds__(64 * NWF * NWT) void gemm_bf16_kernel(GemmArgs a) {
-  using C = Bf16Cfg<MODE, NWF, NWT, TF, TT>;
+template <int MODE, int NWF, int NWT, int TF, int TT, int BK, int MINW>
+__global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_kernel(GemmArgs a) {
+  using C = Bf16Cfg<MODE, NWF, NWT, TF, TT, BK>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16_t* Ws = reinterpret_cast<bf16_t*>(lds_raw);
-  bf16_t* Xs = Ws + C::BW * C::LDK;
-  int* pre = reinterpret_cast<int*>(Xs + C::BT * C::LDK);
+  bf16_t* lds = reinterpret_cast<bf16_t*>(lds_raw);
+  int* pre = reinterpret_cast<int*>(lds_raw + C::kTileBytes);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -112,44 +207,46 @@ __global__ __launch_bounds__(64 * NWF * NWT) void gemm_bf16_kernel(GemmArgs a) {
   const int wt = wave / NWF;  // wave position along tokens
   const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
   const int total = build_tile_prefix<C::BT>(a, n_ftiles, pre);
+  const int nk = (a.K + BK - 1) / BK;
 
-  for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
+  for (int tile = xcd_worker_index(); tile < total; tile += gridDim.x) {
     const int q = find_group(pre, a.nq, tile);
     const int local = tile - pre[q];
-    const int ft = local % n_ftiles;
-    const int tt_idx = local / n_ftiles;
-    const int row_lo = (a.offsets ? a.offsets[a.q_lo + q] : 0) + tt_idx * C::BT;
+    const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
     const int row_hi = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
+    int ft, tt_idx;
+    decode_tile(local, (row_hi - g_lo + C::BT - 1) / C::BT, n_ftiles, &tt_idx, &ft);
+    const int row_lo = g_lo + tt_idx * C::BT;
     const int n_tok = min(C::BT, row_hi - row_lo);
     const int f0 = ft * C::FEAT;
     const int widx = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
     const bf16_t* Wg = static_cast<const bf16_t*>(a.W) + size_t(widx) * a.w_group_stride;
     const bf16_t* Xg = static_cast<const bf16_t*>(a.X) + size_t(row_lo) * a.ldx;
 
-    // per-thread source rows of the loader (nullptr: outside the matrix -> zeros)
+    // per-thread source rows of the loader.  Rows outside the matrix are clamped to a valid row: their
+    // products land in outputs the epilogue never stores, so no zero fill (and no branch) is needed.
     const bf16_t* wsrc[C::W_CHUNKS];
     const bf16_t* xsrc[C::X_CHUNKS];
-    const int kc = (tid & 7) * 8;
+    const int kc = (tid % C::CPR) * 8;
+    const int lr0 = tid / C::CPR;
+    constexpr int LR_STEP = C::kThreads / C::CPR;
 #pragma unroll
     for (int i = 0; i < C::W_CHUNKS; ++i) {
-      const int lr = (tid >> 3) + i * (C::kThreads / 8);
+      const int lr = lr0 + i * LR_STEP;
       int grow;
-      bool ok;
       if constexpr (MODE == kModeSwiglu) {
         const int w_of = lr / (TF * 32), tf = (lr / 32) % TF, fr = lr & 31;
-        const int feat = f0 + (w_of * (TF / 2) + tf / 2) * 32 + fr;
-        ok = feat < a.N;
+        const int feat = min(f0 + (w_of * (TF / 2) + tf / 2) * 32 + fr, a.N - 1);
         grow = (tf & 1) * a.N + feat;
       } else {
-        grow = f0 + lr;
-        ok = grow < a.N;
+        grow = min(f0 + lr, a.N - 1);
       }
-      wsrc[i] = ok ? Wg + size_t(grow) * a.ldw + kc : nullptr;
+      wsrc[i] = Wg + size_t(grow) * a.ldw + kc;
     }
 #pragma unroll
     for (int i = 0; i < C::X_CHUNKS; ++i) {
-      const int lr = (tid >> 3) + i * (C::kThreads / 8);
-      xsrc[i] = lr < n_tok ? Xg + size_t(lr) * a.ldx + kc : nullptr;
+      const int lr = min(lr0 + i * LR_STEP, n_tok - 1);
+      xsrc[i] = Xg + size_t(lr) * a.ldx + kc;
     }
 
     f32x16_t acc[TF][TT];
@@ -161,88 +258,89 @@ __global__ __launch_bounds__(64 * NWF * NWT) void gemm_bf16_kernel(GemmArgs a) {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     uint4 wreg[C::W_CHUNKS], xreg[C::X_CHUNKS];
-    auto gload = [&](int k0) {
-      const bool kin = (k0 + kc) < a.K;
+    // the last K slice may be partial (K % 8 == 0 always holds): chunks past K must read as zero there
+    const int k_tail = a.K - (nk - 1) * BK;
+    auto gload = [&](int it) {
+      const int k0 = it * BK;
+      if (it + 1 < nk || k_tail == BK) {
+#pragma unroll
+        for (int i = 0; i < C::W_CHUNKS; ++i) wreg[i] = *reinterpret_cast<const uint4*>(wsrc[i] + k0);
+#pragma unroll
+        for (int i = 0; i < C::X_CHUNKS; ++i) xreg[i] = *reinterpret_cast<const uint4*>(xsrc[i] + k0);
+      } else {
+        const bool kin = kc < k_tail;
+#pragma unroll
+        for (int i = 0; i < C::W_CHUNKS; ++i)
+          wreg[i] = kin ? *reinterpret_cast<const uint4*>(wsrc[i] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < C::X_CHUNKS; ++i)
+          xreg[i] = kin ? *reinterpret_cast<const uint4*>(xsrc[i] + k0) : make_uint4(0, 0, 0, 0);
+      }
+    };
+    auto sstore = [&](int stage) {
+      bf16_t* Ws = lds + stage * C::kStageElems;
+      bf16_t* Xs = Ws + C::BW * C::LDK;
 #pragma unroll
       for (int i = 0; i < C::W_CHUNKS; ++i)
-        wreg[i] = (wsrc[i] && kin) ? *reinterpret_cast<const uint4*>(wsrc[i] + k0) : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(Ws + (lr0 + i * LR_STEP) * C::LDK + kc) = wreg[i];
 #pragma unroll
       for (int i = 0; i < C::X_CHUNKS; ++i)
-        xreg[i] = (xsrc[i] && kin) ? *reinterpret_cast<const uint4*>(xsrc[i] + k0) : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(Xs + (lr0 + i * LR_STEP) * C::LDK + kc) = xreg[i];
     };
 
     gload(0);
-    for (int k0 = 0; k0 < a.K; k0 += C::BK) {
-      __syncthreads();  // previous tile's LDS reads are done
+    sstore(0);
+    if (nk > 1) gload(1);
+    __syncthreads();
+    for (int it = 0; it < nk; ++it) {
+      const int cur = it & 1;
+      if (it + 1 < nk) sstore(cur ^ 1);
+      if (it + 2 < nk) gload(it + 2);
+      const bf16_t* Ws = lds + cur * C::kStageElems;
+      const bf16_t* Xs = Ws + C::BW * C::LDK;
+      // fragments of k-step s+1 are requested before the MFMAs of k-step s are issued
+      constexpr int KS = BK / 16;
+      bf16x8_t af[2][TF], bfr[2][TT];
+      const bf16_t* wrow = Ws + (wf * TF * 32 + (lane & 31)) * C::LDK + (lane >> 5) * 8;
+      const bf16_t* xrow = Xs + (wt * TT * 32 + (lane & 31)) * C::LDK + (lane >> 5) * 8;
 #pragma unroll
-      for (int i = 0; i < C::W_CHUNKS; ++i) {
-        const int lr = (tid >> 3) + i * (C::kThreads / 8);
-        *reinterpret_cast<uint4*>(Ws + lr * C::LDK + kc) = wreg[i];
-      }
+      for (int i = 0; i < TF; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::LDK);
 #pragma unroll
-      for (int i = 0; i < C::X_CHUNKS; ++i) {
-        const int lr = (tid >> 3) + i * (C::kThreads / 8);
-        *reinterpret_cast<uint4*>(Xs + lr * C::LDK + kc) = xreg[i];
-      }
-      __syncthreads();
-      if (k0 + C::BK < a.K) gload(k0 + C::BK);
+      for (int j = 0; j < TT; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::LDK);
 #pragma unroll
-      for (int kk = 0; kk < C::BK; kk += 16) {
-        bf16x8_t af[TF], bfr[TT];
-        const int ko = kk + (lane >> 5) * 8;
+      for (int st = 0; st < KS; ++st) {
+        if (st + 1 < KS) {
 #pragma unroll
-        for (int i = 0; i < TF; ++i)
-          af[i] = *reinterpret_cast<const bf16x8_t*>(Ws + ((wf * TF + i) * 32 + (lane & 31)) * C::LDK + ko);
+          for (int i = 0; i < TF; ++i)
+            af[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::LDK + (st + 1) * 16);
 #pragma unroll
-        for (int j = 0; j < TT; ++j)
-          bfr[j] = *reinterpret_cast<const bf16x8_t*>(Xs + ((wt * TT + j) * 32 + (lane & 31)) * C::LDK + ko);
+          for (int j = 0; j < TT; ++j)
+            bfr[(st + 1) & 1][j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::LDK + (st + 1) * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < TF; ++i)
 #pragma unroll
           for (int j = 0; j < TT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][i], bfr[st & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      __syncthreads();
     }
 
-    // epilogue.  acc[i][j][r]: weight-row offset 8*(r/4) + 4*(lane/32) + r%4 inside the 32-row tile,
-    // token lane%32 inside the 32-token tile.
-    const int tok_in = lane & 31;
-    const int half = lane >> 5;
+    if constexpr (MODE != kModeLogits) {
+      // the K loop ended with a barrier: the ring is free and takes the output tile
+      store_tile_via_lds<MODE, NWF, NWT, TF, TT>(acc, lds_raw, a, row_lo, n_tok, f0, wf, wt);
+      __syncthreads();
+    } else {
+      // logits: acc[i][j][r] is expert 8*(r/4) + 4*(lane/32) + r%4 of tile i, token lane%32 of tile j
+      const int tok_in = lane & 31;
+      const int half = lane >> 5;
 #pragma unroll
-    for (int j = 0; j < TT; ++j) {
-      const int tl = (wt * TT + j) * 32 + tok_in;
-      if (tl >= n_tok) continue;
-      const size_t row = size_t(row_lo) + tl;
-      if constexpr (MODE == kModeSwiglu) {
-        bf16_t* o = static_cast<bf16_t*>(a.out) + row * a.ldo;
-#pragma unroll
-        for (int i = 0; i < TF; i += 2) {
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            const int feat = f0 + (wf * (TF / 2) + i / 2) * 32 + g4 * 8 + half * 4;
-            if (feat < a.N) {
-              float h0 = silu_mul(acc[i][j][g4 * 4 + 0], acc[i + 1][j][g4 * 4 + 0]);
-              float h1 = silu_mul(acc[i][j][g4 * 4 + 1], acc[i + 1][j][g4 * 4 + 1]);
-              float h2 = silu_mul(acc[i][j][g4 * 4 + 2], acc[i + 1][j][g4 * 4 + 2]);
-              float h3 = silu_mul(acc[i][j][g4 * 4 + 3], acc[i + 1][j][g4 * 4 + 3]);
-              *reinterpret_cast<uint2*>(o + feat) = make_uint2(pack_bf16x2(h0, h1), pack_bf16x2(h2, h3));
-            }
-          }
-        }
-      } else if constexpr (MODE == kModeStore) {
-        bf16_t* o = static_cast<bf16_t*>(a.out) + row * a.ldo;
-#pragma unroll
-        for (int i = 0; i < TF; ++i) {
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            const int feat = f0 + (wf * TF + i) * 32 + g4 * 8 + half * 4;
-            if (feat < a.N)
-              *reinterpret_cast<uint2*>(o + feat) =
-                  make_uint2(pack_bf16x2(acc[i][j][g4 * 4 + 0], acc[i][j][g4 * 4 + 1]),
-                             pack_bf16x2(acc[i][j][g4 * 4 + 2], acc[i][j][g4 * 4 + 3]));
-          }
-        }
-      } else {  // logits
+      for (int j = 0; j < TT; ++j) {
+        const int tl = (wt * TT + j) * 32 + tok_in;
+        if (tl >= n_tok) continue;
+        const size_t row = size_t(row_lo) + tl;
         float* o = static_cast<float*>(a.out) + row * size_t(a.N);
         const int cls = a.token_class ? a.token_class[row] : -1;
         const float* cb = (cls >= 0 && cls < a.n_classes && a.class_bias) ? a.class_bias + size_t(cls) * a.N : nullptr;
@@ -261,6 +359,193 @@ __global__ __launch_bounds__(64 * NWF * NWT) void gemm_bf16_kernel(GemmArgs a) {
         }
       }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA kernel with direct global -> LDS loads (global_load_lds_dwordx4) and an NSTAGE ring.
+//   A wave-level load instruction writes 64 x 16 B = 1 KB of consecutive LDS (lane L at base + 16 L), so
+//   tile rows are stored unpadded (BK*2 bytes each) and bank conflicts are avoided by an XOR swizzle of
+//   the 16-byte chunk index with the row index: chunk c of row r sits at position c ^ ((r / RPB) % CPR),
+//   RPB = rows per 256 bytes.  The lane that fills position p of row r therefore fetches chunk
+//   p ^ ((r / RPB) % CPR) from global memory.
+//   Slices it+1 .. it+NSTAGE-1 are in flight while slice `it` is multiplied; one barrier per slice.
+//   Waits on the loads are written by hand (the compiler does not see these loads).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr_uniform), "v"(gptr)
+               : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int MODE, int NWF, int NWT, int TF, int TT, int BK, int NSTAGE>
+struct DmaCfg {
+  static constexpr int NW = NWF * NWT;
+  static constexpr int kThreads = 64 * NW;
+  static constexpr int BW = NWF * TF * 32;
+  static constexpr int BT = NWT * TT * 32;
+  static constexpr int ROWS = BW + BT;
+  static constexpr int RB = BK * 2;        // bytes per tile row
+  static constexpr int CPR = BK / 8;       // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;     // rows written by one wave instruction
+  static constexpr int IPS = ROWS / RPI;   // instructions per stage
+  static constexpr int IPW = IPS / NW;     // ... per wave
+  static constexpr int RPB = 256 / RB;     // rows per 256 bytes of bank space
+  static constexpr int kStageBytes = ROWS * RB;
+  static constexpr int FEAT = (MODE == kModeSwiglu) ? BW / 2 : BW;
+  static constexpr int KS = BK / 16;
+  static constexpr size_t kRingBytes = size_t(NSTAGE) * kStageBytes;
+  static constexpr size_t kOutBytes = size_t(BT) * FEAT * 2;  // the output tile is staged in the ring's place
+  static constexpr size_t kTileBytes = kRingBytes > kOutBytes ? kRingBytes : kOutBytes;
+  static constexpr size_t kLdsBytes = kTileBytes + 520 * 4;
+  static_assert(BK == 32 || BK == 64, "row of 64 or 128 bytes");
+  static_assert(IPS % NW == 0, "instructions divide over the waves");
+  static_assert(NSTAGE >= 2 && NSTAGE <= 5, "ring depth");
+  static_assert((NSTAGE - 1) * IPW < 64, "vmcnt range");
+  static_assert(MODE != kModeSwiglu || TF % 2 == 0, "gate/up tiles come in pairs");
+};
+
+template <int MODE, int NWF, int NWT, int TF, int TT, int BK, int NSTAGE, int MINW>
+__global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(GemmArgs a) {
+  using C = DmaCfg<MODE, NWF, NWT, TF, TT, BK, NSTAGE>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  int* pre = reinterpret_cast<int*>(lds_raw + C::kTileBytes);
+  const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wf = wave % NWF;
+  const int wt = wave / NWF;
+  const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
+  const int total = build_tile_prefix<C::BT>(a, n_ftiles, pre);
+  const int nk = (a.K + BK - 1) / BK;
+  const int k_tail = a.K - (nk - 1) * BK;  // elements in the last slice (multiple of 8)
+
+  // fragment-read geometry: lane reads row (lane & 31) of a 32-row MFMA tile, chunk 2*ks + lane/32
+  const int frag_swz = ((lane & 31) / C::RPB) % C::CPR;
+  // loader geometry: lane fills position d_pos of row d_row inside the 1 KB block of an instruction
+  const int d_row = lane / C::CPR;
+  const int d_pos = lane % C::CPR;
+
+  for (int tile = xcd_worker_index(); tile < total; tile += gridDim.x) {
+    const int q = find_group(pre, a.nq, tile);
+    const int local = tile - pre[q];
+    const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
+    const int row_hi = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
+    int ft, tt_idx;
+    decode_tile(local, (row_hi - g_lo + C::BT - 1) / C::BT, n_ftiles, &tt_idx, &ft);
+    const int row_lo = g_lo + tt_idx * C::BT;
+    const int n_tok = min(C::BT, row_hi - row_lo);
+    const int f0 = ft * C::FEAT;
+    const int widx = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
+    const bf16_t* Wg = static_cast<const bf16_t*>(a.W) + size_t(widx) * a.w_group_stride;
+    const bf16_t* Xg = static_cast<const bf16_t*>(a.X) + size_t(row_lo) * a.ldx;
+
+    // source pointer of this lane for each of the wave's load instructions (rows outside the matrix are
+    // clamped to a valid row: their products are never stored)
+    const bf16_t* src[C::IPW];
+    int src_chunk[C::IPW];
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i) {
+      const int sr = (wave * C::IPW + i) * C::RPI + d_row;  // row of the stage: weights first, then tokens
+      const int c = d_pos ^ ((sr / C::RPB) % C::CPR);       // chunk this lane must fetch
+      src_chunk[i] = c;
+      if (sr < C::BW) {
+        int grow;
+        if constexpr (MODE == kModeSwiglu) {
+          const int w_of = sr / (TF * 32), tf = (sr / 32) % TF, fr = sr & 31;
+          const int feat = min(f0 + (w_of * (TF / 2) + tf / 2) * 32 + fr, a.N - 1);
+          grow = (tf & 1) * a.N + feat;
+        } else {
+          grow = min(f0 + sr, a.N - 1);
+        }
+        src[i] = Wg + size_t(grow) * a.ldw + c * 8;
+      } else {
+        src[i] = Xg + size_t(min(sr - C::BW, n_tok - 1)) * a.ldx + c * 8;
+      }
+    }
+
+    auto issue_to = [&](int slice, int it_) {  // K slice `slice` goes to the ring stage of iteration it_
+      const unsigned dst0 = lds_base + (it_ % NSTAGE) * C::kStageBytes + wave * C::IPW * 1024;
+      const int k0 = slice * BK;
+      if (slice + 1 < nk || k_tail == BK) {
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i) lds_dma16(src[i] + k0, dst0 + i * 1024);
+      } else {  // partial last slice: chunks past K are zero-filled by a plain LDS store
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i) {
+          if (src_chunk[i] * 8 < k_tail) {
+            lds_dma16(src[i] + k0, dst0 + i * 1024);
+          } else {
+            *reinterpret_cast<uint4*>(lds_raw + (dst0 - lds_base) + i * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+          }
+        }
+      }
+    };
+
+    f32x16_t acc[TF][TT];
+#pragma unroll
+    for (int i = 0; i < TF; ++i)
+#pragma unroll
+      for (int j = 0; j < TT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+#pragma unroll
+    for (int s0 = 0; s0 < NSTAGE - 1; ++s0)
+      if (s0 < nk) issue_to(s0, s0);
+
+    for (int it = 0; it < nk; ++it) {
+      // slices it+1 .. min(it+NSTAGE-2, nk-1) were issued after slice `it` and may stay in flight
+      const int younger = min(NSTAGE - 2, nk - 1 - it);
+      if (younger >= 3) wait_vmcnt<3 * C::IPW>();
+      else if (younger == 2) wait_vmcnt<2 * C::IPW>();
+      else if (younger == 1) wait_vmcnt<1 * C::IPW>();
+      else wait_vmcnt<0>();
+      __syncthreads();  // slice `it` is complete in LDS; every wave is done with slice it-1
+      if (it + NSTAGE - 1 < nk) issue_to(it + NSTAGE - 1, it + NSTAGE - 1);  // refills the stage of slice it-1
+      const unsigned char* Ws = lds_raw + (it % NSTAGE) * C::kStageBytes;
+      const unsigned char* Xs = Ws + C::BW * C::RB;
+      const unsigned char* wrow = Ws + (wf * TF * 32 + (lane & 31)) * C::RB;
+      const unsigned char* xrow = Xs + (wt * TT * 32 + (lane & 31)) * C::RB;
+      bf16x8_t af[2][TF], bfr[2][TT];
+      {
+        const int off = (((lane >> 5)) ^ frag_swz) * 16;
+#pragma unroll
+        for (int i = 0; i < TF; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::RB + off);
+#pragma unroll
+        for (int j = 0; j < TT; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::RB + off);
+      }
+#pragma unroll
+      for (int st = 0; st < C::KS; ++st) {
+        if (st + 1 < C::KS) {
+          const int off = (((st + 1) * 2 + (lane >> 5)) ^ frag_swz) * 16;
+#pragma unroll
+          for (int i = 0; i < TF; ++i)
+            af[(st + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::RB + off);
+#pragma unroll
+          for (int j = 0; j < TT; ++j)
+            bfr[(st + 1) & 1][j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::RB + off);
+        }
+        // keep the fragment loads of the next k-step ahead of this k-step's MFMAs
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TF; ++i)
+#pragma unroll
+          for (int j = 0; j < TT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][i], bfr[st & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __syncthreads();  // every wave has left the ring: it now takes the output tile
+    static_assert(MODE != kModeLogits, "the router has its own kernel");
+    store_tile_via_lds<MODE, NWF, NWT, TF, TT>(acc, lds_raw, a, row_lo, n_tok, f0, wf, wt);
+    __syncthreads();  // the next tile's loads overwrite the staged tile
   }
 }
 
@@ -386,6 +671,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
 }
 
 // host-side launcher: picks the kernel for the dtype, sizes a persistent grid.
-int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, hipStream_t stream);
+int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int est_rows_per_group, hipStream_t stream);
 
 }  // namespace semmoe

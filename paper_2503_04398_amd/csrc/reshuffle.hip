@@ -4,6 +4,7 @@
 // 256-token workgroup come from LDS bitmaps (rank = popcount of the key's bits below the token),
 // ranks across workgroups from small exclusive scans; no atomic's ordering reaches an output.
 #include "common.hpp"
+#include "scan_util.hpp"
 
 namespace semmoe {
 
@@ -16,8 +17,9 @@ struct ReshuffleWs {
   int32_t* quota;       // [D]   borderline candidates kept
   int32_t* free_pre;    // [D+1] exclusive prefix of free slots
   int32_t* border_pre;  // [NB][D] borderline candidates of rank r in earlier blocks
-  int32_t* spill_cnt;   // [NB]  -> exclusive prefix after the scan
-  int32_t* rank_hist;   // [NB][D] -> base position after the scan
+  int32_t* spill_cnt;   // [NB]  spilled tokens per block
+  int32_t* rank_hist;   // [NB][D] -> position base inside the rank after the scan
+  int32_t* rank_start;  // [D+1] first position of each rank in the shuffled order
 };
 
 __device__ __forceinline__ int bitmap_rank(const uint32_t* words, int t) {
@@ -74,16 +76,14 @@ __global__ __launch_bounds__(kTokBlock) void rs_pref_kernel(int T, int k, int D,
 }
 
 // K2: thresholds per rank, free-slot prefix, borderline prefix over blocks (one workgroup)
-__global__ __launch_bounds__(1024) void rs_threshold_kernel(int NB, int k, int D, int cap, ReshuffleWs w) {
-  extern __shared__ int32_t tot[];  // D*(k+1) totals, then D free counts
+__global__ __launch_bounds__(kScanThreads) void rs_threshold_kernel(int NB, int k, int D, int cap, ReshuffleWs w) {
+  __shared__ int32_t tot[SEMMOE_MAX_D * (SEMMOE_MAX_K + 1)];
+  __shared__ int32_t free_cnt[SEMMOE_MAX_D + 1];
+  __shared__ int32_t thr_sh[SEMMOE_MAX_D];
+  __shared__ int32_t border_tot[SEMMOE_MAX_D];
+  __shared__ int32_t scratch[kScanThreads];
   const int nkeys = D * (k + 1);
-  int32_t* free_cnt = tot + nkeys;
-  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) {
-    int s = 0;
-    for (int b = 0; b < NB; ++b) s += w.cnt[size_t(b) * nkeys + x];
-    tot[x] = s;
-  }
-  __syncthreads();
+  column_prefix(w.cnt, nkeys, [](int c) { return c; }, nkeys, NB, static_cast<int32_t*>(nullptr), 0, tot, scratch);
   if (threadIdx.x < D) {
     const int r = threadIdx.x;
     // walk the confidence levels from the top: the level at which the candidates overflow `cap` is the
@@ -100,27 +100,17 @@ __global__ __launch_bounds__(1024) void rs_threshold_kernel(int NB, int k, int D
       cum += n;
     }
     w.thr[r] = thr;
+    thr_sh[r] = thr;
     w.quota[r] = quota;
     free_cnt[r] = cap - cum;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int s = 0;
-    for (int r = 0; r < D; ++r) {
-      w.free_pre[r] = s;
-      s += free_cnt[r];
-    }
-    w.free_pre[D] = s;
-  }
-  if (threadIdx.x < D) {
-    const int r = threadIdx.x;
-    const int thr = w.thr[r];
-    int s = 0;
-    for (int b = 0; b < NB; ++b) {
-      w.border_pre[size_t(b) * D + r] = s;
-      if (thr >= 0) s += w.cnt[size_t(b) * nkeys + r * (k + 1) + thr];
-    }
-  }
+  wave_exclusive_scan_lds(free_cnt, D);
+  for (int r = threadIdx.x; r <= D; r += blockDim.x) w.free_pre[r] = free_cnt[r];
+  const int kp1 = k + 1;
+  const int32_t* thr_p = thr_sh;
+  column_prefix(w.cnt, nkeys, [=](int r) { return thr_p[r] >= 0 ? r * kp1 + thr_p[r] : -1; }, D, NB, w.border_pre, D,
+                border_tot, scratch);
 }
 
 // K3: keep phase.  token_rank[i] = pref if kept, -1 if spilled; spill count per block
@@ -161,38 +151,23 @@ __global__ __launch_bounds__(kTokBlock) void rs_keep_kernel(int T, int D, int32_
   if (t == 0) w.spill_cnt[blockIdx.x] = (int32_t)*spill_total;
 }
 
-// generic single-workgroup exclusive scan of n ints in place (n small); total goes to *total if given
-__global__ __launch_bounds__(1024) void rs_scan_kernel(int n, int32_t* __restrict__ v) {
-  __shared__ int32_t part[1024];
-  const int per = (n + 1023) / 1024;
-  const int lo = min((int)threadIdx.x * per, n), hi = min(lo + per, n);
-  int s = 0;
-  for (int x = lo; x < hi; ++x) s += v[x];
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    int add = (threadIdx.x >= off) ? part[threadIdx.x - off] : 0;
-    __syncthreads();
-    part[threadIdx.x] += add;
-    __syncthreads();
-  }
-  int run = part[threadIdx.x] - s;
-  for (int x = lo; x < hi; ++x) {
-    const int c = v[x];
-    v[x] = run;
-    run += c;
-  }
-}
-
 // K5: spilled tokens take the free slots in rank order; per-block histogram of the final ranks
 __global__ __launch_bounds__(kTokBlock) void rs_assign_kernel(int T, int D, int32_t* __restrict__ token_rank,
                                                               ReshuffleWs w) {
-  extern __shared__ uint32_t sm[];  // [kWords] spilled bitmap, [D] rank histogram
+  extern __shared__ uint32_t sm[];  // [kWords] spilled bitmap, [D] rank histogram, [1] spills in earlier blocks
   uint32_t* spbm = sm;
   int32_t* hist = reinterpret_cast<int32_t*>(sm + kWords);
-  for (int x = threadIdx.x; x < kWords + D; x += blockDim.x) sm[x] = 0;
+  int32_t* spill_before = hist + D;
+  for (int x = threadIdx.x; x < kWords + D + 1; x += blockDim.x) sm[x] = 0;
   __syncthreads();
   const int t = threadIdx.x;
+  {  // spilled tokens in blocks before this one
+    int part = 0;
+    for (int b = t; b < (int)blockIdx.x; b += blockDim.x) part += w.spill_cnt[b];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
+    if ((t & 63) == 0 && part) atomicAdd(spill_before, part);
+  }
   const int i = blockIdx.x * kTokBlock + t;
   int rank = -1;
   if (i < T) {
@@ -202,7 +177,7 @@ __global__ __launch_bounds__(kTokBlock) void rs_assign_kernel(int T, int D, int3
   __syncthreads();
   if (i < T) {
     if (rank < 0) {
-      const int s = w.spill_cnt[blockIdx.x] + bitmap_rank(spbm, t);
+      const int s = *spill_before + bitmap_rank(spbm, t);
       int r = 0;
       while (r + 1 < D && w.free_pre[r + 1] <= s) ++r;  // free_pre[r] <= s < free_pre[r+1]
       rank = r;
@@ -214,28 +189,16 @@ __global__ __launch_bounds__(kTokBlock) void rs_assign_kernel(int T, int D, int3
   for (int x = threadIdx.x; x < D; x += blockDim.x) w.rank_hist[size_t(blockIdx.x) * D + x] = hist[x];
 }
 
-// K6: rank_count, and base position of (block, rank) in the shuffled order (one workgroup)
-__global__ __launch_bounds__(64) void rs_rank_scan_kernel(int NB, int D, int32_t* __restrict__ rank_count,
-                                                          ReshuffleWs w) {
-  __shared__ int32_t total[SEMMOE_MAX_D];
-  const int r = threadIdx.x;
-  if (r < D) {
-    int s = 0;
-    for (int b = 0; b < NB; ++b) s += w.rank_hist[size_t(b) * D + r];
-    total[r] = s;
-    rank_count[r] = s;
-  }
+// K6: rank_count, first position of each rank, and position base of (block, rank) inside the rank
+__global__ __launch_bounds__(kScanThreads) void rs_rank_scan_kernel(int NB, int D, int32_t* __restrict__ rank_count,
+                                                                     ReshuffleWs w) {
+  __shared__ int32_t total[SEMMOE_MAX_D + 1];
+  __shared__ int32_t scratch[kScanThreads];
+  column_prefix(w.rank_hist, D, [](int c) { return c; }, D, NB, w.rank_hist, D, total, scratch);
+  for (int r = threadIdx.x; r < D; r += blockDim.x) rank_count[r] = total[r];
   __syncthreads();
-  if (r < D) {
-    int start = 0;
-    for (int x = 0; x < r; ++x) start += total[x];
-    int run = start;
-    for (int b = 0; b < NB; ++b) {
-      const int c = w.rank_hist[size_t(b) * D + r];
-      w.rank_hist[size_t(b) * D + r] = run;
-      run += c;
-    }
-  }
+  wave_exclusive_scan_lds(total, D);
+  for (int r = threadIdx.x; r <= D; r += blockDim.x) w.rank_start[r] = total[r];
 }
 
 // K7: stable scatter: shf (new position -> token) and inv_shf
@@ -254,7 +217,7 @@ __global__ __launch_bounds__(kTokBlock) void rs_scatter_kernel(int T, int D, con
   }
   __syncthreads();
   if (i < T) {
-    const int pos = w.rank_hist[size_t(blockIdx.x) * D + rank] + bitmap_rank(bm + rank * kWords, t);
+    const int pos = w.rank_start[rank] + w.rank_hist[size_t(blockIdx.x) * D + rank] + bitmap_rank(bm + rank * kWords, t);
     inv_shf[i] = pos;
     shf[pos] = i;
   }
@@ -277,14 +240,15 @@ static bool carve_reshuffle(const semmoe_config* cfg, void* ws, size_t bytes, Re
   w->border_pre = c.take<int32_t>(NB * cfg->D);
   w->spill_cnt = c.take<int32_t>(NB);
   w->rank_hist = c.take<int32_t>(NB * cfg->D);
+  w->rank_start = c.take<int32_t>(cfg->D + 1);
   return c.ok;
 }
 
 size_t ws_reshuffle(const semmoe_config* cfg) {
   const size_t NB = cdiv(cfg->T, kTokBlock);
   const size_t nkeys = size_t(cfg->D) * (cfg->k + 1);
-  const size_t counts[8] = {size_t(cfg->T), NB * nkeys, size_t(cfg->D), size_t(cfg->D), size_t(cfg->D) + 1,
-                            NB * cfg->D, NB, NB * cfg->D};
+  const size_t counts[9] = {size_t(cfg->T), NB * nkeys, size_t(cfg->D), size_t(cfg->D), size_t(cfg->D) + 1,
+                            NB * cfg->D, NB, NB * cfg->D, size_t(cfg->D) + 1};
   size_t b = 0;
   for (size_t n : counts) b = align_up(b, 256) + n * 4;
   return b + 256;
@@ -317,11 +281,10 @@ extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, cons
   const int nkeys = D * (k + 1);
   hipLaunchKernelGGL(rs_pref_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, cfg->E, per_home, topk_ids,
                      expert_to_rank, w);
-  hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(1024), (nkeys + D) * 4, s, NB, k, D, cfg->cap, w);
+  hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, k, D, cfg->cap, w);
   hipLaunchKernelGGL(rs_keep_kernel, dim3(NB), dim3(kTokBlock), (D * kWords + 1) * 4, s, T, D, token_rank, w);
-  hipLaunchKernelGGL(rs_scan_kernel, dim3(1), dim3(1024), 0, s, NB, w.spill_cnt);
-  hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D) * 4, s, T, D, token_rank, w);
-  hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(64), 0, s, NB, D, rank_count, w);
+  hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D + 1) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, D, rank_count, w);
   hipLaunchKernelGGL(rs_scatter_kernel, dim3(NB), dim3(kTokBlock), D * kWords * 4, s, T, D, token_rank, shf, inv_shf,
                      w);
   SEMMOE_LAUNCH_CHECK();

@@ -5,8 +5,6 @@
 
 namespace semmoe {
 
-constexpr int kMaxPerLane = SEMMOE_MAX_E / 64;  // experts held by one lane
-
 // Sigmoid as a fixed sequence of individually rounded fp32 operations (no contraction), so that any
 // implementation of the same sequence gives the same bits.
 __device__ __forceinline__ float sigmoid_exact_seq(float x) {
@@ -26,52 +24,51 @@ __device__ __forceinline__ float sigmoid_exact_seq(float x) {
   return __fdiv_rn(1.0f, __fadd_rn(1.0f, z));
 }
 
-struct Best {
-  float v;
-  int e;
-};
+// ---- wave-wide reductions through DPP row shifts / broadcasts (no LDS permutes) ---------------------------
+// After the four row_shr steps lane 15 of every 16-lane row holds the row's result; row_bcast:15 folds row r
+// into row r+1, row_bcast:31 folds rows 0-1 into rows 2-3; lane 63 then holds the result of the wave.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float old, float v) {
+  return __int_as_float(
+      __builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
 
-// (v, e) beats (v2, e2) when v is larger, or equal with the lower index
-__device__ __forceinline__ bool beats(float v, int e, float v2, int e2) { return v > v2 || (v == v2 && e < e2); }
-
-__device__ __forceinline__ Best wave_argmax(Best b) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const float v2 = __shfl_xor(b.v, off);
-    const int e2 = __shfl_xor(b.e, off);
-    if (beats(v2, e2, b.v, b.e)) {
-      b.v = v2;
-      b.e = e2;
-    }
-  }
-  return b;
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_f32<0x111, 0xf>(v, v));  // row_shr:1 (lanes without a source keep their own value)
+  v = fmaxf(v, dpp_f32<0x112, 0xf>(v, v));  // row_shr:2
+  v = fmaxf(v, dpp_f32<0x114, 0xf>(v, v));  // row_shr:4
+  v = fmaxf(v, dpp_f32<0x118, 0xf>(v, v));  // row_shr:8
+  v = fmaxf(v, dpp_f32<0x142, 0xf>(v, v));  // row_bcast:15
+  v = fmaxf(v, dpp_f32<0x143, 0xf>(v, v));  // row_bcast:31
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
+  v += dpp_f32<0x111, 0xf>(0.0f, v);
+  v += dpp_f32<0x112, 0xf>(0.0f, v);
+  v += dpp_f32<0x114, 0xf>(0.0f, v);
+  v += dpp_f32<0x118, 0xf>(0.0f, v);
+  v += dpp_f32<0x142, 0xa>(0.0f, v);  // rows 1 and 3 take the sum of the row before
+  v += dpp_f32<0x143, 0xc>(0.0f, v);  // rows 2 and 3 take the sum of rows 0-1
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 constexpr int kNoExpert = 0x7fffffff;
 
-// One wavefront per token.  Lane l holds experts l, l+64, l+128, ...
-__global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, const float* __restrict__ logits,
-                                                          const float* __restrict__ sel_bias,
-                                                          int32_t* __restrict__ topk_ids,
-                                                          float* __restrict__ topk_w) {
-  const int lane = threadIdx.x & 63;
-  const int token = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (token >= cfg.T) return;  // whole wave leaves together
+// Selection for one token by one wavefront.  `row` points at the token's E fp32 logits (global or LDS).
+// Lane l holds experts l, l+64, l+128, ...
+template <int NC>
+__device__ __forceinline__ void select_row_nc(const semmoe_config& cfg, const float* row,
+                                              const float* __restrict__ sel_bias, int lane,
+                                              int32_t* __restrict__ ids_out, float* __restrict__ w_out) {
   const int E = cfg.E, k = cfg.k;
-  const float* row = logits + size_t(token) * E;
   const float NEG = -__builtin_inff();
 
-  float val[kMaxPerLane];  // selection score (logit, or s' in sigmoid mode)
-  float aux[kMaxPerLane];  // softmax: logit; sigmoid: s
+  float val[NC];  // selection score (logit, or s' in sigmoid mode)
+  float aux[NC];  // softmax: logit; sigmoid: s
   uint32_t live = 0;       // bit c: entry c may still be selected
 #pragma unroll
-  for (int c = 0; c < kMaxPerLane; ++c) {
+  for (int c = 0; c < NC; ++c) {
     const int e = lane + 64 * c;
     val[c] = NEG;
     aux[c] = 0.0f;
@@ -89,18 +86,27 @@ __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, con
     }
   }
 
-  auto local_best = [&](uint32_t mask) {
-    Best b{NEG, kNoExpert};
+  // arg-max over the entries whose bit is set in `mask`: largest value, equal values -> lowest expert id.
+  // Expert id = lane + 64*c, so among equal values the lowest slot c wins, then the lowest lane.
+  auto wave_argmax = [&](uint32_t mask, float* vmax) -> int {
+    float m = NEG;
 #pragma unroll
-    for (int c = 0; c < kMaxPerLane; ++c)
-      if ((mask >> c) & 1u) {
-        const int e = lane + 64 * c;
-        if (b.e == kNoExpert || beats(val[c], e, b.v, b.e)) {
-          b.v = val[c];
-          b.e = e;
-        }
-      }
-    return b;
+    for (int c = 0; c < NC; ++c)
+      if ((mask >> c) & 1u) m = fmaxf(m, val[c]);
+    const unsigned long long any = __ballot(mask != 0);
+    if (any == 0ull) {
+      *vmax = NEG;
+      return kNoExpert;
+    }
+    const float wm = wave_max(m);
+    *vmax = wm;
+    int e = kNoExpert;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const unsigned long long hit = __ballot(((mask >> c) & 1u) && val[c] == wm);
+      if (e == kNoExpert && hit != 0ull) e = (__ffsll((long long)hit) - 1) + 64 * c;
+    }
+    return e;
   };
 
   if (cfg.score == SEMMOE_SIGMOID && cfg.n_group > 1) {
@@ -110,27 +116,31 @@ __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, con
     for (int g = 0; g < cfg.n_group; ++g) {
       uint32_t in_g = 0;
 #pragma unroll
-      for (int c = 0; c < kMaxPerLane; ++c) {
+      for (int c = 0; c < NC; ++c) {
         const int e = lane + 64 * c;
         if (e < E && e / gs == g) in_g |= 1u << c;
       }
-      const Best b1 = wave_argmax(local_best(in_g));
-      if (b1.e != kNoExpert && (b1.e & 63) == lane) in_g &= ~(1u << (b1.e >> 6));
-      const Best b2 = wave_argmax(local_best(in_g));
-      const float sc = (b2.e == kNoExpert) ? b1.v : __fadd_rn(b1.v, b2.v);
+      float v1, v2;
+      const int e1 = wave_argmax(in_g, &v1);
+      if (e1 != kNoExpert && (e1 & 63) == lane) in_g &= ~(1u << (e1 >> 6));
+      const int e2 = wave_argmax(in_g, &v2);
+      const float sc = (e2 == kNoExpert) ? v1 : __fadd_rn(v1, v2);
       if (lane == g) my_gscore = sc;
     }
-    uint64_t keep = 0;
+    // the topk_group best groups: lanes hold one group score each (slot 0 only)
+    unsigned long long keep = 0;
     bool taken = false;
     for (int r = 0; r < cfg.topk_group; ++r) {
-      Best b{(lane < cfg.n_group && !taken) ? my_gscore : NEG, (lane < cfg.n_group && !taken) ? lane : kNoExpert};
-      b = wave_argmax(b);
-      keep |= 1ull << b.e;
-      if (lane == b.e) taken = true;
+      const bool cand = lane < cfg.n_group && !taken;
+      const float wm = wave_max(cand ? my_gscore : NEG);
+      const unsigned long long hit = __ballot(cand && my_gscore == wm);
+      const int g = __ffsll((long long)hit) - 1;
+      keep |= 1ull << g;
+      if (lane == g) taken = true;
     }
     uint32_t allowed = 0;
 #pragma unroll
-    for (int c = 0; c < kMaxPerLane; ++c) {
+    for (int c = 0; c < NC; ++c) {
       const int e = lane + 64 * c;
       if (e < E && ((keep >> (e / gs)) & 1ull)) allowed |= 1u << c;
     }
@@ -141,26 +151,27 @@ __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, con
   int my_id = 0;
   float my_val = 0.0f;  // softmax: winning logit; sigmoid: s of the winner
   for (int j = 0; j < k; ++j) {
-    const Best b = wave_argmax(local_best(live));
-    const int owner = b.e & 63, slot = b.e >> 6;
+    float vm;
+    const int e = wave_argmax(live, &vm);
+    const int owner = e & 63, slot = e >> 6;
     float a = 0.0f;
 #pragma unroll
-    for (int c = 0; c < kMaxPerLane; ++c)
+    for (int c = 0; c < NC; ++c)
       if (c == slot) a = aux[c];
-    a = __shfl(a, owner);
+    a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), owner));
     if (lane == owner) live &= ~(1u << slot);
     if (lane == j) {
-      my_id = b.e;
+      my_id = e;
       my_val = a;
     }
   }
 
   float w;
   if (cfg.score == SEMMOE_SOFTMAX) {
-    const float mx = __shfl(my_val, 0);  // the first winner is the row maximum
+    const float mx = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val), 0));  // first winner = row max
     float part = 0.0f;
 #pragma unroll
-    for (int c = 0; c < kMaxPerLane; ++c)
+    for (int c = 0; c < NC; ++c)
       if (lane + 64 * c < E) part += expf(aux[c] - mx);
     const float denom = wave_sum(part);
     w = (lane < k) ? expf(my_val - mx) / denom : 0.0f;
@@ -171,8 +182,172 @@ __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, con
     w *= cfg.routed_scale;
   }
   if (lane < k) {
-    topk_ids[size_t(token) * k + lane] = my_id;
-    topk_w[size_t(token) * k + lane] = w;
+    ids_out[lane] = my_id;
+    w_out[lane] = w;
+  }
+}
+
+// NC = experts per lane, chosen from E so that the unrolled loops carry no dead slots
+__device__ __forceinline__ void select_row(const semmoe_config& cfg, const float* row, const float* __restrict__ sel_bias,
+                                           int lane, int32_t* __restrict__ ids_out, float* __restrict__ w_out) {
+  if (cfg.E <= 64) select_row_nc<1>(cfg, row, sel_bias, lane, ids_out, w_out);
+  else if (cfg.E <= 128) select_row_nc<2>(cfg, row, sel_bias, lane, ids_out, w_out);
+  else if (cfg.E <= 256) select_row_nc<4>(cfg, row, sel_bias, lane, ids_out, w_out);
+  else select_row_nc<8>(cfg, row, sel_bias, lane, ids_out, w_out);
+}
+
+__global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, const float* __restrict__ logits,
+                                                          const float* __restrict__ sel_bias,
+                                                          int32_t* __restrict__ topk_ids,
+                                                          float* __restrict__ topk_w) {
+  const int lane = threadIdx.x & 63;
+  const int token = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (token >= cfg.T) return;  // whole wave leaves together
+  select_row(cfg, logits + size_t(token) * cfg.E, sel_bias, lane, topk_ids + size_t(token) * cfg.k,
+             topk_w + size_t(token) * cfg.k);
+}
+
+// Fused router for bf16: logits of TT*32 tokens x all experts, then the selection, in one kernel.
+//   X and W_r slices of 64 K-elements are brought into an NSTAGE ring in LDS by direct global->LDS loads
+//   (each wave instruction moves 8 rows x 128 contiguous bytes), chunk-swizzled as in the grouped GEMM.
+//   4 waves; wave w owns expert tiles w*TF .. w*TF+TF-1 (32 experts each) for all TT token tiles.
+//   MFMA A operand = W_r rows (experts), B operand = X rows (tokens): a lane ends with 4 consecutive experts
+//   of one token per register group.  After the K loop the fp32 logits (+ bias terms) are parked in LDS and
+//   each wave selects for its share of the tokens.
+template <int TF, int TT, int NSTAGE>
+struct RouteCfg {
+  static constexpr int BW = 4 * TF * 32;   // expert rows per stage
+  static constexpr int BT = TT * 32;       // token rows per stage
+  static constexpr int ROWS = BW + BT;
+  static constexpr int BK = 64, RB = 128, CPR = 8, RPI = 8, RPB = 2;
+  static constexpr int IPS = ROWS / RPI;   // wave instructions per stage
+  static constexpr int IPW = IPS / 4;
+  static constexpr int kStageBytes = ROWS * RB;
+  static_assert(IPS % 4 == 0, "instructions divide over the waves");
+  static_assert((NSTAGE - 1) * IPW < 64, "vmcnt range");
+};
+
+template <int TF, int TT, int NSTAGE>
+__global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, const bf16_t* __restrict__ X,
+                                                          const bf16_t* __restrict__ W_r,
+                                                          const float* __restrict__ b_g,
+                                                          const int32_t* __restrict__ token_class,
+                                                          const float* __restrict__ class_bias,
+                                                          const float* __restrict__ sel_bias,
+                                                          float* __restrict__ logits_out,
+                                                          int32_t* __restrict__ topk_ids,
+                                                          float* __restrict__ topk_w) {
+  using C = RouteCfg<TF, TT, NSTAGE>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
+  float* lg = reinterpret_cast<float*>(lds_raw);  // [BT][E + 4] after the K loop
+  const int T = cfg.T, E = cfg.E, K = cfg.d;
+  const int ldl = E + 4;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lrow = lane & 31, half = lane >> 5;
+  const int nk = (K + C::BK - 1) / C::BK;
+  const int k_tail = K - (nk - 1) * C::BK;
+  const int frag_swz = (lrow / C::RPB) % C::CPR;
+  const int d_row = lane / C::CPR, d_pos = lane % C::CPR;
+  const int n_tiles = (T + C::BT - 1) / C::BT;
+
+  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int tok0 = tile * C::BT;
+    const bf16_t* src[C::IPW];
+    int src_chunk[C::IPW];
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i) {
+      const int sr = (wave * C::IPW + i) * C::RPI + d_row;
+      const int c = d_pos ^ ((sr / C::RPB) % C::CPR);
+      src_chunk[i] = c;
+      src[i] = (sr < C::BW) ? W_r + size_t(min(sr, E - 1)) * K + c * 8
+                            : X + size_t(min(tok0 + sr - C::BW, T - 1)) * K + c * 8;
+    }
+    auto issue = [&](int slice) {
+      const unsigned dst0 = lds_base + (slice % NSTAGE) * C::kStageBytes + wave * C::IPW * 1024;
+      const int k0 = slice * C::BK;
+      if (slice + 1 < nk || k_tail == C::BK) {
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i) lds_dma16(src[i] + k0, dst0 + i * 1024);
+      } else {
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i) {
+          if (src_chunk[i] * 8 < k_tail) lds_dma16(src[i] + k0, dst0 + i * 1024);
+          else *reinterpret_cast<uint4*>(lds_raw + (dst0 - lds_base) + i * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+        }
+      }
+    };
+
+    f32x16_t acc[TF][TT];
+#pragma unroll
+    for (int i = 0; i < TF; ++i)
+#pragma unroll
+      for (int j = 0; j < TT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+#pragma unroll
+    for (int s0 = 0; s0 < NSTAGE - 1; ++s0)
+      if (s0 < nk) issue(s0);
+    for (int it = 0; it < nk; ++it) {
+      const int younger = min(NSTAGE - 2, nk - 1 - it);
+      if (younger >= 4) wait_vmcnt<4 * C::IPW>();
+      else if (younger == 3) wait_vmcnt<3 * C::IPW>();
+      else if (younger == 2) wait_vmcnt<2 * C::IPW>();
+      else if (younger == 1) wait_vmcnt<1 * C::IPW>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+      if (it + NSTAGE - 1 < nk) issue(it + NSTAGE - 1);
+      const unsigned char* Ws = lds_raw + (it % NSTAGE) * C::kStageBytes;
+      const unsigned char* Xs = Ws + C::BW * C::RB;
+      const unsigned char* wrow = Ws + (wave * TF * 32 + lrow) * C::RB;
+      const unsigned char* xrow = Xs + lrow * C::RB;
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        const int off = ((st * 2 + half) ^ frag_swz) * 16;
+        bf16x8_t af[TF], bfr[TT];
+#pragma unroll
+        for (int i = 0; i < TF; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::RB + off);
+#pragma unroll
+        for (int j = 0; j < TT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::RB + off);
+#pragma unroll
+        for (int i = 0; i < TF; ++i)
+#pragma unroll
+          for (int j = 0; j < TT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    __syncthreads();  // every wave is done with the ring: its first bytes now hold the logits
+
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+      const int tl = j * 32 + lrow;
+      const int tok = tok0 + tl;
+      const int cls = (token_class && tok < T) ? token_class[tok] : -1;
+      const float* cb = (cls >= 0 && cls < cfg.num_classes && class_bias) ? class_bias + size_t(cls) * E : nullptr;
+#pragma unroll
+      for (int i = 0; i < TF; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int e = (wave * TF + i) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          if (e < E) {
+            float v = acc[i][j][r];
+            if (b_g) v += b_g[e];
+            if (cb) v += cb[e];
+            lg[tl * ldl + e] = v;
+            if (logits_out && tok < T) logits_out[size_t(tok) * E + e] = v;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    for (int tl = wave; tl < C::BT; tl += 4) {
+      const int tok = tok0 + tl;
+      if (tok < T)
+        select_row(cfg, lg + tl * ldl, sel_bias, lane, topk_ids + size_t(tok) * cfg.k, topk_w + size_t(tok) * cfg.k);
+    }
+    __syncthreads();  // the next tile's loads overwrite the logits
   }
 }
 
@@ -223,13 +398,51 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
   if ((token_class == nullptr) != (class_bias == nullptr)) return SEMMOE_EINVAL;
   if (token_class && cfg->num_classes <= 0) return SEMMOE_EINVAL;
   if (!aligned16(X) || !aligned16(W_r)) return SEMMOE_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (cfg->T == 0) return SEMMOE_OK;
+  if (cfg->dtype == SEMMOE_BF16) {
+    // fused MFMA router: tokens per workgroup = 64 when that still fills the chip, else 32
+    const bf16_t* Xb = static_cast<const bf16_t*>(X);
+    const bf16_t* Wb = static_cast<const bf16_t*>(W_r);
+    const int tf = cfg->E <= 128 ? 1 : (cfg->E <= 256 ? 2 : 4);
+    const bool wide = cdiv(cfg->T, 64) >= 256 && tf <= 2;
+    const int bt = wide ? 64 : 32;
+    int dev = 0, ncu = 256;
+    SEMMOE_HIP(hipGetDevice(&dev));
+    SEMMOE_HIP(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    const int n_tiles = cdiv(cfg->T, bt);
+#define SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_)                                                                          \
+  do {                                                                                                              \
+    using RC = RouteCfg<TF_, TT_, NS_>;                                                                             \
+    size_t lds = size_t(NS_) * RC::kStageBytes;                                                                     \
+    const size_t lg_bytes = size_t(RC::BT) * (cfg->E + 4) * 4;                                                      \
+    if (lg_bytes > lds) lds = lg_bytes;                                                                             \
+    const int per_cu = lds <= 80 * 1024 ? 2 : 1;                                                                    \
+    const int grid = n_tiles < ncu * per_cu ? n_tiles : ncu * per_cu;                                               \
+    if (lds > 48 * 1024)                                                                                            \
+      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_fused_kernel<TF_, TT_, NS_>),              \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));                        \
+    hipLaunchKernelGGL((route_fused_kernel<TF_, TT_, NS_>), dim3(grid), dim3(256), lds, s, *cfg, Xb, Wb, b_g,       \
+                       token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                            \
+  } while (0)
+    if (tf == 1) {
+      if (wide) SEMMOE_ROUTE_LAUNCH(1, 2, 5); else SEMMOE_ROUTE_LAUNCH(1, 1, 6);
+    } else if (tf == 2) {
+      if (wide) SEMMOE_ROUTE_LAUNCH(2, 2, 3); else SEMMOE_ROUTE_LAUNCH(2, 1, 4);
+    } else {
+      SEMMOE_ROUTE_LAUNCH(4, 1, 2);
+    }
+#undef SEMMOE_ROUTE_LAUNCH
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  // fp32: tiled FMA GEMM into the logits buffer, then the selection kernel
   float* logits = logits_out;
   if (!logits) {
     Carver c(ws, ws_bytes);
     logits = c.take<float>(size_t(cfg->T) * cfg->E);
     if (!c.ok) return SEMMOE_EWORKSPACE;
   }
-  hipStream_t s = static_cast<hipStream_t>(stream);
   GemmArgs a{};
   a.X = X; a.ldx = cfg->d;
   a.W = W_r; a.w_group_stride = 0; a.ldw = cfg->d;
@@ -238,7 +451,7 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
   a.group_to_weight = nullptr;
   a.out = logits; a.ldo = cfg->E;
   a.b_g = b_g; a.token_class = token_class; a.class_bias = class_bias; a.n_classes = cfg->num_classes;
-  st = launch_gemm(kModeLogits, cfg->dtype, a, cfg->T, s);
+  st = launch_gemm(kModeLogits, cfg->dtype, a, cfg->T, cfg->T, s);
   if (st != SEMMOE_OK) return st;
   return launch_select(cfg, s, logits, sel_bias, topk_ids, topk_w);
 }

@@ -323,3 +323,22 @@ def test_empty_and_degenerate_inputs():
     dw = O.dispatch(WL.hidden(w), ids, want[0], want[2], phys, 2)
     Yo = O.expert_ffn(dw["X_perm"], dw["expert_offsets"], inv, lambda e: weights[e], 2)
     H.assert_close(Y, Yo, "bf16", "Y")
+
+
+@pytest.mark.parametrize("tile", [0, 3, 4, 6, 11, 12, 14, 15, 16, 17, 18])
+def test_every_gemm_tile_shape_on_a_ragged_problem(tile):
+    """each tile shape of the bf16 grouped GEMMs (register-staged, direct-to-LDS ring, skinny), with ragged
+    groups, partial K slices (d % 64 = 8, F % 32 = 8) and partial feature tiles"""
+    _say("gemm tile", tile)
+    w = WL.small(T=700, d=200, E=8, k=2, F=72, D=2, dtype="bf16", C=2)
+    m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
+    try:
+        m.set_tuning(0, tile)
+        m.set_tuning(1, tile)
+        lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, rank=-1)
+        H.assert_close(Y, Yo, "bf16", "Y")
+        out = lay.combine()
+        H.assert_close(out, O.moe_definition(inp.X, ids, want_w, lambda e: weights[e]), "bf16", "Out")
+    finally:
+        m.set_tuning(0, -1)
+        m.set_tuning(1, -1)
