@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=8192)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--all-ranks", action="store_true", help="FFN over every rank's experts instead of rank 0")
+    ap.add_argument("--device-weights", action="store_true",
+                    help="draw the expert weights on the device (seeded torch generator) instead of the numpy "
+                         "generator: for quick looks at the big workloads; the CPU baseline is then skipped")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a one-GPU hot path (logical ranks are simulated on one device); "
@@ -97,10 +100,18 @@ def main():
     cb = up(WL.class_bias(w))
     W_gu = torch.empty(E, 2 * F, d, dtype=adt, device=dev)
     W_down = torch.empty(E, d, F, dtype=adt, device=dev)
-    for e in range(E):
-        wgu, wdn = WL.expert_weight(w, e)
-        W_gu[e].copy_(up(wgu, True))
-        W_down[e].copy_(up(wdn, True))
+    if args.device_weights:
+        g = torch.Generator(device=dev)
+        g.manual_seed(w.seed + 17)
+        for e in range(E):
+            W_gu[e].copy_((torch.randn(2 * F, d, generator=g, device=dev) * w.weight_std).to(adt))
+            W_down[e].copy_((torch.randn(d, F, generator=g, device=dev) * w.weight_std).to(adt))
+        args.no_cpu = True
+    else:
+        for e in range(E):
+            wgu, wdn = WL.expert_weight(w, e)
+            W_gu[e].copy_(up(wgu, True))
+            W_down[e].copy_(up(wdn, True))
     m = S.SemMoE(S.Config.from_workload(w), device=dev)
     i32 = dict(dtype=torch.int32, device=dev)
     ids = torch.empty(T, k, **i32)

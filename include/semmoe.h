@@ -73,10 +73,13 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *   SEMMOE_TUNE_GATEUP_TILE / SEMMOE_TUNE_DOWN_TILE: tile-shape id of the bf16 grouped GEMMs
  *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny tiles for decode)
  *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs
+ *   SEMMOE_TUNE_INDEX_PATH: which implementation of the index kernels runs (default: single workgroup for
+ *     T <= 2048, several workgroups above; the single-workgroup kernels hold at most T = 32768); both give identical results
  */
 #define SEMMOE_TUNE_GATEUP_TILE 0
 #define SEMMOE_TUNE_DOWN_TILE 1
 #define SEMMOE_TUNE_BLOCKS_PER_CU 2
+#define SEMMOE_TUNE_INDEX_PATH 3 /* reshuffle / dispatch index: 1 = multi-workgroup kernels, 2 = single workgroup */
 int32_t semmoe_set_tuning(int32_t key, int32_t value);
 
 /*

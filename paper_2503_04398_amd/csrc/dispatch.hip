@@ -141,6 +141,125 @@ __global__ __launch_bounds__(kTokBlock) void dp_slot_kernel(int T, int k, int E,
   }
 }
 
+// Single-workgroup variant of the index half for T <= kSingleMaxT (one launch instead of three; small
+// kernels cost a fixed few microseconds each).  Positions are walked in chunks of 1024 in shuffled order.
+constexpr int kSingleMaxT = 32768;  // what the single-workgroup kernel can hold
+constexpr int kSingleAutoT = 2048;  // up to here it is also the faster choice (measured: one CU is slow beyond)
+constexpr int kChunk = 1024;
+
+__global__ __launch_bounds__(kChunk) void dp_single_kernel(int T, int k, int E, int D,
+                                                           const int32_t* __restrict__ ids,
+                                                           const int32_t* __restrict__ token_rank,
+                                                           const int32_t* __restrict__ shf,
+                                                           const int32_t* __restrict__ phys,
+                                                           int32_t* __restrict__ slot_of_pair,
+                                                           int32_t* __restrict__ pair_of_slot,
+                                                           int32_t* __restrict__ expert_offsets,
+                                                           int32_t* __restrict__ rank_offsets,
+                                                           uint32_t* __restrict__ send_matrix,
+                                                           unsigned long long* __restrict__ remote_pairs) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  // layout: off[E+1] | run[E] | ktot[E] | send[D*D] | bm[E][32] | wpre[E][32] | remote (u64)
+  int32_t* off = reinterpret_cast<int32_t*>(lds_raw);
+  int32_t* run = off + (E + 1);
+  int32_t* ktot = run + E;
+  uint32_t* send = reinterpret_cast<uint32_t*>(ktot + E);
+  uint32_t* bm = send + D * D;
+  int32_t* wpre = reinterpret_cast<int32_t*>(bm + E * 32);
+  unsigned long long* remote_sh = reinterpret_cast<unsigned long long*>(
+      (reinterpret_cast<uintptr_t>(wpre + E * 32) + 7) & ~uintptr_t(7));
+  const int t = threadIdx.x;
+  const int m = E / D;
+  for (int x = t; x <= E; x += kChunk) off[x] = 0;
+  for (int x = t; x < E; x += kChunk) run[x] = 0;
+  for (int x = t; x < D * D; x += kChunk) send[x] = 0;
+  if (t == 0) *remote_sh = 0ull;
+  __syncthreads();
+  // pair counts per physical expert and the send matrix
+  for (int pos = t; pos < T; pos += kChunk) {
+    const int tok = shf[pos];
+    if ((unsigned)tok >= (unsigned)T) continue;
+    const int s = token_rank[tok];
+    for (int j = 0; j < k; ++j) {
+      const int e = ids[size_t(tok) * k + j];
+      if ((unsigned)e >= (unsigned)E) continue;
+      const int q = phys[e];
+      if ((unsigned)q >= (unsigned)E) continue;
+      atomicAdd(&off[q], 1);
+      if ((unsigned)s < (unsigned)D) atomicAdd(&send[s * D + q / m], 1u);
+    }
+  }
+  __syncthreads();
+  wave_exclusive_scan_lds(off, E);
+  for (int q = t; q <= E; q += kChunk) {
+    expert_offsets[q] = off[q];
+    if (q % m == 0) rank_offsets[q / m] = off[q];
+  }
+  unsigned long long remote = 0;
+  for (int x = t; x < D * D; x += kChunk) {
+    send_matrix[x] = send[x];
+    if (x / D != x % D) remote += send[x];
+  }
+  if (remote) atomicAdd(remote_sh, remote);
+  __syncthreads();
+  if (t == 0) *remote_pairs = *remote_sh;
+
+  const int hw = t >> 5, w = t & 31;
+  for (int c0 = 0; c0 < T; c0 += kChunk) {
+    for (int x = t; x < E * 32; x += kChunk) bm[x] = 0;
+    __syncthreads();
+    const int pos = c0 + t;
+    int tok = -1;
+    if (pos < T) {
+      tok = shf[pos];
+      if ((unsigned)tok >= (unsigned)T) tok = -1;
+    }
+    int q[SEMMOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      q[j] = -1;
+      if (j < k && tok >= 0) {
+        const int e = ids[size_t(tok) * k + j];
+        if ((unsigned)e < (unsigned)E) {
+          const int qq = phys[e];
+          if ((unsigned)qq < (unsigned)E) {
+            q[j] = qq;
+            atomicOr(&bm[qq * 32 + (t >> 5)], 1u << (t & 31));
+          }
+        }
+      }
+    }
+    __syncthreads();
+    for (int key = hw; key < E; key += kChunk / 32) {  // 32-word popcount prefix per expert, one half-wave each
+      const int v = __popc(bm[key * 32 + w]);
+      int incl = v;
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {
+        const int u = __shfl_up(incl, o, 32);
+        if (w >= o) incl += u;
+      }
+      wpre[key * 32 + w] = incl - v;
+      if (w == 31) ktot[key] = incl;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      if (q[j] < 0) continue;
+      const int slot = off[q[j]] + run[q[j]] + wpre[q[j] * 32 + (t >> 5)] +
+                       __popc(bm[q[j] * 32 + (t >> 5)] & ((1u << (t & 31)) - 1u));
+      const int pair = tok * k + j;
+      slot_of_pair[pair] = slot;
+      pair_of_slot[slot] = pair;
+    }
+    __syncthreads();
+    for (int x = t; x < E; x += kChunk) run[x] += ktot[x];
+  }
+}
+
+static size_t dp_single_lds(int E, int D) {
+  return size_t(E + 1 + E + E) * 4 + size_t(D) * D * 4 + size_t(E) * 32 * 4 * 2 + 16 + 8;
+}
+
 // D4: move rows.  One workgroup per token; each thread owns 16-byte chunks of the row.
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -196,6 +315,18 @@ static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, cons
   if (!carve_dispatch(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
   const int T = cfg->T, k = cfg->k, E = cfg->E, D = cfg->D;
   const int NB = cdiv(T, kTokBlock);
+  const int path = tuning_value(SEMMOE_TUNE_INDEX_PATH);
+  if ((path != 1 && T <= kSingleAutoT) || path == 2) {
+    if (T > kSingleMaxT) return SEMMOE_EUNSUPPORTED;
+    const size_t lds = dp_single_lds(E, D);
+    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(dp_single_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+    hipLaunchKernelGGL(dp_single_kernel, dim3(1), dim3(kChunk), lds, s, T, k, E, D, topk_ids, token_rank, shf,
+                       phys_of_expert, slot_of_pair, pair_of_slot, expert_offsets, rank_offsets, send_matrix,
+                       reinterpret_cast<unsigned long long*>(remote_pairs));
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
   if (NB > 0) {
     hipLaunchKernelGGL(dp_count_kernel, dim3(NB), dim3(kTokBlock), (E * kWords + D * D) * 4, s, T, k, E, D, topk_ids,
                        token_rank, shf, phys_of_expert, w);

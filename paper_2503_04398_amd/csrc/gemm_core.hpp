@@ -470,22 +470,19 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(Gem
       }
     }
 
-    auto issue_to = [&](int slice, int it_) {  // K slice `slice` goes to the ring stage of iteration it_
-      const unsigned dst0 = lds_base + (it_ % NSTAGE) * C::kStageBytes + wave * C::IPW * 1024;
+    // instruction i (of the wave's IPW) of the load of K slice `slice` into the ring stage of iteration it_
+    auto issue_one = [&](int slice, int it_, int i) {
+      const unsigned dst = lds_base + (it_ % NSTAGE) * C::kStageBytes + (wave * C::IPW + i) * 1024;
       const int k0 = slice * BK;
-      if (slice + 1 < nk || k_tail == BK) {
-#pragma unroll
-        for (int i = 0; i < C::IPW; ++i) lds_dma16(src[i] + k0, dst0 + i * 1024);
+      if (slice + 1 < nk || k_tail == BK || src_chunk[i] * 8 < k_tail) {
+        lds_dma16(src[i] + k0, dst);
       } else {  // partial last slice: chunks past K are zero-filled by a plain LDS store
-#pragma unroll
-        for (int i = 0; i < C::IPW; ++i) {
-          if (src_chunk[i] * 8 < k_tail) {
-            lds_dma16(src[i] + k0, dst0 + i * 1024);
-          } else {
-            *reinterpret_cast<uint4*>(lds_raw + (dst0 - lds_base) + i * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
-          }
-        }
+        *reinterpret_cast<uint4*>(lds_raw + (dst - lds_base) + lane * 16) = make_uint4(0, 0, 0, 0);
       }
+    };
+    auto issue_to = [&](int slice, int it_) {
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i) issue_one(slice, it_, i);
     };
 
     f32x16_t acc[TF][TT];
@@ -508,7 +505,9 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(Gem
       else if (younger == 1) wait_vmcnt<1 * C::IPW>();
       else wait_vmcnt<0>();
       __syncthreads();  // slice `it` is complete in LDS; every wave is done with slice it-1
-      if (it + NSTAGE - 1 < nk) issue_to(it + NSTAGE - 1, it + NSTAGE - 1);  // refills the stage of slice it-1
+      // refill the stage slice it-1 lived in.  All loads of the slice are issued at once, as early as possible:
+      // spreading them over the k-steps was measured slower (the lead over the next barrier is what counts)
+      if (it + NSTAGE - 1 < nk) issue_to(it + NSTAGE - 1, it + NSTAGE - 1);
       const unsigned char* Ws = lds_raw + (it % NSTAGE) * C::kStageBytes;
       const unsigned char* Xs = Ws + C::BW * C::RB;
       const unsigned char* wrow = Ws + (wf * TF * 32 + (lane & 31)) * C::RB;

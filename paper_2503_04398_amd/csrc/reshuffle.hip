@@ -223,6 +223,193 @@ __global__ __launch_bounds__(kTokBlock) void rs_scatter_kernel(int T, int D, con
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Single-workgroup variant for T <= kSingleMaxT: the whole of rebatch_tokens in one launch, every
+// intermediate in LDS.  Tokens are walked in chunks of 1024 (one per thread) in index order; inside a chunk
+// the stable rank of a token among equal keys is again "popcount of the key's bitmap below the token",
+// with a 32-word prefix per key computed by half-waves; across chunks a running count per key.
+// Small kernels here cost a fixed few microseconds each, so for small batches one launch beats seven.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSingleMaxT = 32768;  // what the single-workgroup kernel can hold
+constexpr int kSingleAutoT = 2048;  // up to here it is also the faster choice (measured: one CU is slow beyond)
+constexpr int kChunk = 1024;
+
+struct SingleLds {
+  uint16_t pc[kSingleMaxT];                 // pref | conf << 8
+  uint8_t tr[kSingleMaxT];                  // rank of the token, 0xFF while spilled
+  uint32_t bm[SEMMOE_MAX_D + 1][32];        // chunk bitmaps per key (last row: spilled tokens)
+  int32_t wpre[SEMMOE_MAX_D + 1][32];       // exclusive popcount prefix over the 32 words of a key
+  int32_t ktot[SEMMOE_MAX_D + 1];           // tokens of the key in the chunk
+  int32_t hist[SEMMOE_MAX_D * (SEMMOE_MAX_K + 1)];
+  int32_t thr[SEMMOE_MAX_D], quota[SEMMOE_MAX_D], free_pre[SEMMOE_MAX_D + 1];
+  int32_t border_run[SEMMOE_MAX_D], rank_cnt[SEMMOE_MAX_D + 1], rank_run[SEMMOE_MAX_D];
+  int32_t spill_run, any_border, any_spill;
+};
+
+// bitmaps of keys [key_lo, key_hi) are set: per key the exclusive prefix of word popcounts and the key total.
+// Half-wave h of the workgroup handles keys key_lo + h, key_lo + h + 32, ...  Ends with a barrier.
+__device__ __forceinline__ void chunk_word_prefix(SingleLds& L, int key_lo, int key_hi) {
+  const int hw = threadIdx.x >> 5, w = threadIdx.x & 31;
+  for (int key = key_lo + hw; key < key_hi; key += kChunk / 32) {
+    const int v = __popc(L.bm[key][w]);
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) {
+      const int t = __shfl_up(incl, off, 32);
+      if (w >= off) incl += t;
+    }
+    L.wpre[key][w] = incl - v;
+    if (w == 31) L.ktot[key] = incl;
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ int chunk_rank(const SingleLds& L, int key, int t) {
+  return L.wpre[key][t >> 5] + __popc(L.bm[key][t >> 5] & ((1u << (t & 31)) - 1u));
+}
+
+__global__ __launch_bounds__(kChunk) void rs_single_kernel(int T, int k, int D, int E, int cap, int per_home,
+                                                           const int32_t* __restrict__ ids,
+                                                           const int32_t* __restrict__ e2r,
+                                                           int32_t* __restrict__ token_rank,
+                                                           int32_t* __restrict__ shf, int32_t* __restrict__ inv_shf,
+                                                           int32_t* __restrict__ rank_count) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  SingleLds& L = *reinterpret_cast<SingleLds*>(lds_raw);
+  const int t = threadIdx.x;
+  const int nkeys = D * (k + 1);
+  for (int x = t; x < nkeys; x += kChunk) L.hist[x] = 0;
+  if (t <= D) L.rank_cnt[t] = 0;
+  if (t < D) { L.border_run[t] = 0; L.rank_run[t] = 0; }
+  if (t == 0) { L.spill_run = 0; L.any_border = 0; L.any_spill = 0; }
+  __syncthreads();
+
+  // pref / conf per token and the (pref, conf) histogram
+  for (int i = t; i < T; i += kChunk) {
+    int r[SEMMOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      r[j] = -1;
+      if (j < k) {
+        const int e = ids[size_t(i) * k + j];
+        if ((unsigned)e < (unsigned)E) {
+          const int rr = e2r[e];
+          if ((unsigned)rr < (unsigned)D) r[j] = rr;
+        }
+      }
+    }
+    const int home = i / per_home;
+    int best_r = home, best_c = 0;
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) best_c += (r[j] == home);
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      if (r[j] < 0) continue;
+      int c = 0;
+#pragma unroll
+      for (int j2 = 0; j2 < SEMMOE_MAX_K; ++j2) c += (r[j2] == r[j]);
+      if (c > best_c || (c == best_c && best_r != home && r[j] < best_r)) {
+        best_c = c;
+        best_r = r[j];
+      }
+    }
+    L.pc[i] = (uint16_t)(best_r | (best_c << 8));
+    atomicAdd(&L.hist[best_r * (k + 1) + best_c], 1);
+  }
+  __syncthreads();
+
+  // thresholds per rank (see rs_threshold_kernel), free-slot prefix
+  if (t < D) {
+    int cum = 0, thr = -1, quota = 0;
+    for (int c = k; c >= 0; --c) {
+      const int n = L.hist[t * (k + 1) + c];
+      if (cum + n > cap) {
+        thr = c;
+        quota = cap - cum;
+        cum = cap;
+        break;
+      }
+      cum += n;
+    }
+    L.thr[t] = thr;
+    L.quota[t] = quota;
+    L.free_pre[t] = cap - cum;
+    if (thr >= 0) L.any_border = 1;
+  }
+  __syncthreads();
+  wave_exclusive_scan_lds(L.free_pre, D);
+  const bool any_border = L.any_border != 0;
+
+  // keep + spill, chunk by chunk
+  for (int c0 = 0; c0 < T; c0 += kChunk) {
+    const int i = c0 + t;
+    int pref = 0, conf = 0, thr = -1;
+    bool kept = true, border = false;
+    if (i < T) {
+      pref = L.pc[i] & 0xff;
+      conf = L.pc[i] >> 8;
+      thr = L.thr[pref];
+      border = thr >= 0 && conf == thr;
+      kept = thr < 0 || conf > thr;  // borderline tokens are decided below
+    }
+    if (any_border) {
+      for (int x = t; x < (D + 1) * 32; x += kChunk) (&L.bm[0][0])[x] = 0;
+      __syncthreads();
+      if (border) atomicOr(&L.bm[pref][t >> 5], 1u << (t & 31));
+      __syncthreads();
+      chunk_word_prefix(L, 0, D);
+      if (border) kept = L.border_run[pref] + chunk_rank(L, pref, t) < L.quota[pref];
+      const bool spilled = i < T && !kept;
+      if (spilled) atomicOr(&L.bm[D][t >> 5], 1u << (t & 31));
+      __syncthreads();
+      if (t < D) L.border_run[t] += L.ktot[t];
+      chunk_word_prefix(L, D, D + 1);
+      int rank = pref;
+      if (spilled) {
+        const int sidx = L.spill_run + chunk_rank(L, D, t);
+        int r = 0;
+        while (r + 1 < D && L.free_pre[r + 1] <= sidx) ++r;
+        rank = r;
+      }
+      if (i < T) {
+        L.tr[i] = (uint8_t)rank;
+        atomicAdd(&L.rank_cnt[rank], 1);
+      }
+      __syncthreads();
+      if (t == 0) L.spill_run += L.ktot[D];
+    } else if (i < T) {
+      L.tr[i] = (uint8_t)pref;
+      atomicAdd(&L.rank_cnt[pref], 1);
+    }
+  }
+  __syncthreads();
+  for (int r = t; r < D; r += kChunk) rank_count[r] = L.rank_cnt[r];
+  __syncthreads();
+  wave_exclusive_scan_lds(L.rank_cnt, D);  // now the first position of each rank
+
+  // stable scatter by rank
+  for (int c0 = 0; c0 < T; c0 += kChunk) {
+    const int i = c0 + t;
+    for (int x = t; x < D * 32; x += kChunk) (&L.bm[0][0])[x] = 0;
+    __syncthreads();
+    int rank = 0;
+    if (i < T) {
+      rank = L.tr[i];
+      atomicOr(&L.bm[rank][t >> 5], 1u << (t & 31));
+    }
+    __syncthreads();
+    chunk_word_prefix(L, 0, D);
+    if (i < T) {
+      const int pos = L.rank_cnt[rank] + L.rank_run[rank] + chunk_rank(L, rank, t);
+      token_rank[i] = rank;
+      inv_shf[i] = pos;
+      shf[pos] = i;
+    }
+    __syncthreads();
+    if (t < D) L.rank_run[t] += L.ktot[t];
+  }
+}
+
 __global__ void rs_zero_kernel(int n, int32_t* __restrict__ v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) v[i] = 0;
@@ -279,6 +466,20 @@ extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, cons
   }
   const int per_home = cdiv(T, D);
   const int nkeys = D * (k + 1);
+  const int path = tuning_value(SEMMOE_TUNE_INDEX_PATH);
+  if ((path != 1 && T <= kSingleAutoT && D < 255) || path == 2) {
+    if (T > kSingleMaxT || D >= 255) return SEMMOE_EUNSUPPORTED;
+    static bool attr_set = false;
+    if (!attr_set) {
+      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rs_single_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(sizeof(SingleLds))));
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(rs_single_kernel, dim3(1), dim3(kChunk), sizeof(SingleLds), s, T, k, D, cfg->E, cfg->cap,
+                       per_home, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
   hipLaunchKernelGGL(rs_pref_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, cfg->E, per_home, topk_ids,
                      expert_to_rank, w);
   hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, k, D, cfg->cap, w);

@@ -22,6 +22,15 @@ def _say(*a):
     print(*a, flush=True)
 
 
+@pytest.fixture(params=[1, 2], ids=["multi_wg", "single_wg"])
+def index_path(request):
+    """run the test with each implementation of the index kernels (reshuffle, dispatch index)"""
+    m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
+    m.set_tuning(3, request.param)
+    yield request.param
+    m.set_tuning(3, -1)
+
+
 # ------------------------------------------------------------------------------------------- route
 @pytest.mark.parametrize("E,k,T,renorm", [(16, 2, 100, False), (128, 8, 300, True), (256, 8, 77, True),
                                            (64, 1, 65, True), (200, 5, 33, False), (512, 16, 40, True)])
@@ -126,8 +135,8 @@ def _planted(T, E, D, k, seed, noise):
     (256, 16, 4, 2, 1.0, 0.2), (1000, 128, 8, 8, 1.0, 0.5), (777, 64, 16, 4, 1.0, 0.3), (300, 32, 32, 2, 1.0, 0.5),
     (513, 16, 4, 4, 1.25, 0.4), (100, 8, 1, 2, 1.0, 0.5), (2049, 64, 64, 1, 1.0, 0.0), (64, 16, 8, 2, 8.0, 0.3),
     (5, 16, 4, 2, 1.0, 0.5), (4000, 256, 32, 8, 1.0, 0.6)])
-def test_reshuffle_bit_exact(T, E, D, k, cf, noise):
-    _say("reshuffle", T, E, D, k, cf)
+def test_reshuffle_bit_exact(T, E, D, k, cf, noise, index_path):
+    _say("reshuffle", T, E, D, k, cf, "path", index_path)
     ids, e2r = _planted(T, E, D, k, seed=T + D, noise=noise)
     cap = int(math.ceil(cf * T / D))
     w = WL.small(T=T, E=E, D=D, k=k)
@@ -141,12 +150,33 @@ def test_reshuffle_bit_exact(T, E, D, k, cf, noise):
     assert (got[3] <= cap).all()
 
 
+def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit():
+    """beyond what the single-workgroup kernels hold; multi-workgroup kernels by default"""
+    T, E, D, k = 40000, 64, 16, 4
+    _say("reshuffle + dispatch index, large T", T)
+    ids, e2r = _planted(T, E, D, k, seed=5, noise=0.4)
+    phys = np.argsort(np.argsort(e2r, kind="stable"), kind="stable").astype(np.int32)
+    w = WL.small(T=T, E=E, D=D, k=k, d=8)
+    lay = H.Layer(w)
+    lay.set_routing(ids)
+    lay.set_placement(e2r, phys, np.argsort(phys).astype(np.int32))
+    got = lay.reshuffle()
+    want = O.reshuffle(ids, e2r, D, w.cap)
+    for g, w_ in zip(got, want):
+        assert (g == w_).all()
+    lay.X = None
+    dg = lay.dispatch(with_rows=False)
+    dw = O.dispatch(None, ids, want[0], want[2], phys, D)
+    for name in ("slot_of_pair", "pair_of_slot", "expert_offsets", "rank_offsets", "send_matrix"):
+        assert (dg[name] == dw[name]).all(), name
+
+
 # ------------------------------------------------------------------------------------------- dispatch
 @pytest.mark.parametrize("dtype,T,E,D,k,d", [("bf16", 700, 128, 8, 8, 64), ("fp32", 256, 16, 4, 2, 40),
                                               ("bf16", 1030, 256, 32, 8, 136), ("bf16", 90, 8, 2, 1, 8),
                                               ("fp32", 300, 24, 3, 3, 16), ("bf16", 513, 512, 64, 16, 24)])
-def test_dispatch_bit_exact(dtype, T, E, D, k, d):
-    _say("dispatch", dtype, T, E, D, k, d)
+def test_dispatch_bit_exact(dtype, T, E, D, k, d, index_path):
+    _say("dispatch", dtype, T, E, D, k, d, "path", index_path)
     w = WL.small(T=T, E=E, D=D, k=k, d=d, dtype=dtype)
     ids, e2r = _planted(T, E, D, k, seed=T, noise=0.4)
     m = E // D
