@@ -71,8 +71,13 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  * Tuning knobs for benchmarks (process-wide, not thread-safe).  value < 0 restores the default, which the
  * library picks per shape.  Results never depend on them beyond fp32 summation order inside a GEMM tile.
  *   SEMMOE_TUNE_GATEUP_TILE / SEMMOE_TUNE_DOWN_TILE: tile-shape id of the bf16 grouped GEMMs
- *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny tiles for decode)
+ *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny tiles for decode;
+ *     20, 21: four waves on a 256 x 256 tile with loads placed between the MFMAs, K a multiple of 32 and at
+ *     least 128; other K run as 16)
  *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs
+ *   SEMMOE_TUNE_HEAD_TAIL: with the 256 x 256 tile shapes (16, 20, 21) a GEMM runs as two launches: the tiles that
+ *     fill whole rounds of the persistent grid, then the rest as quarter tiles over the whole chip; 0 = one launch
+ *   SEMMOE_TUNE_GRID_CAP: most workgroups a grouped GEMM launches (default: compute units x blocks per CU)
  *   SEMMOE_TUNE_INDEX_PATH: which implementation of the index kernels runs (default: single workgroup for
  *     T <= 2048, several workgroups above; the single-workgroup kernels hold at most T = 32768); both give identical results
  */
@@ -80,6 +85,8 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
 #define SEMMOE_TUNE_DOWN_TILE 1
 #define SEMMOE_TUNE_BLOCKS_PER_CU 2
 #define SEMMOE_TUNE_INDEX_PATH 3 /* reshuffle / dispatch index: 1 = multi-workgroup kernels, 2 = single workgroup */
+#define SEMMOE_TUNE_HEAD_TAIL 5  /* 0: one launch per GEMM; default: big tiles for the full rounds + quarter tiles */
+#define SEMMOE_TUNE_GRID_CAP 4   /* upper limit of the persistent GEMM grids (tests: many tiles per workgroup) */
 int32_t semmoe_set_tuning(int32_t key, int32_t value);
 
 /*

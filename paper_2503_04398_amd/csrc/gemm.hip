@@ -1,5 +1,6 @@
 // Kernel instantiations and the host launcher of the grouped GEMM core.
 #include "gemm_core.hpp"
+#include "gemm_w4.hpp"
 
 namespace semmoe {
 
@@ -21,14 +22,18 @@ static int num_cu() {
 
 int tuning_value(int key) { return (key >= 0 && key < 8) ? g_tune[key] : -1; }
 
+static int grid_for(long long tile_bound, long long cap) {
+  if (g_tune[SEMMOE_TUNE_GRID_CAP] > 0 && cap > g_tune[SEMMOE_TUNE_GRID_CAP]) cap = g_tune[SEMMOE_TUNE_GRID_CAP];
+  return (int)(tile_bound < cap ? tile_bound : cap);
+}
+
 template <int MODE, int NWF, int NWT, int TF, int TT, int BK, int MINW = 1>
 static int32_t launch_bf16(const GemmArgs& a, int max_rows, int blocks_per_cu, hipStream_t stream) {
   using C = Bf16Cfg<MODE, NWF, NWT, TF, TT, BK>;
   const int n_ftiles = cdiv(a.N, C::FEAT);
   const long long bound = (long long)(max_rows / C::BT + a.nq) * n_ftiles;
   if (bound <= 0) return SEMMOE_OK;
-  const long long cap = (long long)num_cu() * blocks_per_cu;
-  const int grid = (int)(bound < cap ? bound : cap);
+  const int grid = grid_for(bound, (long long)num_cu() * blocks_per_cu);
   auto kern = gemm_bf16_kernel<MODE, NWF, NWT, TF, TT, BK, MINW>;
   if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
   if (C::kLdsBytes > 48 * 1024) {
@@ -50,8 +55,7 @@ static int32_t launch_dma(const GemmArgs& a, int max_rows, int blocks_per_cu, hi
   const int n_ftiles = cdiv(a.N, C::FEAT);
   const long long bound = (long long)(max_rows / C::BT + a.nq) * n_ftiles;
   if (bound <= 0) return SEMMOE_OK;
-  const long long cap = (long long)num_cu() * blocks_per_cu;
-  const int grid = (int)(bound < cap ? bound : cap);
+  const int grid = grid_for(bound, (long long)num_cu() * blocks_per_cu);
   auto kern = gemm_bf16_dma_kernel<MODE, NWF, NWT, TF, TT, BK, NSTAGE, MINW>;
   if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
   if (C::kLdsBytes > 48 * 1024) {
@@ -65,6 +69,62 @@ static int32_t launch_dma(const GemmArgs& a, int max_rows, int blocks_per_cu, hi
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
+}
+
+// Four-wave 256 x 256 kernel; shapes it does not take are reported with SEMMOE_EUNSUPPORTED before any launch.
+template <int MODE, int BK, int NSTAGE, int DMA_EVERY>
+static int32_t launch_w4(const GemmArgs& a, int max_rows, hipStream_t stream) {
+  using C = W4Cfg<MODE, BK, NSTAGE, DMA_EVERY>;
+  const int w_rows = (MODE == kModeSwiglu) ? 2 * a.N : a.N;
+  if (a.K % BK != 0 || a.K / BK < NSTAGE) return SEMMOE_EUNSUPPORTED;
+  if ((unsigned long long)w_rows * a.ldw * 2 >= (1ull << 32) || (unsigned long long)C::BT * a.ldx * 2 >= (1ull << 32))
+    return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
+  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  const int n_ftiles = cdiv(a.N, C::FEAT);
+  const long long bound = (long long)(max_rows / C::BT + a.nq) * n_ftiles;
+  if (bound <= 0) return SEMMOE_OK;
+  const int grid = grid_for(bound, num_cu());
+  auto kern = gemm_bf16_w4_kernel<MODE, BK, NSTAGE, DMA_EVERY>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(C::kLdsBytes)));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+// Tail launch of a head/tail split: quarter tiles (128 x 128) of the parent tiles the head launch left over.
+template <int MODE>
+static int32_t launch_tail(GemmArgs a, int max_rows, int head_grid, hipStream_t stream) {
+  using C = Bf16Cfg<MODE, 2, 2, 2, 2, 64>;
+  const int n_ftiles_p = cdiv(a.N, 2 * C::FEAT);
+  const long long bound_p = (long long)(max_rows / (2 * C::BT) + a.nq) * n_ftiles_p;  // parent tiles, at most
+  const long long left_p = bound_p < head_grid ? bound_p : head_grid / 2;              // ... the head leaves over
+  if (left_p <= 0) return SEMMOE_OK;
+  a.sched_mode = 2;
+  a.sched_g = head_grid;
+  const int grid = grid_for(left_p * 4, (long long)num_cu() * 2);
+  auto kern = gemm_bf16_kernel<MODE, 2, 2, 2, 2, 64, 1>;
+  if (C::kLdsBytes > 48 * 1024) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     int(C::kLdsBytes)));
+      attr_set = true;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+// grid of a launch with 256 x 256 tiles and one workgroup per compute unit (the head launch of a split)
+static int big_tile_grid(const GemmArgs& a, int max_rows, int feat) {
+  const long long bound = (long long)(max_rows / 256 + a.nq) * cdiv(a.N, feat);
+  return grid_for(bound, num_cu());
 }
 
 template <int MODE>
@@ -95,8 +155,14 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
     case 16: return launch_dma<MODE, 2, 4, 4, 2, 64, 2>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 256, K 64 x 2
     case 17: return launch_bf16<MODE, 4, 1, 2, 1, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 32 (decode)
     case 18: return launch_bf16<MODE, 4, 1, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 64
-    default: return SEMMOE_EINVAL;
+    default: break;
   }
+  if (id == 20 || id == 21) {  // four waves, 256 x 256, loads interleaved with the MFMAs
+    const int32_t st = id == 20 ? launch_w4<MODE, 32, 4, 4>(a, max_rows, s) : launch_w4<MODE, 32, 4, 2>(a, max_rows, s);
+    if (st != SEMMOE_EUNSUPPORTED) return st;
+    return launch_bf16_tile<MODE>(16, a, max_rows, bpc, s);  // K not a multiple of the slice, or too short
+  }
+  return SEMMOE_EINVAL;
 }
 
 // Default tile shape from the mean rows per group the caller expects (the true, ragged row counts live on
@@ -106,6 +172,13 @@ static int default_tile(int est_rows_per_group) {
   if (est_rows_per_group >= 96) return 0;
   if (est_rows_per_group >= 48) return 18;
   return 17;
+}
+
+// Head/tail split: for the tile shapes of 256 x 256 with a persistent grid of one workgroup per compute unit.
+static bool split_launch(int id) {
+  const bool big = id == 16 || id == 20 || id == 21;
+  const int t = g_tune[SEMMOE_TUNE_HEAD_TAIL];
+  return big && t != 0;
 }
 
 int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int est_rows_per_group,
@@ -120,12 +193,22 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
       case kModeSwiglu: {
         const int id = g_tune[SEMMOE_TUNE_GATEUP_TILE] >= 0 ? g_tune[SEMMOE_TUNE_GATEUP_TILE]
                                                             : default_tile(est_rows_per_group);
-        return launch_bf16_tile<kModeSwiglu>(id, a, max_rows, bpc, stream);
+        if (!split_launch(id)) return launch_bf16_tile<kModeSwiglu>(id, a, max_rows, bpc, stream);
+        GemmArgs h = a;
+        h.sched_mode = 1;
+        const int32_t st = launch_bf16_tile<kModeSwiglu>(id, h, max_rows, 1, stream);
+        if (st != SEMMOE_OK) return st;
+        return launch_tail<kModeSwiglu>(a, max_rows, big_tile_grid(a, max_rows, 128), stream);
       }
       default: {
         const int id = g_tune[SEMMOE_TUNE_DOWN_TILE] >= 0 ? g_tune[SEMMOE_TUNE_DOWN_TILE]
                                                           : default_tile(est_rows_per_group);
-        return launch_bf16_tile<kModeStore>(id, a, max_rows, bpc, stream);
+        if (!split_launch(id)) return launch_bf16_tile<kModeStore>(id, a, max_rows, bpc, stream);
+        GemmArgs h = a;
+        h.sched_mode = 1;
+        const int32_t st = launch_bf16_tile<kModeStore>(id, h, max_rows, 1, stream);
+        if (st != SEMMOE_OK) return st;
+        return launch_tail<kModeStore>(a, max_rows, big_tile_grid(a, max_rows, 256), stream);
       }
     }
   }

@@ -31,6 +31,13 @@ struct GemmArgs {
   const int32_t* token_class;
   const float* class_bias;
   int n_classes;
+  // Split of the tile list between two launches (bf16 kernels).  The list of 256 x 256 "parent" tiles is cut
+  // at the last multiple of the head launch's grid size: the head launch (1) takes the tiles before the cut, one
+  // full round per workgroup after the other; the tail launch (2) takes the rest as quarter tiles, which fill the
+  // chip where the parent tiles of a last, partial round would leave most of it idle.  When more than half a
+  // round is left over, the head launch takes the whole list instead (quarter tiles are less efficient).
+  int sched_mode;         // 0: the whole list, 1: head, 2: tail (kernel tile = a quarter of the parent tile)
+  int sched_g;            // tail: grid size of the head launch
 };
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -40,8 +47,7 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 
 // Tile list: group q (local index) owns tiles [tile_prefix[q], tile_prefix[q+1]); inside a group the
 // feature tile runs fastest.  Returns total tile count.  `pre` is LDS of nq+1 ints.
-template <int BT>
-__device__ __forceinline__ int build_tile_prefix(const GemmArgs& a, int n_ftiles, int* pre) {
+__device__ __forceinline__ int build_tile_prefix(const GemmArgs& a, int n_ftiles, int* pre, int BT) {
   // wave 0 scans: lane l owns groups [l*per, (l+1)*per)
   const int tid = threadIdx.x;
   if (tid < 64) {
@@ -68,6 +74,12 @@ __device__ __forceinline__ int build_tile_prefix(const GemmArgs& a, int n_ftiles
   }
   __syncthreads();
   return pre[a.nq];
+}
+
+// number of parent tiles the head launch of a split takes, of `listed`, with a head grid of g workgroups
+__device__ __forceinline__ int head_tiles(int listed, int g) {
+  const int rem = listed % g;
+  return (2 * rem > g) ? listed : listed - rem;
 }
 
 __device__ __forceinline__ int find_group(const int* pre, int nq, int t) {
@@ -206,16 +218,28 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_kernel(GemmArg
   const int wf = wave % NWF;  // wave position along weight rows
   const int wt = wave / NWF;  // wave position along tokens
   const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
-  const int total = build_tile_prefix<C::BT>(a, n_ftiles, pre);
+  const bool tail = a.sched_mode == 2;
+  // tail: the list is built for the parent tiles (twice this kernel's tile in both directions)
+  const int n_ftiles_list = tail ? (a.N + 2 * C::FEAT - 1) / (2 * C::FEAT) : n_ftiles;
+  const int bt_list = tail ? 2 * C::BT : C::BT;
+  const int listed = build_tile_prefix(a, n_ftiles_list, pre, bt_list);
+  const int cutoff = tail ? head_tiles(listed, a.sched_g) : 0;
+  const int total = tail ? (listed - cutoff) * 4 : listed;
   const int nk = (a.K + BK - 1) / BK;
 
-  for (int tile = xcd_worker_index(); tile < total; tile += gridDim.x) {
+  for (int item = xcd_worker_index(); item < total; item += gridDim.x) {
+    const int tile = tail ? cutoff + (item >> 2) : item;
     const int q = find_group(pre, a.nq, tile);
     const int local = tile - pre[q];
     const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
     const int row_hi = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
     int ft, tt_idx;
-    decode_tile(local, (row_hi - g_lo + C::BT - 1) / C::BT, n_ftiles, &tt_idx, &ft);
+    decode_tile(local, (row_hi - g_lo + bt_list - 1) / bt_list, n_ftiles_list, &tt_idx, &ft);
+    if (tail) {  // quarter (item & 3) of the parent tile; quarters outside the matrix are skipped
+      tt_idx = tt_idx * 2 + ((item >> 1) & 1);
+      ft = ft * 2 + (item & 1);
+      if (g_lo + tt_idx * C::BT >= row_hi || ft * C::FEAT >= a.N) continue;  // uniform: no barrier is skipped
+    }
     const int row_lo = g_lo + tt_idx * C::BT;
     const int n_tok = min(C::BT, row_hi - row_lo);
     const int f0 = ft * C::FEAT;
@@ -422,7 +446,8 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(Gem
   const int wf = wave % NWF;
   const int wt = wave / NWF;
   const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
-  const int total = build_tile_prefix<C::BT>(a, n_ftiles, pre);
+  const int listed = build_tile_prefix(a, n_ftiles, pre, C::BT);
+  const int total = a.sched_mode == 1 ? head_tiles(listed, int(gridDim.x)) : listed;
   const int nk = (a.K + BK - 1) / BK;
   const int k_tail = a.K - (nk - 1) * BK;  // elements in the last slice (multiple of 8)
 
@@ -569,7 +594,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
   const int tx = tid & 15;  // tokens 4*tx .. 4*tx+3
   const int ty = tid >> 4;  // weight rows 4*ty .. 4*ty+3
   const int n_ftiles = (a.N + FEAT - 1) / FEAT;
-  const int total = build_tile_prefix<C::BT>(a, n_ftiles, pre);
+  const int total = build_tile_prefix(a, n_ftiles, pre, C::BT);
 
   for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
     const int q = find_group(pre, a.nq, tile);

@@ -1,0 +1,340 @@
+// Grouped bf16 GEMM for large groups: one 256 x 256 output tile per workgroup, four waves, each wave a
+// 128 x 128 quadrant (4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers), one wave per SIMD.
+//
+// Why this shape on gfx950: a quadrant of 128 x 128 needs 8 fragment reads (8 KB) from LDS per 16 MFMAs,
+// half the LDS traffic per flop of a 128 x 64 quadrant, and the MFMA pipe of a SIMD is fed by a single
+// instruction stream in which everything else is placed by hand between the MFMAs:
+//   * the K slices of the tile stream through a ring of NSTAGE LDS stages filled by direct global->LDS
+//     loads; the loads of a slice are issued one at a time, every DMA_EVERY-th MFMA, so that no wave
+//     ever sits in a burst of load instructions while its MFMA pipe idles;
+//   * the fragments of k-step s+1 are read while the MFMAs of k-step s run, also across the slice
+//     boundary: the one barrier per slice sits before the last k-step of the slice, when every wave
+//     already holds that k-step's fragments in registers.  After it the stage of the slice is free (its
+//     refill is NSTAGE slices ahead) and the next slice is known to be complete;
+//   * the stream of slices does not stop at a tile boundary: the loads run NSTAGE slices ahead of the
+//     MFMAs, into the next tile of this workgroup, so the epilogue of a tile (accumulators -> a small
+//     per-wave LDS staging area -> 16-byte coalesced stores, no barrier) overlaps the loads of the next.
+// Needs K % BK == 0 and K / BK >= NSTAGE; other shapes take the kernels of gemm_core.hpp.
+#pragma once
+#include <type_traits>
+
+#include "gemm_core.hpp"
+
+namespace semmoe {
+
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// hardware conversion (v_cvt_pk_bf16_f32, round to nearest even)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  f32x2_t v = {lo, hi};
+  bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+  return *reinterpret_cast<uint32_t*>(&b);
+}
+
+// A pointer the program knows to be uniform, moved to scalar registers even where the compiler parked it in
+// vector registers.
+template <typename T>
+__device__ __forceinline__ const T* scalar_ptr(const T* p) {
+  const uint64_t b = reinterpret_cast<uint64_t>(p);
+  const uint64_t bs = (uint64_t(uint32_t(__builtin_amdgcn_readfirstlane(int(b >> 32)))) << 32) |
+                      uint32_t(__builtin_amdgcn_readfirstlane(int(uint32_t(b))));
+  return reinterpret_cast<const T*>(bs);
+}
+
+// Uniform 32-bit load through the scalar cache.  A vector load here would make the compiler wait for every
+// outstanding vector memory operation, that is for the whole ring of tile loads in flight.
+__device__ __forceinline__ int uniform_load(const int32_t* p) {
+  int v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(scalar_ptr(p)) : "memory");
+  return v;
+}
+
+// global -> LDS, 16 bytes per lane: address = uniform base + per-lane byte offset; lane L writes LDS[m0 + 16 L]
+__device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, unsigned lds_addr_uniform) {
+  sbase = scalar_ptr(static_cast<const unsigned char*>(sbase));
+  lds_addr_uniform = unsigned(__builtin_amdgcn_readfirstlane(int(lds_addr_uniform)));
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr_uniform), "v"(voff), "s"(sbase)
+               : "memory", "m0");
+}
+
+__device__ __forceinline__ float silu_mul_fast(float g, float u) {
+  // silu(g) * u with one exp2 and one reciprocal
+  return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * g)) * u;
+}
+
+template <int MODE, int BK, int NSTAGE, int DMA_EVERY>
+struct W4Cfg {
+  static constexpr int kThreads = 256;
+  static constexpr int BW = 256, BT = 256, ROWS = BW + BT;
+  static constexpr int RB = BK * 2;        // bytes per tile row of a slice
+  static constexpr int CPR = BK / 8;       // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;     // rows written by one wave-level load
+  static constexpr int IPS = ROWS / RPI;   // loads per slice
+  static constexpr int IPW = IPS / 4;      // ... per wave
+  static constexpr int RPB = 256 / RB;     // rows per 256 bytes of bank space
+  static constexpr int KS = BK / 16;       // k-steps (MFMA depth 16) per slice
+  static constexpr int kStageBytes = ROWS * RB;
+  static constexpr int FEAT = (MODE == kModeSwiglu) ? BW / 2 : BW;
+  static constexpr size_t kRingBytes = size_t(NSTAGE) * kStageBytes;
+  static constexpr int kStgRow = 128 + 16;             // staging row: 64 bf16 + pad against bank conflicts
+  static constexpr int kStgWave = 32 * kStgRow;        // 32 tokens per pass
+  static constexpr size_t kLdsBytes = kRingBytes + 4 * kStgWave + 520 * 4;
+  static_assert(BK == 32 || BK == 64, "row of 64 or 128 bytes");  // 64 x 2 stages stalls on HBM latency: not instantiated
+  static_assert(KS * 16 / DMA_EVERY >= IPW, "the loads of a slice fit between two barriers");
+  static_assert(NSTAGE >= 2 && (NSTAGE - 1) * IPW < 64, "vmcnt range");
+};
+
+struct TileRef {
+  int row_lo, n_tok, f0, widx;
+};
+
+__device__ __forceinline__ TileRef locate_tile(const GemmArgs& a, const int* pre, int tile, int n_ftiles, int BT,
+                                               int FEAT) {
+  const int q = __builtin_amdgcn_readfirstlane(find_group(pre, a.nq, tile));
+  const int local = tile - __builtin_amdgcn_readfirstlane(pre[q]);
+  const int g_lo = a.offsets ? uniform_load(a.offsets + a.q_lo + q) : 0;
+  const int row_hi = a.offsets ? uniform_load(a.offsets + a.q_lo + q + 1) : a.n_rows_single;
+  int ft, tt;
+  decode_tile(local, (row_hi - g_lo + BT - 1) / BT, n_ftiles, &tt, &ft);
+  // the divisions above run on the vector ALU: tell the compiler that the results are uniform
+  tt = __builtin_amdgcn_readfirstlane(tt);
+  ft = __builtin_amdgcn_readfirstlane(ft);
+  TileRef t;
+  t.row_lo = g_lo + tt * BT;
+  t.n_tok = min(BT, row_hi - t.row_lo);
+  t.f0 = ft * FEAT;
+  t.widx = a.group_to_weight ? uniform_load(a.group_to_weight + a.q_lo + q) : (a.q_lo + q);
+  return t;
+}
+
+template <int MODE, int BK, int NSTAGE, int DMA_EVERY>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
+  using C = W4Cfg<MODE, BK, NSTAGE, DMA_EVERY>;
+  static_assert(MODE != kModeLogits, "the router has its own kernel");
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wf = wave & 1;   // quadrant along weight rows
+  const int wt = wave >> 1;  // quadrant along tokens
+  unsigned char* stg = lds_raw + C::kRingBytes + wave * C::kStgWave;
+  int* pre = reinterpret_cast<int*>(lds_raw + C::kRingBytes + 4 * C::kStgWave);
+
+  const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
+  const int G = gridDim.x;
+  const int listed = __builtin_amdgcn_readfirstlane(build_tile_prefix(a, n_ftiles, pre, C::BT));
+  const int total = a.sched_mode == 1 ? head_tiles(listed, G) : listed;  // head launch of a split
+  const int nk = a.K / BK;
+  const int worker = xcd_worker_index();
+  if (worker >= total) return;  // whole workgroup: no barrier is pending
+
+  // fragment-read geometry: lane reads row (lane & 31) of a 32-row MFMA tile, chunk 2*ks + lane/32
+  const int frag_swz = ((lane & 31) / C::RPB) % C::CPR;
+  const unsigned frag_w = (wf * 128 + (lane & 31)) * C::RB;
+  // token blocks of 32 alternate between the two token waves (block b -> wave b % 2, its MFMA column b / 2), so
+  // that a partly filled tile leaves both with the same number of empty columns to skip
+  const unsigned frag_x = (C::BW + wt * 32 + (lane & 31)) * C::RB;
+  // loader geometry: lane fills position d_pos of row d_row inside the 1 KB block of a load.  Waves 0 and 1
+  // load the 256 weight rows of a slice, waves 2 and 3 the 256 token rows.
+  const int d_row = lane / C::CPR;
+  const int d_pos = lane % C::CPR;
+  const bool loads_w = wave < 2;
+
+  // ---- load stream state (runs NSTAGE slices ahead of the MFMAs, across tiles)
+  int i_tile = worker;
+  int i_slice = 0;
+  int i_stage = 0;
+  bool i_done = false;
+  bool i_go = false;                      // set at the first barrier of the main loop: before it no stage is free
+  const unsigned char* i_base = nullptr;  // uniform: weight panel or token panel of the tile, advanced by RB per slice
+  uint32_t i_off[C::IPW];                 // per lane: byte offset of the row + chunk it fetches
+
+  auto i_setup = [&](int tile) {
+    const TileRef t = locate_tile(a, pre, tile, n_ftiles, C::BT, C::FEAT);
+    if (loads_w) {
+      i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.W) + size_t(t.widx) * a.w_group_stride);
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i) {
+        const int sr = (wave * C::IPW + i) * C::RPI + d_row;  // weight row of the tile
+        const int c = d_pos ^ ((sr / C::RPB) % C::CPR);
+        int grow;
+        if constexpr (MODE == kModeSwiglu) {
+          // quadrant wf: MFMA tiles 0,2 are gate rows, 1,3 the matching up rows, of two blocks of 32 features
+          const int tf = (sr >> 5) & 3, fr = sr & 31;
+          const int feat = min(t.f0 + ((sr >> 7) * 2 + (tf >> 1)) * 32 + fr, a.N - 1);
+          grow = (tf & 1) * a.N + feat;
+        } else {
+          grow = min(t.f0 + sr, a.N - 1);
+        }
+        i_off[i] = uint32_t(grow) * uint32_t(a.ldw) * 2u + uint32_t(c) * 16u;
+      }
+    } else {
+      i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.X) + size_t(t.row_lo) * a.ldx);
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i) {
+        const int sr = (wave * C::IPW + i) * C::RPI + d_row - C::BW;  // token row of the tile
+        const int c = d_pos ^ (((sr + C::BW) / C::RPB) % C::CPR);
+        i_off[i] = uint32_t(min(sr, t.n_tok - 1)) * uint32_t(a.ldx) * 2u + uint32_t(c) * 16u;
+      }
+    }
+  };
+  auto i_next_slice = [&]() {
+    i_base += C::RB;
+    i_stage = (i_stage + 1 == NSTAGE) ? 0 : i_stage + 1;
+    if (++i_slice == nk) {
+      i_slice = 0;
+      i_tile += G;
+      if (i_tile < total) i_setup(i_tile); else i_done = true;
+    }
+  };
+  // load number i of the current slice of the stream; after the last one the stream moves to the next slice
+  auto i_issue = [&](auto idx) {
+    constexpr int i = decltype(idx)::value;
+    const bool on = i_go && !i_done;
+    if (on) lds_dma16_s(i_base, i_off[i], lds_base + i_stage * C::kStageBytes + (wave * C::IPW + i) * 1024);
+    if constexpr (i == C::IPW - 1) {
+      if (on) i_next_slice();
+    }
+  };
+
+  // ---- fragments
+  bf16x8_t af[2][4], bfr[2][4];
+  auto frag = [&](int stage, int ks, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
+    const unsigned char* S = lds_raw + stage * C::kStageBytes;
+    const int off = ((ks * 2 + (lane >> 5)) ^ frag_swz) * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(S + frag_w + i * 32 * C::RB + off);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(S + frag_x + j * 64 * C::RB + off);
+  };
+
+  // ---- prologue: the first NSTAGE slices of the first tile
+  i_setup(i_tile);
+  for (int s = 0; s < NSTAGE; ++s) {  // nk >= NSTAGE: these slices belong to the first tile
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i)
+      lds_dma16_s(i_base + s * C::RB, i_off[i], lds_base + s * C::kStageBytes + (wave * C::IPW + i) * 1024);
+  }
+  i_base += (NSTAGE - 1) * C::RB;  // the stream stands at its slice NSTAGE-1 ...
+  i_slice = NSTAGE - 1;
+  i_stage = NSTAGE - 1;
+  i_next_slice();                  // ... and moves on (possibly into the next tile)
+  wait_vmcnt<(NSTAGE - 1) * C::IPW>();
+  __syncthreads();
+  frag(0, 0, af[0], bfr[0]);
+  int c_stage = 0;
+
+  for (int tile = worker; tile < total; tile += G) {
+    const TileRef t = locate_tile(a, pre, tile, n_ftiles, C::BT, C::FEAT);
+    const int nj = min(4, max(0, (t.n_tok - wt * 32 + 63) >> 6));  // MFMA columns of this wave that hold tokens
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // the K loop in two copies: tiles full of tokens run without any test around the MFMAs
+    auto k_loop = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    for (int it = 0; it < nk; ++it) {
+      const int n_stage = (c_stage + 1 == NSTAGE) ? 0 : c_stage + 1;
+#pragma unroll
+      for (int ks = 0; ks < C::KS; ++ks) {
+        constexpr int kLast = C::KS - 1;
+        const int cur = ks & 1;  // KS is even: k-step 0 of a slice always finds its fragments in buffer 0
+        if (ks == kLast) {
+          // this wave's reads of the current slice are complete once this k-step's fragments have arrived
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          // its share of the next slice has landed; younger slices may stay in flight (all of them were
+          // issued, unless the stream has ended)
+          if (!i_done) wait_vmcnt<(NSTAGE - 2) * C::IPW>(); else wait_vmcnt<0>();
+          __syncthreads();
+          i_go = true;
+          frag(n_stage, 0, af[cur ^ 1], bfr[cur ^ 1]);
+        } else {
+          frag(c_stage, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (FULL || j < nj)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+            // position in the load stream = MFMAs since the barrier (the last k-step comes first after it)
+            const int m = ((ks == kLast) ? 0 : (ks + 1) * 16) + j * 4 + i;
+            if (m % DMA_EVERY == DMA_EVERY - 1 && m / DMA_EVERY < C::IPW) {
+              switch (m / DMA_EVERY) {   // compile-time after unrolling
+#define SEMMOE_W4_CASE(n) case n: if constexpr (n < C::IPW) i_issue(std::integral_constant<int, n>{}); break;
+                SEMMOE_W4_CASE(0) SEMMOE_W4_CASE(1) SEMMOE_W4_CASE(2) SEMMOE_W4_CASE(3)
+                SEMMOE_W4_CASE(4) SEMMOE_W4_CASE(5) SEMMOE_W4_CASE(6) SEMMOE_W4_CASE(7)
+                SEMMOE_W4_CASE(8) SEMMOE_W4_CASE(9) SEMMOE_W4_CASE(10) SEMMOE_W4_CASE(11)
+                SEMMOE_W4_CASE(12) SEMMOE_W4_CASE(13) SEMMOE_W4_CASE(14) SEMMOE_W4_CASE(15)
+#undef SEMMOE_W4_CASE
+                default: break;
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
+      c_stage = n_stage;
+    }
+    };
+    if (nj == 4) k_loop(std::true_type{}); else k_loop(std::false_type{});
+
+    // ---- epilogue: no barrier; the ring already holds the next tile's first slices
+    bf16_t* out = static_cast<bf16_t*>(a.out);
+    const int tok_in = lane & 31, half = lane >> 5;
+    const int r_row = lane >> 3, r_chunk = lane & 7;  // read-back: 8 lanes per staged row
+    constexpr int kPasses = (MODE == kModeSwiglu) ? 1 : 2;  // 64 output features per pass
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (j >= nj) break;
+#pragma unroll
+      for (int h = 0; h < kPasses; ++h) {
+        __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps the live set of converted values small
+        unsigned char* wp = stg + tok_in * C::kStgRow + half * 8;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {  // block of 32 features inside the pass
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            uint2 v;
+            if constexpr (MODE == kModeSwiglu) {
+              const f32x16_t& g = acc[2 * b][j];
+              const f32x16_t& u = acc[2 * b + 1][j];
+              v.x = cvt_pk_bf16(silu_mul_fast(g[g4 * 4 + 0], u[g4 * 4 + 0]), silu_mul_fast(g[g4 * 4 + 1], u[g4 * 4 + 1]));
+              v.y = cvt_pk_bf16(silu_mul_fast(g[g4 * 4 + 2], u[g4 * 4 + 2]), silu_mul_fast(g[g4 * 4 + 3], u[g4 * 4 + 3]));
+            } else {
+              const f32x16_t& c = acc[2 * h + b][j];
+              v.x = cvt_pk_bf16(c[g4 * 4 + 0], c[g4 * 4 + 1]);
+              v.y = cvt_pk_bf16(c[g4 * 4 + 2], c[g4 * 4 + 3]);
+            }
+            *reinterpret_cast<uint2*>(wp + (b * 4 + g4) * 16) = v;
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+        const int feat = t.f0 + (MODE == kModeSwiglu ? wf * 64 : wf * 128 + h * 64) + r_chunk * 8;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int sr = p * 8 + r_row;
+          const int row = (j * 2 + wt) * 32 + sr;
+          const uint4 v = *reinterpret_cast<const uint4*>(stg + sr * C::kStgRow + r_chunk * 16);
+          if (row < t.n_tok && feat < a.N)
+            *reinterpret_cast<uint4*>(out + (size_t(t.row_lo) + row) * a.ldo + feat) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+  }
+  wait_vmcnt<0>();  // nothing may still be writing into this workgroup's LDS when it ends
+}
+
+}  // namespace semmoe

@@ -372,3 +372,27 @@ def test_every_gemm_tile_shape_on_a_ragged_problem(tile):
     finally:
         m.set_tuning(0, -1)
         m.set_tuning(1, -1)
+
+
+@pytest.mark.parametrize("tile,grid_cap,split", [(20, -1, -1), (21, -1, -1), (16, -1, -1), (20, 3, -1), (21, 5, -1),
+                                                 (21, 1, 0), (16, 7, -1), (20, 4, 0), (16, 2, 0)])
+def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
+    """the 256 x 256 kernels: groups of several token tiles with a ragged last one, a partial feature tile
+    (F = 192 against 128 per tile), K a multiple of 64; grid_cap: few workgroups, so that each walks many tiles
+    and the load stream runs across tile boundaries; split: one launch, or full rounds of big tiles + the rest
+    as quarter tiles"""
+    _say("big gemm tile", tile, "grid cap", grid_cap, "split", split)
+    w = WL.small(T=2500, d=256, E=4, k=2, F=192, D=2, dtype="bf16", C=2)
+    m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
+    try:
+        m.set_tuning(0, tile)
+        m.set_tuning(1, tile)
+        m.set_tuning(4, grid_cap)
+        m.set_tuning(5, split)
+        lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, rank=-1)
+        H.assert_close(Y, Yo, "bf16", "Y")
+        out = lay.combine()
+        H.assert_close(out, O.moe_definition(inp.X, ids, want_w, lambda e: weights[e]), "bf16", "Out")
+    finally:
+        for key in (0, 1, 4, 5):
+            m.set_tuning(key, -1)
