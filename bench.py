@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--device-weights", action="store_true",
                     help="draw the expert weights on the device (seeded torch generator) instead of the numpy "
                          "generator: for quick looks at the big workloads; the CPU baseline is then skipped")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times before the timed loops: under rocprofv3 "
+                         "--pmc its FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a one-GPU hot path (logical ranks are simulated on one device); "
@@ -169,6 +172,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)    # 256 MiB read + 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # the timed region: exactly K steps, nothing between the calls
     t0 = time.perf_counter()
     for s in range(args.steps):

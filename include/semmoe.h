@@ -76,7 +76,8 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *     least 128; other K run as 16)
  *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs
  *   SEMMOE_TUNE_HEAD_TAIL: with the 256 x 256 tile shapes (16, 20, 21) a GEMM runs as two launches: the tiles that
- *     fill whole rounds of the persistent grid, then the rest as quarter tiles over the whole chip; 0 = one launch
+ *     fill whole rounds of the persistent grid, then the rest as quarter tiles over the whole chip, when at most
+ *     value/16 of a round is left over (default 8); 0 = always one launch
  *   SEMMOE_TUNE_GRID_CAP: most workgroups a grouped GEMM launches (default: compute units x blocks per CU)
  *   SEMMOE_TUNE_INDEX_PATH: which implementation of the index kernels runs (default: single workgroup for
  *     T <= 2048, several workgroups above; the single-workgroup kernels hold at most T = 32768); both give identical results

@@ -99,22 +99,21 @@ static int32_t launch_w4(const GemmArgs& a, int max_rows, hipStream_t stream) {
 // Tail launch of a head/tail split: quarter tiles (128 x 128) of the parent tiles the head launch left over.
 template <int MODE>
 static int32_t launch_tail(GemmArgs a, int max_rows, int head_grid, hipStream_t stream) {
-  using C = Bf16Cfg<MODE, 2, 2, 2, 2, 64>;
+  using C = DmaCfg<MODE, 2, 2, 2, 2, 64, 4>;  // deep ring: a quarter tile is a long, thin K loop on a mostly idle chip
   const int n_ftiles_p = cdiv(a.N, 2 * C::FEAT);
   const long long bound_p = (long long)(max_rows / (2 * C::BT) + a.nq) * n_ftiles_p;  // parent tiles, at most
-  const long long left_p = bound_p < head_grid ? bound_p : head_grid / 2;              // ... the head leaves over
+  const long long left_p = bound_p < head_grid ? bound_p : (long long)head_grid * a.sched_thr / 16;  // ... left over
   if (left_p <= 0) return SEMMOE_OK;
   a.sched_mode = 2;
   a.sched_g = head_grid;
-  const int grid = grid_for(left_p * 4, (long long)num_cu() * 2);
-  auto kern = gemm_bf16_kernel<MODE, 2, 2, 2, 2, 64, 1>;
-  if (C::kLdsBytes > 48 * 1024) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     int(C::kLdsBytes)));
-      attr_set = true;
-    }
+  const int grid = grid_for(left_p * 4, num_cu());
+  auto kern = gemm_bf16_dma_kernel<MODE, 2, 2, 2, 2, 64, 4, 1>;
+  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(C::kLdsBytes)));
+    attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
@@ -168,7 +167,7 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
 // Default tile shape from the mean rows per group the caller expects (the true, ragged row counts live on
 // the device): big direct-to-LDS tiles when groups fill them, small register-staged tiles otherwise.
 static int default_tile(int est_rows_per_group) {
-  if (est_rows_per_group >= 192) return 16;
+  if (est_rows_per_group >= 192) return 20;
   if (est_rows_per_group >= 96) return 0;
   if (est_rows_per_group >= 48) return 18;
   return 17;
@@ -179,6 +178,12 @@ static bool split_launch(int id) {
   const bool big = id == 16 || id == 20 || id == 21;
   const int t = g_tune[SEMMOE_TUNE_HEAD_TAIL];
   return big && t != 0;
+}
+
+// left-over share of a round (in sixteenths) up to which the split happens
+static int split_threshold() {
+  const int t = g_tune[SEMMOE_TUNE_HEAD_TAIL];
+  return (t >= 1 && t <= 16) ? t : 8;
 }
 
 int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int est_rows_per_group,
@@ -196,9 +201,10 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         if (!split_launch(id)) return launch_bf16_tile<kModeSwiglu>(id, a, max_rows, bpc, stream);
         GemmArgs h = a;
         h.sched_mode = 1;
+        h.sched_thr = split_threshold();
         const int32_t st = launch_bf16_tile<kModeSwiglu>(id, h, max_rows, 1, stream);
         if (st != SEMMOE_OK) return st;
-        return launch_tail<kModeSwiglu>(a, max_rows, big_tile_grid(a, max_rows, 128), stream);
+        return launch_tail<kModeSwiglu>(h, max_rows, big_tile_grid(a, max_rows, 128), stream);
       }
       default: {
         const int id = g_tune[SEMMOE_TUNE_DOWN_TILE] >= 0 ? g_tune[SEMMOE_TUNE_DOWN_TILE]
@@ -206,9 +212,10 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         if (!split_launch(id)) return launch_bf16_tile<kModeStore>(id, a, max_rows, bpc, stream);
         GemmArgs h = a;
         h.sched_mode = 1;
+        h.sched_thr = split_threshold();
         const int32_t st = launch_bf16_tile<kModeStore>(id, h, max_rows, 1, stream);
         if (st != SEMMOE_OK) return st;
-        return launch_tail<kModeStore>(a, max_rows, big_tile_grid(a, max_rows, 256), stream);
+        return launch_tail<kModeStore>(h, max_rows, big_tile_grid(a, max_rows, 256), stream);
       }
     }
   }

@@ -38,6 +38,7 @@ struct GemmArgs {
   // round is left over, the head launch takes the whole list instead (quarter tiles are less efficient).
   int sched_mode;         // 0: the whole list, 1: head, 2: tail (kernel tile = a quarter of the parent tile)
   int sched_g;            // tail: grid size of the head launch
+  int sched_thr;          // the split happens when at most sched_thr / 16 of a round is left over
 };
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -77,9 +78,9 @@ __device__ __forceinline__ int build_tile_prefix(const GemmArgs& a, int n_ftiles
 }
 
 // number of parent tiles the head launch of a split takes, of `listed`, with a head grid of g workgroups
-__device__ __forceinline__ int head_tiles(int listed, int g) {
+__device__ __forceinline__ int head_tiles(int listed, int g, int thr16) {
   const int rem = listed % g;
-  return (2 * rem > g) ? listed : listed - rem;
+  return (16 * rem > thr16 * g) ? listed : listed - rem;
 }
 
 __device__ __forceinline__ int find_group(const int* pre, int nq, int t) {
@@ -117,6 +118,51 @@ __device__ __forceinline__ void decode_tile(int local, int n_ttiles, int n_ftile
     *tt = l2 / rest;
     *ft = full + l2 % rest;
   }
+}
+
+// Walk of one launch over the tile list.  Whole list / head launch: items are the listed tiles up to `total`.
+// Tail launch: items are the quarters of the parent tiles (twice the kernel's tile in both directions) from
+// `cutoff` on.
+struct TileWalk {
+  bool tail;
+  int n_ftiles_list, bt_list, cutoff, total;
+};
+
+__device__ __forceinline__ TileWalk make_walk(const GemmArgs& a, int* pre, int BT, int FEAT) {
+  TileWalk w;
+  w.tail = a.sched_mode == 2;
+  w.n_ftiles_list = w.tail ? (a.N + 2 * FEAT - 1) / (2 * FEAT) : (a.N + FEAT - 1) / FEAT;
+  w.bt_list = w.tail ? 2 * BT : BT;
+  const int listed = build_tile_prefix(a, w.n_ftiles_list, pre, w.bt_list);
+  w.cutoff = w.tail ? head_tiles(listed, a.sched_g, a.sched_thr) : 0;
+  w.total = w.tail ? (listed - w.cutoff) * 4 : (a.sched_mode == 1 ? head_tiles(listed, int(gridDim.x), a.sched_thr) : listed);
+  return w;
+}
+
+struct TileAt {
+  int q, row_lo, n_tok, f0;
+};
+
+// false: the item lies outside the matrix (a quarter of a partly filled parent tile); uniform over the workgroup
+__device__ __forceinline__ bool walk_tile(const GemmArgs& a, const TileWalk& w, const int* pre, int item, int BT,
+                                          int FEAT, TileAt* t) {
+  const int tile = w.tail ? w.cutoff + (item >> 2) : item;
+  const int q = find_group(pre, a.nq, tile);
+  const int local = tile - pre[q];
+  const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
+  const int row_hi = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
+  int ft, tt;
+  decode_tile(local, (row_hi - g_lo + w.bt_list - 1) / w.bt_list, w.n_ftiles_list, &tt, &ft);
+  if (w.tail) {
+    tt = tt * 2 + ((item >> 1) & 1);
+    ft = ft * 2 + (item & 1);
+    if (g_lo + tt * BT >= row_hi || ft * FEAT >= a.N) return false;
+  }
+  t->q = q;
+  t->row_lo = g_lo + tt * BT;
+  t->n_tok = min(BT, row_hi - t->row_lo);
+  t->f0 = ft * FEAT;
+  return true;
 }
 
 // Output tile of a bf16 GEMM: accumulators -> LDS (bf16, 16-byte chunks swizzled by the row so that the 32
@@ -217,32 +263,13 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_kernel(GemmArg
   const int wave = tid >> 6;
   const int wf = wave % NWF;  // wave position along weight rows
   const int wt = wave / NWF;  // wave position along tokens
-  const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
-  const bool tail = a.sched_mode == 2;
-  // tail: the list is built for the parent tiles (twice this kernel's tile in both directions)
-  const int n_ftiles_list = tail ? (a.N + 2 * C::FEAT - 1) / (2 * C::FEAT) : n_ftiles;
-  const int bt_list = tail ? 2 * C::BT : C::BT;
-  const int listed = build_tile_prefix(a, n_ftiles_list, pre, bt_list);
-  const int cutoff = tail ? head_tiles(listed, a.sched_g) : 0;
-  const int total = tail ? (listed - cutoff) * 4 : listed;
+  const TileWalk walk = make_walk(a, pre, C::BT, C::FEAT);
   const int nk = (a.K + BK - 1) / BK;
 
-  for (int item = xcd_worker_index(); item < total; item += gridDim.x) {
-    const int tile = tail ? cutoff + (item >> 2) : item;
-    const int q = find_group(pre, a.nq, tile);
-    const int local = tile - pre[q];
-    const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
-    const int row_hi = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
-    int ft, tt_idx;
-    decode_tile(local, (row_hi - g_lo + bt_list - 1) / bt_list, n_ftiles_list, &tt_idx, &ft);
-    if (tail) {  // quarter (item & 3) of the parent tile; quarters outside the matrix are skipped
-      tt_idx = tt_idx * 2 + ((item >> 1) & 1);
-      ft = ft * 2 + (item & 1);
-      if (g_lo + tt_idx * C::BT >= row_hi || ft * C::FEAT >= a.N) continue;  // uniform: no barrier is skipped
-    }
-    const int row_lo = g_lo + tt_idx * C::BT;
-    const int n_tok = min(C::BT, row_hi - row_lo);
-    const int f0 = ft * C::FEAT;
+  for (int item = xcd_worker_index(); item < walk.total; item += gridDim.x) {
+    TileAt at;
+    if (!walk_tile(a, walk, pre, item, C::BT, C::FEAT, &at)) continue;  // uniform: no barrier is skipped
+    const int q = at.q, row_lo = at.row_lo, n_tok = at.n_tok, f0 = at.f0;
     const int widx = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
     const bf16_t* Wg = static_cast<const bf16_t*>(a.W) + size_t(widx) * a.w_group_stride;
     const bf16_t* Xg = static_cast<const bf16_t*>(a.X) + size_t(row_lo) * a.ldx;
@@ -445,9 +472,7 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(Gem
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wf = wave % NWF;
   const int wt = wave / NWF;
-  const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
-  const int listed = build_tile_prefix(a, n_ftiles, pre, C::BT);
-  const int total = a.sched_mode == 1 ? head_tiles(listed, int(gridDim.x)) : listed;
+  const TileWalk walk = make_walk(a, pre, C::BT, C::FEAT);
   const int nk = (a.K + BK - 1) / BK;
   const int k_tail = a.K - (nk - 1) * BK;  // elements in the last slice (multiple of 8)
 
@@ -457,16 +482,10 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(Gem
   const int d_row = lane / C::CPR;
   const int d_pos = lane % C::CPR;
 
-  for (int tile = xcd_worker_index(); tile < total; tile += gridDim.x) {
-    const int q = find_group(pre, a.nq, tile);
-    const int local = tile - pre[q];
-    const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
-    const int row_hi = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
-    int ft, tt_idx;
-    decode_tile(local, (row_hi - g_lo + C::BT - 1) / C::BT, n_ftiles, &tt_idx, &ft);
-    const int row_lo = g_lo + tt_idx * C::BT;
-    const int n_tok = min(C::BT, row_hi - row_lo);
-    const int f0 = ft * C::FEAT;
+  for (int item = xcd_worker_index(); item < walk.total; item += gridDim.x) {
+    TileAt at;
+    if (!walk_tile(a, walk, pre, item, C::BT, C::FEAT, &at)) continue;  // uniform: no barrier is skipped
+    const int q = at.q, row_lo = at.row_lo, n_tok = at.n_tok, f0 = at.f0;
     const int widx = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
     const bf16_t* Wg = static_cast<const bf16_t*>(a.W) + size_t(widx) * a.w_group_stride;
     const bf16_t* Xg = static_cast<const bf16_t*>(a.X) + size_t(row_lo) * a.ldx;

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
   const int G = gridDim.x;
   const int listed = __builtin_amdgcn_readfirstlane(build_tile_prefix(a, n_ftiles, pre, C::BT));
-  const int total = a.sched_mode == 1 ? head_tiles(listed, G) : listed;  // head launch of a split
+  const int total = a.sched_mode == 1 ? head_tiles(listed, G, a.sched_thr) : listed;  // head launch of a split
   const int nk = a.K / BK;
   const int worker = xcd_worker_index();
   if (worker >= total) return;  // whole workgroup: no barrier is pending
