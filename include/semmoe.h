@@ -72,10 +72,10 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  * library picks per shape.  Results never depend on them beyond fp32 summation order inside a GEMM tile.
  *   SEMMOE_TUNE_GATEUP_TILE / SEMMOE_TUNE_DOWN_TILE: tile-shape id of the bf16 grouped GEMMs
  *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny tiles for decode;
- *     20, 21: four waves on a 256 x 256 tile with loads placed between the MFMAs, K a multiple of 32 and at
- *     least 128; other K run as 16)
+ *     20, 21, 22: four waves on a 256 x 256 tile with loads placed between the MFMAs; K must be a multiple of the
+ *     K slice (32 for 20 and 21, 64 for 22) and hold at least a ring of slices (128); other K run as 16)
  *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs
- *   SEMMOE_TUNE_HEAD_TAIL: with the 256 x 256 tile shapes (16, 20, 21) a GEMM runs as two launches: the tiles that
+ *   SEMMOE_TUNE_HEAD_TAIL: with the 256 x 256 tile shapes (16, 20, 21, 22) a GEMM runs as two launches: the tiles that
  *     fill whole rounds of the persistent grid, then the rest as quarter tiles over the whole chip, when at most
  *     value/16 of a round is left over (default 8); 0 = always one launch
  *   SEMMOE_TUNE_GRID_CAP: most workgroups a grouped GEMM launches (default: compute units x blocks per CU)

@@ -156,8 +156,13 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
     case 18: return launch_bf16<MODE, 4, 1, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 64
     default: break;
   }
-  if (id == 20 || id == 21) {  // four waves, 256 x 256, loads interleaved with the MFMAs
-    const int32_t st = id == 20 ? launch_w4<MODE, 32, 4, 4>(a, max_rows, s) : launch_w4<MODE, 32, 4, 2>(a, max_rows, s);
+  if (id >= 20 && id <= 22) {  // four waves, 256 x 256, loads interleaved with the MFMAs
+    int32_t st;
+    switch (id) {
+      case 20: st = launch_w4<MODE, 32, 4, 4>(a, max_rows, s); break;  // K slices of 32, ring of 4, a load every 4th MFMA
+      case 21: st = launch_w4<MODE, 32, 4, 2>(a, max_rows, s); break;  // ... every 2nd MFMA
+      default: st = launch_w4<MODE, 64, 2, 2>(a, max_rows, s); break;  // K slices of 64, ring of 2 (the fastest measured)
+    }
     if (st != SEMMOE_EUNSUPPORTED) return st;
     return launch_bf16_tile<MODE>(16, a, max_rows, bpc, s);  // K not a multiple of the slice, or too short
   }
@@ -167,7 +172,7 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
 // Default tile shape from the mean rows per group the caller expects (the true, ragged row counts live on
 // the device): big direct-to-LDS tiles when groups fill them, small register-staged tiles otherwise.
 static int default_tile(int est_rows_per_group) {
-  if (est_rows_per_group >= 192) return 20;
+  if (est_rows_per_group >= 192) return 22;
   if (est_rows_per_group >= 96) return 0;
   if (est_rows_per_group >= 48) return 18;
   return 17;
@@ -175,7 +180,7 @@ static int default_tile(int est_rows_per_group) {
 
 // Head/tail split: for the tile shapes of 256 x 256 with a persistent grid of one workgroup per compute unit.
 static bool split_launch(int id) {
-  const bool big = id == 16 || id == 20 || id == 21;
+  const bool big = id == 16 || (id >= 20 && id <= 22);
   const int t = g_tune[SEMMOE_TUNE_HEAD_TAIL];
   return big && t != 0;
 }

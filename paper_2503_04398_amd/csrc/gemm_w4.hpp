@@ -80,7 +80,7 @@ struct W4Cfg {
   static constexpr int kStgRow = 128 + 16;             // staging row: 64 bf16 + pad against bank conflicts
   static constexpr int kStgWave = 32 * kStgRow;        // 32 tokens per pass
   static constexpr size_t kLdsBytes = kRingBytes + 4 * kStgWave + 520 * 4;
-  static_assert(BK == 32 || BK == 64, "row of 64 or 128 bytes");  // 64 x 2 stages stalls on HBM latency: not instantiated
+  static_assert(BK == 32 || BK == 64, "row of 64 or 128 bytes");
   static_assert(KS * 16 / DMA_EVERY >= IPW, "the loads of a slice fit between two barriers");
   static_assert(NSTAGE >= 2 && (NSTAGE - 1) * IPW < 64, "vmcnt range");
 };
@@ -152,7 +152,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   const unsigned char* i_base = nullptr;  // uniform: weight panel or token panel of the tile, advanced by RB per slice
   uint32_t i_off[C::IPW];                 // per lane: byte offset of the row + chunk it fetches
 
-  auto i_setup = [&](int tile) {
+  // (the lambdas are forced inline: one left as a call makes the argument block a stack object, and every access
+  // to it a scratch load that waits for all the tile loads in flight)
+  auto i_setup = [&](int tile) __attribute__((always_inline)) {
     const TileRef t = locate_tile(a, pre, tile, n_ftiles, C::BT, C::FEAT);
     if (loads_w) {
       i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.W) + size_t(t.widx) * a.w_group_stride);
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
       }
     }
   };
-  auto i_next_slice = [&]() {
+  auto i_next_slice = [&]() __attribute__((always_inline)) {
     i_base += C::RB;
     i_stage = (i_stage + 1 == NSTAGE) ? 0 : i_stage + 1;
     if (++i_slice == nk) {
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
     }
   };
   // load number i of the current slice of the stream; after the last one the stream moves to the next slice
-  auto i_issue = [&](auto idx) {
+  auto i_issue = [&](auto idx) __attribute__((always_inline)) {
     constexpr int i = decltype(idx)::value;
     const bool on = i_go && !i_done;
     if (on) lds_dma16_s(i_base, i_off[i], lds_base + i_stage * C::kStageBytes + (wave * C::IPW + i) * 1024);
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
 
   // ---- fragments
   bf16x8_t af[2][4], bfr[2][4];
-  auto frag = [&](int stage, int ks, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) {
+  auto frag = [&](int stage, int ks, bf16x8_t(&fa)[4], bf16x8_t(&fb)[4]) __attribute__((always_inline)) {
     const unsigned char* S = lds_raw + stage * C::kStageBytes;
     const int off = ((ks * 2 + (lane >> 5)) ^ frag_swz) * 16;
 #pragma unroll
@@ -229,7 +231,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
 
   for (int tile = worker; tile < total; tile += G) {
     const TileRef t = locate_tile(a, pre, tile, n_ftiles, C::BT, C::FEAT);
-    const int nj = min(4, max(0, (t.n_tok - wt * 32 + 63) >> 6));  // MFMA columns of this wave that hold tokens
+    // MFMA columns of this wave that hold tokens (the others are computed on clamped rows and never stored:
+    // skipping their MFMAs was measured to gain nothing, the loop is bound by the loads)
+    const int nj = min(4, max(0, (t.n_tok - wt * 32 + 63) >> 6));
     f32x16_t acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -238,16 +242,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // the K loop in two copies: tiles full of tokens run without any test around the MFMAs
-    auto k_loop = [&](auto full_tag) {
-    constexpr bool FULL = decltype(full_tag)::value;
     for (int it = 0; it < nk; ++it) {
       const int n_stage = (c_stage + 1 == NSTAGE) ? 0 : c_stage + 1;
-#pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks) {
+      // one k-step; the k-step index is a compile-time constant (a pragma-unrolled loop over it was left partly
+      // rolled by the compiler, which turns the fragment buffers into scratch memory)
+      auto k_step = [&](auto ks_tag) __attribute__((always_inline)) {
+        constexpr int ks = decltype(ks_tag)::value;
         constexpr int kLast = C::KS - 1;
-        const int cur = ks & 1;  // KS is even: k-step 0 of a slice always finds its fragments in buffer 0
-        if (ks == kLast) {
+        constexpr int cur = ks & 1;  // KS is even: k-step 0 of a slice always finds its fragments in buffer 0
+        if constexpr (ks == kLast) {
           // this wave's reads of the current slice are complete once this k-step's fragments have arrived
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           // its share of the next slice has landed; younger slices may stay in flight (all of them were
@@ -264,10 +267,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            if (FULL || j < nj)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
             // position in the load stream = MFMAs since the barrier (the last k-step comes first after it)
-            const int m = ((ks == kLast) ? 0 : (ks + 1) * 16) + j * 4 + i;
+            const int m = ((ks == kLast) ? 0 : (ks + 1) * 16) + j * 4 + i;  // constant after unrolling
             if (m % DMA_EVERY == DMA_EVERY - 1 && m / DMA_EVERY < C::IPW) {
               switch (m / DMA_EVERY) {   // compile-time after unrolling
 #define SEMMOE_W4_CASE(n) case n: if constexpr (n < C::IPW) i_issue(std::integral_constant<int, n>{}); break;
@@ -282,11 +284,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
             __builtin_amdgcn_sched_barrier(0);
           }
         }
+      };
+      k_step(std::integral_constant<int, 0>{});
+      k_step(std::integral_constant<int, 1>{});
+      if constexpr (C::KS == 4) {
+        k_step(std::integral_constant<int, 2>{});
+        k_step(std::integral_constant<int, 3>{});
       }
       c_stage = n_stage;
     }
-    };
-    if (nj == 4) k_loop(std::true_type{}); else k_loop(std::false_type{});
 
     // ---- epilogue: no barrier; the ring already holds the next tile's first slices
     bf16_t* out = static_cast<bf16_t*>(a.out);
@@ -298,7 +304,17 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
       if (j >= nj) break;
 #pragma unroll
       for (int h = 0; h < kPasses; ++h) {
-        __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps the live set of converted values small
+        // One pass at a time.  The accumulators of the pass are pinned to the accumulation registers up to
+        // here: left alone, the compiler moves all 256 of them to vector registers at the end of the K loop, and
+        // the register pressure of that spills the load offsets inside the K loop.
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MODE == kModeSwiglu) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) asm volatile("" : "+a"(acc[i][j]));
+        } else {
+          asm volatile("" : "+a"(acc[2 * h][j]));
+          asm volatile("" : "+a"(acc[2 * h + 1][j]));
+        }
         unsigned char* wp = stg + tok_in * C::kStgRow + half * 8;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {  // block of 32 features inside the pass

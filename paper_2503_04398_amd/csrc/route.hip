@@ -43,6 +43,36 @@ __device__ __forceinline__ float wave_max(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Selection scores are compared as integers: key(x) orders like x (and -0 like +0), integer max needs no NaN
+// canonicalisation, and the row-shift folds into the max instruction.  key is its own inverse.
+__device__ __forceinline__ int to_key(float x) {
+  const int b = __float_as_int(x + 0.0f);
+  return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float from_key(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i32(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// One instruction per step: v_max_i32 with the row shift / broadcast applied to its first source.  Lanes
+// whose shifted source does not exist are disabled by the DPP rules and keep their value.  The two wait states
+// that a DPP read needs after a vector-ALU write of the same register are written out (s_nop 1).
+#define SEMMOE_DPP_MAX(ctrl) \
+  asm volatile("s_nop 1\n\tv_max_i32_dpp %0, %0, %0 " ctrl " row_mask:0xf bank_mask:0xf" : "+v"(v))
+__device__ __forceinline__ int wave_max_key(int v) {
+  SEMMOE_DPP_MAX("row_shr:1");
+  SEMMOE_DPP_MAX("row_shr:2");
+  SEMMOE_DPP_MAX("row_shr:4");
+  SEMMOE_DPP_MAX("row_shr:8");
+  SEMMOE_DPP_MAX("row_bcast:15");
+  SEMMOE_DPP_MAX("row_bcast:31");
+  asm volatile("s_nop 1" ::: "memory");
+  return __builtin_amdgcn_readlane(v, 63);
+}
+#undef SEMMOE_DPP_MAX
+
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<0x111, 0xf>(0.0f, v);
   v += dpp_f32<0x112, 0xf>(0.0f, v);
@@ -55,156 +85,213 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 constexpr int kNoExpert = 0x7fffffff;
 
-// Selection for one token by one wavefront.  `row` points at the token's E fp32 logits (global or LDS).
-// Lane l holds experts l, l+64, l+128, ...
-template <int NC>
-__device__ __forceinline__ void select_row_nc(const semmoe_config& cfg, const float* row,
-                                              const float* __restrict__ sel_bias, int lane,
-                                              int32_t* __restrict__ ids_out, float* __restrict__ w_out) {
+// Selection for NT tokens by one wavefront, the NT dependent chains of wave-wide reductions interleaved in one
+// instruction stream (a single chain leaves the vector ALU idle most of the time).  rows[t] points at token t's
+// E fp32 logits (global or LDS), nullptr = no token.  Lane l holds experts l, l+64, l+128, ...
+template <int NC, int NT>
+__device__ __forceinline__ void select_rows(const semmoe_config& cfg, const float* const (&rows)[NT],
+                                            const float* __restrict__ sel_bias, int lane,
+                                            int32_t* const (&ids_out)[NT], float* const (&w_out)[NT]) {
   const int E = cfg.E, k = cfg.k;
   const float NEG = -__builtin_inff();
+  const int NEGK = to_key(NEG);
 
-  float val[NC];  // selection score (logit, or s' in sigmoid mode)
-  float aux[NC];  // softmax: logit; sigmoid: s
-  uint32_t live = 0;       // bit c: entry c may still be selected
+  int val[NT][NC];    // key of the selection score (logit, or s' in sigmoid mode)
+  float aux[NT][NC];  // softmax: logit; sigmoid: s
+  uint32_t live[NT];  // bit c: entry c may still be selected
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    const int e = lane + 64 * c;
-    val[c] = NEG;
-    aux[c] = 0.0f;
-    if (e < E) {
-      const float x = row[e];
-      if (cfg.score == SEMMOE_SIGMOID) {
-        const float s = sigmoid_exact_seq(x);
-        aux[c] = s;
-        val[c] = __fadd_rn(s, sel_bias ? sel_bias[e] : 0.0f);
-      } else {
-        aux[c] = x;
-        val[c] = x;
+  for (int t = 0; t < NT; ++t) {
+    live[t] = 0;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int e = lane + 64 * c;
+      val[t][c] = NEGK;
+      aux[t][c] = 0.0f;
+      if (e < E && rows[t]) {
+        const float x = rows[t][e];
+        if (cfg.score == SEMMOE_SIGMOID) {
+          const float sg = sigmoid_exact_seq(x);
+          aux[t][c] = sg;
+          val[t][c] = to_key(__fadd_rn(sg, sel_bias ? sel_bias[e] : 0.0f));
+        } else {
+          aux[t][c] = x;
+          val[t][c] = to_key(x);
+        }
+        live[t] |= 1u << c;
       }
-      live |= 1u << c;
     }
   }
 
-  // arg-max over the entries whose bit is set in `mask`: largest value, equal values -> lowest expert id.
+  // arg-max over the entries whose bit is set in mask[t]: largest value, equal values -> lowest expert id.
   // Expert id = lane + 64*c, so among equal values the lowest slot c wins, then the lowest lane.
-  auto wave_argmax = [&](uint32_t mask, float* vmax) -> int {
-    float m = NEG;
+  // No entry at all: kNoExpert and -inf.
+  auto wave_argmax = [&](const uint32_t(&mask)[NT], int(&vmax)[NT], int(&arg)[NT]) {
+    int m[NT];
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
-      if ((mask >> c) & 1u) m = fmaxf(m, val[c]);
-    const unsigned long long any = __ballot(mask != 0);
-    if (any == 0ull) {
-      *vmax = NEG;
-      return kNoExpert;
-    }
-    const float wm = wave_max(m);
-    *vmax = wm;
-    int e = kNoExpert;
+    for (int t = 0; t < NT; ++t) {
+      m[t] = NEGK;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const unsigned long long hit = __ballot(((mask >> c) & 1u) && val[c] == wm);
-      if (e == kNoExpert && hit != 0ull) e = (__ffsll((long long)hit) - 1) + 64 * c;
+      for (int c = 0; c < NC; ++c)
+        if ((mask[t] >> c) & 1u) m[t] = max(m[t], val[t][c]);
     }
-    return e;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) vmax[t] = wave_max_key(m[t]);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      int e = kNoExpert;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const unsigned long long hit = __ballot(((mask[t] >> c) & 1u) && val[t][c] == vmax[t]);
+        if (e == kNoExpert && hit != 0ull) e = (__ffsll((long long)hit) - 1) + 64 * c;
+      }
+      arg[t] = e;
+    }
   };
 
   if (cfg.score == SEMMOE_SIGMOID && cfg.n_group > 1) {
     // group score = sum of the group's two largest s'; keep the topk_group best groups
     const int gs = E / cfg.n_group;
-    float my_gscore = NEG;  // lane g holds the score of group g
+    int my_gscore[NT];  // lane g holds the key of the score of group g
+#pragma unroll
+    for (int t = 0; t < NT; ++t) my_gscore[t] = NEGK;
     for (int g = 0; g < cfg.n_group; ++g) {
-      uint32_t in_g = 0;
+      uint32_t in_g[NT];
+      uint32_t base = 0;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         const int e = lane + 64 * c;
-        if (e < E && e / gs == g) in_g |= 1u << c;
+        if (e < E && e / gs == g) base |= 1u << c;
       }
-      float v1, v2;
-      const int e1 = wave_argmax(in_g, &v1);
-      if (e1 != kNoExpert && (e1 & 63) == lane) in_g &= ~(1u << (e1 >> 6));
-      const int e2 = wave_argmax(in_g, &v2);
-      const float sc = (e2 == kNoExpert) ? v1 : __fadd_rn(v1, v2);
-      if (lane == g) my_gscore = sc;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) in_g[t] = base & live[t];
+      int v1[NT], v2[NT];
+      int e1[NT], e2[NT];
+      wave_argmax(in_g, v1, e1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        if (e1[t] != kNoExpert && (e1[t] & 63) == lane) in_g[t] &= ~(1u << (e1[t] >> 6));
+      wave_argmax(in_g, v2, e2);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const float sc = (e2[t] == kNoExpert) ? from_key(v1[t]) : __fadd_rn(from_key(v1[t]), from_key(v2[t]));
+        if (lane == g) my_gscore[t] = to_key(sc);
+      }
     }
     // the topk_group best groups: lanes hold one group score each (slot 0 only)
-    unsigned long long keep = 0;
-    bool taken = false;
-    for (int r = 0; r < cfg.topk_group; ++r) {
-      const bool cand = lane < cfg.n_group && !taken;
-      const float wm = wave_max(cand ? my_gscore : NEG);
-      const unsigned long long hit = __ballot(cand && my_gscore == wm);
-      const int g = __ffsll((long long)hit) - 1;
-      keep |= 1ull << g;
-      if (lane == g) taken = true;
-    }
-    uint32_t allowed = 0;
+    unsigned long long keep[NT];
+    bool taken[NT];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int e = lane + 64 * c;
-      if (e < E && ((keep >> (e / gs)) & 1ull)) allowed |= 1u << c;
+    for (int t = 0; t < NT; ++t) {
+      keep[t] = 0;
+      taken[t] = false;
     }
-    live &= allowed;
+    for (int r = 0; r < cfg.topk_group; ++r) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const bool cand = lane < cfg.n_group && !taken[t];
+        const int wm = wave_max_key(cand ? my_gscore[t] : NEGK);
+        const unsigned long long hit = __ballot(cand && my_gscore[t] == wm);
+        const int g = __ffsll((long long)hit) - 1;
+        keep[t] |= 1ull << g;
+        if (lane == g) taken[t] = true;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      uint32_t allowed = 0;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int e = lane + 64 * c;
+        if (e < E && ((keep[t] >> (e / gs)) & 1ull)) allowed |= 1u << c;
+      }
+      live[t] &= allowed;
+    }
   }
 
   // k rounds of wave-wide arg-max; lane j keeps the j-th winner
-  int my_id = 0;
-  float my_val = 0.0f;  // softmax: winning logit; sigmoid: s of the winner
-  for (int j = 0; j < k; ++j) {
-    float vm;
-    const int e = wave_argmax(live, &vm);
-    const int owner = e & 63, slot = e >> 6;
-    float a = 0.0f;
+  int my_id[NT];
+  float my_val[NT];  // softmax: winning logit; sigmoid: s of the winner
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
-      if (c == slot) a = aux[c];
-    a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), owner));
-    if (lane == owner) live &= ~(1u << slot);
-    if (lane == j) {
-      my_id = e;
-      my_val = a;
+  for (int t = 0; t < NT; ++t) {
+    my_id[t] = 0;
+    my_val[t] = 0.0f;
+  }
+  for (int j = 0; j < k; ++j) {
+    int vm[NT];
+    int e[NT];
+    wave_argmax(live, vm, e);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int owner = e[t] & 63, slot = e[t] >> 6;
+      float a = 0.0f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+        if (c == slot) a = aux[t][c];
+      a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), owner));
+      if (lane == owner) live[t] &= ~(1u << slot);
+      if (lane == j) {
+        my_id[t] = e[t];
+        my_val[t] = a;
+      }
     }
   }
 
-  float w;
-  if (cfg.score == SEMMOE_SOFTMAX) {
-    const float mx = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val), 0));  // first winner = row max
-    float part = 0.0f;
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
-      if (lane + 64 * c < E) part += expf(aux[c] - mx);
-    const float denom = wave_sum(part);
-    w = (lane < k) ? expf(my_val - mx) / denom : 0.0f;
-    if (cfg.renorm) w = w / wave_sum(w);
-  } else {
-    w = (lane < k) ? my_val : 0.0f;
-    if (cfg.renorm) w = w / wave_sum(w);
-    w *= cfg.routed_scale;
-  }
-  if (lane < k) {
-    ids_out[lane] = my_id;
-    w_out[lane] = w;
+  for (int t = 0; t < NT; ++t) {
+    float w;
+    if (cfg.score == SEMMOE_SOFTMAX) {
+      const float mx = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val[t]), 0));  // first winner = row max
+      float part = 0.0f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+        if (lane + 64 * c < E) part += expf(aux[t][c] - mx);
+      const float denom = wave_sum(part);
+      w = (lane < k) ? expf(my_val[t] - mx) / denom : 0.0f;
+      if (cfg.renorm) w = w / wave_sum(w);
+    } else {
+      w = (lane < k) ? my_val[t] : 0.0f;
+      if (cfg.renorm) w = w / wave_sum(w);
+      w *= cfg.routed_scale;
+    }
+    if (lane < k && rows[t]) {
+      ids_out[t][lane] = my_id[t];
+      w_out[t][lane] = w;
+    }
   }
 }
 
 // NC = experts per lane, chosen from E so that the unrolled loops carry no dead slots
-__device__ __forceinline__ void select_row(const semmoe_config& cfg, const float* row, const float* __restrict__ sel_bias,
-                                           int lane, int32_t* __restrict__ ids_out, float* __restrict__ w_out) {
-  if (cfg.E <= 64) select_row_nc<1>(cfg, row, sel_bias, lane, ids_out, w_out);
-  else if (cfg.E <= 128) select_row_nc<2>(cfg, row, sel_bias, lane, ids_out, w_out);
-  else if (cfg.E <= 256) select_row_nc<4>(cfg, row, sel_bias, lane, ids_out, w_out);
-  else select_row_nc<8>(cfg, row, sel_bias, lane, ids_out, w_out);
+template <int NT>
+__device__ __forceinline__ void select_rows_any(const semmoe_config& cfg, const float* const (&rows)[NT],
+                                                const float* __restrict__ sel_bias, int lane,
+                                                int32_t* const (&ids_out)[NT], float* const (&w_out)[NT]) {
+  if (cfg.E <= 64) select_rows<1, NT>(cfg, rows, sel_bias, lane, ids_out, w_out);
+  else if (cfg.E <= 128) select_rows<2, NT>(cfg, rows, sel_bias, lane, ids_out, w_out);
+  else if (cfg.E <= 256) select_rows<4, NT>(cfg, rows, sel_bias, lane, ids_out, w_out);
+  else select_rows<8, NT>(cfg, rows, sel_bias, lane, ids_out, w_out);
 }
+
+constexpr int kSelTokens = 2;  // tokens a wave selects for at a time
 
 __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, const float* __restrict__ logits,
                                                           const float* __restrict__ sel_bias,
                                                           int32_t* __restrict__ topk_ids,
                                                           float* __restrict__ topk_w) {
   const int lane = threadIdx.x & 63;
-  const int token = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (token >= cfg.T) return;  // whole wave leaves together
-  select_row(cfg, logits + size_t(token) * cfg.E, sel_bias, lane, topk_ids + size_t(token) * cfg.k,
-             topk_w + size_t(token) * cfg.k);
+  const int token0 = (blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * kSelTokens;
+  if (token0 >= cfg.T) return;  // whole wave leaves together
+  const float* rows[kSelTokens];
+  int32_t* ids_out[kSelTokens];
+  float* w_out[kSelTokens];
+#pragma unroll
+  for (int t = 0; t < kSelTokens; ++t) {
+    const int token = token0 + t;
+    const bool ok = token < cfg.T;
+    rows[t] = ok ? logits + size_t(token) * cfg.E : nullptr;
+    ids_out[t] = ok ? topk_ids + size_t(token) * cfg.k : nullptr;
+    w_out[t] = ok ? topk_w + size_t(token) * cfg.k : nullptr;
+  }
+  select_rows_any<kSelTokens>(cfg, rows, sel_bias, lane, ids_out, w_out);
 }
 
 // Fused router for bf16: logits of TT*32 tokens x all experts, then the selection, in one kernel.
@@ -279,13 +366,17 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       }
     };
 
-    f32x16_t acc[TF][TT];
+    // two accumulator sets (even / odd k-steps): halves the chain of dependent MFMAs inside a slice
+    f32x16_t acc[TF][TT], acc2[TF][TT];
 #pragma unroll
     for (int i = 0; i < TF; ++i)
 #pragma unroll
       for (int j = 0; j < TT; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) {
+          acc[i][j][r] = 0.0f;
+          acc2[i][j][r] = 0.0f;
+        }
 
 #pragma unroll
     for (int s0 = 0; s0 < NSTAGE - 1; ++s0)
@@ -303,21 +394,32 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       const unsigned char* Xs = Ws + C::BW * C::RB;
       const unsigned char* wrow = Ws + (wave * TF * 32 + lrow) * C::RB;
       const unsigned char* xrow = Xs + lrow * C::RB;
+      // all fragment reads of the slice are requested before the first MFMA (the per-slice work is small: the
+      // loop is bound by latencies, not by throughput)
+      bf16x8_t af[4][TF], bfr[4][TT];
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
         const int off = ((st * 2 + half) ^ frag_swz) * 16;
-        bf16x8_t af[TF], bfr[TT];
 #pragma unroll
-        for (int i = 0; i < TF; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::RB + off);
+        for (int i = 0; i < TF; ++i) af[st][i] = *reinterpret_cast<const bf16x8_t*>(wrow + i * 32 * C::RB + off);
 #pragma unroll
-        for (int j = 0; j < TT; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::RB + off);
+        for (int j = 0; j < TT; ++j) bfr[st][j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::RB + off);
+      }
+#pragma unroll
+      for (int st = 0; st < 4; st += 2) {
 #pragma unroll
         for (int i = 0; i < TF; ++i)
 #pragma unroll
-          for (int j = 0; j < TT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < TT; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st][i], bfr[st][j], acc[i][j], 0, 0, 0);
+            acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st + 1][i], bfr[st + 1][j], acc2[i][j], 0, 0, 0);
+          }
       }
     }
+#pragma unroll
+    for (int i = 0; i < TF; ++i)
+#pragma unroll
+      for (int j = 0; j < TT; ++j) acc[i][j] += acc2[i][j];
     __syncthreads();  // every wave is done with the ring: its first bytes now hold the logits
 
 #pragma unroll
@@ -342,10 +444,20 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       }
     }
     __syncthreads();
-    for (int tl = wave; tl < C::BT; tl += 4) {
-      const int tok = tok0 + tl;
-      if (tok < T)
-        select_row(cfg, lg + tl * ldl, sel_bias, lane, topk_ids + size_t(tok) * cfg.k, topk_w + size_t(tok) * cfg.k);
+    for (int tl0 = wave; tl0 < C::BT; tl0 += 4 * kSelTokens) {
+      const float* rows[kSelTokens];
+      int32_t* ids_out[kSelTokens];
+      float* w_out[kSelTokens];
+#pragma unroll
+      for (int t = 0; t < kSelTokens; ++t) {
+        const int tl = tl0 + 4 * t;
+        const int tok = tok0 + tl;
+        const bool ok = tl < C::BT && tok < T;
+        rows[t] = ok ? lg + tl * ldl : nullptr;
+        ids_out[t] = ok ? topk_ids + size_t(tok) * cfg.k : nullptr;
+        w_out[t] = ok ? topk_w + size_t(tok) * cfg.k : nullptr;
+      }
+      select_rows_any<kSelTokens>(cfg, rows, sel_bias, lane, ids_out, w_out);
     }
     __syncthreads();  // the next tile's loads overwrite the logits
   }
@@ -368,7 +480,7 @@ static int32_t launch_select(const semmoe_config* cfg, hipStream_t stream, const
                              const float* sel_bias, int32_t* topk_ids, float* topk_w) {
   if (cfg->T == 0) return SEMMOE_OK;
   const int waves_per_block = 4;
-  hipLaunchKernelGGL(select_topk_kernel, dim3(cdiv(cfg->T, waves_per_block)), dim3(64 * waves_per_block), 0, stream,
+  hipLaunchKernelGGL(select_topk_kernel, dim3(cdiv(cfg->T, waves_per_block * kSelTokens)), dim3(64 * waves_per_block), 0, stream,
                      *cfg, logits, sel_bias, topk_ids, topk_w);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;

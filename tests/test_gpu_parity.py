@@ -374,8 +374,9 @@ def test_every_gemm_tile_shape_on_a_ragged_problem(tile):
         m.set_tuning(1, -1)
 
 
-@pytest.mark.parametrize("tile,grid_cap,split", [(20, -1, -1), (21, -1, -1), (16, -1, -1), (20, 3, -1), (21, 5, -1),
-                                                 (21, 1, 0), (16, 7, -1), (20, 4, 0), (16, 2, 0)])
+@pytest.mark.parametrize("tile,grid_cap,split", [(20, -1, -1), (21, -1, -1), (22, -1, -1), (16, -1, -1), (20, 3, -1),
+                                                 (22, 5, -1), (21, 1, 0), (16, 7, -1), (22, 4, 0), (16, 2, 0),
+                                                 (22, 1, 16), (20, 6, 3)])
 def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
     """the 256 x 256 kernels: groups of several token tiles with a ragged last one, a partial feature tile
     (F = 192 against 128 per tile), K a multiple of 64; grid_cap: few workgroups, so that each walks many tiles
