@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--device-weights", action="store_true",
                     help="draw the expert weights on the device (seeded torch generator) instead of the numpy "
                          "generator: for quick looks at the big workloads; the CPU baseline is then skipped")
+    ap.add_argument("--zero-weights", action="store_true",
+                    help="diagnostic: expert weights all zero (same launches, tiles and bytes; shows how much of the GEMM "
+                         "time depends on the data values, i.e. on power-limited clocks); the CPU baseline is skipped")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times before the timed loops: under rocprofv3 "
                          "--pmc its FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
@@ -103,7 +106,11 @@ def main():
     cb = up(WL.class_bias(w))
     W_gu = torch.empty(E, 2 * F, d, dtype=adt, device=dev)
     W_down = torch.empty(E, d, F, dtype=adt, device=dev)
-    if args.device_weights:
+    if args.zero_weights:
+        W_gu.zero_()
+        W_down.zero_()
+        args.no_cpu = True
+    elif args.device_weights:
         g = torch.Generator(device=dev)
         g.manual_seed(w.seed + 17)
         for e in range(E):
@@ -217,7 +224,8 @@ def main():
 
     # ---------------- algorithmic bytes / flops per launch
     alg = {
-        "route": ("hbm", T * d * b + E * d * b + T * k * 8 + 2 * 4 * T * E),
+        # the bf16 router is one fused kernel (logits never leave the chip); fp32 writes and re-reads them
+        "route": ("hbm", T * d * b + E * d * b + T * k * 8 + (0 if w.dtype == "bf16" else 2 * 4 * T * E)),
         "reshuffle": ("hbm", T * k * 4 + E * 4 + 3 * T * 4),
         "dispatch_index": ("hbm", 2 * T * k * 4 + 2 * T * 4 + 2 * P * 4),
         "dispatch_rows": ("hbm", (T + P) * d * b + P * 4),
@@ -245,7 +253,8 @@ def main():
             traffic = None
     roofline = dict(roof[dominant])
     roofline.pop("ms")
-    roofline.update({"kernel": dominant, "traffic": traffic})
+    roofline.update({"kernel": dominant + (" (gate/up + SwiGLU and down grouped GEMMs, head and tail launches)"
+                                           if dominant == "expert_ffn" else ""), "traffic": traffic})
 
     out = {
         "metric": "MoE-layer tokens/s on 1 MI355X",
