@@ -58,6 +58,35 @@ def cpu_baseline(w, n_tokens):
                       "reshuffle, dispatch, rank-0 expert FFN, combine), %.1f s" % (n_tokens, dt)}
 
 
+def achievable_peaks(m, torch, dev):
+    """what this chip sustains on a plain device copy and on an MFMA-only loop (library probes), live"""
+    def timed(fn, n):
+        fn(); fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+    nbytes = 512 << 20   # read + written: 1 GiB, four times the Infinity Cache
+    src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    t_copy = timed(lambda: m.probe_copy(dst, src, nbytes), 10)
+    sink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+    out = {"hbm_copy_GBps": round(2 * nbytes / t_copy / 1e9, 1)}
+    iters = 20000
+    for name, ops in (("constant", torch.ones(256 * 1024, dtype=torch.bfloat16, device=dev)),
+                      ("random", torch.randn(256 * 1024, device=dev).to(torch.bfloat16))):
+        flops = [0.0]
+        def run():
+            flops[0] = m.probe_mfma(ops, iters, sink)
+        t = timed(run, 5)
+        out["mfma_only_%s_operands_TFLOPs" % name] = round(flops[0] / t / 1e12, 1)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -279,6 +308,7 @@ def main():
                        "place(host)": round(t_place * 1e3, 3)},
         "device": torch.cuda.get_device_name(0),
     }
+    out["achievable"] = achievable_peaks(m, torch, dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_sample, T))
     print(json.dumps(out))

@@ -224,6 +224,19 @@ int32_t semmoe_shared_ffn(const semmoe_config* cfg, void* stream, const void* X,
 int32_t semmoe_combine(const semmoe_config* cfg, void* stream, const void* Y, const int32_t* slot_of_pair,
                        const float* topk_w, const void* Y_shared, void* Out);
 
+/*
+ * Probes of what the chip sustains, for reading roofline fractions against (not part of the layer; no passage of
+ * the paper).  Both enqueue one kernel on `stream`; the caller times it.
+ *   semmoe_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte aligned, bytes % 16 == 0; moves
+ *     2*bytes through HBM.
+ *   semmoe_probe_mfma: 256 workgroups of 4 waves, each wave 16 independent 32x32x16 bf16 MFMAs per iteration on operand
+ *     fragments read once from `operands` (device, 64 sets x 8 fragments x 64 lanes x 16 bytes = 512 KiB, any finite
+ *     bf16 values: the data decide the power drawn and so the clock); `sink` (device, 256*256 floats) receives
+ *     checksums; *flops_out (host, may be NULL) = flops of the launch.
+ */
+int32_t semmoe_probe_copy(void* stream, void* dst, const void* src, size_t bytes);
+int32_t semmoe_probe_mfma(void* stream, const void* operands, int32_t iters, float* sink, double* flops_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -86,6 +86,8 @@ _SIGS = {
     "semmoe_expert_ffn": ([_P, _P, C.c_int32] + [_P] * 7 + [C.c_size_t], C.c_int32),
     "semmoe_shared_ffn": ([_P, _P, _P, C.c_int32, _P, _P, _P, _P, C.c_size_t], C.c_int32),
     "semmoe_combine": ([_P] * 7, C.c_int32),
+    "semmoe_probe_copy": ([_P, _P, _P, C.c_size_t], C.c_int32),
+    "semmoe_probe_mfma": ([_P, _P, C.c_int32, _P, C.POINTER(C.c_double)], C.c_int32),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -226,6 +228,16 @@ class SemMoE:
         self._check("semmoe_shared_ffn", self.lib.semmoe_shared_ffn(
             C.byref(c), _stream(), _ptr(X), int(n_tokens), _ptr(W_gu_sh), _ptr(W_down_sh), _ptr(Y_shared),
             _ptr(self.ws), self.ws_bytes))
+
+    def probe_copy(self, dst, src, nbytes):
+        self._check("semmoe_probe_copy", self.lib.semmoe_probe_copy(_stream(), _ptr(dst), _ptr(src), int(nbytes)))
+
+    def probe_mfma(self, operands, iters, sink):
+        """returns the flops of the launch"""
+        fl = C.c_double(0.0)
+        self._check("semmoe_probe_mfma", self.lib.semmoe_probe_mfma(_stream(), _ptr(operands), int(iters), _ptr(sink),
+                                                                    C.byref(fl)))
+        return fl.value
 
     def combine(self, Y, slot_of_pair, topk_w, Out, Y_shared=None):
         c = self._cfg()

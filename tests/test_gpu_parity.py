@@ -397,3 +397,19 @@ def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
     finally:
         for key in (0, 1, 4, 5):
             m.set_tuning(key, -1)
+
+
+def test_probes_copy_and_mfma_loop():
+    """the two probes bench.py reads achievable rates from: the copy copies, the MFMA loop's checksum is the exact sum"""
+    m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
+    src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device=H.DEV)
+    dst = torch.zeros_like(src)
+    m.probe_copy(dst, src, src.numel())
+    ops = torch.ones(256 * 1024, dtype=torch.bfloat16, device=H.DEV)
+    sink = torch.zeros(256 * 256, dtype=torch.float32, device=H.DEV)
+    flops = m.probe_mfma(ops, 3, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    assert flops == 256 * 4 * 16 * 3 * 2.0 * 32 * 32 * 16
+    # all-ones operands: every accumulator element is 16 per MFMA; a lane sums 16 tiles x 16 elements
+    assert (H.to_np(sink) == 3 * 16.0 * 256).all()
