@@ -80,12 +80,14 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *     value/16 of a round is left over (default 8); 0 = always one launch
  *   SEMMOE_TUNE_GRID_CAP: most workgroups a grouped GEMM launches (default: compute units x blocks per CU)
  *   SEMMOE_TUNE_INDEX_PATH: which implementation of the index kernels runs (default: single workgroup for
- *     T <= 2048, several workgroups above; the single-workgroup kernels hold at most T = 32768); both give identical results
+ *     T <= 2048; above, two launches per call in which every workgroup derives its prefixes from the table of
+ *     per-workgroup counts, up to T = 131072; beyond, one kernel per phase); the single-workgroup kernels hold at
+ *     most T = 32768; all give identical results
  */
 #define SEMMOE_TUNE_GATEUP_TILE 0
 #define SEMMOE_TUNE_DOWN_TILE 1
 #define SEMMOE_TUNE_BLOCKS_PER_CU 2
-#define SEMMOE_TUNE_INDEX_PATH 3 /* reshuffle / dispatch index: 1 = multi-workgroup kernels, 2 = single workgroup */
+#define SEMMOE_TUNE_INDEX_PATH 3 /* reshuffle / dispatch index: 1 = one kernel per phase, 2 = single workgroup, 3 = two launches */
 #define SEMMOE_TUNE_HEAD_TAIL 5  /* 0: one launch per GEMM; default: big tiles for the full rounds + quarter tiles */
 #define SEMMOE_TUNE_GRID_CAP 4   /* upper limit of the persistent GEMM grids (tests: many tiles per workgroup) */
 int32_t semmoe_set_tuning(int32_t key, int32_t value);

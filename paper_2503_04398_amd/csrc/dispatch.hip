@@ -14,6 +14,7 @@ constexpr int kWords = kTokBlock / 32;
 struct DispatchWs {
   int32_t* cnt;        // [NB][E]    per-block pair counts per physical expert -> base slot after the scan
   uint32_t* send_part; // [NB][D*D]  per-block send matrices
+  uint32_t* remote_part;  // [NB]    per-block pairs whose expert sits on another rank than the token
 };
 
 __device__ __forceinline__ int bitmap_rank(const uint32_t* words, int t) {
@@ -61,21 +62,28 @@ __global__ __launch_bounds__(kTokBlock) void dp_count_kernel(int T, int k, int E
                                                              const int32_t* __restrict__ token_rank,
                                                              const int32_t* __restrict__ shf,
                                                              const int32_t* __restrict__ phys, DispatchWs w) {
-  extern __shared__ uint32_t lds[];  // [E][kWords] bitmaps, [D*D] send counts
+  extern __shared__ uint32_t lds[];  // [E][kWords] bitmaps, [D*D] send counts, [1] remote pairs
   uint32_t* bm = lds;
   uint32_t* send = lds + E * kWords;
-  for (int x = threadIdx.x; x < D * D; x += blockDim.x) send[x] = 0;
+  for (int x = threadIdx.x; x < D * D + 1; x += blockDim.x) send[x] = 0;
   int q[SEMMOE_MAX_K];
   const int tok = fill_bitmaps(T, k, E, ids, shf, phys, bm, q);
+  int remote = 0;
   if (tok >= 0) {
     const int s = token_rank[tok];
     const int m = E / D;
     if ((unsigned)s < (unsigned)D) {
 #pragma unroll
       for (int j = 0; j < SEMMOE_MAX_K; ++j)
-        if (q[j] >= 0) atomicAdd(&send[s * D + q[j] / m], 1u);
+        if (q[j] >= 0) {
+          atomicAdd(&send[s * D + q[j] / m], 1u);
+          remote += (q[j] / m != s);
+        }
     }
   }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) remote += __shfl_xor(remote, o);
+  if ((threadIdx.x & 63) == 0 && remote) atomicAdd(&send[D * D], (uint32_t)remote);
   for (int x = threadIdx.x; x < E; x += blockDim.x) {
     int c = 0;
 #pragma unroll
@@ -84,6 +92,7 @@ __global__ __launch_bounds__(kTokBlock) void dp_count_kernel(int T, int k, int E
   }
   __syncthreads();
   for (int x = threadIdx.x; x < D * D; x += blockDim.x) w.send_part[size_t(blockIdx.x) * D * D + x] = send[x];
+  if (threadIdx.x == 0) w.remote_part[blockIdx.x] = send[D * D];
 }
 
 // D2: expert_offsets, rank_offsets, slot base of (block, expert) relative to the expert's first slot,
@@ -140,6 +149,95 @@ __global__ __launch_bounds__(kTokBlock) void dp_slot_kernel(int T, int k, int E,
     pair_of_slot[slot] = pair;
   }
 }
+
+// D2 + D3 in one launch: every workgroup sums the [NB][E] count table itself (column totals -> expert offsets,
+// prefix over the workgroups before it -> its base inside each expert) instead of waiting for a scan kernel;
+// the entries of the send matrix are summed by the workgroups in turn; workgroup 0 writes the offsets and the
+// remote-pair count.
+__global__ __launch_bounds__(kTokBlock) void dp_fused_kernel(int T, int k, int E, int D, int NB,
+                                                             const int32_t* __restrict__ ids,
+                                                             const int32_t* __restrict__ shf,
+                                                             const int32_t* __restrict__ phys,
+                                                             int32_t* __restrict__ slot_of_pair,
+                                                             int32_t* __restrict__ pair_of_slot,
+                                                             int32_t* __restrict__ expert_offsets,
+                                                             int32_t* __restrict__ rank_offsets,
+                                                             uint32_t* __restrict__ send_matrix,
+                                                             unsigned long long* __restrict__ remote_pairs,
+                                                             DispatchWs w) {
+  extern __shared__ uint32_t lds[];  // [E][kWords] bitmaps | off[E+1] | pre[E] | remote (u64, 8-byte aligned)
+  uint32_t* bm = lds;
+  int32_t* off = reinterpret_cast<int32_t*>(lds + E * kWords);
+  int32_t* pre = off + (E + 1);
+  unsigned long long* remote_sh = reinterpret_cast<unsigned long long*>(
+      (reinterpret_cast<uintptr_t>(pre + E) + 7) & ~uintptr_t(7));
+  const int t = threadIdx.x, b = blockIdx.x;
+  for (int x = t; x < 2 * E + 1; x += kTokBlock) off[x] = 0;
+  if (t == 0) *remote_sh = 0ull;
+  __syncthreads();
+  for (int base = t; base < NB * E; base += 8 * kTokBlock) {  // eight loads in flight per thread
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * kTokBlock;
+      v[u] = idx < NB * E ? w.cnt[idx] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (v[u] == 0) continue;
+      const int idx = base + u * kTokBlock;
+      const int bb = idx / E, e = idx - bb * E;
+      atomicAdd(&off[e], v[u]);  // integer sums: the order does not matter
+      if (bb < b) atomicAdd(&pre[e], v[u]);
+    }
+  }
+  // send matrix: entry x is summed over the workgroups' partial matrices by workgroup x % NB
+  const int DD = D * D;
+  for (int x = b; x < DD; x += NB) {
+    uint32_t part = 0;
+    for (int bb = t; bb < NB; bb += kTokBlock) part += w.send_part[size_t(bb) * DD + x];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
+    if ((t & 63) == 0 && part) atomicAdd(remote_sh, (unsigned long long)part);  // reused as the entry's accumulator
+    __syncthreads();
+    if (t == 0) {
+      send_matrix[x] = (uint32_t)*remote_sh;
+      *remote_sh = 0ull;
+    }
+    __syncthreads();
+  }
+  if (b == 0) {  // remote pairs: sum of the workgroups' counts
+    unsigned long long part = 0;
+    for (int bb = t; bb < NB; bb += kTokBlock) part += w.remote_part[bb];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
+    if ((t & 63) == 0 && part) atomicAdd(remote_sh, part);
+  }
+  __syncthreads();
+  wave_exclusive_scan_lds(off, E);  // ends with a barrier
+  if (b == 0) {
+    const int m = E / D;
+    for (int q = t; q <= E; q += kTokBlock) {
+      expert_offsets[q] = off[q];
+      if (q % m == 0) rank_offsets[q / m] = off[q];
+    }
+    if (t == 0) *remote_pairs = *remote_sh;
+  }
+  int q[SEMMOE_MAX_K];
+  const int tok = fill_bitmaps(T, k, E, ids, shf, phys, bm, q);
+  if (tok < 0) return;
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+    if (q[j] < 0) continue;
+    const int slot = off[q[j]] + pre[q[j]] + bitmap_rank(bm + q[j] * kWords, t);
+    const int pair = tok * k + j;
+    slot_of_pair[pair] = slot;
+    pair_of_slot[slot] = pair;
+  }
+}
+
+static size_t dp_fused_lds(int E) { return size_t(E) * kWords * 4 + size_t(2 * E + 1) * 4 + 16; }
+constexpr int kFusedMaxNB = 512;  // beyond, every block reading the whole table costs more than the scan kernel
 
 // Single-workgroup variant of the index half for T <= kSingleMaxT (one launch instead of three; small
 // kernels cost a fixed few microseconds each).  Positions are walked in chunks of 1024 in shuffled order.
@@ -291,12 +389,13 @@ static bool carve_dispatch(const semmoe_config* cfg, void* ws, size_t bytes, Dis
   Carver c(ws, bytes);
   w->cnt = c.take<int32_t>(NB * cfg->E);
   w->send_part = c.take<uint32_t>(NB * cfg->D * cfg->D);
+  w->remote_part = c.take<uint32_t>(NB);
   return c.ok;
 }
 
 size_t ws_dispatch(const semmoe_config* cfg) {
   const size_t NB = cdiv(cfg->T, kTokBlock);
-  return align_up(NB * cfg->E * 4, 256) + align_up(NB * cfg->D * cfg->D * 4, 256) + 512;
+  return align_up(NB * cfg->E * 4, 256) + align_up(NB * cfg->D * cfg->D * 4, 256) + align_up(NB * 4, 256) + 512;
 }
 
 }  // namespace semmoe
@@ -328,8 +427,15 @@ static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, cons
     return SEMMOE_OK;
   }
   if (NB > 0) {
-    hipLaunchKernelGGL(dp_count_kernel, dim3(NB), dim3(kTokBlock), (E * kWords + D * D) * 4, s, T, k, E, D, topk_ids,
+    hipLaunchKernelGGL(dp_count_kernel, dim3(NB), dim3(kTokBlock), (E * kWords + D * D + 1) * 4, s, T, k, E, D, topk_ids,
                        token_rank, shf, phys_of_expert, w);
+  }
+  if (NB > 0 && ((path != 1 && NB <= kFusedMaxNB) || path == 3)) {
+    hipLaunchKernelGGL(dp_fused_kernel, dim3(NB), dim3(kTokBlock), dp_fused_lds(E), s, T, k, E, D, NB, topk_ids, shf,
+                       phys_of_expert, slot_of_pair, pair_of_slot, expert_offsets, rank_offsets, send_matrix,
+                       reinterpret_cast<unsigned long long*>(remote_pairs), w);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
   }
   hipLaunchKernelGGL(dp_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, E, D, expert_offsets, rank_offsets, send_matrix,
                      reinterpret_cast<unsigned long long*>(remote_pairs), w);

@@ -224,6 +224,172 @@ __global__ __launch_bounds__(kTokBlock) void rs_scatter_kernel(int T, int D, con
 }
 
 // ------------------------------------------------------------------------------------------------
+// Two-launch variant: rs_pref_kernel, then this kernel.  Everything after the per-block (pref, conf) histograms
+// follows from those histograms alone, so every workgroup derives what it needs from the [NB][D*(k+1)] table
+// (its column totals and the prefix over the workgroups before it) instead of waiting for scan kernels:
+//   * thresholds, quotas and free slots per rank from the totals (as rs_threshold_kernel);
+//   * borderline candidates of rank r before this block = prefix[r][thr_r]; the first quota_r of a rank's
+//     borderline candidates (in token order) are kept, so max(0, prefix - quota_r) of them were spilled before
+//     this block, plus every candidate below the threshold: that is the block's first global spill index S_b;
+//   * spilled tokens take the free slots in rank order, so the tokens of rank r that come before this block are
+//     its kept ones (from the prefix) plus |[0, S_b) cut with rank r's range of spill indices|.
+// Five dependent launches fewer; each costs about as much as this whole kernel.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kTokBlock) void rs_fused_kernel(int T, int NB, int k, int D, int cap,
+                                                             int32_t* __restrict__ token_rank,
+                                                             int32_t* __restrict__ shf, int32_t* __restrict__ inv_shf,
+                                                             int32_t* __restrict__ rank_count, ReshuffleWs w) {
+  extern __shared__ int32_t fused_sm[];
+  const int nkeys = D * (k + 1);
+  int32_t* tot = fused_sm;            // [nkeys] column totals
+  int32_t* pre = tot + nkeys;         // [nkeys] totals over the blocks before this one
+  int32_t* thr = pre + nkeys;         // [D]
+  int32_t* quota = thr + D;           // [D]
+  int32_t* free_pre = quota + D;      // [D+1] free slots per rank -> exclusive prefix
+  int32_t* sp_tot = free_pre + D + 1; // [D] spilled candidates of rank r, all blocks
+  int32_t* sp_pre = sp_tot + D;       // [D] ... in the blocks before this one
+  int32_t* kept_tot = sp_pre + D;     // [D] kept candidates of rank r, all blocks
+  int32_t* kept_pre = kept_tot + D;   // [D]
+  int32_t* rstart = kept_pre + D;     // [D+1] first shuffled position of rank r
+  int32_t* rbefore = rstart + D + 1;  // [D] tokens of final rank r in the blocks before this one
+  int32_t* scal = rbefore + D;        // [2] S_b, spill bitmap guard
+  uint32_t* bm = reinterpret_cast<uint32_t*>(scal + 2);  // [D][kWords]
+  uint32_t* spbm = bm + D * kWords;                       // [kWords]
+  const int t = threadIdx.x, b = blockIdx.x;
+
+  for (int x = t; x < 2 * nkeys; x += kTokBlock) tot[x] = 0;
+  for (int x = t; x < D * kWords + kWords; x += kTokBlock) bm[x] = 0;
+  __syncthreads();
+  for (int base = t; base < NB * nkeys; base += 8 * kTokBlock) {  // eight loads in flight per thread
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * kTokBlock;
+      v[u] = idx < NB * nkeys ? w.cnt[idx] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (v[u] == 0) continue;
+      const int idx = base + u * kTokBlock;
+      const int bb = idx / nkeys, key = idx - bb * nkeys;
+      atomicAdd(&tot[key], v[u]);  // integer sums: the order does not matter
+      if (bb < b) atomicAdd(&pre[key], v[u]);
+    }
+  }
+  __syncthreads();
+  if (t < D) {
+    const int r = t;
+    // the confidence level at which rank r's candidates overflow cap is its borderline level (-1: all kept)
+    int cum = 0, th = -1, q = 0;
+    for (int c = k; c >= 0; --c) {
+      const int n = tot[r * (k + 1) + c];
+      if (cum + n > cap) {
+        th = c;
+        q = cap - cum;
+        cum = cap;
+        break;
+      }
+      cum += n;
+    }
+    thr[r] = th;
+    quota[r] = q;
+    free_pre[r] = cap - cum;
+    kept_tot[r] = cum;
+    int st = 0, sp = 0, kp = 0;
+    for (int c = 0; c <= k; ++c) {
+      const int nt = tot[r * (k + 1) + c], np = pre[r * (k + 1) + c];
+      if (th < 0 || c > th) kp += np;
+      else if (c < th) { st += nt; sp += np; }
+      else { st += nt - q; sp += max(0, np - q); kp += min(q, np); }
+    }
+    sp_tot[r] = st;
+    sp_pre[r] = sp;
+    kept_pre[r] = kp;
+  }
+  __syncthreads();
+  if (t < 64) {  // one wave: scans over the D <= 64 ranks
+    const int r = t;
+    const int fr = r < D ? free_pre[r] : 0;
+    int incl = fr, s_tot = r < D ? sp_tot[r] : 0, s_b = r < D ? sp_pre[r] : 0;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int u = __shfl_up(incl, off);
+      if (t >= off) incl += u;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      s_tot += __shfl_xor(s_tot, off);
+      s_b += __shfl_xor(s_b, off);
+    }
+    const int fpre = incl - fr;  // spill indices [fpre, fpre + fr) land on rank r; the last rank takes any overflow
+    const bool last = r == D - 1;
+    const int a_tot = r < D ? (last ? max(0, s_tot - fpre) : min(max(s_tot - fpre, 0), fr)) : 0;
+    const int a_pre = r < D ? (last ? max(0, s_b - fpre) : min(max(s_b - fpre, 0), fr)) : 0;
+    const int cnt = r < D ? kept_tot[r] + a_tot : 0;
+    int cincl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int u = __shfl_up(cincl, off);
+      if (t >= off) cincl += u;
+    }
+    if (r < D) {
+      free_pre[r] = fpre;
+      rstart[r] = cincl - cnt;
+      rbefore[r] = kept_pre[r] + a_pre;
+      if (b == 0) rank_count[r] = cnt;
+    }
+    if (r == D - 1) free_pre[D] = incl;
+    if (t == 0) scal[0] = s_b;
+  }
+  __syncthreads();
+
+  // keep phase: borderline candidates are ranked inside the block by their bitmap
+  const int i = b * kTokBlock + t;
+  int pref = 0, conf = 0, th = -1;
+  if (i < T) {
+    const int pc = w.pc[i];
+    pref = pc & 0xff;
+    conf = pc >> 8;
+    th = thr[pref];
+    if (th >= 0 && conf == th) atomicOr(&bm[pref * kWords + (t >> 5)], 1u << (t & 31));
+  }
+  __syncthreads();
+  int rank = -1;
+  if (i < T) {
+    bool kept;
+    if (th < 0 || conf > th) kept = true;
+    else if (conf < th) kept = false;
+    else kept = pre[pref * (k + 1) + th] + bitmap_rank(bm + pref * kWords, t) < quota[pref];
+    if (kept) rank = pref;
+    else atomicOr(&spbm[t >> 5], 1u << (t & 31));
+  }
+  __syncthreads();
+  for (int x = t; x < D * kWords; x += kTokBlock) bm[x] = 0;  // the bitmaps now take the final ranks
+  if (i < T && rank < 0) {
+    const int s = scal[0] + bitmap_rank(spbm, t);
+    int r = 0;
+    while (r + 1 < D && free_pre[r + 1] <= s) ++r;  // free_pre[r] <= s < free_pre[r+1]
+    rank = r;
+  }
+  __syncthreads();
+  if (i < T) {
+    token_rank[i] = rank;
+    atomicOr(&bm[rank * kWords + (t >> 5)], 1u << (t & 31));
+  }
+  __syncthreads();
+  if (i < T) {
+    const int pos = rstart[rank] + rbefore[rank] + bitmap_rank(bm + rank * kWords, t);
+    inv_shf[i] = pos;
+    shf[pos] = i;
+  }
+}
+
+static size_t rs_fused_lds(int D, int k) {
+  return (size_t(2) * D * (k + 1) + size_t(D) * 9 + 2 + 2 + size_t(D) * kWords + kWords) * 4;
+}
+constexpr int kFusedMaxNB = 512;  // beyond, every block reading the whole table costs more than the scan kernels
+
+// ------------------------------------------------------------------------------------------------
 // Single-workgroup variant for T <= kSingleMaxT: the whole of rebatch_tokens in one launch, every
 // intermediate in LDS.  Tokens are walked in chunks of 1024 (one per thread) in index order; inside a chunk
 // the stable rank of a token among equal keys is again "popcount of the key's bitmap below the token",
@@ -482,6 +648,13 @@ extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, cons
   }
   hipLaunchKernelGGL(rs_pref_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, cfg->E, per_home, topk_ids,
                      expert_to_rank, w);
+  if ((path != 1 && NB <= kFusedMaxNB) || path == 3) {
+    if (D > 64) return SEMMOE_EUNSUPPORTED;
+    hipLaunchKernelGGL(rs_fused_kernel, dim3(NB), dim3(kTokBlock), rs_fused_lds(D, k), s, T, NB, k, D, cfg->cap,
+                       token_rank, shf, inv_shf, rank_count, w);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
   hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, k, D, cfg->cap, w);
   hipLaunchKernelGGL(rs_keep_kernel, dim3(NB), dim3(kTokBlock), (D * kWords + 1) * 4, s, T, D, token_rank, w);
   hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D + 1) * 4, s, T, D, token_rank, w);

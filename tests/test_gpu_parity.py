@@ -22,7 +22,7 @@ def _say(*a):
     print(*a, flush=True)
 
 
-@pytest.fixture(params=[1, 2], ids=["multi_wg", "single_wg"])
+@pytest.fixture(params=[1, 2, 3], ids=["multi_wg", "single_wg", "two_launch"])
 def index_path(request):
     """run the test with each implementation of the index kernels (reshuffle, dispatch index)"""
     m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
