@@ -71,7 +71,8 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  * Tuning knobs for benchmarks (process-wide, not thread-safe).  value < 0 restores the default, which the
  * library picks per shape.  Results never depend on them beyond fp32 summation order inside a GEMM tile.
  *   SEMMOE_TUNE_GATEUP_TILE / SEMMOE_TUNE_DOWN_TILE: tile-shape id of the bf16 grouped GEMMs
- *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny tiles for decode;
+ *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny register-staged tiles;
+ *     19, 25, 26, 27: skinny tiles with a direct-to-LDS ring for decode;
  *     20, 21, 22: four waves on a 256 x 256 tile with loads placed between the MFMAs; K must be a multiple of the
  *     K slice (32 for 20 and 21, 64 for 22) and hold at least a ring of slices (128); other K run as 16)
  *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs

@@ -96,18 +96,25 @@ static int32_t launch_w4(const GemmArgs& a, int max_rows, hipStream_t stream) {
   return SEMMOE_OK;
 }
 
-// Tail launch of a head/tail split: quarter tiles (128 x 128) of the parent tiles the head launch left over.
+// Tail launch of a head/tail split: the parent tiles (256 x 256) the head launch left over, cut into 128 x 64
+// pieces (weight rows x tokens: 2 along the features, 4 along the tokens), two workgroups per CU with a ring of 3.
+// A piece is a long, thin K loop with little arithmetic per slice: its speed is the bytes it keeps in flight over
+// the latency of a load.  One workgroup per CU with a ring of 6 is faster when few parent tiles are left (config 2:
+// 28 tiles, FFN 256 -> 246 us) and slower when many are (configs 3 and 4: +5 %); the count is only known on the device.
 template <int MODE>
 static int32_t launch_tail(GemmArgs a, int max_rows, int head_grid, hipStream_t stream) {
-  using C = DmaCfg<MODE, 2, 2, 2, 2, 64, 4>;  // deep ring: a quarter tile is a long, thin K loop on a mostly idle chip
-  const int n_ftiles_p = cdiv(a.N, 2 * C::FEAT);
-  const long long bound_p = (long long)(max_rows / (2 * C::BT) + a.nq) * n_ftiles_p;  // parent tiles, at most
+  using C = DmaCfg<MODE, 2, 2, 2, 1, 64, 3>;
+  constexpr int kSubT = 256 / C::BT, kSubF = 256 / C::BW;
+  const int n_ftiles_p = cdiv(a.N, kSubF * C::FEAT);
+  const long long bound_p = (long long)(max_rows / 256 + a.nq) * n_ftiles_p;  // parent tiles, at most
   const long long left_p = bound_p < head_grid ? bound_p : (long long)head_grid * a.sched_thr / 16;  // ... left over
   if (left_p <= 0) return SEMMOE_OK;
   a.sched_mode = 2;
   a.sched_g = head_grid;
-  const int grid = grid_for(left_p * 4, num_cu());
-  auto kern = gemm_bf16_dma_kernel<MODE, 2, 2, 2, 2, 64, 4, 1>;
+  a.sched_sub_t = kSubT;
+  a.sched_sub_f = kSubF;
+  const int grid = grid_for(left_p * kSubT * kSubF, (long long)num_cu() * 2);
+  auto kern = gemm_bf16_dma_kernel<MODE, 2, 2, 2, 1, 64, 3, 1>;
   if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
   static bool attr_set = false;
   if (!attr_set) {
@@ -154,6 +161,10 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
     case 16: return launch_dma<MODE, 2, 4, 4, 2, 64, 2>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 256, K 64 x 2
     case 17: return launch_bf16<MODE, 4, 1, 2, 1, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 32 (decode)
     case 18: return launch_bf16<MODE, 4, 1, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);       // 256 x 64
+    case 19: return launch_dma<MODE, 4, 1, 2, 1, 64, 4>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 32, ring of 4 (decode)
+    case 25: return launch_dma<MODE, 4, 1, 2, 2, 64, 3>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 64, ring of 3
+    case 26: return launch_dma<MODE, 2, 2, 2, 1, 64, 3>(a, max_rows, bpc > 0 ? bpc : 2, s);     // 128 x 64, ring of 3, two per CU
+    case 27: return launch_dma<MODE, 2, 2, 2, 1, 64, 4>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 128 x 64, ring of 4
     default: break;
   }
   if (id >= 20 && id <= 22) {  // four waves, 256 x 256, loads interleaved with the MFMAs
@@ -174,8 +185,7 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
 static int default_tile(int est_rows_per_group) {
   if (est_rows_per_group >= 192) return 22;
   if (est_rows_per_group >= 96) return 0;
-  if (est_rows_per_group >= 48) return 18;
-  return 17;
+  return 26;  // few rows per group (decode): the weights stream through; narrow tiles, deep ring, two per CU
 }
 
 // Head/tail split: for the tile shapes of 256 x 256 with a persistent grid of one workgroup per compute unit.

@@ -36,9 +36,10 @@ struct GemmArgs {
   // full round per workgroup after the other; the tail launch (2) takes the rest as quarter tiles, which fill the
   // chip where the parent tiles of a last, partial round would leave most of it idle.  When more than half a
   // round is left over, the head launch takes the whole list instead (quarter tiles are less efficient).
-  int sched_mode;         // 0: the whole list, 1: head, 2: tail (kernel tile = a quarter of the parent tile)
+  int sched_mode;         // 0: the whole list, 1: head, 2: tail (kernel tile = the parent tile cut sub_t x sub_f ways)
   int sched_g;            // tail: grid size of the head launch
   int sched_thr;          // the split happens when at most sched_thr / 16 of a round is left over
+  int sched_sub_t, sched_sub_f;  // tail: pieces per parent tile along tokens and along features
 };
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -121,21 +122,24 @@ __device__ __forceinline__ void decode_tile(int local, int n_ttiles, int n_ftile
 }
 
 // Walk of one launch over the tile list.  Whole list / head launch: items are the listed tiles up to `total`.
-// Tail launch: items are the quarters of the parent tiles (twice the kernel's tile in both directions) from
-// `cutoff` on.
+// Tail launch: items are the pieces of the parent tiles (sub_t x sub_f kernel tiles each) from `cutoff` on.
 struct TileWalk {
   bool tail;
+  int sub_t, sub_f;
   int n_ftiles_list, bt_list, cutoff, total;
 };
 
 __device__ __forceinline__ TileWalk make_walk(const GemmArgs& a, int* pre, int BT, int FEAT) {
   TileWalk w;
   w.tail = a.sched_mode == 2;
-  w.n_ftiles_list = w.tail ? (a.N + 2 * FEAT - 1) / (2 * FEAT) : (a.N + FEAT - 1) / FEAT;
-  w.bt_list = w.tail ? 2 * BT : BT;
+  w.sub_t = w.tail ? a.sched_sub_t : 1;
+  w.sub_f = w.tail ? a.sched_sub_f : 1;
+  w.n_ftiles_list = (a.N + w.sub_f * FEAT - 1) / (w.sub_f * FEAT);
+  w.bt_list = w.sub_t * BT;
   const int listed = build_tile_prefix(a, w.n_ftiles_list, pre, w.bt_list);
   w.cutoff = w.tail ? head_tiles(listed, a.sched_g, a.sched_thr) : 0;
-  w.total = w.tail ? (listed - w.cutoff) * 4 : (a.sched_mode == 1 ? head_tiles(listed, int(gridDim.x), a.sched_thr) : listed);
+  w.total = w.tail ? (listed - w.cutoff) * w.sub_t * w.sub_f
+                   : (a.sched_mode == 1 ? head_tiles(listed, int(gridDim.x), a.sched_thr) : listed);
   return w;
 }
 
@@ -146,7 +150,8 @@ struct TileAt {
 // false: the item lies outside the matrix (a quarter of a partly filled parent tile); uniform over the workgroup
 __device__ __forceinline__ bool walk_tile(const GemmArgs& a, const TileWalk& w, const int* pre, int item, int BT,
                                           int FEAT, TileAt* t) {
-  const int tile = w.tail ? w.cutoff + (item >> 2) : item;
+  const int pieces = w.sub_t * w.sub_f;
+  const int tile = w.tail ? w.cutoff + item / pieces : item;
   const int q = find_group(pre, a.nq, tile);
   const int local = tile - pre[q];
   const int g_lo = a.offsets ? a.offsets[a.q_lo + q] : 0;
@@ -154,8 +159,9 @@ __device__ __forceinline__ bool walk_tile(const GemmArgs& a, const TileWalk& w, 
   int ft, tt;
   decode_tile(local, (row_hi - g_lo + w.bt_list - 1) / w.bt_list, w.n_ftiles_list, &tt, &ft);
   if (w.tail) {
-    tt = tt * 2 + ((item >> 1) & 1);
-    ft = ft * 2 + (item & 1);
+    const int piece = item % pieces;
+    tt = tt * w.sub_t + piece / w.sub_f;
+    ft = ft * w.sub_f + piece % w.sub_f;
     if (g_lo + tt * BT >= row_hi || ft * FEAT >= a.N) return false;
   }
   t->q = q;
@@ -455,7 +461,7 @@ struct DmaCfg {
   static constexpr size_t kLdsBytes = kTileBytes + 520 * 4;
   static_assert(BK == 32 || BK == 64, "row of 64 or 128 bytes");
   static_assert(IPS % NW == 0, "instructions divide over the waves");
-  static_assert(NSTAGE >= 2 && NSTAGE <= 5, "ring depth");
+  static_assert(NSTAGE >= 2 && NSTAGE <= 6, "ring depth");
   static_assert((NSTAGE - 1) * IPW < 64, "vmcnt range");
   static_assert(MODE != kModeSwiglu || TF % 2 == 0, "gate/up tiles come in pairs");
 };
@@ -544,7 +550,8 @@ __global__ __launch_bounds__(64 * NWF * NWT, MINW) void gemm_bf16_dma_kernel(Gem
     for (int it = 0; it < nk; ++it) {
       // slices it+1 .. min(it+NSTAGE-2, nk-1) were issued after slice `it` and may stay in flight
       const int younger = min(NSTAGE - 2, nk - 1 - it);
-      if (younger >= 3) wait_vmcnt<3 * C::IPW>();
+      if (younger >= 4) wait_vmcnt<4 * C::IPW>();
+      else if (younger == 3) wait_vmcnt<3 * C::IPW>();
       else if (younger == 2) wait_vmcnt<2 * C::IPW>();
       else if (younger == 1) wait_vmcnt<1 * C::IPW>();
       else wait_vmcnt<0>();

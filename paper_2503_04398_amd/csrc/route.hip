@@ -389,7 +389,6 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       else if (younger == 1) wait_vmcnt<1 * C::IPW>();
       else wait_vmcnt<0>();
       __syncthreads();
-      if (it + NSTAGE - 1 < nk) issue(it + NSTAGE - 1);
       const unsigned char* Ws = lds_raw + (it % NSTAGE) * C::kStageBytes;
       const unsigned char* Xs = Ws + C::BW * C::RB;
       const unsigned char* wrow = Ws + (wave * TF * 32 + lrow) * C::RB;
@@ -405,6 +404,10 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
 #pragma unroll
         for (int j = 0; j < TT; ++j) bfr[st][j] = *reinterpret_cast<const bf16x8_t*>(xrow + j * 32 * C::RB + off);
       }
+      // the refill of the stage freed by the barrier goes out while the fragment reads are in flight
+      __builtin_amdgcn_sched_barrier(0);
+      if (it + NSTAGE - 1 < nk) issue(it + NSTAGE - 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int st = 0; st < 4; st += 2) {
 #pragma unroll

@@ -355,7 +355,7 @@ def test_empty_and_degenerate_inputs():
     H.assert_close(Y, Yo, "bf16", "Y")
 
 
-@pytest.mark.parametrize("tile", [0, 3, 4, 6, 11, 12, 14, 15, 16, 17, 18])
+@pytest.mark.parametrize("tile", [0, 3, 4, 6, 11, 12, 14, 15, 16, 17, 18, 19, 25, 26, 27])
 def test_every_gemm_tile_shape_on_a_ragged_problem(tile):
     """each tile shape of the bf16 grouped GEMMs (register-staged, direct-to-LDS ring, skinny), with ragged
     groups, partial K slices (d % 64 = 8, F % 32 = 8) and partial feature tiles"""
