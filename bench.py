@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--device-weights", action="store_true",
                     help="draw the expert weights on the device (seeded torch generator) instead of the numpy "
                          "generator: for quick looks at the big workloads; the CPU baseline is then skipped")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step in a HIP graph and time K replays (reported beside the eager figure)")
     ap.add_argument("--zero-weights", action="store_true",
                     help="diagnostic: expert weights all zero (same launches, tiles and bytes; shows how much of the GEMM "
                          "time depends on the data values, i.e. on power-limited clocks); the CPU baseline is skipped")
@@ -221,6 +223,32 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    ms_graph = None
+    if args.graph:
+        # one step captured in a HIP graph (the library only launches kernels: nothing in it is a memset node), then K
+        # replays; replays are checked against the eager result, with eager work and syncs in between
+        ref = Out.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step()
+        for _ in range(3):
+            Out.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Out, ref), "graph replay differs from the eager step"
+            step()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) / args.steps * 1e3
     # the same K steps again with HIP events (on the stream the kernels run on) between the calls: per-stage
     # times.  The events serialise the host side a little, so this loop is a few percent slower.
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
@@ -300,6 +328,7 @@ def main():
         "roofline": roofline,
         "stages": roof,
         "ms_per_step_with_stage_events": round(ms_evented, 4),
+        "ms_per_step_graph_replay": None if ms_graph is None else round(ms_graph, 4),
         "remote_pair_fraction": {"vanilla_placement_home_ranks": round(int(rp2.item()) / P, 4),
                                  "semmoe_placement_home_ranks": round(int(rp3.item()) / P, 4),
                                  "semmoe_placement_reshuffle": round(remote / P, 4)},

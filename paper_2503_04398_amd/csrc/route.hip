@@ -271,7 +271,7 @@ __device__ __forceinline__ void select_rows_any(const semmoe_config& cfg, const 
   else select_rows<8, NT>(cfg, rows, sel_bias, lane, ids_out, w_out);
 }
 
-constexpr int kSelTokens = 2;  // tokens a wave selects for at a time
+constexpr int kSelTokens = 2;  // tokens a wave selects for at a time (four gain nothing: the selection is bound by instruction issue)
 
 __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, const float* __restrict__ logits,
                                                           const float* __restrict__ sel_bias,
