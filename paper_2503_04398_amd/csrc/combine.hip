@@ -6,6 +6,14 @@
 
 namespace semmoe {
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// streaming read of a 16-byte chunk that no later kernel needs in cache
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <bool BF16, int KU>
 __global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int P, const uint4* __restrict__ Y,
                                                       const int32_t* __restrict__ slot_of_pair,
@@ -29,7 +37,7 @@ __global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int
     uint4 v[KMAX];
 #pragma unroll
     for (int j = 0; j < KMAX; ++j)
-      v[j] = (sl[j] >= 0) ? Y[size_t(sl[j]) * row_chunks + c] : make_uint4(0, 0, 0, 0);
+      v[j] = (sl[j] >= 0) ? load_stream16(&Y[size_t(sl[j]) * row_chunks + c]) : make_uint4(0, 0, 0, 0);
     uint4 sh = make_uint4(0, 0, 0, 0);
     if (Y_shared) sh = Y_shared[size_t(tok) * row_chunks + c];
     if constexpr (BF16) {
