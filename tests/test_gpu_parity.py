@@ -171,6 +171,37 @@ def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit():
         assert (dg[name] == dw[name]).all(), name
 
 
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_index_kernels_on_random_shapes(seed, index_path):
+    """reshuffle + dispatch index on seeded random shapes (ragged T, D up to 64, k up to 16, tight and loose
+    capacity, clustered and noisy routing), every implementation of the index kernels, bit for bit"""
+    r = np.random.default_rng(1000 + seed)
+    D = int(r.choice([1, 2, 4, 8, 16, 32, 64]))
+    m = int(r.choice([1, 2, 4, 8]))
+    E = D * m
+    k = int(min(E, r.choice([1, 2, 4, 8, 16])))
+    T = int(r.integers(1, 6000))
+    cf = float(r.choice([1.0, 1.0, 1.1, 2.0]))
+    noise = float(r.choice([0.0, 0.2, 0.6, 1.0]))
+    _say("index kernels, random shape", dict(T=T, E=E, D=D, k=k, cf=cf, noise=noise), "path", index_path)
+    ids, e2r = _planted(T, E, D, k, seed=seed, noise=noise)
+    phys = np.argsort(np.argsort(e2r, kind="stable"), kind="stable").astype(np.int32)
+    cap = int(math.ceil(cf * T / D))
+    w = WL.small(T=T, E=E, D=D, k=k, d=8)
+    lay = H.Layer(w, cap=cap)
+    lay.set_routing(ids)
+    lay.set_placement(e2r, phys, np.argsort(phys).astype(np.int32))
+    got = lay.reshuffle()
+    want = O.reshuffle(ids, e2r, D, cap)
+    for g, w_, name in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == w_).all(), name
+    dg = lay.dispatch(with_rows=False)
+    dw = O.dispatch(None, ids, want[0], want[2], phys, D)
+    for name in ("slot_of_pair", "pair_of_slot", "expert_offsets", "rank_offsets", "send_matrix"):
+        assert (dg[name] == dw[name]).all(), name
+    assert int(dg["remote_pairs"]) == int(dw["remote_pairs"])
+
+
 # ------------------------------------------------------------------------------------------- dispatch
 @pytest.mark.parametrize("dtype,T,E,D,k,d", [("bf16", 700, 128, 8, 8, 64), ("fp32", 256, 16, 4, 2, 40),
                                               ("bf16", 1030, 256, 32, 8, 136), ("bf16", 90, 8, 2, 1, 8),
