@@ -444,3 +444,31 @@ def test_probes_copy_and_mfma_loop():
     assert flops == 256 * 4 * 16 * 3 * 2.0 * 32 * 32 * 16
     # all-ones operands: every accumulator element is 16 per MFMA; a lane sums 16 tiles x 16 elements
     assert (H.to_np(sink) == 3 * 16.0 * 256).all()
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_whole_path_on_random_shapes_with_default_kernels(seed):
+    """the whole layer on seeded random shapes with the library's own choice of kernels (tile shapes by rows per
+    expert, split launches, fall-backs for K that the big tiles do not take), and a random cap on the GEMM grids so
+    that the split between head and tail launches lands at different places"""
+    r = np.random.default_rng(2000 + seed)
+    D = int(r.choice([1, 2, 4]))
+    E = D * int(r.choice([1, 2, 4]))
+    k = int(min(E, r.choice([1, 2, 4])))
+    T = int(r.integers(200, 3000))
+    d = int(r.choice([64, 128, 192, 200, 256, 320]))
+    F = int(r.choice([64, 72, 128, 192, 256]))
+    grid_cap = int(r.choice([-1, 2, 3, 5, 9]))
+    rank = int(r.integers(-1, D))
+    _say("whole path, random shape", dict(T=T, d=d, E=E, k=k, F=F, D=D, grid_cap=grid_cap, rank=rank))
+    w = WL.small(T=T, d=d, E=E, k=k, F=F, D=D, dtype="bf16", C=max(1, min(4, E // max(1, E // D))))
+    m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
+    try:
+        m.set_tuning(4, grid_cap)
+        lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, rank=rank)
+        H.assert_close(Y, Yo, "bf16", "Y")
+        if rank < 0:
+            out = lay.combine()
+            H.assert_close(out, O.moe_definition(inp.X, ids, want_w, lambda e: weights[e]), "bf16", "Out")
+    finally:
+        m.set_tuning(4, -1)
