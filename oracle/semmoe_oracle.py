@@ -350,6 +350,58 @@ def reshuffle(ids, expert_to_rank, D: int, cap: int):
             rank_count.astype(np.int32))
 
 
+def reshuffle_rounds(ids, expert_to_rank, D: int, cap: int, rounds: int):
+    """Capacity-bounded assignment with gain-aware spill rounds: the refinement of step 3 of
+    `reshuffle` for the case where capacity binds (the objective of Sec. 3.3 for a fixed
+    placement asks for the assignment with the most local pairs; `align` of Alg. 3 only asks for
+    equal shards).  Instead of sending every spilled token to whatever slot is free, the tokens
+    that are still unplaced propose again, each to its best rank among those that still have room:
+      round t = 0 .. rounds-1:  room = ranks with a free slot;  every unplaced token i proposes
+        pref_t(i) = argmax over ranks with room of g[i,r] (ties -> home(i) if it is such a
+        maximiser, else the smallest), conf_t(i) = g[i, pref_t(i)];  rank r accepts its proposers
+        in the order (conf desc, i asc) up to its free slots.
+      then the tokens still unplaced take the remaining free slots in ascending rank order
+        (ascending i), as in `reshuffle`.
+    Round 0 is the keep phase of `reshuffle`, so rounds = 1 gives the same assignment.  Every
+    round either fills a rank or places every proposer, so D rounds place everything that can
+    be placed by proposal.  Returns (token_rank, shf, inv_shf, rank_count) int32."""
+    ids = np.asarray(ids)
+    T, k = ids.shape
+    assert cap * D >= T and rounds >= 1
+    g = gain_matrix(ids, expert_to_rank, D)
+    home = home_rank(T, D)
+    token_rank = np.full(T, -1, dtype=np.int64)
+    free = np.full(D, cap, dtype=np.int64)
+    for _ in range(rounds):
+        room = [r for r in range(D) if free[r] > 0]
+        proposers = {r: [] for r in room}
+        for i in range(T):
+            if token_rank[i] >= 0:
+                continue
+            mx = max(g[i, r] for r in room)
+            if home[i] in proposers and g[i, home[i]] == mx:
+                p = int(home[i])
+            else:
+                p = min(r for r in room if g[i, r] == mx)
+            proposers[p].append((-int(mx), i))
+        if not any(proposers.values()):
+            break
+        for r in room:
+            proposers[r].sort()
+            for _, i in proposers[r][:free[r]]:
+                token_rank[i] = r
+            free[r] -= min(free[r], len(proposers[r]))
+    free_slots = [r for r in range(D) for _ in range(int(free[r]))]
+    for s, i in enumerate([i for i in range(T) if token_rank[i] < 0]):
+        token_rank[i] = free_slots[s]
+    shf = np.argsort(token_rank, kind="stable")
+    inv_shf = np.zeros(T, dtype=np.int64)
+    inv_shf[shf] = np.arange(T)
+    rank_count = np.bincount(token_rank, minlength=D)
+    return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
+            rank_count.astype(np.int32))
+
+
 def home_assignment(T: int, D: int):
     """no reshuffle: tokens stay on their home rank; identity permutation"""
     tr = home_rank(T, D)

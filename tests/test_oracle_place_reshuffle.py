@@ -244,6 +244,85 @@ def test_greedy_reshuffle_is_optimal_for_one_hot_gains(seed):
     assert O.local_pairs(ids, e2r, tr) == O.reshuffle_bruteforce(ids, e2r, D, 3)
 
 
+# ------------------------------------------------------------------ gain-aware spill rounds
+@pytest.mark.parametrize("T,E,D,k,cf,rounds", [(64, 16, 4, 2, 1.0, 1), (203, 32, 8, 4, 1.0, 3), (100, 16, 4, 3, 1.5, 2),
+                                                (37, 8, 2, 1, 1.0, 2), (150, 24, 6, 4, 1.0, 6)])
+def test_reshuffle_rounds_invariants_and_round_one_is_the_greedy(T, E, D, k, cf, rounds):
+    ids, _, _ = _planted_ids(T, E, D, k, seed=T, noise=0.3)
+    load, co = O.coact_hist(ids, E)
+    e2r, _, _ = O.place(load, co, D)
+    cap = int(np.ceil(cf * T / D))
+    _check_reshuffle_invariants(ids, e2r, D, cap, O.reshuffle_rounds(ids, e2r, D, cap, rounds))
+    one = O.reshuffle_rounds(ids, e2r, D, cap, 1)
+    ref = O.reshuffle(ids, e2r, D, cap)
+    for a, b in zip(one, ref):
+        assert (a == b).all()
+
+
+def test_reshuffle_rounds_hand_example():
+    # D=3, cap=1, T=3, home = [0,1,2]; experts 0 and 3 on rank 0, expert 1 on rank 1, expert 2 on rank 2
+    e2r = np.array([0, 1, 2, 0])
+    ids = np.array([[1, 1, 2],      # g = (0,2,1): pref 1 conf 2
+                    [1, 1, 3],      # g = (1,2,0): pref 1 conf 2
+                    [1, 2, 3]])     # g = (1,1,1): tie -> home 2, conf 1
+    # round 0: rank 1 gets tokens 0 and 1 (conf 2 both) -> keeps token 0 (lower index); rank 2 keeps token 2.
+    # greedy: token 1 spills to the free slot of rank 0 (gain 1).
+    tr1, *_ = O.reshuffle_rounds(ids, e2r, 3, 1, 1)
+    assert list(tr1) == [1, 0, 2]
+    # round 1: only rank 0 has room: token 1 proposes rank 0 (gain 1): same here, both give 2 + 1 + 1 = 4 local pairs
+    tr2, *_ = O.reshuffle_rounds(ids, e2r, 3, 1, 2)
+    assert list(tr2) == [1, 0, 2]
+    # now a case where the second round matters: cap 2, T = 4, home = [0,0,1,1] (D = 2 would leave no choice; D = 3)
+    e2r = np.array([0, 1, 2])
+    ids = np.array([[1, 1], [1, 1], [1, 2], [1, 0]])
+    # D=3, cap=2, home = [0,0,1,1]; gains: t0 (0,2,0), t1 (0,2,0), t2 (0,1,1), t3 (1,1,0)
+    # round 0: rank 1 proposers t0,t1 (conf 2), t2 (tie 1,1 -> home 1), t3 (tie rank0/1: home 1 is a maximiser -> 1):
+    #   accepts t0,t1.  greedy spill: t2 -> first free slot = rank 0 (gain 0), t3 -> rank 0 (gain 1): local = 2+2+0+1 = 5
+    tr1, *_ = O.reshuffle_rounds(ids, e2r, 3, 2, 1)
+    assert list(tr1) == [1, 1, 0, 0] and O.local_pairs(ids, e2r, tr1) == 5
+    # round 1: room = ranks 0, 2: t2 proposes rank 2 (gain 1), t3 proposes rank 0 (gain 1): local = 2+2+1+1 = 6 = optimum
+    tr2, *_ = O.reshuffle_rounds(ids, e2r, 3, 2, 2)
+    assert list(tr2) == [1, 1, 2, 0] and O.local_pairs(ids, e2r, tr2) == 6
+    assert O.reshuffle_bruteforce(ids, e2r, 3, 2) == 6
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_reshuffle_rounds_between_greedy_and_optimum_on_tiny_inputs(seed):
+    r = np.random.default_rng(50 + seed)
+    T, D = int(r.integers(5, 9)), int(r.integers(2, 4))
+    E, k = 2 * D, int(r.integers(1, 4))
+    ids = WL.uniform_random_ids(T, E, min(k, E), seed=300 + seed)
+    e2r, _, _ = O.vanilla_placement(E, D)
+    cap = -(-T // D)
+    opt = O.reshuffle_bruteforce(ids, e2r, D, cap)
+    for rounds in (1, 2, D):
+        tr, *_ = O.reshuffle_rounds(ids, e2r, D, cap, rounds)
+        assert (np.bincount(tr, minlength=D) <= cap).all()
+        assert O.local_pairs(ids, e2r, tr) <= opt
+
+
+def test_reshuffle_rounds_gain_over_greedy_when_capacity_binds():
+    """skewed classes, capacity binds on the popular ranks: proposing again beats filling free slots in rank order
+    (fixed seeded case; the optimum from the exact solver bounds both)"""
+    T, E, D, k = 160, 32, 8, 4
+    ids, _, _ = _planted_ids(T, E, D, k, seed=11, noise=0.2)
+    r = np.random.default_rng(4)
+    skew = r.choice(D, size=T, p=(np.arange(D) + 1.0) ** -1.5 / ((np.arange(D) + 1.0) ** -1.5).sum())
+    e2r, _, _ = O.vanilla_placement(E, D)
+    m = E // D
+    ids = np.stack([r.choice(np.arange(c * m, c * m + m), size=k, replace=False) if r.random() > 0.3
+                    else r.choice(E, size=k, replace=False) for c in skew]).astype(np.int32)
+    cap = T // D
+    lp = [O.local_pairs(ids, e2r, O.reshuffle_rounds(ids, e2r, D, cap, n)[0]) for n in (1, 2, 3, D)]
+    _, opt = O.reshuffle_exact(ids, e2r, D, cap)
+    assert lp[0] == O.local_pairs(ids, e2r, O.reshuffle(ids, e2r, D, cap)[0])
+    assert lp[0] < lp[1] <= opt and lp[-1] <= opt and lp[-1] >= lp[1]
+    # D rounds place every token by proposal: a further round changes nothing
+    a = O.reshuffle_rounds(ids, e2r, D, cap, D)[0]
+    b = O.reshuffle_rounds(ids, e2r, D, cap, D + 3)[0]
+    assert (a == b).all()
+
+
 def test_home_assignment():
     tr, shf, inv, rc = O.home_assignment(10, 4)
     assert list(tr) == [0, 0, 0, 1, 1, 1, 2, 2, 2, 3] and list(rc) == [3, 3, 3, 1]
