@@ -279,6 +279,29 @@ def main():
                      torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rp3)
     torch.cuda.synchronize()
 
+    # ---------------- next row: reshuffle with gain-aware spill rounds (not part of the timed step)
+    rounds_report = {}
+    for R in (2, 3, D):
+        if str(R) in rounds_report:
+            continue
+        tr2, shf2, ish2 = (torch.empty(T, **i32) for _ in range(3))
+        rc2 = torch.empty(D, **i32)
+        for _ in range(3):
+            m.reshuffle_rounds(ids, e2r, R, tr2, shf2, ish2, rc2)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            m.reshuffle_rounds(ids, e2r, R, tr2, shf2, ish2, rc2)
+        e1.record()
+        torch.cuda.synchronize()
+        rpr = torch.empty(1, dtype=torch.int64, device=dev)
+        m.dispatch_index(ids, tr2, shf2, phys, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                         torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rpr)
+        torch.cuda.synchronize()
+        rounds_report[str(R)] = {"ms": round(e0.elapsed_time(e1) / 20, 4),
+                                 "remote_pair_fraction": round(int(rpr.item()) / P, 4)}
+
     # ---------------- algorithmic bytes / flops per launch
     alg = {
         # the bf16 router is one fused kernel (logits never leave the chip); fp32 writes and re-reads them
@@ -332,6 +355,7 @@ def main():
         "remote_pair_fraction": {"vanilla_placement_home_ranks": round(int(rp2.item()) / P, 4),
                                  "semmoe_placement_home_ranks": round(int(rp3.item()) / P, 4),
                                  "semmoe_placement_reshuffle": round(remote / P, 4)},
+        "reshuffle_with_spill_rounds": rounds_report,
         "load_imbalance_max_over_median": round(float(col.max() / max(np.median(col), 1)), 4),
         "offline_ms": {"route+coact_hist(profile batch of %d)" % Tp: round(t_hist * 1e3, 3),
                        "place(host)": round(t_place * 1e3, 3)},

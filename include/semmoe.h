@@ -162,6 +162,20 @@ int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* 
                          int32_t* rank_count, void* ws, size_t ws_bytes);
 
 /*
+ * reshuffle with gain-aware spill rounds - the capacity-bounded assignment pushed towards the objective of Sec. 3.3
+ * (the most local pairs for a fixed placement), which the keep/spill of `semmoe_reshuffle` only approximates when
+ * capacity binds.  Round 0 is the keep phase of `semmoe_reshuffle`.  In each further round every token still unplaced
+ * proposes to its best rank among those with a free slot (equal gains -> home(i) if it is one of them, else the
+ * smallest), and a rank accepts its proposers in the order (conf desc, i asc) up to its free slots.  After `rounds`
+ * rounds (at most D are needed) the tokens left take the free slots in ascending rank order as in `semmoe_reshuffle`.
+ * rounds = 1 gives exactly `semmoe_reshuffle`.  One launch per round plus one.  Same arguments and outputs as
+ * `semmoe_reshuffle`; T <= 131072 (SEMMOE_EUNSUPPORTED above), rounds >= 1.
+ */
+int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                const int32_t* expert_to_rank, int32_t rounds, int32_t* token_rank, int32_t* shf,
+                                int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes);
+
+/*
  * dispatch - the dispatch all2all of expert parallelism (Sec. 1) as a single-device permutation.
  *   Pairs are ordered by physical expert q = phys_of_expert[ids[i,j]], pairs of one expert by shuffled
  *   pair index p' = inv_shf[i]*k + j (arrival order of a rank-ordered all2all).  slot = that position.

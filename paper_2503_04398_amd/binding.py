@@ -80,6 +80,7 @@ _SIGS = {
     "semmoe_coact_hist": ([_P, _P, _P, C.c_int32, _P, _P], C.c_int32),
     "semmoe_place": ([_P, _P, _P, C.c_int64, C.c_int64, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
+    "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch": ([_P] * 15 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_index": ([_P] * 13 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_rows": ([_P] * 5, C.c_int32),
@@ -194,6 +195,12 @@ class SemMoE:
         c = self._cfg(**({"cap": cap} if cap is not None else {}))
         self._check("semmoe_reshuffle", self.lib.semmoe_reshuffle(
             C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), _ptr(token_rank), _ptr(shf),
+            _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def reshuffle_rounds(self, topk_ids, expert_to_rank, rounds, token_rank, shf, inv_shf, rank_count, cap=None):
+        c = self._cfg(**({"cap": cap} if cap is not None else {}))
+        self._check("semmoe_reshuffle_rounds", self.lib.semmoe_reshuffle_rounds(
+            C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), int(rounds), _ptr(token_rank), _ptr(shf),
             _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
 
     def dispatch(self, X, topk_ids, token_rank, shf, phys_of_expert, X_perm, slot_of_pair, pair_of_slot,

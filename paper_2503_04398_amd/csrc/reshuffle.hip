@@ -20,6 +20,9 @@ struct ReshuffleWs {
   int32_t* spill_cnt;   // [NB]  spilled tokens per block
   int32_t* rank_hist;   // [NB][D] -> position base inside the rank after the scan
   int32_t* rank_start;  // [D+1] first position of each rank in the shuffled order
+  int32_t* cnt2;        // [NB][D*(k+1)]  second count table (spill rounds: tables of consecutive rounds alternate)
+  int32_t* free_a;      // [D]   free slots at the start of a round (spill rounds; alternates with free_b)
+  int32_t* free_b;      // [D]
 };
 
 __device__ __forceinline__ int bitmap_rank(const uint32_t* words, int t) {
@@ -384,6 +387,243 @@ __global__ __launch_bounds__(kTokBlock) void rs_fused_kernel(int T, int NB, int 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Gain-aware spill rounds (the refinement of `align` towards the objective of Sec. 3.3: the most local pairs
+// under the capacity bound).  Round 0 is the keep phase; in every further round the tokens still unplaced propose
+// again, each to its best rank among those with room, and a rank accepts by (conf desc, i asc) up to its free
+// slots; what is left after the last round fills the free slots in rank order.
+// One launch per round: the launch that decides round t reads the table of round-t proposals (as rs_fused_kernel
+// reads the table of the keep phase: totals and the prefix over the workgroups before it give thresholds, quotas
+// and the free slots after the round in closed form), and, unless it is the last, lets its unplaced tokens propose
+// for round t+1 and writes their table.  Tokens of final rank r before a workgroup accumulate round by round in
+// rank_hist.  LAST: spill of what is left + scatter, as in rs_fused_kernel.
+// ------------------------------------------------------------------------------------------------
+template <bool LAST>
+__global__ __launch_bounds__(kTokBlock) void rs_round_kernel(int T, int NB, int k, int D, int E, int cap, int round,
+                                                             int per_home, const int32_t* __restrict__ ids,
+                                                             const int32_t* __restrict__ e2r,
+                                                             const int32_t* __restrict__ table_in,
+                                                             int32_t* __restrict__ table_out,
+                                                             const int32_t* __restrict__ free_in,
+                                                             int32_t* __restrict__ free_out,
+                                                             int32_t* __restrict__ token_rank,
+                                                             int32_t* __restrict__ shf, int32_t* __restrict__ inv_shf,
+                                                             int32_t* __restrict__ rank_count, ReshuffleWs w) {
+  extern __shared__ int32_t round_sm[];
+  const int nkeys = D * (k + 1);
+  int32_t* tot = round_sm;            // [nkeys] column totals of this round's proposals
+  int32_t* pre = tot + nkeys;         // [nkeys] ... over the workgroups before this one
+  int32_t* hist = pre + nkeys;        // [nkeys] next round's proposals of this workgroup
+  int32_t* thr = hist + nkeys;        // [D]
+  int32_t* quota = thr + D;           // [D]
+  int32_t* free_nx = quota + D;       // [D+1] free slots after this round -> (LAST) exclusive prefix
+  int32_t* sp_tot = free_nx + D + 1;  // [D] rejected proposers of rank r, all workgroups
+  int32_t* sp_pre = sp_tot + D;       // [D] ... in the workgroups before this one
+  int32_t* acc_pre = sp_pre + D;      // [D] accepted proposers of rank r in the workgroups before this one
+  int32_t* rstart = acc_pre + D;      // [D+1]
+  int32_t* rbefore = rstart + D + 1;  // [D]
+  int32_t* scal = rbefore + D;        // [2]
+  uint32_t* bm = reinterpret_cast<uint32_t*>(scal + 2);  // [D][kWords]
+  uint32_t* spbm = bm + D * kWords;                       // [kWords]
+  const int t = threadIdx.x, b = blockIdx.x;
+
+  for (int x = t; x < 3 * nkeys; x += kTokBlock) tot[x] = 0;
+  for (int x = t; x < D * kWords + kWords; x += kTokBlock) bm[x] = 0;
+  __syncthreads();
+  for (int base = t; base < NB * nkeys; base += 8 * kTokBlock) {  // eight loads in flight per thread
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * kTokBlock;
+      v[u] = idx < NB * nkeys ? table_in[idx] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (v[u] == 0) continue;
+      const int idx = base + u * kTokBlock;
+      const int bb = idx / nkeys, key = idx - bb * nkeys;
+      atomicAdd(&tot[key], v[u]);
+      if (bb < b) atomicAdd(&pre[key], v[u]);
+    }
+  }
+  __syncthreads();
+  if (t < D) {
+    const int r = t;
+    const int fr = round == 0 ? cap : free_in[r];
+    int cum = 0, th = -1, q = 0;
+    for (int c = k; c >= 0; --c) {
+      const int n = tot[r * (k + 1) + c];
+      if (cum + n > fr) {
+        th = c;
+        q = fr - cum;
+        cum = fr;
+        break;
+      }
+      cum += n;
+    }
+    thr[r] = th;
+    quota[r] = q;
+    free_nx[r] = fr - cum;
+    int st = 0, sp = 0, kp = 0;
+    for (int c = 0; c <= k; ++c) {
+      const int nt = tot[r * (k + 1) + c], np = pre[r * (k + 1) + c];
+      if (th < 0 || c > th) kp += np;
+      else if (c < th) { st += nt; sp += np; }
+      else { st += nt - q; sp += max(0, np - q); kp += min(q, np); }
+    }
+    sp_tot[r] = st;
+    sp_pre[r] = sp;
+    acc_pre[r] = kp;
+    // tokens of final rank r in the workgroups before this one, accumulated over the rounds
+    const int before = (round == 0 ? 0 : w.rank_hist[size_t(b) * D + r]) + kp;
+    if (!LAST) w.rank_hist[size_t(b) * D + r] = before;
+    rbefore[r] = before;
+    if (!LAST && b == 0) free_out[r] = fr - cum;
+  }
+  __syncthreads();
+  if (LAST && t < 64) {  // one wave: scans over the D <= 64 ranks
+    const int r = t;
+    const int fr = r < D ? free_nx[r] : 0;
+    int incl = fr, s_tot = r < D ? sp_tot[r] : 0, s_b = r < D ? sp_pre[r] : 0;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int u = __shfl_up(incl, off);
+      if (t >= off) incl += u;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      s_tot += __shfl_xor(s_tot, off);
+      s_b += __shfl_xor(s_b, off);
+    }
+    const int fpre = incl - fr;
+    const bool last_rank = r == D - 1;
+    const int a_tot = r < D ? (last_rank ? max(0, s_tot - fpre) : min(max(s_tot - fpre, 0), fr)) : 0;
+    const int a_pre = r < D ? (last_rank ? max(0, s_b - fpre) : min(max(s_b - fpre, 0), fr)) : 0;
+    const int cnt = r < D ? (cap - fr) + a_tot : 0;  // placed by proposal in all rounds + its share of the spill
+    int cincl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int u = __shfl_up(cincl, off);
+      if (t >= off) cincl += u;
+    }
+    if (r < D) {
+      free_nx[r] = fpre;
+      rstart[r] = cincl - cnt;
+      rbefore[r] += a_pre;
+      if (b == 0) rank_count[r] = cnt;
+    }
+    if (r == D - 1) free_nx[D] = incl;
+    if (t == 0) scal[0] = s_b;
+  }
+  __syncthreads();
+
+  // decide this round for the tokens that proposed in it
+  const int i = b * kTokBlock + t;
+  int rank = -2;  // -2: no token; -1: unplaced
+  int pref = 0, conf = 0, th = -1;
+  bool proposer = false;
+  if (i < T) {
+    rank = round == 0 ? -1 : token_rank[i];
+    proposer = rank < 0;
+    if (proposer) {
+      const int pc = w.pc[i];
+      pref = pc & 0xff;
+      conf = pc >> 8;
+      th = thr[pref];
+      if (th >= 0 && conf == th) atomicOr(&bm[pref * kWords + (t >> 5)], 1u << (t & 31));
+    }
+  }
+  __syncthreads();
+  if (proposer) {
+    bool kept;
+    if (th < 0 || conf > th) kept = true;
+    else if (conf < th) kept = false;
+    else kept = pre[pref * (k + 1) + th] + bitmap_rank(bm + pref * kWords, t) < quota[pref];
+    if (kept) rank = pref;
+  }
+  if constexpr (!LAST) {
+    if (i < T && proposer) {
+      token_rank[i] = rank;
+      if (rank < 0) {
+        // propose again: best rank with room after this round; equal gains -> home if it is one of them, else
+        // the smallest; no rank of the token has room -> gain 0 (home if it has room, else the smallest with room)
+        int rr[SEMMOE_MAX_K];
+#pragma unroll
+        for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+          rr[j] = -1;
+          if (j < k) {
+            const int e = ids[size_t(i) * k + j];
+            if ((unsigned)e < (unsigned)E) {
+              const int x = e2r[e];
+              if ((unsigned)x < (unsigned)D && free_nx[x] > 0) rr[j] = x;
+            }
+          }
+        }
+        const int home = i / per_home;
+        const bool home_room = free_nx[home] > 0;
+        int best_r = -1, best_c = 0;
+        if (home_room) {
+          best_r = home;
+#pragma unroll
+          for (int j = 0; j < SEMMOE_MAX_K; ++j) best_c += (rr[j] == home);
+        }
+#pragma unroll
+        for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+          if (rr[j] < 0) continue;
+          int c = 0;
+#pragma unroll
+          for (int j2 = 0; j2 < SEMMOE_MAX_K; ++j2) c += (rr[j2] == rr[j]);
+          const bool home_best = home_room && best_r == home;
+          if (best_r < 0 || c > best_c || (c == best_c && !home_best && rr[j] < best_r)) {
+            best_c = c;
+            best_r = rr[j];
+          }
+        }
+        if (best_r < 0 || (best_c == 0 && !home_room)) {  // gain 0 everywhere with room: the smallest rank with room
+          best_r = -1;
+          for (int r = 0; r < D; ++r)
+            if (free_nx[r] > 0) { best_r = r; break; }
+          best_c = 0;
+        }
+        if (best_r >= 0) {  // some rank has room (else no further round can place anything)
+          w.pc[i] = best_r | (best_c << 8);
+          atomicAdd(&hist[best_r * (k + 1) + best_c], 1);
+        } else {
+          w.pc[i] = 0;      // never accepted: a rank without room has quota 0 at every level
+          atomicAdd(&hist[0], 1);
+        }
+      }
+    }
+    __syncthreads();
+    for (int x = t; x < nkeys; x += kTokBlock) table_out[size_t(b) * nkeys + x] = hist[x];
+  } else {
+    if (proposer && rank < 0) atomicOr(&spbm[t >> 5], 1u << (t & 31));
+    __syncthreads();
+    for (int x = t; x < D * kWords; x += kTokBlock) bm[x] = 0;  // the bitmaps now take the final ranks
+    if (proposer && rank < 0) {
+      const int s = scal[0] + bitmap_rank(spbm, t);
+      int r = 0;
+      while (r + 1 < D && free_nx[r + 1] <= s) ++r;
+      rank = r;
+    }
+    __syncthreads();
+    if (i < T) {
+      token_rank[i] = rank;
+      atomicOr(&bm[rank * kWords + (t >> 5)], 1u << (t & 31));
+    }
+    __syncthreads();
+    if (i < T) {
+      const int pos = rstart[rank] + rbefore[rank] + bitmap_rank(bm + rank * kWords, t);
+      inv_shf[i] = pos;
+      shf[pos] = i;
+    }
+  }
+}
+
+static size_t rs_round_lds(int D, int k) {
+  return (size_t(3) * D * (k + 1) + size_t(D) * 8 + 2 + 2 + size_t(D) * kWords + kWords) * 4;
+}
+
 static size_t rs_fused_lds(int D, int k) {
   return (size_t(2) * D * (k + 1) + size_t(D) * 9 + 2 + 2 + size_t(D) * kWords + kWords) * 4;
 }
@@ -594,14 +834,18 @@ static bool carve_reshuffle(const semmoe_config* cfg, void* ws, size_t bytes, Re
   w->spill_cnt = c.take<int32_t>(NB);
   w->rank_hist = c.take<int32_t>(NB * cfg->D);
   w->rank_start = c.take<int32_t>(cfg->D + 1);
+  w->cnt2 = c.take<int32_t>(NB * nkeys);
+  w->free_a = c.take<int32_t>(cfg->D);
+  w->free_b = c.take<int32_t>(cfg->D);
   return c.ok;
 }
 
 size_t ws_reshuffle(const semmoe_config* cfg) {
   const size_t NB = cdiv(cfg->T, kTokBlock);
   const size_t nkeys = size_t(cfg->D) * (cfg->k + 1);
-  const size_t counts[9] = {size_t(cfg->T), NB * nkeys, size_t(cfg->D), size_t(cfg->D), size_t(cfg->D) + 1,
-                            NB * cfg->D, NB, NB * cfg->D, size_t(cfg->D) + 1};
+  const size_t counts[12] = {size_t(cfg->T), NB * nkeys, size_t(cfg->D), size_t(cfg->D), size_t(cfg->D) + 1,
+                             NB * cfg->D, NB, NB * cfg->D, size_t(cfg->D) + 1, NB * nkeys, size_t(cfg->D),
+                             size_t(cfg->D)};
   size_t b = 0;
   for (size_t n : counts) b = align_up(b, 256) + n * 4;
   return b + 256;
@@ -661,6 +905,51 @@ extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, cons
   hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, D, rank_count, w);
   hipLaunchKernelGGL(rs_scatter_kernel, dim3(NB), dim3(kTokBlock), D * kWords * 4, s, T, D, token_rank, shf, inv_shf,
                      w);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                           const int32_t* expert_to_rank, int32_t rounds, int32_t* token_rank,
+                                           int32_t* shf, int32_t* inv_shf, int32_t* rank_count, void* ws,
+                                           size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, false, false);
+  if (st != SEMMOE_OK) return st;
+  if (!topk_ids || !expert_to_rank || !token_rank || !shf || !inv_shf || !rank_count) return SEMMOE_EINVAL;
+  if (cfg->cap < 0 || rounds < 1) return SEMMOE_EINVAL;
+  if ((long long)cfg->cap * cfg->D < cfg->T) return SEMMOE_ESHAPE;
+  if (cfg->k >= 128 || cfg->D > 64) return SEMMOE_EUNSUPPORTED;
+  ReshuffleWs w;
+  if (!carve_reshuffle(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int T = cfg->T, D = cfg->D, k = cfg->k;
+  const int NB = cdiv(T, kTokBlock);
+  if (T == 0) {
+    hipLaunchKernelGGL(rs_zero_kernel, dim3(1), dim3(64), 0, s, D, rank_count);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  if (NB > kFusedMaxNB) return SEMMOE_EUNSUPPORTED;  // every workgroup reads the whole count table
+  if (rounds > D) rounds = D;                        // D rounds place everything a proposal can place
+  const int per_home = cdiv(T, D);
+  const int nkeys = D * (k + 1);
+  const size_t lds = rs_round_lds(D, k);
+  hipLaunchKernelGGL(rs_pref_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, cfg->E, per_home, topk_ids,
+                     expert_to_rank, w);
+  for (int r = 0; r < rounds; ++r) {
+    const int32_t* tin = (r % 2 == 0) ? w.cnt : w.cnt2;
+    int32_t* tout = (r % 2 == 0) ? w.cnt2 : w.cnt;
+    const int32_t* fin = (r % 2 == 1) ? w.free_a : w.free_b;
+    int32_t* fout = (r % 2 == 0) ? w.free_a : w.free_b;
+    if (r + 1 < rounds)
+      hipLaunchKernelGGL(rs_round_kernel<false>, dim3(NB), dim3(kTokBlock), lds, s, T, NB, k, D, cfg->E, cfg->cap, r,
+                         per_home, topk_ids, expert_to_rank, tin, tout, fin, fout, token_rank, shf, inv_shf,
+                         rank_count, w);
+    else
+      hipLaunchKernelGGL(rs_round_kernel<true>, dim3(NB), dim3(kTokBlock), lds, s, T, NB, k, D, cfg->E, cfg->cap, r,
+                         per_home, topk_ids, expert_to_rank, tin, tout, fin, fout, token_rank, shf, inv_shf,
+                         rank_count, w);
+  }
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
 }

@@ -116,6 +116,12 @@ class Layer:
         torch.cuda.synchronize()
         return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
 
+    def reshuffle_rounds(self, rounds, cap=None):
+        self.m.reshuffle_rounds(self.ids, self.e2r, rounds, self.token_rank, self.shf, self.inv_shf, self.rank_count,
+                                cap=cap)
+        torch.cuda.synchronize()
+        return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
+
     def set_assignment(self, token_rank, shf, inv_shf):
         self.token_rank.copy_(torch.from_numpy(np.asarray(token_rank, dtype=np.int32)))
         self.shf.copy_(torch.from_numpy(np.asarray(shf, dtype=np.int32)))

@@ -59,6 +59,14 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
     want = O.reshuffle(ids, e2r, w.D, w.cap)
     for g, x, nm in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
         assert (g == x).all(), nm
+    # the next row: gain-aware spill rounds at the full size (three rounds), bit for bit, and what they buy
+    got3 = lay.reshuffle_rounds(3)
+    want3 = O.reshuffle_rounds(ids, e2r, w.D, w.cap, 3)
+    for g, x, nm in zip(got3, want3, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == x).all(), "rounds: " + nm
+    _say("  [%5.1fs] reshuffle with 3 spill rounds bit-exact; remote-pair fraction %.4f (1 round: %.4f)"
+         % (time.time() - t0, O.remote_fraction(ids, e2r, want3[0]), O.remote_fraction(ids, e2r, want[0])))
+    got = lay.reshuffle()          # the layer below runs on the plain reshuffle
     tr, shf, ishf, rc = want
     dg = lay.dispatch()
     dw = O.dispatch(None, ids, tr, ishf, phys, w.D)

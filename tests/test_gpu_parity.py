@@ -150,6 +150,30 @@ def test_reshuffle_bit_exact(T, E, D, k, cf, noise, index_path):
     assert (got[3] <= cap).all()
 
 
+@pytest.mark.parametrize("T,E,D,k,cf,noise", [
+    (256, 16, 4, 2, 1.0, 0.2), (1000, 128, 8, 8, 1.0, 0.5), (777, 64, 16, 4, 1.0, 0.3), (300, 32, 32, 2, 1.0, 0.5),
+    (513, 16, 4, 4, 1.25, 0.4), (100, 8, 1, 2, 1.0, 0.5), (2049, 64, 64, 1, 1.0, 0.0), (5, 16, 4, 2, 1.0, 0.5),
+    (4000, 256, 32, 8, 1.0, 0.6), (3000, 48, 3, 16, 1.0, 0.1)])
+@pytest.mark.parametrize("rounds", [1, 2, 3, 64])
+def test_reshuffle_rounds_bit_exact(T, E, D, k, cf, noise, rounds):
+    """gain-aware spill rounds against the oracle, bit for bit; rounds = 1 is also the plain reshuffle"""
+    _say("reshuffle rounds", T, E, D, k, cf, "rounds", rounds)
+    ids, e2r = _planted(T, E, D, k, seed=T + D, noise=noise)
+    cap = int(math.ceil(cf * T / D))
+    w = WL.small(T=T, E=E, D=D, k=k)
+    lay = H.Layer(w, cap=cap)
+    lay.set_routing(ids)
+    lay.e2r = H.to_dev(e2r)
+    got = lay.reshuffle_rounds(rounds)
+    want = O.reshuffle_rounds(ids, e2r, D, cap, min(rounds, D))
+    for g, w_, name in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == w_).all(), (name, np.flatnonzero(g != w_)[:8])
+    assert (got[3] <= cap).all()
+    if rounds == 1:
+        for g, w_ in zip(got, O.reshuffle(ids, e2r, D, cap)):
+            assert (g == w_).all()
+
+
 def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit():
     """beyond what the single-workgroup kernels hold; multi-workgroup kernels by default"""
     T, E, D, k = 40000, 64, 16, 4
