@@ -402,6 +402,92 @@ def reshuffle_rounds(ids, expert_to_rank, D: int, cap: int, rounds: int):
             rank_count.astype(np.int32))
 
 
+# --------------------------------------------------------------------------------------------
+# table-driven (predictive) reshuffle: the paper's online mechanism, from token ids alone
+# --------------------------------------------------------------------------------------------
+
+
+def token_expert_table(keys, ids, V: int, E: int, table=None) -> np.ndarray:
+    """Token-to-expert activation table of Sec. 3.2: table[v,e] = #{(i,j): keys[i] = v and ids[i,j] = e},
+    accumulated over profiling batches when `table` is passed back in."""
+    keys = np.asarray(keys)
+    ids = np.asarray(ids)
+    if table is None:
+        table = np.zeros((V, E), dtype=np.int64)
+    for i in range(ids.shape[0]):
+        for j in range(ids.shape[1]):
+            table[keys[i], ids[i, j]] += 1
+    return table
+
+
+def lookup_tables(table, expert_to_rank, D: int, k: int):
+    """Token-to-device schedule table and its confidence (the tables T and T_p of Alg. 2 / Alg. 3) from the
+    activation table and a placement.  The confidence table of Sec. 3.2 is C_p[v,e] = table[v,e] / sum_e table[v,e];
+    the probability that an activation of token v lands on device r is the sum of C_p over r's experts:
+        mass[v,r] = sum_{e on r} table[v,e];   dev[v]  = argmax_r mass[v,r] (equal -> smallest r);
+        T_p[v] = mass[v,dev[v]] / sum_r mass[v,r].
+    Kept in integers so that every implementation takes the same decisions:
+        conf_q16[v] = floor(65536 * T_p[v]);   level[v] = round-half-up(k * T_p[v]) in [0,k]
+    (k * T_p is the number of the token's k activations expected on that device: the keep priority).
+    A key never seen in profiling has dev = -1, conf_q16 = 0, level = 0.
+    Returns (dev[V], conf_q16[V], level[V]) int32."""
+    table = np.asarray(table, dtype=np.int64)
+    V, E = table.shape
+    e2r = np.asarray(expert_to_rank)
+    dev = np.full(V, -1, dtype=np.int32)
+    conf = np.zeros(V, dtype=np.int32)
+    level = np.zeros(V, dtype=np.int32)
+    for v in range(V):
+        mass = [0] * D
+        for e in range(E):
+            mass[int(e2r[e])] += int(table[v, e])
+        tot = sum(mass)
+        if tot == 0:
+            continue
+        best = max(range(D), key=lambda r: (mass[r], -r))
+        dev[v] = best
+        conf[v] = (65536 * mass[best]) // tot
+        level[v] = (2 * k * mass[best] + tot) // (2 * tot)
+    return dev, conf, level
+
+
+def reshuffle_lookup(keys, dev, conf_q16, level, thr_q16: int, D: int, cap: int):
+    """`rebatch_tokens` of Alg. 3 as the paper runs it, before the gate: the device id of a token comes from
+    the schedule table, dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).  The inter-layer table A is not built on
+    this path: its device is read as the token's home shard and its confidence A_p as the constant thr_q16
+    (in 1/65536).  So pref(i) = dev[keys[i]] and conf(i) = level[keys[i]] when conf_q16[keys[i]] > thr_q16
+    (and the key was seen), else pref(i) = home(i), conf(i) = 0; then keep / spill / shuffle exactly as in
+    `reshuffle` (steps 2-4).  Returns (token_rank, shf, inv_shf, rank_count) int32."""
+    keys = np.asarray(keys)
+    T = keys.shape[0]
+    assert cap * D >= T
+    home = home_rank(T, D)
+    pref = np.zeros(T, dtype=np.int64)
+    conf = np.zeros(T, dtype=np.int64)
+    for i in range(T):
+        v = int(keys[i])
+        if dev[v] >= 0 and conf_q16[v] > thr_q16:
+            pref[i], conf[i] = dev[v], level[v]
+        else:
+            pref[i], conf[i] = home[i], 0
+    token_rank = np.full(T, -1, dtype=np.int64)
+    kept = np.zeros(D, dtype=np.int64)
+    for r in range(D):
+        cand = [i for i in range(T) if pref[i] == r]
+        cand.sort(key=lambda i: (-conf[i], i))
+        for i in cand[:cap]:
+            token_rank[i] = r
+        kept[r] = min(len(cand), cap)
+    free_slots = [r for r in range(D) for _ in range(int(cap - kept[r]))]
+    for s, i in enumerate([i for i in range(T) if token_rank[i] < 0]):
+        token_rank[i] = free_slots[s]
+    shf = np.argsort(token_rank, kind="stable")
+    inv_shf = np.zeros(T, dtype=np.int64)
+    inv_shf[shf] = np.arange(T)
+    return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
+            np.bincount(token_rank, minlength=D).astype(np.int32))
+
+
 def home_assignment(T: int, D: int):
     """no reshuffle: tokens stay on their home rank; identity permutation"""
     tr = home_rank(T, D)

@@ -323,6 +323,110 @@ def test_reshuffle_rounds_gain_over_greedy_when_capacity_binds():
     assert (a == b).all()
 
 
+# ------------------------------------------------------------------ table-driven reshuffle
+def test_token_expert_table_counts_and_accumulates():
+    r = np.random.default_rng(0)
+    T, V, E, k = 300, 20, 12, 3
+    keys = r.integers(0, V, T)
+    ids = WL.uniform_random_ids(T, E, k, seed=3)
+    tab = O.token_expert_table(keys, ids, V, E)
+    assert tab.sum() == T * k
+    assert (tab.sum(axis=1) == np.bincount(keys, minlength=V) * k).all()        # every token activates k experts
+    assert (tab.sum(axis=0) == np.bincount(ids.reshape(-1), minlength=E)).all() # column sums = expert loads
+    v, e = int(keys[7]), int(ids[7, 1])
+    assert tab[v, e] == sum(1 for i in range(T) for j in range(k) if keys[i] == v and ids[i, j] == e)
+    half = O.token_expert_table(keys[:100], ids[:100], V, E)
+    both = O.token_expert_table(keys[100:], ids[100:], V, E, table=half)
+    assert (both == tab).all()
+
+
+def test_lookup_tables_hand_example():
+    # V=4, E=4, D=2 (experts 0,1 on rank 0; 2,3 on rank 1), k=2
+    e2r = np.array([0, 0, 1, 1])
+    tab = np.array([[3, 1, 0, 0],     # all mass on rank 0: dev 0, T_p = 1
+                    [1, 0, 2, 1],     # mass (1,3): dev 1, T_p = 3/4
+                    [1, 1, 1, 1],     # tie (2,2): smallest rank, T_p = 1/2
+                    [0, 0, 0, 0]])    # never seen
+    dev, conf, level = O.lookup_tables(tab, e2r, 2, 2)
+    assert list(dev) == [0, 1, 0, -1]
+    assert list(conf) == [65536, 49152, 32768, 0]
+    assert list(level) == [2, 2, 1, 0]          # round-half-up of 2, 1.5, 1.0
+
+
+def test_reshuffle_lookup_threshold_extremes_and_perfect_prediction():
+    T, D, V = 120, 4, 8
+    r = np.random.default_rng(1)
+    keys = r.integers(0, V, T)
+    dev = (np.arange(V) % D).astype(np.int32)
+    conf = np.full(V, 60000, dtype=np.int32)
+    level = np.full(V, 2, dtype=np.int32)
+    # a threshold nobody passes: everybody stays home, identity permutation
+    out = O.reshuffle_lookup(keys, dev, conf, level, 65536, D, T // D)
+    for a, b in zip(out, O.home_assignment(T, D)):
+        assert (a == b).all()
+    # unbounded capacity, everybody passes: the table decides alone
+    tr, shf, inv, rc = O.reshuffle_lookup(keys, dev, conf, level, 0, D, T)
+    assert (tr == dev[keys]).all()
+    _check_reshuffle_invariants(np.zeros((T, 1), dtype=np.int32), None, D, T, (tr, shf, inv, rc))
+    # unseen keys stay home whatever the threshold
+    dev2 = dev.copy()
+    dev2[3] = -1
+    tr2, *_ = O.reshuffle_lookup(keys, dev2, conf, level, 0, D, T)
+    home = O.home_rank(T, D)
+    assert (tr2[keys == 3] == home[keys == 3]).all()
+
+
+def test_reshuffle_lookup_with_one_key_per_token_reproduces_the_perfect_predictor():
+    """one key per token and a table built from the very batch: the level is the token's best gain exactly, the
+    predicted device a maximiser of its gains; where no token has tied gains the two paths agree bit for bit"""
+    T, E, D, k = 96, 16, 4, 2
+    ids, _, _ = _planted_ids(T, E, D, k, seed=5, noise=0.3)
+    e2r, _, _ = O.vanilla_placement(E, D)
+    keys = np.arange(T)
+    tab = O.token_expert_table(keys, ids, T, E)
+    dev, conf, level = O.lookup_tables(tab, e2r, D, k)
+    g = O.gain_matrix(ids, e2r, D)
+    assert (level == g.max(axis=1)).all()
+    assert (g[np.arange(T), dev] == g.max(axis=1)).all()
+    cap = T // D
+    got = O.reshuffle_lookup(keys, dev, conf, level, -1, D, cap)
+    assert (np.bincount(got[0], minlength=D) <= cap).all()
+    assert O.local_pairs(ids, e2r, got[0]) <= O.reshuffle_exact(ids, e2r, D, cap)[1]
+    # k = 1: gains are one-hot, no ties: identical to `reshuffle`
+    ids1 = ids[:, :1]
+    tab1 = O.token_expert_table(keys, ids1, T, E)
+    d1, c1, l1 = O.lookup_tables(tab1, e2r, D, 1)
+    for a, b in zip(O.reshuffle_lookup(keys, d1, c1, l1, -1, D, cap), O.reshuffle(ids1, e2r, D, cap)):
+        assert (a == b).all()
+
+
+def test_reshuffle_lookup_on_clustered_synthetic_tokens_recovers_most_of_the_perfect_predictor():
+    """keys carry the class; routing concentrates on the class's cluster: a table from a profiling batch must put a
+    class's tokens on the rank of its cluster, and the local activation rate must be close to the perfect predictor's"""
+    w = WL.small(T=512, E=16, D=4, k=2, C=4, d=32, bias_lo=3.0, bias_hi=3.0)
+
+    def routed(profile):
+        L = O.route_logits(WL.hidden(w, profile), WL.router_weight(w), None, WL.token_class(w, profile),
+                           WL.class_bias(w))
+        return O.select_topk(L.astype(np.float32), w.k, w.score, w.renorm)[0]
+    idp, ids = routed(True), routed(False)
+    e2r, _, _ = O.place(*O.coact_hist(idp, w.E), w.D)
+    V = WL.vocab_size(w)
+    tab = O.token_expert_table(WL.token_key(w, True), idp, V, w.E)
+    dev, conf, level = O.lookup_tables(tab, e2r, w.D, w.k)
+    keys = WL.token_key(w)
+    tr_pred, *_ = O.reshuffle_lookup(keys, dev, conf, level, 32768, w.D, w.cap)
+    tr_perf, *_ = O.reshuffle(ids, e2r, w.D, w.cap)
+    lar_pred = 1 - O.remote_fraction(ids, e2r, tr_pred)
+    lar_perf = 1 - O.remote_fraction(ids, e2r, tr_perf)
+    lar_home = 1 - O.remote_fraction(ids, e2r, O.home_rank(w.T, w.D))
+    assert lar_home < 0.4 and lar_pred > 0.75 and lar_pred <= lar_perf + 1e-12
+    cls_of_key = np.arange(V) // WL.KEYS_PER_CLASS
+    for c in range(w.C):
+        seen = dev[(cls_of_key == c) & (dev >= 0)]
+        assert len(seen) and (seen == np.bincount(seen).argmax()).mean() > 0.9
+
+
 def test_home_assignment():
     tr, shf, inv, rc = O.home_assignment(10, 4)
     assert list(tr) == [0, 0, 0, 1, 1, 1, 2, 2, 2, 3] and list(rc) == [3, 3, 3, 1]

@@ -22,7 +22,7 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 # stream ids (one per tensor kind)
-_S_X, _S_WR, _S_PERM, _S_CLASS, _S_BIAS, _S_WGU, _S_WDOWN, _S_FREE, _S_SH = range(9)
+_S_X, _S_WR, _S_PERM, _S_CLASS, _S_BIAS, _S_WGU, _S_WDOWN, _S_FREE, _S_SH, _S_KEY = range(10)
 PROFILE_SEED_OFFSET = 1000
 
 
@@ -192,6 +192,24 @@ def token_class(w: Workload, profile: bool = False, n: Optional[int] = None) -> 
         free = _rng(w, _S_FREE, 0, profile).random(n) < w.free_frac
         cls[free] = -1
     return cls
+
+
+KEYS_PER_CLASS = 64
+
+
+def vocab_size(w: Workload) -> int:
+    """size of the synthetic vocabulary: KEYS_PER_CLASS keys per latent class + as many class-free keys"""
+    return (w.C + 1) * KEYS_PER_CLASS
+
+
+def token_key(w: Workload, profile: bool = False, n: Optional[int] = None) -> np.ndarray:
+    """token_key[T] int32 in [0, vocab_size): a synthetic token id.  Every class owns KEYS_PER_CLASS keys
+    (the tokens of a class are uniform over them); class-free tokens draw from the last KEYS_PER_CLASS keys.
+    Stands in for the vocabulary ids the paper's lookup tables are indexed by."""
+    cls = token_class(w, profile, n)
+    sub = _rng(w, _S_KEY, 0, profile).integers(0, KEYS_PER_CLASS, size=cls.shape[0])
+    base = np.where(cls >= 0, cls, w.C).astype(np.int64) * KEYS_PER_CLASS
+    return (base + sub).astype(np.int32)
 
 
 def expert_weight(w: Workload, e: int) -> Tuple[np.ndarray, np.ndarray]:
