@@ -185,6 +185,18 @@ def main():
     t0 = time.perf_counter()
     e2r_h, phys_h, inv_h = m.place(load.cpu().numpy().astype(np.uint64), coact.cpu().numpy().astype(np.uint64))
     t_place = time.perf_counter() - t0
+    # token-to-expert activation table of the same profile batch -> schedule table (host)
+    V = WL.vocab_size(w)
+    keys_p = up(WL.token_key(w, profile=True))
+    table = torch.zeros(V, E, **i32)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    mp.token_expert_hist(keys_p, idp, Tp, V, table)
+    torch.cuda.synchronize()
+    t_table = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    sched_dev, sched_conf, sched_level = m.lookup_tables(table.cpu().numpy().view(np.uint32), e2r_h)
+    t_lookup = time.perf_counter() - t0
     e2r, phys, inv = up(e2r_h), up(phys_h), up(inv_h)
     del Xp, mp
 
@@ -302,6 +314,30 @@ def main():
         rounds_report[str(R)] = {"ms": round(e0.elapsed_time(e1) / 20, 4),
                                  "remote_pair_fraction": round(int(rpr.item()) / P, 4)}
 
+    # ---------------- next row: reshuffle from the schedule table, by token key alone (not part of the timed step)
+    keys = up(WL.token_key(w))
+    tabs = [up(t) for t in (sched_dev, sched_conf, sched_level)]
+    lookup_report = {"vocabulary": V, "keys_seen_in_profile": int((sched_dev >= 0).sum())}
+    for thr in (0, 16384, 32768):
+        tr2, shf2, ish2 = (torch.empty(T, **i32) for _ in range(3))
+        rc2 = torch.empty(D, **i32)
+        for _ in range(3):
+            m.reshuffle_lookup(keys, V, tabs[0], tabs[1], tabs[2], thr, tr2, shf2, ish2, rc2)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            m.reshuffle_lookup(keys, V, tabs[0], tabs[1], tabs[2], thr, tr2, shf2, ish2, rc2)
+        e1.record()
+        torch.cuda.synchronize()
+        rpr = torch.empty(1, dtype=torch.int64, device=dev)
+        m.dispatch_index(ids, tr2, shf2, phys, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                         torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rpr)
+        torch.cuda.synchronize()
+        lookup_report["thr_%.2f" % (thr / 65536)] = {
+            "ms": round(e0.elapsed_time(e1) / 20, 4), "remote_pair_fraction": round(int(rpr.item()) / P, 4),
+            "tokens_moved_off_home": int((tr2 != home).sum().item())}
+
     # ---------------- algorithmic bytes / flops per launch
     alg = {
         # the bf16 router is one fused kernel (logits never leave the chip); fp32 writes and re-reads them
@@ -356,9 +392,12 @@ def main():
                                  "semmoe_placement_home_ranks": round(int(rp3.item()) / P, 4),
                                  "semmoe_placement_reshuffle": round(remote / P, 4)},
         "reshuffle_with_spill_rounds": rounds_report,
+        "reshuffle_from_schedule_table": lookup_report,
         "load_imbalance_max_over_median": round(float(col.max() / max(np.median(col), 1)), 4),
         "offline_ms": {"route+coact_hist(profile batch of %d)" % Tp: round(t_hist * 1e3, 3),
-                       "place(host)": round(t_place * 1e3, 3)},
+                       "place(host)": round(t_place * 1e3, 3),
+                       "token_expert_hist(profile batch)": round(t_table * 1e3, 3),
+                       "lookup_tables(host)": round(t_lookup * 1e3, 3)},
         "device": torch.cuda.get_device_name(0),
     }
     out["achievable"] = achievable_peaks(m, torch, dev)

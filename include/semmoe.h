@@ -149,6 +149,29 @@ int32_t semmoe_place(const semmoe_config* cfg, const uint64_t* load, const uint6
                      int32_t* expert_of_phys);
 
 /*
+ * token_expert_hist - the token-to-expert activation table of Sec. 3.2, built while profiling:
+ * table[v,e] += #{(i,j): token_key[i] = v and ids[i,j] = e}.  ACCUMULATES over batches: the caller zeroes the table
+ * before the first one.  Pairs whose key lies outside [0,V) or whose expert lies outside [0,E) are skipped.
+ * dev in : token_key[T_batch] i32, topk_ids[T_batch,k].  dev in/out: table[V,E] u32.  cfg->T is ignored.
+ */
+int32_t semmoe_token_expert_hist(const semmoe_config* cfg, void* stream, const int32_t* token_key,
+                                 const int32_t* topk_ids, int32_t T_batch, int32_t V, uint32_t* table);
+
+/*
+ * lookup_tables - the token-to-device schedule table and its confidence (the tables T and T_p read by Alg. 2 and
+ * Alg. 3) from the activation table and a placement; offline, on the host.  With the confidence of Sec. 3.2,
+ * C_p[v,e] = table[v,e] / sum_e table[v,e], the probability that an activation of key v lands on rank r is
+ * mass[v,r] / tot[v] with mass[v,r] = sum of table[v,e] over the experts of r.  In integers:
+ *   dev[v] = argmax_r mass[v,r] (equal -> smallest r);  conf_q16[v] = floor(65536 * mass[v,dev[v]] / tot[v]);
+ *   level[v] = floor((2 k mass[v,dev[v]] + tot[v]) / (2 tot[v])), the expected number of the token's k activations on
+ *   that rank rounded half up: the keep priority, in [0,k].  A key with tot[v] = 0 gets dev = -1, conf_q16 = level = 0.
+ * host in : table[V,E] u32, expert_to_rank[E] (each in [0,D), else SEMMOE_EINVAL).  host out: dev[V], conf_q16[V],
+ *           level[V] i32.
+ */
+int32_t semmoe_lookup_tables(const semmoe_config* cfg, const uint32_t* table, const int32_t* expert_to_rank, int32_t V,
+                             int32_t* dev, int32_t* conf_q16, int32_t* level);
+
+/*
  * reshuffle - Alg. 3 `rebatch_tokens` (device ids, argsort, group_by_key, align, concat) with the
  * device id taken from the token's actual top-k:  g[i,r] = #{j: expert_to_rank[ids[i,j]] = r};
  * pref(i) = argmax_r g[i,r] (equal -> home(i) = i / ceil(T/D) if it is a maximiser, else the smallest);
@@ -174,6 +197,20 @@ int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* 
 int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
                                 const int32_t* expert_to_rank, int32_t rounds, int32_t* token_rank, int32_t* shf,
                                 int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes);
+
+/*
+ * reshuffle from the schedule table - Alg. 3 `rebatch_tokens` as it runs before the gate: the device id of a token is
+ * looked up by its key, dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).  The inter-layer table A is not built here: its
+ * device is the token's home shard and its confidence A_p the constant thr_q16 (in 1/65536).  So
+ *   pref(i) = dev[key_i], conf(i) = level[key_i]  if key_i in [0,V), dev[key_i] in [0,D) and conf_q16[key_i] > thr_q16,
+ *   pref(i) = home(i),    conf(i) = 0             otherwise;
+ * keep, spill and shuffle then exactly as in `semmoe_reshuffle`.  Two launches.
+ * dev in : token_key[T], dev[V], conf_q16[V], level[V] i32.  dev out: token_rank[T], shf[T], inv_shf[T], rank_count[D].
+ */
+int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* stream, const int32_t* token_key, int32_t V,
+                                const int32_t* dev, const int32_t* conf_q16, const int32_t* level, int32_t thr_q16,
+                                int32_t* token_rank, int32_t* shf, int32_t* inv_shf, int32_t* rank_count, void* ws,
+                                size_t ws_bytes);
 
 /*
  * dispatch - the dispatch all2all of expert parallelism (Sec. 1) as a single-device permutation.

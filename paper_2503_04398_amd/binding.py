@@ -78,9 +78,12 @@ _SIGS = {
     "semmoe_route": ([_P] * 12 + [C.c_size_t], C.c_int32),
     "semmoe_route_from_logits": ([_P] * 6, C.c_int32),
     "semmoe_coact_hist": ([_P, _P, _P, C.c_int32, _P, _P], C.c_int32),
+    "semmoe_token_expert_hist": ([_P, _P, _P, _P, C.c_int32, C.c_int32, _P], C.c_int32),
+    "semmoe_lookup_tables": ([_P, _P, _P, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_place": ([_P, _P, _P, C.c_int64, C.c_int64, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
+    "semmoe_reshuffle_lookup": ([_P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch": ([_P] * 15 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_index": ([_P] * 13 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_rows": ([_P] * 5, C.c_int32),
@@ -178,6 +181,23 @@ class SemMoE:
         self._check("semmoe_coact_hist", self.lib.semmoe_coact_hist(
             C.byref(c), _stream(), _ptr(topk_ids), int(T_batch), _ptr(load), _ptr(coact)))
 
+    def token_expert_hist(self, token_key, topk_ids, T_batch, V, table):
+        c = self._cfg()
+        self._check("semmoe_token_expert_hist", self.lib.semmoe_token_expert_hist(
+            C.byref(c), _stream(), _ptr(token_key), _ptr(topk_ids), int(T_batch), int(V), _ptr(table)))
+
+    def lookup_tables(self, table_u32, expert_to_rank):
+        """host call: numpy uint32 [V,E] and int32 [E] in, three numpy int32 [V] arrays out"""
+        import numpy as np
+        table_u32 = np.ascontiguousarray(table_u32, dtype=np.uint32)
+        e2r = np.ascontiguousarray(expert_to_rank, dtype=np.int32)
+        V = table_u32.shape[0]
+        dev, conf, level = (np.zeros(V, dtype=np.int32) for _ in range(3))
+        c = self._cfg()
+        self._check("semmoe_lookup_tables", self.lib.semmoe_lookup_tables(
+            C.byref(c), _ptr(table_u32), _ptr(e2r), int(V), _ptr(dev), _ptr(conf), _ptr(level)))
+        return dev, conf, level
+
     def place(self, load_u64, coact_u64, alpha=1, gamma=0, ft_passes=8):
         """host call: numpy uint64 in, three numpy int32 arrays out"""
         import numpy as np
@@ -202,6 +222,13 @@ class SemMoE:
         self._check("semmoe_reshuffle_rounds", self.lib.semmoe_reshuffle_rounds(
             C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), int(rounds), _ptr(token_rank), _ptr(shf),
             _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def reshuffle_lookup(self, token_key, V, dev, conf_q16, level, thr_q16, token_rank, shf, inv_shf, rank_count,
+                         cap=None):
+        c = self._cfg(**({"cap": cap} if cap is not None else {}))
+        self._check("semmoe_reshuffle_lookup", self.lib.semmoe_reshuffle_lookup(
+            C.byref(c), _stream(), _ptr(token_key), int(V), _ptr(dev), _ptr(conf_q16), _ptr(level), int(thr_q16),
+            _ptr(token_rank), _ptr(shf), _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
 
     def dispatch(self, X, topk_ids, token_rank, shf, phys_of_expert, X_perm, slot_of_pair, pair_of_slot,
                  expert_offsets, rank_offsets, send_matrix, remote_pairs):

@@ -59,6 +59,20 @@ __global__ __launch_bounds__(256) void coact_global_kernel(int E, int k, int T, 
   }
 }
 
+// Token-to-expert activation table (Sec. 3.2): table[key, e] += 1 for every (token, slot) pair.  One thread per
+// pair; the table ([V, E], far larger than LDS) takes the atomics directly.  Keys of a batch are spread over the
+// vocabulary, so the adds rarely collide.
+__global__ __launch_bounds__(256) void token_expert_kernel(int E, int k, int V, int n, const int32_t* __restrict__ keys,
+                                                           const int32_t* __restrict__ ids,
+                                                           uint32_t* __restrict__ table) {
+  const long long np = (long long)n * k;
+  for (long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x; p < np; p += (long long)gridDim.x * blockDim.x) {
+    const int v = keys[p / k];
+    const int e = ids[p];
+    if ((unsigned)v < (unsigned)V && (unsigned)e < (unsigned)E) atomicAdd(&table[size_t(v) * E + e], 1u);
+  }
+}
+
 }  // namespace semmoe
 
 using namespace semmoe;
@@ -85,6 +99,21 @@ extern "C" int32_t semmoe_coact_hist(const semmoe_config* cfg, void* stream, con
     hipLaunchKernelGGL(coact_global_kernel, dim3(grid), dim3(256), 0, s, cfg->E, cfg->k, T_batch, topk_ids, load,
                        coact);
   }
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_token_expert_hist(const semmoe_config* cfg, void* stream, const int32_t* token_key,
+                                            const int32_t* topk_ids, int32_t T_batch, int32_t V, uint32_t* table) {
+  int32_t st = validate_config(cfg, false, false, false);
+  if (st != SEMMOE_OK) return st;
+  if (T_batch < 0 || V <= 0 || !token_key || !topk_ids || !table) return SEMMOE_EINVAL;
+  if (T_batch == 0) return SEMMOE_OK;
+  const long long np = (long long)T_batch * cfg->k;
+  const long long want = (np + 255) / 256;
+  const int grid = want < 4096 ? int(want) : 4096;
+  hipLaunchKernelGGL(token_expert_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), cfg->E, cfg->k,
+                     V, T_batch, token_key, topk_ids, table);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
 }

@@ -90,3 +90,37 @@ extern "C" int32_t semmoe_place(const semmoe_config* cfg, const uint64_t* load, 
   for (int e = 0; e < E; ++e) expert_of_phys[phys_of_expert[e]] = e;
   return SEMMOE_OK;
 }
+
+// Schedule table and confidence from the activation table (the tables T and T_p that Alg. 2 / Alg. 3 read), for a
+// given placement.  Integer arithmetic throughout so that the result does not depend on the machine.
+extern "C" int32_t semmoe_lookup_tables(const semmoe_config* cfg, const uint32_t* table, const int32_t* expert_to_rank,
+                                        int32_t V, int32_t* dev, int32_t* conf_q16, int32_t* level) {
+  if (!cfg || !table || !expert_to_rank || !dev || !conf_q16 || !level) return SEMMOE_EINVAL;
+  const int E = cfg->E, D = cfg->D, k = cfg->k;
+  if (E <= 0 || D <= 0 || k <= 0 || V <= 0) return SEMMOE_EINVAL;
+  for (int e = 0; e < E; ++e)
+    if (expert_to_rank[e] < 0 || expert_to_rank[e] >= D) return SEMMOE_EINVAL;
+  std::vector<i64> mass(D);
+  for (int v = 0; v < V; ++v) {
+    std::fill(mass.begin(), mass.end(), 0);
+    const uint32_t* row = table + static_cast<size_t>(v) * E;
+    i64 tot = 0;
+    for (int e = 0; e < E; ++e) {
+      mass[expert_to_rank[e]] += row[e];
+      tot += row[e];
+    }
+    if (tot == 0) {  // key never profiled: no prediction
+      dev[v] = -1;
+      conf_q16[v] = 0;
+      level[v] = 0;
+      continue;
+    }
+    int best = 0;
+    for (int r = 1; r < D; ++r)
+      if (mass[r] > mass[best]) best = r;  // equal mass -> smallest rank
+    dev[v] = best;
+    conf_q16[v] = static_cast<int32_t>((65536 * mass[best]) / tot);
+    level[v] = static_cast<int32_t>((2 * static_cast<i64>(k) * mass[best] + tot) / (2 * tot));
+  }
+  return SEMMOE_OK;
+}

@@ -78,6 +78,37 @@ __global__ __launch_bounds__(kTokBlock) void rs_pref_kernel(int T, int k, int D,
   for (int x = threadIdx.x; x < nkeys; x += blockDim.x) w.cnt[size_t(blockIdx.x) * nkeys + x] = hist[x];
 }
 
+// K1 of the table-driven form (Alg. 3 `rebatch_tokens` before the gate): the device id and keep priority of a
+// token come from the schedule table indexed by the token's key instead of from its top-k.  A key that was never
+// profiled (dev < 0), lies outside the table, or whose confidence does not exceed the threshold keeps the token at
+// home with priority 0.  Writes the same (pref, conf) word and per-block histogram as rs_pref_kernel.
+__global__ __launch_bounds__(kTokBlock) void rs_lookup_kernel(int T, int k, int D, int V, int per_home, int thr_q16,
+                                                              const int32_t* __restrict__ keys,
+                                                              const int32_t* __restrict__ dev,
+                                                              const int32_t* __restrict__ conf_q16,
+                                                              const int32_t* __restrict__ level, ReshuffleWs w) {
+  extern __shared__ int32_t hist[];  // D*(k+1)
+  const int nkeys = D * (k + 1);
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) hist[x] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  if (i < T) {
+    int pref = i / per_home, conf = 0;
+    const int v = keys[i];
+    if ((unsigned)v < (unsigned)V) {
+      const int d = dev[v];
+      if ((unsigned)d < (unsigned)D && conf_q16[v] > thr_q16) {
+        pref = d;
+        conf = min(max(level[v], 0), k);
+      }
+    }
+    w.pc[i] = pref | (conf << 8);
+    atomicAdd(&hist[pref * (k + 1) + conf], 1);
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) w.cnt[size_t(blockIdx.x) * nkeys + x] = hist[x];
+}
+
 // K2: thresholds per rank, free-slot prefix, borderline prefix over blocks (one workgroup)
 __global__ __launch_bounds__(kScanThreads) void rs_threshold_kernel(int NB, int k, int D, int cap, ReshuffleWs w) {
   __shared__ int32_t tot[SEMMOE_MAX_D * (SEMMOE_MAX_K + 1)];
@@ -950,6 +981,46 @@ extern "C" int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* strea
                          per_home, topk_ids, expert_to_rank, tin, tout, fin, fout, token_rank, shf, inv_shf,
                          rank_count, w);
   }
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* stream, const int32_t* token_key, int32_t V,
+                                           const int32_t* dev, const int32_t* conf_q16, const int32_t* level,
+                                           int32_t thr_q16, int32_t* token_rank, int32_t* shf, int32_t* inv_shf,
+                                           int32_t* rank_count, void* ws, size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, false, false);
+  if (st != SEMMOE_OK) return st;
+  if (!token_key || !dev || !conf_q16 || !level || !token_rank || !shf || !inv_shf || !rank_count) return SEMMOE_EINVAL;
+  if (cfg->cap < 0 || V <= 0) return SEMMOE_EINVAL;
+  if ((long long)cfg->cap * cfg->D < cfg->T) return SEMMOE_ESHAPE;
+  if (cfg->k >= 128) return SEMMOE_EUNSUPPORTED;
+  ReshuffleWs w;
+  if (!carve_reshuffle(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int T = cfg->T, D = cfg->D, k = cfg->k;
+  const int NB = cdiv(T, kTokBlock);
+  if (T == 0) {
+    hipLaunchKernelGGL(rs_zero_kernel, dim3(1), dim3(64), 0, s, D, rank_count);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  const int per_home = cdiv(T, D);
+  const int nkeys = D * (k + 1);
+  hipLaunchKernelGGL(rs_lookup_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, V, per_home, thr_q16,
+                     token_key, dev, conf_q16, level, w);
+  if (NB <= kFusedMaxNB && D <= 64) {
+    hipLaunchKernelGGL(rs_fused_kernel, dim3(NB), dim3(kTokBlock), rs_fused_lds(D, k), s, T, NB, k, D, cfg->cap,
+                       token_rank, shf, inv_shf, rank_count, w);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, k, D, cfg->cap, w);
+  hipLaunchKernelGGL(rs_keep_kernel, dim3(NB), dim3(kTokBlock), (D * kWords + 1) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D + 1) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, D, rank_count, w);
+  hipLaunchKernelGGL(rs_scatter_kernel, dim3(NB), dim3(kTokBlock), D * kWords * 4, s, T, D, token_rank, shf, inv_shf,
+                     w);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
 }

@@ -122,6 +122,24 @@ class Layer:
         torch.cuda.synchronize()
         return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
 
+    def token_expert_hist(self, keys, ids, V, table=None):
+        """accumulate one batch into the activation table; returns the device table (int32 storage of the u32 counts)"""
+        if table is None:
+            table = torch.zeros(V, self.w.E, dtype=torch.int32, device=DEV)
+        keys_d = to_dev(np.asarray(keys, dtype=np.int32))
+        ids_d = to_dev(np.asarray(ids, dtype=np.int32))
+        self.m.token_expert_hist(keys_d, ids_d, ids_d.shape[0], V, table)
+        torch.cuda.synchronize()
+        return table
+
+    def reshuffle_lookup(self, keys, dev, conf_q16, level, thr_q16, cap=None):
+        keys_d = to_dev(np.asarray(keys, dtype=np.int32))
+        tabs = [to_dev(np.asarray(t, dtype=np.int32)) for t in (dev, conf_q16, level)]
+        self.m.reshuffle_lookup(keys_d, tabs[0].shape[0], tabs[0], tabs[1], tabs[2], thr_q16, self.token_rank,
+                                self.shf, self.inv_shf, self.rank_count, cap=cap)
+        torch.cuda.synchronize()
+        return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
+
     def set_assignment(self, token_rank, shf, inv_shf):
         self.token_rank.copy_(torch.from_numpy(np.asarray(token_rank, dtype=np.int32)))
         self.shf.copy_(torch.from_numpy(np.asarray(shf, dtype=np.int32)))

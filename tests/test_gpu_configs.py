@@ -51,8 +51,16 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
     assert (load == ol).all() and (co == oc).all()
     oe2r, ophys, oinv = O.place(ol, oc, w.D)
     assert (e2r == oe2r).all() and (phys == ophys).all() and (inv == oinv).all()
+    # the table-driven row: activation table of the profile batch by token key, then the schedule table
+    V = WL.vocab_size(w)
+    pkeys = WL.token_key(w, profile=True)
+    table = H.to_np(play.token_expert_hist(pkeys, pids, V)).astype(np.int64)
+    assert (table == O.token_expert_table(pkeys, pids, V, w.E)).all()
+    sched = play.m.lookup_tables(table.astype(np.uint32), e2r)
+    for g, x, nm in zip(sched, O.lookup_tables(table, e2r, w.D, w.k), ("dev", "conf_q16", "level")):
+        assert (g == x).all(), nm
     del play, pinp
-    _say("  [%5.1fs] coact_hist and place bit-exact" % (time.time() - t0))
+    _say("  [%5.1fs] coact_hist, place, token-expert table and schedule table bit-exact" % (time.time() - t0))
     # ---- reshuffle, dispatch
     lay.set_placement(e2r, phys, inv)
     got = lay.reshuffle()
@@ -66,6 +74,15 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
         assert (g == x).all(), "rounds: " + nm
     _say("  [%5.1fs] reshuffle with 3 spill rounds bit-exact; remote-pair fraction %.4f (1 round: %.4f)"
          % (time.time() - t0, O.remote_fraction(ids, e2r, want3[0]), O.remote_fraction(ids, e2r, want[0])))
+    # the table-driven row at the full size: rebatch from token keys alone, two thresholds
+    keys = WL.token_key(w)
+    for thr in (0, 24576):
+        gotl = lay.reshuffle_lookup(keys, sched[0], sched[1], sched[2], thr)
+        wantl = O.reshuffle_lookup(keys, sched[0], sched[1], sched[2], thr, w.D, w.cap)
+        for g, x, nm in zip(gotl, wantl, ("token_rank", "shf", "inv_shf", "rank_count")):
+            assert (g == x).all(), "lookup: " + nm
+        _say("  [%5.1fs] reshuffle from the schedule table (thr %.3f) bit-exact; remote-pair fraction %.4f"
+             % (time.time() - t0, thr / 65536, O.remote_fraction(ids, e2r, wantl[0])))
     got = lay.reshuffle()          # the layer below runs on the plain reshuffle
     tr, shf, ishf, rc = want
     dg = lay.dispatch()

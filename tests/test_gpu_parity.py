@@ -174,6 +174,76 @@ def test_reshuffle_rounds_bit_exact(T, E, D, k, cf, noise, rounds):
             assert (g == w_).all()
 
 
+@pytest.mark.parametrize("T,E,D,k,V,batches", [
+    (256, 16, 4, 2, 64, 1), (1000, 128, 8, 8, 500, 3), (777, 64, 16, 4, 33, 2), (5, 16, 4, 2, 7, 1),
+    (4000, 256, 32, 8, 1000, 2), (3000, 48, 3, 16, 128, 1), (70000, 32, 4, 2, 9, 1)])
+def test_token_expert_hist_bit_exact(T, E, D, k, V, batches):
+    """token-to-expert activation table against the oracle, accumulated over batches; pairs whose key lies outside
+    the vocabulary or whose expert id lies outside [0,E) are skipped (the oracle is given the valid pairs only)"""
+    _say("token-expert hist", T, E, D, k, V, batches)
+    r = np.random.default_rng(T * 3 + V)
+    lay = H.Layer(WL.small(T=T, E=E, D=D, k=k, d=8))
+    table, want = None, None
+    for b in range(batches):
+        ids, _ = _planted(T, E, D, k, seed=T + b, noise=0.4)
+        keys = r.integers(0, V, size=T).astype(np.int32)
+        if b == batches - 1 and T > 4:
+            keys[1], keys[2] = V + 5, -1
+            ids[3, 0], ids[4, k - 1] = -1, E
+        pair_key = np.repeat(keys, k)
+        pair_id = ids.reshape(-1, 1)
+        ok = (pair_key >= 0) & (pair_key < V) & (pair_id[:, 0] >= 0) & (pair_id[:, 0] < E)
+        want = O.token_expert_table(pair_key[ok], pair_id[ok], V, E, want)
+        table = lay.token_expert_hist(keys, ids, V, table)
+    got = H.to_np(table).astype(np.int64)
+    assert (got == want).all(), np.argwhere(got != want)[:8]
+
+
+@pytest.mark.parametrize("T,E,D,k,cf,V,thr", [
+    (256, 16, 4, 2, 1.0, 64, 0), (1000, 128, 8, 8, 1.0, 200, 20000), (777, 64, 16, 4, 1.0, 33, 30000),
+    (300, 32, 32, 2, 1.0, 100, 0), (513, 16, 4, 4, 1.25, 50, 40000), (100, 8, 1, 2, 1.0, 10, 0),
+    (2049, 64, 64, 1, 1.0, 300, 10000), (5, 16, 4, 2, 1.0, 4, 0), (4000, 256, 32, 8, 1.0, 700, 16384),
+    (3000, 48, 3, 16, 1.0, 256, 65536), (3000, 48, 3, 16, 1.0, 256, -1), (40000, 64, 16, 4, 1.0, 320, 20000)])
+def test_reshuffle_lookup_bit_exact(T, E, D, k, cf, V, thr):
+    """table-driven reshuffle against the oracle, bit for bit: the tables come from the library's own profile pass
+    (device histogram, host tables), checked against the oracle's, then one rebatch from keys alone; a few keys
+    are left unseen and a few lie outside the table"""
+    _say("reshuffle lookup", T, E, D, k, cf, V, thr)
+    r = np.random.default_rng(T + V)
+    ids, e2r = _planted(T, E, D, k, seed=T + D, noise=0.3)
+    # keys follow the planted cluster of the token, so that the table predicts: cluster c owns keys = c mod D
+    g = O.gain_matrix(ids, e2r, D)
+    keys = (g.argmax(axis=1) + D * r.integers(0, max(V // D, 1), size=T)).astype(np.int32) % V
+    seen = r.random(T) < 0.9                      # profile on most tokens only: some keys stay unseen
+    cap = int(math.ceil(cf * T / D))
+    w = WL.small(T=T, E=E, D=D, k=k)
+    lay = H.Layer(w, cap=cap)
+    table = H.to_np(lay.token_expert_hist(keys[seen], ids[seen], V)).astype(np.int64)
+    assert (table == O.token_expert_table(keys[seen], ids[seen], V, E)).all()
+    dev, conf, level = lay.m.lookup_tables(table.astype(np.uint32), e2r)
+    for g_, w_ in zip((dev, conf, level), O.lookup_tables(table, e2r, D, k)):
+        assert (g_ == w_).all()
+    got = lay.reshuffle_lookup(keys, dev, conf, level, thr, cap=cap)
+    want = O.reshuffle_lookup(keys, dev, conf, level, thr, D, cap)
+    for g_, w_, name in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g_ == w_).all(), (name, np.flatnonzero(g_ != w_)[:8])
+    assert (got[3] <= cap).all()
+    if thr >= 65536:                               # 65536 = certainty: nothing exceeds it, everyone stays home
+        assert (got[0] == O.home_rank(T, D)).all()
+    if T > 8:                                      # keys outside the table stay home with priority 0
+        keys2 = keys.copy()
+        keys2[::7] = V + 3
+        keys2[3::7] = -2
+        dev2 = np.concatenate([dev, [-1]]).astype(np.int32)       # the oracle reads them as one more unseen key
+        conf2 = np.concatenate([conf, [0]]).astype(np.int32)
+        lev2 = np.concatenate([level, [0]]).astype(np.int32)
+        kk = np.where((keys2 < 0) | (keys2 >= V), V, keys2)
+        got2 = lay.reshuffle_lookup(keys2, dev, conf, level, thr, cap=cap)
+        want2 = O.reshuffle_lookup(kk, dev2, conf2, lev2, thr, D, cap)
+        for g_, w_ in zip(got2, want2):
+            assert (g_ == w_).all()
+
+
 def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit():
     """beyond what the single-workgroup kernels hold; multi-workgroup kernels by default"""
     T, E, D, k = 40000, 64, 16, 4

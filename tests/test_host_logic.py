@@ -138,6 +138,35 @@ def test_host_place_equals_oracle_on_config2_profile_routing():
         assert (g == w_).all()
 
 
+@pytest.mark.parametrize("V,E,D,k,seed", [(40, 16, 4, 2, 0), (300, 64, 8, 8, 1), (17, 8, 1, 2, 2), (64, 32, 32, 4, 3),
+                                          (128, 48, 3, 16, 4)])
+def test_host_lookup_tables_equal_oracle(V, E, D, k, seed):
+    """schedule table, confidence and keep priority from an activation table: integer for integer; the table has
+    unseen keys, ties between ranks and single-activation keys"""
+    r = np.random.default_rng(seed)
+    table = r.integers(0, 6, size=(V, E)).astype(np.int64) * (r.random((V, E)) < 0.3)
+    table[0] = 0                      # never profiled
+    table[1] = 0
+    table[1, :2] = 1                  # two experts once each: a tie between ranks when they sit apart
+    if V > 2:
+        table[2] = 0
+        table[2, E - 1] = 1           # a single activation
+    e2r = (r.permutation(E) % D).astype(np.int32)
+    want = O.lookup_tables(table, e2r, D, k)
+    m = S.SemMoE(S.Config(T=1, d=8, E=E, k=k, F=8, D=D, cap=1), allocate_workspace=False)
+    got = m.lookup_tables(table.astype(np.uint32), e2r)
+    for g, w_, name in zip(got, want, ("dev", "conf_q16", "level")):
+        assert g.dtype == np.int32 and (g == w_).all(), name
+    assert got[0][0] == -1 and got[1][0] == 0 and got[2][0] == 0
+
+
+def test_host_lookup_tables_reject_bad_arguments():
+    m = S.SemMoE(S.Config(T=1, d=8, E=8, k=2, F=8, D=4, cap=1), allocate_workspace=False)
+    with pytest.raises(S.SemMoEError) as ei:
+        m.lookup_tables(np.ones((4, 8), dtype=np.uint32), np.full(8, 4, dtype=np.int32))   # rank out of range
+    assert ei.value.status == -1
+
+
 def test_host_place_rejects_bad_arguments():
     m = S.SemMoE(S.Config(T=1, d=8, E=15, k=2, F=8, D=4, cap=1), allocate_workspace=False)
     with pytest.raises(S.SemMoEError) as ei:
