@@ -20,6 +20,13 @@ Which passage each function follows
                                key-free form; expert-expert affinity of Alg. 1
   place                        Alg. 1 `expert_place` (+ App. B text), request term dropped
   reshuffle                    Alg. 3 `rebatch_tokens` (argsort, group, align, concat)
+  reshuffle_rounds             the same with gain-aware spill rounds (towards the Sec. 3.3 optimum)
+  token_expert_table / lookup_tables / reshuffle_lookup
+                               token-to-expert activation table and confidence (Sec. 3.2), the
+                               schedule table T / T_p, and Alg. 3 `rebatch_tokens` driven by it
+  request_schedule / request_assignment
+                               Alg. 2 `get_dp_rank` + `schedule` (Attention-DP scenario), with
+                               S_r = argmax_j sum_{i in r} R_ij of Sec. 3.3
   reshuffle_exact              the ILP's communication term (Sec. 3.3) solved exactly
                                for fixed placement: min-cost flow
   dispatch / combine           the two all2all of expert parallelism (Sec. 1) as
@@ -481,6 +488,53 @@ def reshuffle_lookup(keys, dev, conf_q16, level, thr_q16: int, D: int, cap: int)
     free_slots = [r for r in range(D) for _ in range(int(cap - kept[r]))]
     for s, i in enumerate([i for i in range(T) if token_rank[i] < 0]):
         token_rank[i] = free_slots[s]
+    shf = np.argsort(token_rank, kind="stable")
+    inv_shf = np.zeros(T, dtype=np.int64)
+    inv_shf[shf] = np.arange(T)
+    return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
+            np.bincount(token_rank, minlength=D).astype(np.int32))
+
+
+def request_schedule(req_offsets, keys, dev, D: int) -> np.ndarray:
+    """Online request scheduling of the Attention-DP scenario (Alg. 2 `get_dp_rank`, with the request-to-cluster
+    rule S_r = argmax_j sum_{i in r} R_ij of Sec. 3.3).  The schedule table holds one device per token id, so its
+    row read as a vector over devices is one-hot and the score of a request is a count:
+        dev_score[r] = #{tokens i of the request: dev[keys[i]] = r}   (keys never profiled count nowhere).
+    Requests are taken in arrival order; a request goes to the unmasked device of the highest score (equal ->
+    the smallest id), that device is masked, and once every device is masked the mask is cleared: any D
+    consecutive requests of a round land on D different devices.  Returns req_rank[n_req] int32."""
+    off = np.asarray(req_offsets)
+    keys = np.asarray(keys)
+    n_req = off.shape[0] - 1
+    req_rank = np.zeros(n_req, dtype=np.int32)
+    dev_mask = [True] * D
+    for q in range(n_req):
+        dev_score = [0] * D
+        for i in range(int(off[q]), int(off[q + 1])):
+            r = int(dev[int(keys[i])])
+            if r >= 0:
+                dev_score[r] += 1
+        best = -1
+        for r in range(D):
+            if dev_mask[r] and (best < 0 or dev_score[r] > dev_score[best]):
+                best = r
+        req_rank[q] = best
+        dev_mask[best] = False
+        if not any(dev_mask):
+            dev_mask = [True] * D
+    return req_rank
+
+
+def request_assignment(req_offsets, req_rank, D: int):
+    """`schedule(R, dev_id)` of Alg. 2 in the index form the rest of the path reads: every token inherits the rank
+    of its request; shf = tokens stably sorted by rank (so a rank holds its requests in arrival order, each
+    contiguous); inv_shf[shf[q]] = q.  No capacity bound: a DP rank holds whole requests.
+    Returns (token_rank, shf, inv_shf, rank_count) int32."""
+    off = np.asarray(req_offsets)
+    T = int(off[-1])
+    token_rank = np.zeros(T, dtype=np.int64)
+    for q in range(off.shape[0] - 1):
+        token_rank[int(off[q]):int(off[q + 1])] = int(req_rank[q])
     shf = np.argsort(token_rank, kind="stable")
     inv_shf = np.zeros(T, dtype=np.int64)
     inv_shf[shf] = np.arange(T)

@@ -22,7 +22,7 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 # stream ids (one per tensor kind)
-_S_X, _S_WR, _S_PERM, _S_CLASS, _S_BIAS, _S_WGU, _S_WDOWN, _S_FREE, _S_SH, _S_KEY = range(10)
+_S_X, _S_WR, _S_PERM, _S_CLASS, _S_BIAS, _S_WGU, _S_WDOWN, _S_FREE, _S_SH, _S_KEY, _S_REQ = range(11)
 PROFILE_SEED_OFFSET = 1000
 
 
@@ -210,6 +210,39 @@ def token_key(w: Workload, profile: bool = False, n: Optional[int] = None) -> np
     sub = _rng(w, _S_KEY, 0, profile).integers(0, KEYS_PER_CLASS, size=cls.shape[0])
     base = np.where(cls >= 0, cls, w.C).astype(np.int64) * KEYS_PER_CLASS
     return (base + sub).astype(np.int32)
+
+
+def requests(w: Workload, profile: bool = False, n: Optional[int] = None, min_len: int = 16, max_len: int = 1024,
+             topic_frac: float = 0.8) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Synthetic requests for the request-level (Attention-DP) scenario: the batch of n tokens is cut into runs,
+    one per request, with lengths log-uniform in [min_len, max_len] (the last one truncated to fit).  A request
+    has a topic class drawn from the workload's class mix; each of its tokens carries the topic with probability
+    topic_frac, otherwise it is an ordinary token of the batch mix (`token_class`).  Keys follow the classes as in
+    `token_key`.  Returns (req_offsets[n_req+1] int32, token_class[n] int32, token_key[n] int32)."""
+    n = n if n is not None else (w.profile_tokens if profile else w.T)
+    rng = _rng(w, _S_REQ, 0, profile)
+    lens = []
+    left = n
+    while left > 0:
+        ln = int(np.exp(rng.uniform(np.log(min_len), np.log(max_len))))
+        ln = max(1, min(ln, left))
+        lens.append(ln)
+        left -= ln
+    off = np.zeros(len(lens) + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    if w.class_mix == "zipf":
+        p = (np.arange(w.C) + 1.0) ** (-w.zipf_s)
+        p /= p.sum()
+        topic = rng.choice(w.C, size=len(lens), p=p)
+    else:
+        topic = rng.integers(0, w.C, size=len(lens))
+    cls = token_class(w, profile, n).copy()
+    on_topic = rng.random(n) < topic_frac
+    req_of = np.repeat(np.arange(len(lens)), lens)
+    cls[on_topic] = topic[req_of[on_topic]].astype(np.int32)
+    sub = _rng(w, _S_REQ, 1, profile).integers(0, KEYS_PER_CLASS, size=n)
+    base = np.where(cls >= 0, cls, w.C).astype(np.int64) * KEYS_PER_CLASS
+    return off, cls, (base + sub).astype(np.int32)
 
 
 def expert_weight(w: Workload, e: int) -> Tuple[np.ndarray, np.ndarray]:
