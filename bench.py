@@ -338,6 +338,36 @@ def main():
             "ms": round(e0.elapsed_time(e1) / 20, 4), "remote_pair_fraction": round(int(rpr.item()) / P, 4),
             "tokens_moved_off_home": int((tr2 != home).sum().item())}
 
+    # ---------------- next row: request-level scheduling (Attention-DP): requests = runs of tokens of one topic
+    req_off_h, req_cls_h, req_key_h = WL.requests(w)
+    n_req = len(req_off_h) - 1
+    req_off, req_cls, req_key = up(req_off_h), up(req_cls_h), up(req_key_h)
+    ids_r = torch.empty(T, k, **i32)
+    tw_r = torch.empty(T, k, dtype=torch.float32, device=dev)
+    m.route(X, W_r, ids_r, tw_r, token_class=req_cls, class_bias=cb)
+    req_rank = torch.empty(n_req, **i32)
+    tr2, shf2, ish2 = (torch.empty(T, **i32) for _ in range(3))
+    rc2 = torch.empty(D, **i32)
+    request_report = {"requests": n_req}
+    for label, table_dev in (("round_robin", torch.full((V,), -1, **i32)), ("schedule_table", tabs[0])):
+        for _ in range(3):
+            m.request_schedule(req_off, n_req, req_key, V, table_dev, req_rank, tr2, shf2, ish2, rc2)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            m.request_schedule(req_off, n_req, req_key, V, table_dev, req_rank, tr2, shf2, ish2, rc2)
+        e1.record()
+        torch.cuda.synchronize()
+        rpr = torch.empty(1, dtype=torch.int64, device=dev)
+        m.dispatch_index(ids_r, tr2, shf2, phys, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                         torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rpr)
+        torch.cuda.synchronize()
+        rch = rc2.cpu().numpy()
+        request_report[label] = {"ms": round(e0.elapsed_time(e1) / 20, 4),
+                                 "remote_pair_fraction": round(int(rpr.item()) / P, 4),
+                                 "tokens_per_rank_max_over_mean": round(float(rch.max() / max(rch.mean(), 1)), 3)}
+
     # ---------------- algorithmic bytes / flops per launch
     alg = {
         # the bf16 router is one fused kernel (logits never leave the chip); fp32 writes and re-reads them
@@ -393,6 +423,7 @@ def main():
                                  "semmoe_placement_reshuffle": round(remote / P, 4)},
         "reshuffle_with_spill_rounds": rounds_report,
         "reshuffle_from_schedule_table": lookup_report,
+        "request_schedule": request_report,
         "load_imbalance_max_over_median": round(float(col.max() / max(np.median(col), 1)), 4),
         "offline_ms": {"route+coact_hist(profile batch of %d)" % Tp: round(t_hist * 1e3, 3),
                        "place(host)": round(t_place * 1e3, 3),

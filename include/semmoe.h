@@ -213,6 +213,26 @@ int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* stream, const in
                                 size_t ws_bytes);
 
 /*
+ * request_schedule - online request scheduling of the Attention-DP scenario: Alg. 2 `get_dp_rank` and `schedule`,
+ * with the request-to-cluster rule S_r = argmax_j sum_{i in r} R_ij of Sec. 3.3.  Request q owns the tokens
+ * [req_offsets[q], req_offsets[q+1]); the schedule table holds one device per token key (`dev` of
+ * `semmoe_lookup_tables`), so a request's score is a count: dev_score[r] = #{i in q: dev[token_key[i]] = r}; keys
+ * outside [0,V) or with dev outside [0,D) count nowhere.  Requests are taken in order: a request goes to the unmasked
+ * device of the highest score (equal -> the smallest id), that device is masked, and after D allocations the mask is
+ * cleared, so D consecutive requests of a round reach D different ranks.  Every token inherits the rank of its request;
+ * shf = tokens stably sorted by rank (no capacity bound: a rank holds whole requests), inv_shf[shf[p]] = p.
+ * cfg->T = total tokens = req_offsets[n_req]; req_offsets[0] = 0, ascending (offsets are clamped into [0,T] when read;
+ * the result is defined only for ascending ones).  0 <= n_req <= max(T,1); D <= 64 and T < 2^25, else
+ * SEMMOE_EUNSUPPORTED.  Three launches.
+ * dev in : req_offsets[n_req+1], token_key[T], dev[V] i32.
+ * dev out: req_rank[n_req], token_rank[T], shf[T], inv_shf[T], rank_count[D].
+ */
+int32_t semmoe_request_schedule(const semmoe_config* cfg, void* stream, const int32_t* req_offsets, int32_t n_req,
+                                const int32_t* token_key, int32_t V, const int32_t* dev, int32_t* req_rank,
+                                int32_t* token_rank, int32_t* shf, int32_t* inv_shf, int32_t* rank_count, void* ws,
+                                size_t ws_bytes);
+
+/*
  * dispatch - the dispatch all2all of expert parallelism (Sec. 1) as a single-device permutation.
  *   Pairs are ordered by physical expert q = phys_of_expert[ids[i,j]], pairs of one expert by shuffled
  *   pair index p' = inv_shf[i]*k + j (arrival order of a rank-ordered all2all).  slot = that position.

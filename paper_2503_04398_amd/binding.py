@@ -84,6 +84,7 @@ _SIGS = {
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_lookup": ([_P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
+    "semmoe_request_schedule": ([_P, _P, _P, C.c_int32, _P, C.c_int32] + [_P] * 7 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch": ([_P] * 15 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_index": ([_P] * 13 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_rows": ([_P] * 5, C.c_int32),
@@ -228,6 +229,12 @@ class SemMoE:
         c = self._cfg(**({"cap": cap} if cap is not None else {}))
         self._check("semmoe_reshuffle_lookup", self.lib.semmoe_reshuffle_lookup(
             C.byref(c), _stream(), _ptr(token_key), int(V), _ptr(dev), _ptr(conf_q16), _ptr(level), int(thr_q16),
+            _ptr(token_rank), _ptr(shf), _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def request_schedule(self, req_offsets, n_req, token_key, V, dev, req_rank, token_rank, shf, inv_shf, rank_count):
+        c = self._cfg()
+        self._check("semmoe_request_schedule", self.lib.semmoe_request_schedule(
+            C.byref(c), _stream(), _ptr(req_offsets), int(n_req), _ptr(token_key), int(V), _ptr(dev), _ptr(req_rank),
             _ptr(token_rank), _ptr(shf), _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
 
     def dispatch(self, X, topk_ids, token_rank, shf, phys_of_expert, X_perm, slot_of_pair, pair_of_slot,

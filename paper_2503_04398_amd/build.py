@@ -21,7 +21,7 @@ LIB = os.path.join(LIBDIR, "libsemmoe.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = ["common.hip", "gemm.hip", "route.hip", "hist.hip", "reshuffle.hip", "dispatch.hip", "ffn.hip",
-           "combine.hip", "probe.hip", "place.cpp"]
+           "combine.hip", "request.hip", "probe.hip", "place.cpp"]
 
 HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions

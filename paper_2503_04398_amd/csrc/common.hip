@@ -45,6 +45,7 @@ extern "C" int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* byte
   if (ws_reshuffle(cfg) > b) b = ws_reshuffle(cfg);
   if (ws_dispatch(cfg) > b) b = ws_dispatch(cfg);
   if (ws_ffn(cfg) > b) b = ws_ffn(cfg);
+  if (ws_request(cfg) > b) b = ws_request(cfg);
   *bytes_out = b;
   return SEMMOE_OK;
 }

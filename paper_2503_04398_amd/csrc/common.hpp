@@ -59,6 +59,7 @@ size_t ws_route(const semmoe_config* cfg);
 size_t ws_reshuffle(const semmoe_config* cfg);
 size_t ws_dispatch(const semmoe_config* cfg);
 size_t ws_ffn(const semmoe_config* cfg);
+size_t ws_request(const semmoe_config* cfg);
 int tuning_value(int key);  // current value of a SEMMOE_TUNE_* knob (-1: default)
 
 // ---- device helpers -----------------------------------------------------------------------------

@@ -140,6 +140,18 @@ class Layer:
         torch.cuda.synchronize()
         return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
 
+    def request_schedule(self, req_offsets, keys, dev):
+        off_d = to_dev(np.asarray(req_offsets, dtype=np.int32))
+        keys_d = to_dev(np.asarray(keys, dtype=np.int32))
+        dev_d = to_dev(np.asarray(dev, dtype=np.int32))
+        n_req = off_d.shape[0] - 1
+        req_rank = torch.full((max(n_req, 1),), -7, dtype=torch.int32, device=DEV)
+        self.m.request_schedule(off_d, n_req, keys_d, dev_d.shape[0], dev_d, req_rank, self.token_rank, self.shf,
+                                self.inv_shf, self.rank_count)
+        torch.cuda.synchronize()
+        return (to_np(req_rank)[:n_req],) + tuple(
+            to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
+
     def set_assignment(self, token_rank, shf, inv_shf):
         self.token_rank.copy_(torch.from_numpy(np.asarray(token_rank, dtype=np.int32)))
         self.shf.copy_(torch.from_numpy(np.asarray(shf, dtype=np.int32)))

@@ -83,6 +83,14 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
             assert (g == x).all(), "lookup: " + nm
         _say("  [%5.1fs] reshuffle from the schedule table (thr %.3f) bit-exact; remote-pair fraction %.4f"
              % (time.time() - t0, thr / 65536, O.remote_fraction(ids, e2r, wantl[0])))
+    # the request-level row at the full size: requests = runs of tokens of one topic, ranks from the schedule table
+    roff, _, rkeys = WL.requests(w)
+    gotq = lay.request_schedule(roff, rkeys, sched[0])
+    wrr = O.request_schedule(roff, rkeys, sched[0], w.D)
+    for g, x, nm in zip(gotq, (wrr,) + O.request_assignment(roff, wrr, w.D),
+                        ("req_rank", "token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == x).all(), "request schedule: " + nm
+    _say("  [%5.1fs] request schedule of %d requests bit-exact" % (time.time() - t0, len(roff) - 1))
     got = lay.reshuffle()          # the layer below runs on the plain reshuffle
     tr, shf, ishf, rc = want
     dg = lay.dispatch()

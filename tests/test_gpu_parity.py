@@ -244,6 +244,47 @@ def test_reshuffle_lookup_bit_exact(T, E, D, k, cf, V, thr):
             assert (g_ == w_).all()
 
 
+@pytest.mark.parametrize("T,D,V,n_req,seed", [
+    (256, 4, 64, 7, 0), (1000, 8, 500, 40, 1), (777, 16, 33, 100, 2), (5, 4, 7, 5, 3), (4000, 32, 1000, 64, 4),
+    (3000, 3, 128, 1, 5), (2049, 64, 300, 200, 6), (100, 1, 10, 9, 7), (100000, 8, 1088, 3000, 8),
+    (64, 8, 16, 64, 9)])
+def test_request_schedule_bit_exact(T, D, V, n_req, seed):
+    """request-level scheduling against the oracle, bit for bit: ranks of the requests, the tokens' ranks and the
+    shuffle; random request lengths with empty requests, a table with unseen keys, keys outside the table"""
+    _say("request schedule", T, D, V, n_req, seed)
+    r = np.random.default_rng(seed)
+    cuts = np.sort(r.integers(0, T + 1, size=n_req - 1)) if n_req > 1 else np.zeros(0, dtype=np.int64)
+    if n_req == T:
+        cuts = np.arange(1, T)                      # one token per request
+    off = np.concatenate([[0], cuts, [T]]).astype(np.int32)
+    dev = r.integers(-1, D, size=V).astype(np.int32)
+    # requests lean towards one device each, so that the mask decides often
+    keys = r.integers(0, V, size=T).astype(np.int32)
+    by_dev = [np.flatnonzero(dev == x) for x in range(D)]
+    for q in range(n_req):
+        x = int(r.integers(0, D))
+        if len(by_dev[x]) and off[q + 1] > off[q]:
+            lean = r.random(off[q + 1] - off[q]) < 0.6
+            keys[off[q]:off[q + 1]][lean] = r.choice(by_dev[x], size=int(lean.sum()))
+    lay = H.Layer(WL.small(T=T, E=2 * D, D=D, k=1, d=8))
+    got = lay.request_schedule(off, keys, dev)
+    want_rr = O.request_schedule(off, keys, dev, D)
+    want = (want_rr,) + O.request_assignment(off, want_rr, D)
+    for g, w_, name in zip(got, want, ("req_rank", "token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == w_).all(), (name, np.flatnonzero(g != w_)[:8])
+    if T > 8:                                       # keys outside the table count nowhere
+        keys2 = keys.copy()
+        keys2[::5] = V + 1
+        keys2[2::5] = -3
+        dev2 = np.concatenate([dev, [-1]]).astype(np.int32)
+        kk = np.where((keys2 < 0) | (keys2 >= V), V, keys2)
+        got2 = lay.request_schedule(off, keys2, dev)
+        want_rr2 = O.request_schedule(off, kk, dev2, D)
+        want2 = (want_rr2,) + O.request_assignment(off, want_rr2, D)
+        for g, w_ in zip(got2, want2):
+            assert (g == w_).all()
+
+
 def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit():
     """beyond what the single-workgroup kernels hold; multi-workgroup kernels by default"""
     T, E, D, k = 40000, 64, 16, 4
