@@ -107,6 +107,10 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times before the timed loops: under rocprofv3 "
                          "--pmc its FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
+    ap.add_argument("--balance-study", action="store_true",
+                    help="instead of the timed layer step: sweep the load weight gamma of the placement and the capacity "
+                         "factor of the reshuffle, and print remote-pair fraction, per-rank load imbalance and the FFN "
+                         "time of the slowest rank for each point (one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a one-GPU hot path (logical ranks are simulated on one device); "
@@ -199,6 +203,49 @@ def main():
     t_lookup = time.perf_counter() - t0
     e2r, phys, inv = up(e2r_h), up(phys_h), up(inv_h)
     del Xp, mp
+
+    if args.balance_study:
+        m.route(X, W_r, ids, tw, token_class=tc, class_bias=cb)
+        load_h, coact_h = load.cpu().numpy().astype(np.uint64), coact.cpu().numpy().astype(np.uint64)
+
+        def ffn_ms(rank, reps=5):
+            m.expert_ffn(rank, X_perm, expert_offsets, inv_s, W_gu, W_down, Y)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                m.expert_ffn(rank, X_perm, expert_offsets, inv_s, W_gu, W_down, Y)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        points = []
+        for alpha, gamma, ft in ((1, 0, 8), (1, 1, 8), (1, 0, 0), (64, 1, 0), (32, 1, 0), (16, 1, 0), (8, 1, 0), (4, 1, 0),
+                                 (2, 1, 0), (1, 1, 0), (0, 1, 0)):
+            e2r_s, phys_s, inv_s = (up(a) for a in m.place(load_h, coact_h, alpha, gamma, ft))
+            rank_load = np.bincount(e2r_s.cpu().numpy(), weights=load_h.astype(np.float64), minlength=D)
+            for cf in (1.0, 1.25, 1.5, 2.0, float(D)):
+                cap = min(T, int(np.ceil(cf * T / D)))
+                m.reshuffle(ids, e2r_s, token_rank, shf, inv_shf, rank_count, cap=cap)
+                m.dispatch_index(ids, token_rank, shf, phys_s, slot_of_pair, pair_of_slot, expert_offsets,
+                                 rank_offsets, send_matrix, remote_pairs)
+                m.dispatch_rows(X, slot_of_pair, X_perm)
+                torch.cuda.synchronize()
+                ro = rank_offsets.cpu().numpy()
+                pairs = np.diff(ro)                       # pairs computed by each rank's experts
+                tokens = rank_count.cpu().numpy()         # tokens held by each rank after the reshuffle
+                per_rank = [ffn_ms(r) for r in range(D)]
+                points.append({
+                    "alpha": alpha, "gamma": gamma, "ft_passes": ft, "cf": round(cf, 2),
+                    "remote_pair_fraction": round(int(remote_pairs.item()) / P, 4),
+                    "pairs_per_rank_max_over_mean": round(float(pairs.max() / pairs.mean()), 3),
+                    "tokens_per_rank_max_over_mean": round(float(tokens.max() / tokens.mean()), 3),
+                    "profile_load_per_rank_max_over_mean": round(float(rank_load.max() / rank_load.mean()), 3),
+                    "ffn_ms_slowest_rank": round(max(per_rank), 4), "ffn_ms_mean_rank": round(float(np.mean(per_rank)), 4)})
+        print(json.dumps({"study": "load balance: placement load weight x reshuffle capacity factor",
+                          "config": {"workload": w.name, "T": T, "D": D, "E": E, "k": k}, "dtype": w.dtype,
+                          "data": "synthetic", "points": points, "device": torch.cuda.get_device_name(0)}))
+        return
 
     ffn_rank = -1 if args.all_ranks else 0
     stages = ["route", "reshuffle", "dispatch_index", "dispatch_rows", "expert_ffn", "combine"]
