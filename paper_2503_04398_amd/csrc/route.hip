@@ -271,6 +271,262 @@ __device__ __forceinline__ void select_rows_any(const semmoe_config& cfg, const 
   else select_rows<8, NT>(cfg, rows, sel_bias, lane, ids_out, w_out);
 }
 
+// ---- selection with one token per 16-lane row ---------------------------------------------------------------
+// A wave-wide arg-max spends 64 lanes and a scalar round trip (readlane, ballot, find-first) on one token's
+// few experts per lane.  Here a token lives in one DPP row of 16 lanes (expert id = slot*16 + lane-in-row), so one
+// instruction stream serves four tokens, and a reduction is four row-local steps (xor 1 and xor 2 inside a quad,
+// then the two mirrors) after which every lane of the row holds the result: no broadcast, no scalar registers.
+// NCH independent groups of four tokens are interleaved to fill the dependent-issue gaps.
+#define SEMMOE_ROW_STEP(op, ctrl, x) \
+  asm volatile("s_nop 1\n\t" op " %0, %0, %0 " ctrl " row_mask:0xf bank_mask:0xf" : "+v"(x))
+#define SEMMOE_ROW_REDUCE(op, arr)                                                               \
+  do {                                                                                           \
+    _Pragma("unroll") for (int c_ = 0; c_ < NCH; ++c_) SEMMOE_ROW_STEP(op, "quad_perm:[1,0,3,2]", arr[c_]); \
+    _Pragma("unroll") for (int c_ = 0; c_ < NCH; ++c_) SEMMOE_ROW_STEP(op, "quad_perm:[2,3,0,1]", arr[c_]); \
+    _Pragma("unroll") for (int c_ = 0; c_ < NCH; ++c_) SEMMOE_ROW_STEP(op, "row_half_mirror", arr[c_]);     \
+    _Pragma("unroll") for (int c_ = 0; c_ < NCH; ++c_) SEMMOE_ROW_STEP(op, "row_mirror", arr[c_]);          \
+  } while (0)
+
+// rowp[ch] / idp[ch] / wp[ch]: this lane's token of group ch (the same for the 16 lanes of a row), nullptr = none.
+// Same selection rule as select_rows: k rounds of arg-max, equal values -> lowest expert id.
+template <int NS, int NCH>
+__device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const float* const (&rowp)[NCH],
+                                              const float* __restrict__ sel_bias, int lane,
+                                              int32_t* const (&idp)[NCH], float* const (&wp)[NCH]) {
+  const int E = cfg.E, k = cfg.k, l16 = lane & 15;
+  const bool sigmoid = cfg.score == SEMMOE_SIGMOID;
+  const int NEGK = to_key(-__builtin_inff());
+
+  int val[NCH][NS];    // key of the selection score
+  float aux[NCH][NS];  // sigmoid: s (softmax reads the logit back from the key)
+  uint32_t live[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    live[ch] = 0;
+#pragma unroll
+    for (int c = 0; c < NS; ++c) {
+      const int e = c * 16 + l16;
+      val[ch][c] = NEGK;
+      aux[ch][c] = 0.0f;
+      if (e < E && rowp[ch]) {
+        const float x = rowp[ch][e];
+        if (sigmoid) {
+          const float sg = sigmoid_exact_seq(x);
+          aux[ch][c] = sg;
+          val[ch][c] = to_key(__fadd_rn(sg, sel_bias ? sel_bias[e] : 0.0f));
+        } else {
+          val[ch][c] = to_key(x);
+        }
+        live[ch] |= 1u << c;
+      }
+    }
+  }
+
+  // arg-max of a row over the entries that pass `use(ch, c)`: every lane gets the largest key and the lowest
+  // expert id that holds it (kNoExpert when there is no entry).  A lane first finds its own best entry (the
+  // lowest slot among equals: strict compare), then the row agrees on the value and on the lowest id.
+  auto row_argmax = [&](auto use, int(&vmax)[NCH], int(&arg)[NCH]) __attribute__((always_inline)) {
+    int slot[NCH], own[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      own[ch] = NEGK;
+      slot[ch] = 0;
+#pragma unroll
+      for (int c = 0; c < NS; ++c) {
+        const bool better = use(ch, c) && val[ch][c] > own[ch];
+        own[ch] = better ? val[ch][c] : own[ch];
+        slot[ch] = better ? c : slot[ch];
+      }
+      vmax[ch] = own[ch];
+    }
+    SEMMOE_ROW_REDUCE("v_max_i32_dpp", vmax);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch)
+      arg[ch] = (own[ch] == vmax[ch] && own[ch] != NEGK) ? slot[ch] * 16 + l16 : kNoExpert;
+    SEMMOE_ROW_REDUCE("v_min_i32_dpp", arg);
+  };
+
+  if (sigmoid && cfg.n_group > 1) {
+    // group score = sum of the group's two largest s'; lane g of a row keeps the score of group g
+    const int gs = E / cfg.n_group;
+    int grp[NS];
+#pragma unroll
+    for (int c = 0; c < NS; ++c) grp[c] = (c * 16 + l16) / gs;
+    int gkey[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) gkey[ch] = NEGK;
+    for (int g = 0; g < cfg.n_group; ++g) {
+      int a1[NCH], a2[NCH];  // the two largest keys seen so far (with multiplicity)
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        a1[ch] = NEGK;
+        a2[ch] = NEGK;
+#pragma unroll
+        for (int c = 0; c < NS; ++c)
+          if (((live[ch] >> c) & 1u) && grp[c] == g) {
+            const int v = val[ch][c];
+            a2[ch] = max(a2[ch], min(a1[ch], v));
+            a1[ch] = max(a1[ch], v);
+          }
+      }
+      // merge the sorted pairs of disjoint lane sets: xor 1, xor 2, half mirror, mirror
+#define SEMMOE_PAIR_MERGE(CTRL)                                                    \
+  _Pragma("unroll") for (int ch = 0; ch < NCH; ++ch) {                             \
+    const int b1 = dpp_i32<CTRL, 0xf>(a1[ch], a1[ch]);                             \
+    const int b2 = dpp_i32<CTRL, 0xf>(a2[ch], a2[ch]);                             \
+    a2[ch] = max(min(a1[ch], b1), max(a2[ch], b2));                                \
+    a1[ch] = max(a1[ch], b1);                                                      \
+  }
+      SEMMOE_PAIR_MERGE(0xB1)
+      SEMMOE_PAIR_MERGE(0x4E)
+      SEMMOE_PAIR_MERGE(0x141)
+      SEMMOE_PAIR_MERGE(0x140)
+#undef SEMMOE_PAIR_MERGE
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        const float sc = (a2[ch] == NEGK) ? from_key(a1[ch]) : __fadd_rn(from_key(a1[ch]), from_key(a2[ch]));
+        if (l16 == g) gkey[ch] = to_key(sc);
+      }
+    }
+    uint32_t keep[NCH];
+    bool taken[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      keep[ch] = 0;
+      taken[ch] = false;
+    }
+    for (int r = 0; r < cfg.topk_group; ++r) {
+      int m[NCH], g[NCH];
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) m[ch] = (l16 < cfg.n_group && !taken[ch]) ? gkey[ch] : NEGK;
+      int top[NCH];
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) top[ch] = m[ch];
+      SEMMOE_ROW_REDUCE("v_max_i32_dpp", top);
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch)
+        g[ch] = (l16 < cfg.n_group && !taken[ch] && m[ch] == top[ch]) ? l16 : kNoExpert;
+      SEMMOE_ROW_REDUCE("v_min_i32_dpp", g);
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        keep[ch] |= 1u << (g[ch] & 31);
+        if (l16 == g[ch]) taken[ch] = true;
+      }
+    }
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      uint32_t allowed = 0;
+#pragma unroll
+      for (int c = 0; c < NS; ++c)
+        if (c * 16 + l16 < E && ((keep[ch] >> (grp[c] & 31)) & 1u)) allowed |= 1u << c;
+      live[ch] &= allowed;
+    }
+  }
+
+  // k rounds; lane j of the row keeps the j-th winner
+  int my_id[NCH];
+  float my_val[NCH], mx[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    my_id[ch] = 0;
+    my_val[ch] = 0.0f;
+    mx[ch] = 0.0f;
+  }
+  for (int j = 0; j < k; ++j) {
+    int vm[NCH], e[NCH];
+    row_argmax([&](int ch, int c) { return ((live[ch] >> c) & 1u) != 0; }, vm, e);
+    int abits[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      const bool own = e[ch] != kNoExpert && (e[ch] & 15) == l16;
+      const int slot = (e[ch] >> 4) & 31;
+      abits[ch] = 0;
+#pragma unroll
+      for (int c = 0; c < NS; ++c)
+        if (own && c == slot) abits[ch] = __float_as_int(aux[ch][c]);
+      if (own) live[ch] &= ~(1u << slot);
+    }
+    if (sigmoid) SEMMOE_ROW_REDUCE("v_or_b32_dpp", abits);  // the owner's s reaches every lane of the row
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      const float a = sigmoid ? __int_as_float(abits[ch]) : from_key(vm[ch]);
+      if (l16 == j) {
+        my_id[ch] = e[ch];
+        my_val[ch] = a;
+      }
+      if (j == 0) mx[ch] = a;  // first winner = row maximum
+    }
+  }
+
+  float w[NCH];
+  if (!sigmoid) {
+    float part[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      part[ch] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < NS; ++c)
+        if (c * 16 + l16 < E && rowp[ch]) part[ch] += expf(from_key(val[ch][c]) - mx[ch]);  // key -> logit
+    }
+    SEMMOE_ROW_REDUCE("v_add_f32_dpp", part);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) w[ch] = (l16 < k) ? expf(my_val[ch] - mx[ch]) / part[ch] : 0.0f;
+  } else {
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) w[ch] = (l16 < k) ? my_val[ch] : 0.0f;
+  }
+  if (cfg.renorm) {
+    float tot[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) tot[ch] = w[ch];
+    SEMMOE_ROW_REDUCE("v_add_f32_dpp", tot);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) w[ch] = w[ch] / tot[ch];
+  }
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    if (sigmoid) w[ch] *= cfg.routed_scale;
+    if (l16 < k && rowp[ch]) {
+      idp[ch][l16] = my_id[ch];
+      wp[ch][l16] = w[ch];
+    }
+  }
+}
+#undef SEMMOE_ROW_REDUCE
+#undef SEMMOE_ROW_STEP
+
+constexpr int kRowChains = 2;                   // interleaved groups of four tokens
+constexpr int kRowTokens = 4 * kRowChains;      // tokens a wave selects for per call of the row form
+
+// the row form holds E <= 256 experts (16 slots per lane), k <= 16 winners and 16 group scores per row
+__host__ __device__ inline bool select_by_rows(const semmoe_config& cfg) {
+  return cfg.E <= 256 && cfg.k <= 16 && (cfg.score != SEMMOE_SIGMOID || cfg.n_group <= 16);
+}
+
+// Tokens base .. base + kRowTokens - 1 (those below n_tok) by one wave: token = base + ch*4 + row.
+// row_of(token) -> pointer to its E logits; ids / weights are written to topk_ids / topk_w at tok_global0 + token.
+template <typename RowOf>
+__device__ __forceinline__ void select_tokens_by_rows(const semmoe_config& cfg, int base, int n_tok, RowOf row_of,
+                                                      int tok_global0, const float* __restrict__ sel_bias, int lane,
+                                                      int32_t* __restrict__ topk_ids, float* __restrict__ topk_w) {
+  const float* rowp[kRowChains];
+  int32_t* idp[kRowChains];
+  float* wp[kRowChains];
+#pragma unroll
+  for (int ch = 0; ch < kRowChains; ++ch) {
+    const int tl = base + ch * 4 + (lane >> 4);
+    const bool ok = tl < n_tok && tok_global0 + tl < cfg.T;
+    rowp[ch] = ok ? row_of(tl) : nullptr;
+    idp[ch] = ok ? topk_ids + size_t(tok_global0 + tl) * cfg.k : nullptr;
+    wp[ch] = ok ? topk_w + size_t(tok_global0 + tl) * cfg.k : nullptr;
+  }
+  if (cfg.E <= 16) select_rows16<1, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
+  else if (cfg.E <= 32) select_rows16<2, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
+  else if (cfg.E <= 64) select_rows16<4, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
+  else if (cfg.E <= 128) select_rows16<8, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
+  else select_rows16<16, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
+}
+
 constexpr int kSelTokens = 2;  // tokens a wave selects for at a time (four gain nothing: the selection is bound by instruction issue)
 
 __global__ __launch_bounds__(256) void select_topk_kernel(semmoe_config cfg, const float* __restrict__ logits,
@@ -447,23 +703,40 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       }
     }
     __syncthreads();
-    for (int tl0 = wave; tl0 < C::BT; tl0 += 4 * kSelTokens) {
-      const float* rows[kSelTokens];
-      int32_t* ids_out[kSelTokens];
-      float* w_out[kSelTokens];
+    if (select_by_rows(cfg)) {
+      for (int base = wave * kRowTokens; base < C::BT; base += 4 * kRowTokens)
+        select_tokens_by_rows(
+            cfg, base, C::BT, [&](int tl) { return lg + tl * ldl; }, tok0, sel_bias, lane, topk_ids, topk_w);
+    } else {
+      for (int tl0 = wave; tl0 < C::BT; tl0 += 4 * kSelTokens) {
+        const float* rows[kSelTokens];
+        int32_t* ids_out[kSelTokens];
+        float* w_out[kSelTokens];
 #pragma unroll
-      for (int t = 0; t < kSelTokens; ++t) {
-        const int tl = tl0 + 4 * t;
-        const int tok = tok0 + tl;
-        const bool ok = tl < C::BT && tok < T;
-        rows[t] = ok ? lg + tl * ldl : nullptr;
-        ids_out[t] = ok ? topk_ids + size_t(tok) * cfg.k : nullptr;
-        w_out[t] = ok ? topk_w + size_t(tok) * cfg.k : nullptr;
+        for (int t = 0; t < kSelTokens; ++t) {
+          const int tl = tl0 + 4 * t;
+          const int tok = tok0 + tl;
+          const bool ok = tl < C::BT && tok < T;
+          rows[t] = ok ? lg + tl * ldl : nullptr;
+          ids_out[t] = ok ? topk_ids + size_t(tok) * cfg.k : nullptr;
+          w_out[t] = ok ? topk_w + size_t(tok) * cfg.k : nullptr;
+        }
+        select_rows_any<kSelTokens>(cfg, rows, sel_bias, lane, ids_out, w_out);
       }
-      select_rows_any<kSelTokens>(cfg, rows, sel_bias, lane, ids_out, w_out);
     }
     __syncthreads();  // the next tile's loads overwrite the logits
   }
+}
+
+__global__ __launch_bounds__(256) void select_topk_rows_kernel(semmoe_config cfg, const float* __restrict__ logits,
+                                                               const float* __restrict__ sel_bias,
+                                                               int32_t* __restrict__ topk_ids,
+                                                               float* __restrict__ topk_w) {
+  const int lane = threadIdx.x & 63;
+  const int base = (blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * kRowTokens;
+  if (base >= cfg.T) return;  // whole wave leaves together
+  select_tokens_by_rows(
+      cfg, base, cfg.T, [&](int tl) { return logits + size_t(tl) * cfg.E; }, 0, sel_bias, lane, topk_ids, topk_w);
 }
 
 static int32_t validate_select(const semmoe_config* cfg) {
@@ -483,6 +756,12 @@ static int32_t launch_select(const semmoe_config* cfg, hipStream_t stream, const
                              const float* sel_bias, int32_t* topk_ids, float* topk_w) {
   if (cfg->T == 0) return SEMMOE_OK;
   const int waves_per_block = 4;
+  if (select_by_rows(*cfg)) {
+    hipLaunchKernelGGL(select_topk_rows_kernel, dim3(cdiv(cfg->T, waves_per_block * kRowTokens)),
+                       dim3(64 * waves_per_block), 0, stream, *cfg, logits, sel_bias, topk_ids, topk_w);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
   hipLaunchKernelGGL(select_topk_kernel, dim3(cdiv(cfg->T, waves_per_block * kSelTokens)), dim3(64 * waves_per_block), 0, stream,
                      *cfg, logits, sel_bias, topk_ids, topk_w);
   SEMMOE_LAUNCH_CHECK();

@@ -33,7 +33,8 @@ def index_path(request):
 
 # ------------------------------------------------------------------------------------------- route
 @pytest.mark.parametrize("E,k,T,renorm", [(16, 2, 100, False), (128, 8, 300, True), (256, 8, 77, True),
-                                           (64, 1, 65, True), (200, 5, 33, False), (512, 16, 40, True)])
+                                           (64, 1, 65, True), (200, 5, 33, False), (512, 16, 40, True),
+                                           (256, 16, 1000, True), (24, 3, 9, False), (128, 8, 8193, True)])
 def test_route_from_logits_softmax(E, k, T, renorm):
     _say("route_from_logits softmax", E, k, T, renorm)
     r = np.random.default_rng(E + k)
@@ -54,7 +55,9 @@ def test_route_from_logits_softmax(E, k, T, renorm):
 
 @pytest.mark.parametrize("E,k,T,ng,tg,scale,bias", [(256, 8, 200, 8, 4, 2.5, True), (64, 6, 90, 4, 2, 1.0, False),
                                                      (32, 4, 70, 1, 1, 1.0, True), (128, 8, 50, 16, 3, 1.0, True),
-                                                     (16, 2, 40, 16, 4, 1.0, False)])
+                                                     (16, 2, 40, 16, 4, 1.0, False), (240, 6, 50, 5, 2, 1.0, True),
+                                                     (256, 16, 30, 8, 8, 0.5, True), (40, 3, 20, 20, 5, 1.0, False),
+                                                     (96, 7, 333, 6, 3, 1.0, True)])
 def test_route_from_logits_sigmoid_group_limited(E, k, T, ng, tg, scale, bias):
     _say("route_from_logits sigmoid", E, k, T, ng, tg)
     r = np.random.default_rng(E * 3 + k)
