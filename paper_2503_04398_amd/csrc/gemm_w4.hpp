@@ -58,6 +58,17 @@ __device__ __forceinline__ void lds_dma16_s(const void* sbase, uint32_t voff, un
                : "memory", "m0");
 }
 
+// The same with the LDS address given as a uniform base plus a compile-time offset: one scalar add into m0 and the
+// load, nothing else, so that the pair fits in the shadow of the MFMA issued before it.
+template <int IMM>
+__device__ __forceinline__ void lds_dma16_imm(const void* sbase, uint32_t voff, unsigned lds_base_uniform) {
+  sbase = scalar_ptr(static_cast<const unsigned char*>(sbase));
+  lds_base_uniform = unsigned(__builtin_amdgcn_readfirstlane(int(lds_base_uniform)));
+  asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base_uniform), "v"(voff), "s"(sbase),
+               "n"(IMM)
+               : "memory", "m0", "scc");
+}
+
 __device__ __forceinline__ float silu_mul_fast(float g, float u) {
   // silu(g) * u with one exp2 and one reciprocal
   return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * g)) * u;
@@ -148,7 +159,11 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   int i_slice = 0;
   int i_stage = 0;
   bool i_done = false;
-  bool i_go = false;                      // set at the first barrier of the main loop: before it no stage is free
+  // The loads between the MFMAs are issued unconditionally (a branch per load costs more than the load).  Where the
+  // stream has nothing new to fetch - before the first barrier, when every stage is still full, and after its last
+  // slice - it stands still and the loads fetch its current slice again into the stage that already holds it: the
+  // same bytes over the same bytes, harmless for a wave reading them.
+  unsigned i_dst = 0;                     // uniform: LDS address of this wave's first load of the stream's slice
   const unsigned char* i_base = nullptr;  // uniform: weight panel or token panel of the tile, advanced by RB per slice
   uint32_t i_off[C::IPW];                 // per lane: byte offset of the row + chunk it fetches
 
@@ -184,22 +199,24 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
     }
   };
   auto i_next_slice = [&]() __attribute__((always_inline)) {
+    if (i_slice + 1 == nk && i_tile + G >= total) {  // no further slice: stand still on the last one
+      i_done = true;
+      return;
+    }
     i_base += C::RB;
     i_stage = (i_stage + 1 == NSTAGE) ? 0 : i_stage + 1;
+    i_dst = lds_base + i_stage * C::kStageBytes + wave * C::IPW * 1024;
     if (++i_slice == nk) {
       i_slice = 0;
       i_tile += G;
-      if (i_tile < total) i_setup(i_tile); else i_done = true;
+      i_setup(i_tile);
     }
   };
   // load number i of the current slice of the stream; after the last one the stream moves to the next slice
   auto i_issue = [&](auto idx) __attribute__((always_inline)) {
     constexpr int i = decltype(idx)::value;
-    const bool on = i_go && !i_done;
-    if (on) lds_dma16_s(i_base, i_off[i], lds_base + i_stage * C::kStageBytes + (wave * C::IPW + i) * 1024);
-    if constexpr (i == C::IPW - 1) {
-      if (on) i_next_slice();
-    }
+    lds_dma16_imm<i * 1024>(i_base, i_off[i], i_dst);
+    if constexpr (i == C::IPW - 1) i_next_slice();
   };
 
   // ---- fragments
@@ -220,10 +237,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
     for (int i = 0; i < C::IPW; ++i)
       lds_dma16_s(i_base + s * C::RB, i_off[i], lds_base + s * C::kStageBytes + (wave * C::IPW + i) * 1024);
   }
-  i_base += (NSTAGE - 1) * C::RB;  // the stream stands at its slice NSTAGE-1 ...
+  // The stream stands at slice NSTAGE-1, already fetched.  Where the last load of a window falls behind the
+  // window's first k-step, the k-steps before the first barrier carry that tail: they fetch the rest of the
+  // standing slice once more and the stream moves on when they are through.  Where a whole window fits into its
+  // first k-step no load is placed before the first barrier, and the stream moves on here.
+  i_base += (NSTAGE - 1) * C::RB;
   i_slice = NSTAGE - 1;
   i_stage = NSTAGE - 1;
-  i_next_slice();                  // ... and moves on (possibly into the next tile)
+  i_dst = lds_base + i_stage * C::kStageBytes + wave * C::IPW * 1024;
+  if constexpr (C::IPW * DMA_EVERY <= 16) i_next_slice();
   wait_vmcnt<(NSTAGE - 1) * C::IPW>();
   __syncthreads();
   frag(0, 0, af[0], bfr[0]);
@@ -246,6 +268,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
       const int n_stage = (c_stage + 1 == NSTAGE) ? 0 : c_stage + 1;
       // one k-step; the k-step index is a compile-time constant (a pragma-unrolled loop over it was left partly
       // rolled by the compiler, which turns the fragment buffers into scratch memory)
+      // one k-step; the k-step index is a compile-time constant (a pragma-unrolled loop over it was left partly
+      // rolled by the compiler, which turns the fragment buffers into scratch memory)
       auto k_step = [&](auto ks_tag) __attribute__((always_inline)) {
         constexpr int ks = decltype(ks_tag)::value;
         constexpr int kLast = C::KS - 1;
@@ -257,7 +281,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
           // issued, unless the stream has ended)
           if (!i_done) wait_vmcnt<(NSTAGE - 2) * C::IPW>(); else wait_vmcnt<0>();
           __syncthreads();
-          i_go = true;
           frag(n_stage, 0, af[cur ^ 1], bfr[cur ^ 1]);
         } else {
           frag(c_stage, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
