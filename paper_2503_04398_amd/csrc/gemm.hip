@@ -101,9 +101,9 @@ static int32_t launch_w4(const GemmArgs& a, int max_rows, hipStream_t stream) {
 // A piece is a long, thin K loop with little arithmetic per slice: its speed is the bytes it keeps in flight over
 // the latency of a load.  One workgroup per CU with a ring of 6 is faster when few parent tiles are left (config 2:
 // 28 tiles, FFN 256 -> 246 us) and slower when many are (configs 3 and 4: +5 %); the count is only known on the device.
-template <int MODE>
-static int32_t launch_tail(GemmArgs a, int max_rows, int head_grid, hipStream_t stream) {
-  using C = DmaCfg<MODE, 2, 2, 2, 1, 64, 3>;
+template <int MODE, int RING, int PER_CU>
+static int32_t launch_tail_as(GemmArgs a, int max_rows, int head_grid, hipStream_t stream) {
+  using C = DmaCfg<MODE, 2, 2, 2, 1, 64, RING>;
   constexpr int kSubT = 256 / C::BT, kSubF = 256 / C::BW;
   const int n_ftiles_p = cdiv(a.N, kSubF * C::FEAT);
   const long long bound_p = (long long)(max_rows / 256 + a.nq) * n_ftiles_p;  // parent tiles, at most
@@ -113,8 +113,8 @@ static int32_t launch_tail(GemmArgs a, int max_rows, int head_grid, hipStream_t 
   a.sched_g = head_grid;
   a.sched_sub_t = kSubT;
   a.sched_sub_f = kSubF;
-  const int grid = grid_for(left_p * kSubT * kSubF, (long long)num_cu() * 2);
-  auto kern = gemm_bf16_dma_kernel<MODE, 2, 2, 2, 1, 64, 3, 1>;
+  const int grid = grid_for(left_p * kSubT * kSubF, (long long)num_cu() * PER_CU);
+  auto kern = gemm_bf16_dma_kernel<MODE, 2, 2, 2, 1, 64, RING, 1>;
   if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
   static bool attr_set = false;
   if (!attr_set) {
@@ -125,6 +125,12 @@ static int32_t launch_tail(GemmArgs a, int max_rows, int head_grid, hipStream_t 
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
+}
+
+template <int MODE>
+static int32_t launch_tail(const GemmArgs& a, int max_rows, int head_grid, hipStream_t stream) {
+  if (g_tune[SEMMOE_TUNE_TAIL_RING] == 6) return launch_tail_as<MODE, 6, 1>(a, max_rows, head_grid, stream);
+  return launch_tail_as<MODE, 3, 2>(a, max_rows, head_grid, stream);
 }
 
 // grid of a launch with 256 x 256 tiles and one workgroup per compute unit (the head launch of a split)

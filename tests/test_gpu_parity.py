@@ -568,6 +568,25 @@ def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
             m.set_tuning(key, -1)
 
 
+@pytest.mark.parametrize("grid_cap,split", [(1, 16), (4, 8), (-1, 16)])
+def test_tail_launch_with_the_deep_ring(grid_cap, split):
+    """the tail launch of a split GEMM with a ring of 6 (one workgroup per compute unit) instead of 3"""
+    _say("tail ring 6, grid cap", grid_cap, "split", split)
+    w = WL.small(T=2500, d=512, E=4, k=2, F=192, D=2, dtype="bf16", C=2)
+    m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
+    try:
+        m.set_tuning(0, 22)
+        m.set_tuning(1, 22)
+        m.set_tuning(4, grid_cap)
+        m.set_tuning(5, split)
+        m.set_tuning(6, 6)
+        lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, rank=-1)
+        H.assert_close(Y, Yo, "bf16", "Y")
+    finally:
+        for key in (0, 1, 4, 5, 6):
+            m.set_tuning(key, -1)
+
+
 def test_probes_copy_and_mfma_loop():
     """the two probes bench.py reads achievable rates from: the copy copies, the MFMA loop's checksum is the exact sum"""
     m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
