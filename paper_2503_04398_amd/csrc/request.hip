@@ -39,38 +39,78 @@ __global__ __launch_bounds__(256) void rq_score_kernel(int T, int D, int V, cons
   for (int x = threadIdx.x; x < D; x += blockDim.x) w.score[size_t(q) * D + x] = bins[x];
 }
 
+// wave-wide maximum through DPP row shifts and broadcasts (no LDS permutes); lane 63 ends with the result.  The two
+// wait states a DPP read needs after a vector-ALU write of the same register are written out (s_nop 1).
+#define SEMMOE_RQ_DPP_MAX(ctrl) \
+  asm volatile("s_nop 1\n\tv_max_i32_dpp %0, %0, %0 " ctrl " row_mask:0xf bank_mask:0xf" : "+v"(v))
 __device__ __forceinline__ int wave_max_i32(int v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v = max(v, __shfl_xor(v, s));
-  return v;
+  SEMMOE_RQ_DPP_MAX("row_shr:1");
+  SEMMOE_RQ_DPP_MAX("row_shr:2");
+  SEMMOE_RQ_DPP_MAX("row_shr:4");
+  SEMMOE_RQ_DPP_MAX("row_shr:8");
+  SEMMOE_RQ_DPP_MAX("row_bcast:15");
+  SEMMOE_RQ_DPP_MAX("row_bcast:31");
+  asm volatile("s_nop 1" ::: "memory");
+  return __builtin_amdgcn_readlane(v, 63);
 }
+#undef SEMMOE_RQ_DPP_MAX
+
+constexpr int kRqChunk = 64;  // requests fetched ahead at a time: one per lane (lengths), one LDS row each (scores)
 
 // D <= 64, scores < 2^25 (the host checks both).  key = score * 64 + (63 - device): the largest key is the
-// highest score, the smallest device among equals.
+// highest score, the smallest device among equals.  The walk itself is serial, so everything it needs is fetched
+// ahead, a chunk of requests at a time (scores into LDS, lengths one request per lane), and a step of the walk is
+// a handful of cross-lane instructions: the mask of open devices is used as a lane mask as it stands, results go
+// into lane u of a register with a lane write, and no step waits for global memory.
 __global__ __launch_bounds__(64) void rq_assign_kernel(int n_req, int T, int D, const int32_t* __restrict__ off,
                                                        int32_t* __restrict__ req_rank,
                                                        int32_t* __restrict__ rank_count, RequestWs w) {
+  __shared__ int32_t sc[kRqChunk][64];
   const int lane = threadIdx.x;
   const unsigned long long full = D >= 64 ? ~0ull : ((1ull << D) - 1);
   unsigned long long avail = full;
   int placed = 0;  // tokens on device `lane` so far
-  int s_next = (lane < D && n_req > 0) ? w.score[lane] : 0;
-  for (int q = 0; q < n_req; ++q) {
-    const int s = s_next;
-    if (q + 1 < n_req) s_next = lane < D ? w.score[size_t(q + 1) * D + lane] : 0;  // independent of the mask
-    const int lo = clampi(off[q], 0, T);  // clamped as in rq_score_kernel
-    const int hi = clampi(off[q + 1], lo, T);
-    const bool open = lane < D && ((avail >> lane) & 1ull);
-    const int key = open ? s * 64 + (63 - lane) : -1;
-    const int best = wave_max_i32(key);
-    const int r = 63 - (best & 63);
-    if (lane == r) {
-      w.req_pos[q] = placed;
-      req_rank[q] = r;
-      placed += hi - lo;
+  for (int q0 = 0; q0 < n_req; q0 += kRqChunk) {
+    const int nq = min(kRqChunk, n_req - q0);
+    int len_l = 0;  // lane u: length of request q0 + u (offsets clamped as in rq_score_kernel)
+    if (lane < nq) {
+      const int lo = clampi(off[q0 + lane], 0, T);
+      len_l = clampi(off[q0 + lane + 1], lo, T) - lo;
     }
-    avail &= ~(1ull << r);
-    if (avail == 0) avail = full;
+    __syncthreads();  // the previous chunk's scores have been read
+    for (int u0 = 0; u0 < nq; u0 += 16) {  // sixteen independent loads in flight, then their keys into LDS
+      int v[16];
+#pragma unroll
+      for (int x = 0; x < 16; ++x) v[x] = (u0 + x < nq && lane < D) ? w.score[size_t(q0 + u0 + x) * D + lane] : 0;
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        if (u0 + x < nq) sc[u0 + x][lane] = v[x] * 64 + (63 - lane);  // lanes >= D are never open
+    }
+    __syncthreads();
+    int rank_l = 0, pos_l = 0;  // lane u keeps the result of request q0 + u
+    int key_next = sc[0][lane];
+    for (int u = 0; u < nq; ++u) {
+      const int key = key_next;
+      if (u + 1 < nq) key_next = sc[u + 1][lane];
+      int masked;
+      asm volatile("v_cndmask_b32_e64 %0, -1, %1, %2" : "=v"(masked) : "v"(key), "s"(avail));  // closed lanes: -1
+      const int best = wave_max_i32(masked);
+      const int r = 63 - (best & 63);
+      const int len = __builtin_amdgcn_readlane(len_l, u);
+      const int pos = __builtin_amdgcn_readlane(placed, r);
+      if (lane == r) placed += len;
+      // lane u of the result registers (the wait states cover a lane select or value that came from the vector ALU)
+      asm volatile("s_mov_b32 m0, %4\n\ts_nop 3\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
+                   : "+v"(rank_l), "+v"(pos_l)
+                   : "s"(r), "s"(pos), "s"(u)
+                   : "m0");
+      avail &= ~(1ull << r);
+      if (avail == 0) avail = full;
+    }
+    if (lane < nq) {
+      req_rank[q0 + lane] = rank_l;
+      w.req_pos[q0 + lane] = pos_l;
+    }
   }
   // exclusive prefix of the per-device token counts over the lanes
   int incl = lane < D ? placed : 0;
