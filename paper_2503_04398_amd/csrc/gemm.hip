@@ -127,9 +127,45 @@ static int32_t launch_tail_as(GemmArgs a, int max_rows, int head_grid, hipStream
   return SEMMOE_OK;
 }
 
+// Tail launch with 128 x 128 pieces (four per parent tile), one workgroup per compute unit: the K loop of the
+// four-wave kernel in small.  K must be a multiple of 64 with at least a ring of slices.
+template <int MODE, int NSTAGE>
+static int32_t launch_tail_pieces(GemmArgs a, int max_rows, int head_grid, hipStream_t stream) {
+  using C = DmaCfg<MODE, 2, 2, 2, 2, 64, NSTAGE>;
+  const int w_rows = (MODE == kModeSwiglu) ? 2 * a.N : a.N;
+  if (a.K % 64 != 0 || a.K / 64 < NSTAGE) return SEMMOE_EUNSUPPORTED;
+  if ((unsigned long long)w_rows * a.ldw * 2 >= (1ull << 32) || (unsigned long long)C::BT * a.ldx * 2 >= (1ull << 32))
+    return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
+  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  constexpr int kSubT = 256 / C::BT, kSubF = 256 / C::BW;
+  const int n_ftiles_p = cdiv(a.N, kSubF * C::FEAT);
+  const long long bound_p = (long long)(max_rows / 256 + a.nq) * n_ftiles_p;  // parent tiles, at most
+  const long long left_p = bound_p < head_grid ? bound_p : (long long)head_grid * a.sched_thr / 16;  // ... left over
+  if (left_p <= 0) return SEMMOE_OK;
+  a.sched_mode = 2;
+  a.sched_g = head_grid;
+  a.sched_sub_t = kSubT;
+  a.sched_sub_f = kSubF;
+  const int grid = grid_for(left_p * kSubT * kSubF, num_cu());
+  auto kern = gemm_bf16_piece_kernel<MODE, NSTAGE>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(C::kLdsBytes)));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
 template <int MODE>
 static int32_t launch_tail(const GemmArgs& a, int max_rows, int head_grid, hipStream_t stream) {
-  if (g_tune[SEMMOE_TUNE_TAIL_RING] == 6) return launch_tail_as<MODE, 6, 1>(a, max_rows, head_grid, stream);
+  const int ring = g_tune[SEMMOE_TUNE_TAIL_RING];
+  if (ring == 6) return launch_tail_as<MODE, 6, 1>(a, max_rows, head_grid, stream);
+  if (ring == 3) return launch_tail_as<MODE, 3, 2>(a, max_rows, head_grid, stream);
+  const int32_t st = launch_tail_pieces<MODE, 3>(a, max_rows, head_grid, stream);  // a ring of 4 gains nothing
+  if (st != SEMMOE_EUNSUPPORTED) return st;
   return launch_tail_as<MODE, 3, 2>(a, max_rows, head_grid, stream);
 }
 

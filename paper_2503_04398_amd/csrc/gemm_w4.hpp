@@ -376,4 +376,168 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   wait_vmcnt<0>();  // nothing may still be writing into this workgroup's LDS when it ends
 }
 
+// ------------------------------------------------------------------------------------------------
+// Tail pieces of a head/tail split: 128 x 128 pieces (four per 256 x 256 parent tile), four waves as 2 x 2, each a
+// 64 x 64 quadrant (2 x 2 MFMA tiles).  The K loop is the one of the kernel above in small: slices of 64 through a ring
+// of NSTAGE stages filled by direct global->LDS loads that are issued one at a time behind the MFMAs, unconditionally
+// (a stream with nothing new to fetch re-fetches its standing slice), per-lane 32-bit offsets on a uniform base, the
+// one barrier of a slice before its last k-step, fragments read one k-step ahead.  A piece has 4 MFMAs per k-step, so
+// the loads of a slice take the first half of the window between two barriers and a ring of 3 gives them a whole
+// slice to land.  Pieces are independent (no stream across pieces: most workgroups get one); the output piece is
+// staged through the ring's LDS.  Needs K % 64 == 0 and K / 64 >= NSTAGE.
+// ------------------------------------------------------------------------------------------------
+template <int MODE, int NSTAGE>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
+  using C = DmaCfg<MODE, 2, 2, 2, 2, 64, NSTAGE>;
+  static_assert(C::IPW == 8 && C::KS == 4 && C::RB == 128, "geometry the loop below is written for");
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  int* pre = reinterpret_cast<int*>(lds_raw + C::kTileBytes);
+  const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wf = wave & 1;
+  const int wt = wave >> 1;
+  const TileWalk walk = make_walk(a, pre, C::BT, C::FEAT);
+  const int nk = a.K / 64;
+
+  const int frag_swz = ((lane & 31) / C::RPB) % C::CPR;
+  const unsigned frag_w = (wf * 64 + (lane & 31)) * C::RB;
+  const unsigned frag_x = (C::BW + wt * 64 + (lane & 31)) * C::RB;
+  const int d_row = lane / C::CPR;
+  const int d_pos = lane % C::CPR;
+  const bool loads_w = wave < 2;  // waves 0, 1: the 128 weight rows of a slice; waves 2, 3: the 128 token rows
+
+  for (int item = xcd_worker_index(); item < walk.total; item += gridDim.x) {
+    TileAt at;
+    if (!walk_tile(a, walk, pre, item, C::BT, C::FEAT, &at)) continue;  // uniform: no barrier is skipped
+    const int widx = a.group_to_weight ? a.group_to_weight[a.q_lo + at.q] : (a.q_lo + at.q);
+
+    // ---- load stream of this piece
+    const unsigned char* i_base;
+    uint32_t i_off[C::IPW];
+    if (loads_w) {
+      i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.W) + size_t(widx) * a.w_group_stride);
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i) {
+        const int sr = (wave * C::IPW + i) * C::RPI + d_row;
+        const int c = d_pos ^ ((sr / C::RPB) % C::CPR);
+        int grow;
+        if constexpr (MODE == kModeSwiglu) {
+          // a wave's two MFMA tiles are the gate rows and the matching up rows of one block of 32 features
+          const int w_of = sr >> 6, tf = (sr >> 5) & 1, fr = sr & 31;
+          grow = tf * a.N + min(at.f0 + w_of * 32 + fr, a.N - 1);
+        } else {
+          grow = min(at.f0 + sr, a.N - 1);
+        }
+        i_off[i] = uint32_t(grow) * uint32_t(a.ldw) * 2u + uint32_t(c) * 16u;
+      }
+    } else {
+      i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.X) + size_t(at.row_lo) * a.ldx);
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i) {
+        const int sr = (wave * C::IPW + i) * C::RPI + d_row;
+        const int c = d_pos ^ ((sr / C::RPB) % C::CPR);
+        i_off[i] = uint32_t(min(sr - C::BW, at.n_tok - 1)) * uint32_t(a.ldx) * 2u + uint32_t(c) * 16u;
+      }
+    }
+    int i_slice = 0, i_stage = 0;
+    bool i_done = false;
+    unsigned i_dst = 0;
+    auto i_next_slice = [&]() __attribute__((always_inline)) {
+      if (i_slice + 1 == nk) {  // the piece has no further slice: stand still on the last one
+        i_done = true;
+        return;
+      }
+      ++i_slice;
+      i_base += C::RB;
+      i_stage = (i_stage + 1 == NSTAGE) ? 0 : i_stage + 1;
+      i_dst = lds_base + i_stage * C::kStageBytes + wave * C::IPW * 1024;
+    };
+    auto i_issue = [&](auto idx) __attribute__((always_inline)) {
+      constexpr int i = decltype(idx)::value;
+      lds_dma16_imm<i * 1024>(i_base, i_off[i], i_dst);
+      if constexpr (i == C::IPW - 1) i_next_slice();
+    };
+
+    bf16x8_t af[2][2], bfr[2][2];
+    auto frag = [&](int stage, int ks, bf16x8_t(&fa)[2], bf16x8_t(&fb)[2]) __attribute__((always_inline)) {
+      const unsigned char* S = lds_raw + stage * C::kStageBytes;
+      const int off = ((ks * 2 + (lane >> 5)) ^ frag_swz) * 16;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(S + frag_w + i * 32 * C::RB + off);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(S + frag_x + j * 32 * C::RB + off);
+    };
+
+    // prologue: the first NSTAGE slices; the stream then stands on slice NSTAGE-1, whose last loads are fetched
+    // once more by the k-steps before the first barrier, after which it moves on
+    for (int s0 = 0; s0 < NSTAGE; ++s0) {
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i)
+        lds_dma16_s(i_base + s0 * C::RB, i_off[i], lds_base + s0 * C::kStageBytes + (wave * C::IPW + i) * 1024);
+    }
+    i_base += (NSTAGE - 1) * C::RB;
+    i_slice = NSTAGE - 1;
+    i_stage = NSTAGE - 1;
+    i_dst = lds_base + i_stage * C::kStageBytes + wave * C::IPW * 1024;
+    wait_vmcnt<(NSTAGE - 1) * C::IPW>();
+    __syncthreads();
+    frag(0, 0, af[0], bfr[0]);
+    int c_stage = 0;
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    for (int it = 0; it < nk; ++it) {
+      const int n_stage = (c_stage + 1 == NSTAGE) ? 0 : c_stage + 1;
+      auto k_step = [&](auto ks_tag) __attribute__((always_inline)) {
+        constexpr int ks = decltype(ks_tag)::value;
+        constexpr int cur = ks & 1;
+        if constexpr (ks == 3) {
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          if (!i_done) wait_vmcnt<(NSTAGE - 2) * C::IPW>(); else wait_vmcnt<0>();
+          __syncthreads();
+          frag(n_stage, 0, af[cur ^ 1], bfr[cur ^ 1]);
+        } else {
+          frag(c_stage, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+            // window position = MFMAs since the barrier; a load after each of the first eight
+            const int m = ((ks == 3) ? 0 : (ks + 1) * 4) + j * 2 + i;  // constant after unrolling
+            switch (m) {
+#define SEMMOE_PIECE_CASE(n) case n: i_issue(std::integral_constant<int, n>{}); break;
+              SEMMOE_PIECE_CASE(0) SEMMOE_PIECE_CASE(1) SEMMOE_PIECE_CASE(2) SEMMOE_PIECE_CASE(3)
+              SEMMOE_PIECE_CASE(4) SEMMOE_PIECE_CASE(5) SEMMOE_PIECE_CASE(6) SEMMOE_PIECE_CASE(7)
+#undef SEMMOE_PIECE_CASE
+              default: break;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      };
+      k_step(std::integral_constant<int, 0>{});
+      k_step(std::integral_constant<int, 1>{});
+      k_step(std::integral_constant<int, 2>{});
+      k_step(std::integral_constant<int, 3>{});
+      c_stage = n_stage;
+    }
+    wait_vmcnt<0>();   // the standing stream's last loads: nothing may write into the ring any more
+    __syncthreads();   // every wave has left the ring: it now takes the output piece
+    store_tile_via_lds<MODE, 2, 2, 2, 2>(acc, lds_raw, a, at.row_lo, at.n_tok, at.f0, wf, wt);
+    __syncthreads();   // the next piece's loads overwrite the staged piece
+  }
+}
+
 }  // namespace semmoe

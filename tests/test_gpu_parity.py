@@ -568,10 +568,11 @@ def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
             m.set_tuning(key, -1)
 
 
-@pytest.mark.parametrize("grid_cap,split", [(1, 16), (4, 8), (-1, 16)])
-def test_tail_launch_with_the_deep_ring(grid_cap, split):
-    """the tail launch of a split GEMM with a ring of 6 (one workgroup per compute unit) instead of 3"""
-    _say("tail ring 6, grid cap", grid_cap, "split", split)
+@pytest.mark.parametrize("grid_cap,split,ring", [(1, 16, 6), (4, 8, 6), (-1, 16, 6), (1, 16, 3), (-1, 8, 3),
+                                                  (2, 16, -1), (-1, 16, -1)])
+def test_tail_launch_kernels(grid_cap, split, ring):
+    """the tail launch of a split GEMM: 128 x 128 pieces (default) and the 128 x 64 pieces with a ring of 3 or 6"""
+    _say("tail ring", ring, "grid cap", grid_cap, "split", split)
     w = WL.small(T=2500, d=512, E=4, k=2, F=192, D=2, dtype="bf16", C=2)
     m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
     try:
@@ -579,7 +580,7 @@ def test_tail_launch_with_the_deep_ring(grid_cap, split):
         m.set_tuning(1, 22)
         m.set_tuning(4, grid_cap)
         m.set_tuning(5, split)
-        m.set_tuning(6, 6)
+        m.set_tuning(6, ring)
         lay, inp, ids, want_w, dw, Y, Yo, weights = _run_path(w, rank=-1)
         H.assert_close(Y, Yo, "bf16", "Y")
     finally:
