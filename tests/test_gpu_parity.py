@@ -502,6 +502,30 @@ def test_empty_and_degenerate_inputs():
     lay.X = torch.empty(0, w.d, dtype=torch.bfloat16, device=H.DEV)
     got = lay.dispatch()
     assert (got["expert_offsets"] == 0).all() and (got["rank_offsets"] == 0).all() and int(got["remote_pairs"]) == 0
+    # the widened rows on an empty batch
+    i32 = dict(dtype=torch.int32, device=H.DEV)
+    rc_d = torch.full((4,), 7, **i32)
+    one = torch.zeros(8, **i32)
+    lay.m.reshuffle_rounds(one, lay.e2r, 3, one, one, one, rc_d, cap=0)
+    torch.cuda.synchronize()
+    assert (H.to_np(rc_d) == 0).all()
+    rc_d.fill_(7)
+    lay.m.reshuffle_lookup(one, 8, one, one, one, 0, one, one, one, rc_d, cap=0)
+    torch.cuda.synchronize()
+    assert (H.to_np(rc_d) == 0).all()
+    rc_d.fill_(7)
+    lay.m.request_schedule(one, 0, one, 8, one, one, one, one, one, rc_d)       # no request, no token
+    torch.cuda.synchronize()
+    assert (H.to_np(rc_d) == 0).all()
+    rc_d.fill_(7)
+    rr = torch.full((1,), -5, **i32)
+    lay.m.request_schedule(one, 1, one, 8, one, rr, one, one, one, rc_d)        # one empty request
+    torch.cuda.synchronize()
+    assert (H.to_np(rc_d) == 0).all() and H.to_np(rr).tolist() == [0]
+    table = torch.zeros(8, 16, **i32)
+    lay.m.token_expert_hist(one, one, 0, 8, table)
+    torch.cuda.synchronize()
+    assert int(table.sum().item()) == 0
     # an expert with zero rows writes nothing; all tokens on one expert pair
     w = WL.small(T=130, E=8, D=2, k=2, d=64, F=64)
     ids = np.tile(np.array([[3, 5]], dtype=np.int32), (130, 1))

@@ -86,6 +86,40 @@ def test_calls_reject_null_pointers_and_bad_capacity_without_a_gpu():
     assert lib.semmoe_workspace_bytes(None, None) == -1
 
 
+def test_next_row_calls_reject_bad_arguments_without_a_gpu():
+    """the entry points of the widened rows validate before they launch anything"""
+    m = _mk()
+    lib = m.lib
+    c = m.cfg.c()
+    one = np.zeros(4096, dtype=np.int32)
+    p = one.ctypes.data
+    big = 1 << 20
+    # reshuffle with spill rounds
+    assert lib.semmoe_reshuffle_rounds(C.byref(c), None, p, p, 0, p, p, p, p, p, big) == -1          # rounds < 1
+    assert lib.semmoe_reshuffle_rounds(C.byref(c), None, None, p, 2, p, p, p, p, p, big) == -1
+    assert lib.semmoe_reshuffle_rounds(C.byref(c), None, p, p, 2, p, p, p, p, None, 0) == -3
+    # activation table, schedule tables, table-driven reshuffle
+    assert lib.semmoe_token_expert_hist(C.byref(c), None, None, p, 4, 8, p) == -1
+    assert lib.semmoe_token_expert_hist(C.byref(c), None, p, p, -1, 8, p) == -1
+    assert lib.semmoe_token_expert_hist(C.byref(c), None, p, p, 4, 0, p) == -1                       # empty vocabulary
+    assert lib.semmoe_lookup_tables(C.byref(c), None, p, 8, p, p, p) == -1
+    assert lib.semmoe_lookup_tables(C.byref(c), p, p, 0, p, p, p) == -1
+    assert lib.semmoe_reshuffle_lookup(C.byref(c), None, p, 0, p, p, p, 0, p, p, p, p, p, big) == -1  # V <= 0
+    assert lib.semmoe_reshuffle_lookup(C.byref(c), None, p, 8, None, p, p, 0, p, p, p, p, p, big) == -1
+    assert lib.semmoe_reshuffle_lookup(C.byref(c), None, p, 8, p, p, p, 0, p, p, p, p, p, 8) == -3
+    c.cap = 15
+    assert lib.semmoe_reshuffle_lookup(C.byref(c), None, p, 8, p, p, p, 0, p, p, p, p, p, big) == -2  # cap * D < T
+    c.cap = 16
+    # request scheduling
+    assert lib.semmoe_request_schedule(C.byref(c), None, None, 3, p, 8, p, p, p, p, p, p, p, big) == -1
+    assert lib.semmoe_request_schedule(C.byref(c), None, p, -1, p, 8, p, p, p, p, p, p, p, big) == -1
+    assert lib.semmoe_request_schedule(C.byref(c), None, p, 3, p, 0, p, p, p, p, p, p, p, big) == -1
+    assert lib.semmoe_request_schedule(C.byref(c), None, p, 65, p, 8, p, p, p, p, p, p, p, big) == -2  # n_req > T
+    assert lib.semmoe_request_schedule(C.byref(c), None, p, 0, p, 8, p, p, p, p, p, p, p, big) == -2   # tokens, no request
+    assert lib.semmoe_request_schedule(C.byref(c), None, p, 3, p, 8, p, p, p, p, p, p, None, 0) == -3
+    assert lib.semmoe_set_tuning(99, 1) == -1
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_LIB", None)
     monkeypatch.setenv("SEMMOE_LIB", str(tmp_path / "nope.so"))
