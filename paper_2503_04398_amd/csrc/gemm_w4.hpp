@@ -268,8 +268,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
       const int n_stage = (c_stage + 1 == NSTAGE) ? 0 : c_stage + 1;
       // one k-step; the k-step index is a compile-time constant (a pragma-unrolled loop over it was left partly
       // rolled by the compiler, which turns the fragment buffers into scratch memory)
-      // one k-step; the k-step index is a compile-time constant (a pragma-unrolled loop over it was left partly
-      // rolled by the compiler, which turns the fragment buffers into scratch memory)
       auto k_step = [&](auto ks_tag) __attribute__((always_inline)) {
         constexpr int ks = decltype(ks_tag)::value;
         constexpr int kLast = C::KS - 1;
@@ -281,16 +279,24 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
           // issued, unless the stream has ended)
           if (!i_done) wait_vmcnt<(NSTAGE - 2) * C::IPW>(); else wait_vmcnt<0>();
           __syncthreads();
-          frag(n_stage, 0, af[cur ^ 1], bfr[cur ^ 1]);
-        } else {
-          frag(c_stage, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
         }
+        // the eight fragment reads of the next k-step (the next slice's first one after the barrier) go out one by
+        // one behind the first eight MFMAs: as a burst in front of the MFMAs they cost about 2 %
+        const unsigned char* S_next = lds_raw + ((ks == kLast) ? n_stage : c_stage) * C::kStageBytes;
+        const int off_next = ((((ks == kLast) ? 0 : ks + 1) * 2 + (lane >> 5)) ^ frag_swz) * 16;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+            {
+              const int p = j * 4 + i;  // constant after unrolling
+              if (p < 4)
+                af[cur ^ 1][p] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_w + p * 32 * C::RB + off_next);
+              else if (p < 8)
+                bfr[cur ^ 1][p - 4] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_x + (p - 4) * 64 * C::RB + off_next);
+            }
             // position in the load stream = MFMAs since the barrier (the last k-step comes first after it)
             const int m = ((ks == kLast) ? 0 : (ks + 1) * 16) + j * 4 + i;  // constant after unrolling
             if (m % DMA_EVERY == DMA_EVERY - 1 && m / DMA_EVERY < C::IPW) {
@@ -504,16 +510,23 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           if (!i_done) wait_vmcnt<(NSTAGE - 2) * C::IPW>(); else wait_vmcnt<0>();
           __syncthreads();
-          frag(n_stage, 0, af[cur ^ 1], bfr[cur ^ 1]);
-        } else {
-          frag(c_stage, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
         }
+        // the four fragment reads of the next k-step go out one by one behind the MFMAs
+        const unsigned char* S_next = lds_raw + ((ks == 3) ? n_stage : c_stage) * C::kStageBytes;
+        const int off_next = ((((ks == 3) ? 0 : ks + 1) * 2 + (lane >> 5)) ^ frag_swz) * 16;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+            {
+              const int p = j * 2 + i;  // constant after unrolling
+              if (p < 2)
+                af[cur ^ 1][p] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_w + p * 32 * C::RB + off_next);
+              else
+                bfr[cur ^ 1][p - 2] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_x + (p - 2) * 32 * C::RB + off_next);
+            }
             // window position = MFMAs since the barrier; a load after each of the first eight
             const int m = ((ks == 3) ? 0 : (ks + 1) * 4) + j * 2 + i;  // constant after unrolling
             switch (m) {
