@@ -25,34 +25,48 @@ __device__ __forceinline__ int bitmap_rank(const uint32_t* words, int t) {
   return r;
 }
 
-// fill the [E][kWords] bitmaps of this block's 256 shuffled positions; returns the thread's token (or -1)
-__device__ __forceinline__ int fill_bitmaps(int T, int k, int E, const int32_t* __restrict__ ids,
-                                            const int32_t* __restrict__ shf, const int32_t* __restrict__ phys,
-                                            uint32_t* bm, int* q_out) {
-  for (int x = threadIdx.x; x < E * kWords; x += blockDim.x) bm[x] = 0;
-  __syncthreads();
-  const int t = threadIdx.x;
-  const int pos = blockIdx.x * kTokBlock + t;
+// the thread's token at its shuffled position (or -1) and the physical experts of its k pairs (-1: none): a chain
+// of three dependent loads (shf -> ids -> phys), so callers start it before anything else they have to do
+__device__ __forceinline__ int load_pairs(int T, int k, int E, const int32_t* __restrict__ ids,
+                                          const int32_t* __restrict__ shf, const int32_t* __restrict__ phys,
+                                          int* q_out) {
+  const int pos = blockIdx.x * kTokBlock + threadIdx.x;
   int tok = -1;
   if (pos < T) {
     tok = shf[pos];
     if ((unsigned)tok >= (unsigned)T) tok = -1;
   }
+  int e[SEMMOE_MAX_K];
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) e[j] = (j < k && tok >= 0) ? ids[size_t(tok) * k + j] : -1;
 #pragma unroll
   for (int j = 0; j < SEMMOE_MAX_K; ++j) {
     q_out[j] = -1;
-    if (j < k && tok >= 0) {
-      const int e = ids[size_t(tok) * k + j];
-      if ((unsigned)e < (unsigned)E) {
-        const int q = phys[e];
-        if ((unsigned)q < (unsigned)E) {
-          q_out[j] = q;
-          atomicOr(&bm[q * kWords + (t >> 5)], 1u << (t & 31));
-        }
-      }
+    if ((unsigned)e[j] < (unsigned)E) {
+      const int q = phys[e[j]];
+      if ((unsigned)q < (unsigned)E) q_out[j] = q;
     }
   }
+  return tok;
+}
+
+// set the thread's bits in the [E][kWords] bitmaps of this block's 256 shuffled positions (zeroed here)
+__device__ __forceinline__ void set_bitmaps(int E, uint32_t* bm, const int* q) {
+  for (int x = threadIdx.x; x < E * kWords; x += blockDim.x) bm[x] = 0;
   __syncthreads();
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j)
+    if (q[j] >= 0) atomicOr(&bm[q[j] * kWords + (t >> 5)], 1u << (t & 31));
+  __syncthreads();
+}
+
+// fill the [E][kWords] bitmaps of this block's 256 shuffled positions; returns the thread's token (or -1)
+__device__ __forceinline__ int fill_bitmaps(int T, int k, int E, const int32_t* __restrict__ ids,
+                                            const int32_t* __restrict__ shf, const int32_t* __restrict__ phys,
+                                            uint32_t* bm, int* q_out) {
+  const int tok = load_pairs(T, k, E, ids, shf, phys, q_out);
+  set_bitmaps(E, bm, q_out);
   return tok;
 }
 
@@ -172,6 +186,8 @@ __global__ __launch_bounds__(kTokBlock) void dp_fused_kernel(int T, int k, int E
   unsigned long long* remote_sh = reinterpret_cast<unsigned long long*>(
       (reinterpret_cast<uintptr_t>(pre + E) + 7) & ~uintptr_t(7));
   const int t = threadIdx.x, b = blockIdx.x;
+  int q[SEMMOE_MAX_K];
+  const int tok = load_pairs(T, k, E, ids, shf, phys, q);  // three dependent loads: under way while the table is summed
   for (int x = t; x < 2 * E + 1; x += kTokBlock) off[x] = 0;
   if (t == 0) *remote_sh = 0ull;
   __syncthreads();
@@ -223,8 +239,7 @@ __global__ __launch_bounds__(kTokBlock) void dp_fused_kernel(int T, int k, int E
     }
     if (t == 0) *remote_pairs = *remote_sh;
   }
-  int q[SEMMOE_MAX_K];
-  const int tok = fill_bitmaps(T, k, E, ids, shf, phys, bm, q);
+  set_bitmaps(E, bm, q);
   if (tok < 0) return;
 #pragma unroll
   for (int j = 0; j < SEMMOE_MAX_K; ++j) {
