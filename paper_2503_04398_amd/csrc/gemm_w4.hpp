@@ -90,7 +90,7 @@ struct W4Cfg {
   static constexpr size_t kRingBytes = size_t(NSTAGE) * kStageBytes;
   static constexpr int kStgRow = 128 + 16;             // staging row: 64 bf16 + pad against bank conflicts
   static constexpr int kStgWave = 32 * kStgRow;        // 32 tokens per pass
-  static constexpr size_t kLdsBytes = kRingBytes + 4 * kStgWave + 520 * 4;
+  static constexpr size_t kLdsBytes = kRingBytes + 4 * kStgWave + 4 * 520 * 4;  // + tile prefix + group table
   static_assert(BK == 32 || BK == 64, "row of 64 or 128 bytes");
   static_assert(KS * 16 / DMA_EVERY >= IPW, "the loads of a slice fit between two barriers");
   static_assert(NSTAGE >= 2 && (NSTAGE - 1) * IPW < 64, "vmcnt range");
@@ -100,12 +100,15 @@ struct TileRef {
   int row_lo, n_tok, f0, widx;
 };
 
-__device__ __forceinline__ TileRef locate_tile(const GemmArgs& a, const int* pre, int tile, int n_ftiles, int BT,
-                                               int FEAT) {
+// gtab (LDS, filled once per workgroup): per group its first row, the row after its last, and its weight index.
+// Reading the offsets from global memory here instead costs three dependent scalar loads per tile, in the middle
+// of the K loop of the tile before.
+__device__ __forceinline__ TileRef locate_tile(const GemmArgs& a, const int* pre, const int* gtab, int tile,
+                                               int n_ftiles, int BT, int FEAT) {
   const int q = __builtin_amdgcn_readfirstlane(find_group(pre, a.nq, tile));
   const int local = tile - __builtin_amdgcn_readfirstlane(pre[q]);
-  const int g_lo = a.offsets ? uniform_load(a.offsets + a.q_lo + q) : 0;
-  const int row_hi = a.offsets ? uniform_load(a.offsets + a.q_lo + q + 1) : a.n_rows_single;
+  const int g_lo = __builtin_amdgcn_readfirstlane(gtab[3 * q]);
+  const int row_hi = __builtin_amdgcn_readfirstlane(gtab[3 * q + 1]);
   int ft, tt;
   decode_tile(local, (row_hi - g_lo + BT - 1) / BT, n_ftiles, &tt, &ft);
   // the divisions above run on the vector ALU: tell the compiler that the results are uniform
@@ -115,7 +118,7 @@ __device__ __forceinline__ TileRef locate_tile(const GemmArgs& a, const int* pre
   t.row_lo = g_lo + tt * BT;
   t.n_tok = min(BT, row_hi - t.row_lo);
   t.f0 = ft * FEAT;
-  t.widx = a.group_to_weight ? uniform_load(a.group_to_weight + a.q_lo + q) : (a.q_lo + q);
+  t.widx = __builtin_amdgcn_readfirstlane(gtab[3 * q + 2]);
   return t;
 }
 
@@ -134,9 +137,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   unsigned char* stg = lds_raw + C::kRingBytes + wave * C::kStgWave;
   int* pre = reinterpret_cast<int*>(lds_raw + C::kRingBytes + 4 * C::kStgWave);
 
+  int* gtab = pre + 520;
   const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
   const int G = gridDim.x;
-  const int listed = __builtin_amdgcn_readfirstlane(build_tile_prefix(a, n_ftiles, pre, C::BT));
+  for (int q = tid; q < a.nq; q += C::kThreads) {
+    gtab[3 * q] = a.offsets ? a.offsets[a.q_lo + q] : 0;
+    gtab[3 * q + 1] = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
+    gtab[3 * q + 2] = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
+  }
+  const int listed = __builtin_amdgcn_readfirstlane(build_tile_prefix(a, n_ftiles, pre, C::BT));  // ends with a barrier
   const int total = a.sched_mode == 1 ? head_tiles(listed, G, a.sched_thr) : listed;  // head launch of a split
   const int nk = a.K / BK;
   const int worker = xcd_worker_index();
@@ -169,8 +178,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
 
   // (the lambdas are forced inline: one left as a call makes the argument block a stack object, and every access
   // to it a scratch load that waits for all the tile loads in flight)
+  TileRef s_tile;  // the tile the stream stands in: the MFMAs reach it NSTAGE slices later and take it from here
   auto i_setup = [&](int tile) __attribute__((always_inline)) {
-    const TileRef t = locate_tile(a, pre, tile, n_ftiles, C::BT, C::FEAT);
+    const TileRef t = locate_tile(a, pre, gtab, tile, n_ftiles, C::BT, C::FEAT);
+    s_tile = t;
     if (loads_w) {
       i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.W) + size_t(t.widx) * a.w_group_stride);
 #pragma unroll
@@ -252,7 +263,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   int c_stage = 0;
 
   for (int tile = worker; tile < total; tile += G) {
-    const TileRef t = locate_tile(a, pre, tile, n_ftiles, C::BT, C::FEAT);
+    // the stream is in this tile (K / BK >= NSTAGE: never further), so its tile is this one
+    const TileRef t = s_tile;
     // MFMA columns of this wave that hold tokens (the others are computed on clamped rows and never stored:
     // skipping their MFMAs was measured to gain nothing, the loop is bound by the loads)
     const int nj = min(4, max(0, (t.n_tok - wt * 32 + 63) >> 6));
