@@ -39,7 +39,12 @@ Which passage each function follows
 Pins (tests/test_oracle_*.py): brute force on tiny inputs, closed forms,
 library argsort / matmul special cases, the 1/D local-activation rate of
 class-free routing (the ~25 % baseline of Tables 3-4 at D = 4), planted-cluster
-recovery.  Parity unpinned (the paper gives nothing to check against): the
+recovery; for the rows built on top: spill rounds - hand example, round one = the
+greedy, greedy <= rounds <= optimum; table-driven rebatch - counts, hand example,
+threshold extremes, one key per token = the rebatch on the actual top-k; request
+scheduling - hand example with mask and reset, the request-to-cluster rule where
+the mask cannot bite, every round reaches every rank, brute force over the unmasked
+set.  Parity unpinned (the paper gives nothing to check against): the
 values of alpha, gamma, ft_steps; the behaviour of `align`; Fig. 3's example.
 """
 from __future__ import annotations
