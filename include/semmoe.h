@@ -82,6 +82,9 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *   SEMMOE_TUNE_TAIL_RING: kernel of that second launch.  Default: 128 x 128 pieces, one workgroup per compute unit,
  *     loads placed between the MFMAs (K a multiple of 64, else the next).  3 or 6: 128 x 64 pieces with the loads of a
  *     slice issued in a burst and an LDS ring of 3 (two workgroups per compute unit) or 6 (one)
+ *   SEMMOE_TUNE_ROUTE_SPLIT: bf16 router with at most 512 tokens: parts the K dimension is split into over workgroups
+ *     (partial sums added in order by a second kernel, then the selection kernel); 0 = always the fused kernel,
+ *     default: as many parts as fill the chip, at most 16
  *   SEMMOE_TUNE_GRID_CAP: most workgroups a grouped GEMM launches (default: compute units x blocks per CU)
  *   SEMMOE_TUNE_INDEX_PATH: which implementation of the index kernels runs (default: single workgroup for
  *     T <= 2048; above, two launches per call in which every workgroup derives its prefixes from the table of
@@ -94,6 +97,7 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
 #define SEMMOE_TUNE_INDEX_PATH 3 /* reshuffle / dispatch index: 1 = one kernel per phase, 2 = single workgroup, 3 = two launches */
 #define SEMMOE_TUNE_HEAD_TAIL 5  /* 0: one launch per GEMM; default: big tiles for the full rounds + quarter tiles */
 #define SEMMOE_TUNE_TAIL_RING 6  /* tail launch: default 128 x 128 pieces; 3 or 6: 128 x 64 pieces, that ring depth */
+#define SEMMOE_TUNE_ROUTE_SPLIT 7 /* parts of K in the few-token router; 0 = fused kernel */
 #define SEMMOE_TUNE_GRID_CAP 4   /* upper limit of the persistent GEMM grids (tests: many tiles per workgroup) */
 int32_t semmoe_set_tuning(int32_t key, int32_t value);
 

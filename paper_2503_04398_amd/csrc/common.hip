@@ -27,7 +27,11 @@ int32_t validate_config(const semmoe_config* cfg, bool need_T, bool need_rows, b
   return SEMMOE_OK;
 }
 
-size_t ws_route(const semmoe_config* cfg) { return align_up(size_t(cfg->T) * cfg->E * 4, 256) + 256; }
+size_t ws_route(const semmoe_config* cfg) {
+  const size_t logits = align_up(size_t(cfg->T) * cfg->E * 4, 256);
+  // few tokens: the router splits K over workgroups and keeps up to 16 partial sums per logit
+  return (cfg->T <= 512 ? 17 * logits : logits) + 512;
+}
 
 }  // namespace semmoe
 

@@ -579,7 +579,11 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
                                                           const float* __restrict__ sel_bias,
                                                           float* __restrict__ logits_out,
                                                           int32_t* __restrict__ topk_ids,
-                                                          float* __restrict__ topk_w) {
+                                                          float* __restrict__ topk_w, int n_parts,
+                                                          float* __restrict__ partial) {
+  // n_parts > 1 (few tokens: the token tiles alone would leave most of the chip idle): a work item is (token tile,
+  // part of K); it writes its raw fp32 sums to partial[part][token][expert] and a second kernel adds the parts up
+  // in order, adds the bias terms and hands the logits to the selection kernel.
   using C = RouteCfg<TF, TT, NSTAGE>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
@@ -595,7 +599,10 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
   const int d_row = lane / C::CPR, d_pos = lane % C::CPR;
   const int n_tiles = (T + C::BT - 1) / C::BT;
 
-  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  const int spp = (nk + n_parts - 1) / n_parts;  // slices per part
+  for (int item = blockIdx.x; item < n_tiles * n_parts; item += gridDim.x) {
+    const int tile = item / n_parts, part = item - tile * n_parts;
+    const int s_lo = min(part * spp, nk), n_it = min(nk, s_lo + spp) - s_lo;
     const int tok0 = tile * C::BT;
     const bf16_t* src[C::IPW];
     int src_chunk[C::IPW];
@@ -607,8 +614,9 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       src[i] = (sr < C::BW) ? W_r + size_t(min(sr, E - 1)) * K + c * 8
                             : X + size_t(min(tok0 + sr - C::BW, T - 1)) * K + c * 8;
     }
-    auto issue = [&](int slice) {
-      const unsigned dst0 = lds_base + (slice % NSTAGE) * C::kStageBytes + wave * C::IPW * 1024;
+    auto issue = [&](int it_) {  // slice s_lo + it_ of K into ring stage it_ % NSTAGE
+      const int slice = s_lo + it_;
+      const unsigned dst0 = lds_base + (it_ % NSTAGE) * C::kStageBytes + wave * C::IPW * 1024;
       const int k0 = slice * C::BK;
       if (slice + 1 < nk || k_tail == C::BK) {
 #pragma unroll
@@ -636,9 +644,9 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
 
 #pragma unroll
     for (int s0 = 0; s0 < NSTAGE - 1; ++s0)
-      if (s0 < nk) issue(s0);
-    for (int it = 0; it < nk; ++it) {
-      const int younger = min(NSTAGE - 2, nk - 1 - it);
+      if (s0 < n_it) issue(s0);
+    for (int it = 0; it < n_it; ++it) {
+      const int younger = min(NSTAGE - 2, n_it - 1 - it);
       if (younger >= 4) wait_vmcnt<4 * C::IPW>();
       else if (younger == 3) wait_vmcnt<3 * C::IPW>();
       else if (younger == 2) wait_vmcnt<2 * C::IPW>();
@@ -662,7 +670,7 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       }
       // the refill of the stage freed by the barrier goes out while the fragment reads are in flight
       __builtin_amdgcn_sched_barrier(0);
-      if (it + NSTAGE - 1 < nk) issue(it + NSTAGE - 1);
+      if (it + NSTAGE - 1 < n_it) issue(it + NSTAGE - 1);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int st = 0; st < 4; st += 2) {
@@ -679,6 +687,22 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
     for (int i = 0; i < TF; ++i)
 #pragma unroll
       for (int j = 0; j < TT; ++j) acc[i][j] += acc2[i][j];
+    if (partial) {  // raw sums of this part of K; no wave reads LDS any more, the next item's loads may start
+#pragma unroll
+      for (int j = 0; j < TT; ++j) {
+        const int tok = tok0 + j * 32 + lrow;
+#pragma unroll
+        for (int i = 0; i < TF; ++i) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int e = (wave * TF + i) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (e < E && tok < T) partial[(size_t(part) * T + tok) * E + e] = acc[i][j][r];
+          }
+        }
+      }
+      __syncthreads();
+      continue;
+    }
     __syncthreads();  // every wave is done with the ring: its first bytes now hold the logits
 
 #pragma unroll
@@ -737,6 +761,46 @@ __global__ __launch_bounds__(256) void select_topk_rows_kernel(semmoe_config cfg
   if (base >= cfg.T) return;  // whole wave leaves together
   select_tokens_by_rows(
       cfg, base, cfg.T, [&](int tl) { return logits + size_t(tl) * cfg.E; }, 0, sel_bias, lane, topk_ids, topk_w);
+}
+
+// logits[tok][e] = sum over the parts of K, in ascending order, + b_g[e] + class_bias[token_class[tok]][e]
+__global__ __launch_bounds__(256) void route_reduce_kernel(semmoe_config cfg, int n_parts,
+                                                           const float* __restrict__ partial,
+                                                           const float* __restrict__ b_g,
+                                                           const int32_t* __restrict__ token_class,
+                                                           const float* __restrict__ class_bias,
+                                                           float* __restrict__ logits, float* __restrict__ logits_out) {
+  const size_t n = size_t(cfg.T) * cfg.E;
+  const size_t idx = size_t(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= n) return;
+  const int tok = int(idx / cfg.E), e = int(idx - size_t(tok) * cfg.E);
+  float v = 0.0f;
+  for (int p0 = 0; p0 < n_parts; p0 += 8) {  // eight loads in flight
+    float x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = p0 + u < n_parts ? partial[size_t(p0 + u) * n + idx] : 0.0f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v += x[u];
+  }
+  if (b_g) v += b_g[e];
+  const int cls = token_class ? token_class[tok] : -1;
+  if (cls >= 0 && cls < cfg.num_classes && class_bias) v += class_bias[size_t(cls) * cfg.E + e];
+  logits[idx] = v;
+  if (logits_out) logits_out[idx] = v;
+}
+
+constexpr int kRouteSplitMaxTiles = 16;  // up to this many token tiles of 32 the K dimension is split over workgroups
+constexpr int kRouteSplitMaxParts = 16;
+
+// parts of K for the split router, 1 = the fused kernel.  tune: -1 automatic, 0 never, n > 1 that many parts
+static int route_parts(const semmoe_config* cfg, int ncu) {
+  const int tune = tuning_value(SEMMOE_TUNE_ROUTE_SPLIT);
+  const int n_tiles = cdiv(cfg->T, 32), nk = cdiv(cfg->d, 64);
+  if (cfg->dtype != SEMMOE_BF16 || tune == 0 || n_tiles > kRouteSplitMaxTiles) return 1;
+  int parts = tune > 1 ? tune : ncu / n_tiles;
+  if (parts > kRouteSplitMaxParts) parts = kRouteSplitMaxParts;
+  if (parts > nk / 2) parts = nk / 2;  // at least two slices per part
+  return parts < 2 ? 1 : parts;
 }
 
 static int32_t validate_select(const semmoe_config* cfg) {
@@ -799,7 +863,19 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     const bf16_t* Xb = static_cast<const bf16_t*>(X);
     const bf16_t* Wb = static_cast<const bf16_t*>(W_r);
     const int tf = cfg->E <= 128 ? 1 : (cfg->E <= 256 ? 2 : 4);
-    const bool wide = cdiv(cfg->T, 64) >= 256 && tf <= 2;
+    int dev0 = 0, ncu0 = 256;
+    SEMMOE_HIP(hipGetDevice(&dev0));
+    SEMMOE_HIP(hipDeviceGetAttribute(&ncu0, hipDeviceAttributeMultiprocessorCount, dev0));
+    const int n_parts = route_parts(cfg, ncu0);
+    float* partial = nullptr;
+    float* logits_ws = nullptr;
+    if (n_parts > 1) {
+      Carver c(ws, ws_bytes);
+      partial = c.take<float>(size_t(n_parts) * cfg->T * cfg->E);
+      logits_ws = c.take<float>(size_t(cfg->T) * cfg->E);
+      if (!c.ok) return SEMMOE_EWORKSPACE;
+    }
+    const bool wide = n_parts == 1 && cdiv(cfg->T, 64) >= 256 && tf <= 2;
     const int bt = wide ? 64 : 32;
     int dev = 0, ncu = 256;
     SEMMOE_HIP(hipGetDevice(&dev));
@@ -812,12 +888,13 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     const size_t lg_bytes = size_t(RC::BT) * (cfg->E + 4) * 4;                                                      \
     if (lg_bytes > lds) lds = lg_bytes;                                                                             \
     const int per_cu = lds <= 80 * 1024 ? 2 : 1;                                                                    \
-    const int grid = n_tiles < ncu * per_cu ? n_tiles : ncu * per_cu;                                               \
+    const int items = n_tiles * n_parts;                                                                            \
+    const int grid = items < ncu * per_cu ? items : ncu * per_cu;                                                   \
     if (lds > 48 * 1024)                                                                                            \
       SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_fused_kernel<TF_, TT_, NS_>),              \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));                        \
     hipLaunchKernelGGL((route_fused_kernel<TF_, TT_, NS_>), dim3(grid), dim3(256), lds, s, *cfg, Xb, Wb, b_g,       \
-                       token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                            \
+                       token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w, n_parts, partial);          \
   } while (0)
     if (tf == 1) {
       if (wide) SEMMOE_ROUTE_LAUNCH(1, 2, 5); else SEMMOE_ROUTE_LAUNCH(1, 1, 6);
@@ -828,6 +905,13 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     }
 #undef SEMMOE_ROUTE_LAUNCH
     SEMMOE_LAUNCH_CHECK();
+    if (n_parts > 1) {
+      const size_t n = size_t(cfg->T) * cfg->E;
+      hipLaunchKernelGGL(route_reduce_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, s, *cfg, n_parts, partial,
+                         b_g, token_class, class_bias, logits_ws, logits_out);
+      SEMMOE_LAUNCH_CHECK();
+      return launch_select(cfg, s, logits_ws, sel_bias, topk_ids, topk_w);
+    }
     return SEMMOE_OK;
   }
   // fp32: tiled FMA GEMM into the logits buffer, then the selection kernel

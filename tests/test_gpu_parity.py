@@ -80,15 +80,24 @@ def test_route_from_logits_sigmoid_group_limited(E, k, T, ng, tg, scale, bias):
     assert O.max_rel_err(H.to_np(w), want_w) <= 1e-5
 
 
-@pytest.mark.parametrize("dtype,T,d,E,k", [("fp32", 200, 72, 16, 2), ("bf16", 333, 200, 128, 8),
-                                           ("bf16", 130, 64, 24, 3), ("fp32", 64, 512, 16, 2)])
-def test_route_gemm_and_selection(dtype, T, d, E, k):
-    _say("route", dtype, T, d, E, k)
+@pytest.mark.parametrize("dtype,T,d,E,k,split", [
+    ("fp32", 200, 72, 16, 2, -1), ("bf16", 333, 200, 128, 8, -1), ("bf16", 333, 200, 128, 8, 0),
+    ("bf16", 130, 64, 24, 3, -1), ("fp32", 64, 512, 16, 2, -1), ("bf16", 257, 1032, 256, 8, -1),
+    ("bf16", 257, 1032, 256, 8, 0), ("bf16", 100, 4096, 128, 8, 5), ("bf16", 40, 512, 384, 6, 3),
+    ("bf16", 700, 256, 64, 4, -1), ("bf16", 512, 2048, 128, 8, 16)])
+def test_route_gemm_and_selection(dtype, T, d, E, k, split):
+    """router GEMM + selection; split: the few-token router's parts of K (-1 the library's choice, 0 the fused
+    kernel, n forced; T = 700 is above the few-token limit and always fused)"""
+    _say("route", dtype, T, d, E, k, "split", split)
     w = WL.small(T=T, d=d, E=E, k=k, D=1, C=4, dtype=dtype)
     inp = H.make_inputs(w)
     lay = H.Layer(w)
     b_g = (0.1 * np.random.default_rng(1).standard_normal(E)).astype(np.float32)
-    logits, ids, tw = lay.route(inp, b_g=b_g)
+    lay.m.set_tuning(7, split)
+    try:
+        logits, ids, tw = lay.route(inp, b_g=b_g)
+    finally:
+        lay.m.set_tuning(7, -1)
     want_logits = O.route_logits(inp.X, inp.W_r, b_g, inp.token_class, inp.class_bias)
     err = O.max_rel_err(logits, want_logits)
     assert err <= 1e-5, err              # inputs are exact in both; only fp32 accumulation order differs
