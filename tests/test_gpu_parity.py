@@ -297,9 +297,11 @@ def test_request_schedule_bit_exact(T, D, V, n_req, seed):
             assert (g == w_).all()
 
 
-def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit():
-    """beyond what the single-workgroup kernels hold; multi-workgroup kernels by default"""
-    T, E, D, k = 40000, 64, 16, 4
+@pytest.mark.parametrize("T,E,D,k", [(40000, 64, 16, 4), (131072, 8, 4, 2), (131073, 8, 4, 2)])
+def test_reshuffle_and_dispatch_index_above_the_single_workgroup_limit(T, E, D, k):
+    """beyond what the single-workgroup kernels hold; multi-workgroup kernels by default.  T = 131072 is the last
+    size of the two-launch kernels (512 workgroups read the whole count table), one token more takes the kernels
+    with scan launches in between"""
     _say("reshuffle + dispatch index, large T", T)
     ids, e2r = _planted(T, E, D, k, seed=5, noise=0.4)
     phys = np.argsort(np.argsort(e2r, kind="stable"), kind="stable").astype(np.int32)
