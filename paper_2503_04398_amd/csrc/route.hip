@@ -289,12 +289,12 @@ __device__ __forceinline__ void select_rows_any(const semmoe_config& cfg, const 
 
 // rowp[ch] / idp[ch] / wp[ch]: this lane's token of group ch (the same for the 16 lanes of a row), nullptr = none.
 // Same selection rule as select_rows: k rounds of arg-max, equal values -> lowest expert id.
-template <int NS, int NCH>
+template <int NS, int NCH, bool SIG>
 __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const float* const (&rowp)[NCH],
                                               const float* __restrict__ sel_bias, int lane,
                                               int32_t* const (&idp)[NCH], float* const (&wp)[NCH]) {
   const int E = cfg.E, k = cfg.k, l16 = lane & 15;
-  const bool sigmoid = cfg.score == SEMMOE_SIGMOID;
+  constexpr bool sigmoid = SIG;  // compile-time: the softmax form carries none of the sigmoid form's bookkeeping
   const int NEGK = to_key(-__builtin_inff());
 
   int val[NCH][NS];    // key of the selection score
@@ -325,17 +325,20 @@ __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const fl
   // arg-max of a row over the entries that pass `use(ch, c)`: every lane gets the largest key and the lowest
   // expert id that holds it (kNoExpert when there is no entry).  A lane first finds its own best entry (the
   // lowest slot among equals: strict compare), then the row agrees on the value and on the lowest id.
+  float own_aux[NCH];  // sigmoid: s of the lane's best entry of the last arg-max
   auto row_argmax = [&](auto use, int(&vmax)[NCH], int(&arg)[NCH]) __attribute__((always_inline)) {
     int slot[NCH], own[NCH];
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
       own[ch] = NEGK;
       slot[ch] = 0;
+      own_aux[ch] = 0.0f;
 #pragma unroll
       for (int c = 0; c < NS; ++c) {
         const bool better = use(ch, c) && val[ch][c] > own[ch];
         own[ch] = better ? val[ch][c] : own[ch];
         slot[ch] = better ? c : slot[ch];
+        if constexpr (SIG) own_aux[ch] = better ? aux[ch][c] : own_aux[ch];
       }
       vmax[ch] = own[ch];
     }
@@ -355,15 +358,22 @@ __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const fl
     int gkey[NCH];
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) gkey[ch] = NEGK;
+    const bool whole_slots = gs % 16 == 0;  // a group is a run of gs/16 slots, the same for every lane
+    const int spg = whole_slots ? gs / 16 : 0;
     for (int g = 0; g < cfg.n_group; ++g) {
       int a1[NCH], a2[NCH];  // the two largest keys seen so far (with multiplicity)
 #pragma unroll
       for (int ch = 0; ch < NCH; ++ch) {
         a1[ch] = NEGK;
         a2[ch] = NEGK;
+      }
 #pragma unroll
-        for (int c = 0; c < NS; ++c)
-          if (((live[ch] >> c) & 1u) && grp[c] == g) {
+      for (int c = 0; c < NS; ++c) {
+        // whole slots: a uniform test skips the slots of the other groups; else every lane tests its own entry
+        if (whole_slots && (c < g * spg || c >= (g + 1) * spg)) continue;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch)
+          if (((live[ch] >> c) & 1u) && (whole_slots || grp[c] == g)) {
             const int v = val[ch][c];
             a2[ch] = max(a2[ch], min(a1[ch], v));
             a1[ch] = max(a1[ch], v);
@@ -440,10 +450,7 @@ __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const fl
     for (int ch = 0; ch < NCH; ++ch) {
       const bool own = e[ch] != kNoExpert && (e[ch] & 15) == l16;
       const int slot = (e[ch] >> 4) & 31;
-      abits[ch] = 0;
-#pragma unroll
-      for (int c = 0; c < NS; ++c)
-        if (own && c == slot) abits[ch] = __float_as_int(aux[ch][c]);
+      abits[ch] = (SIG && own) ? __float_as_int(own_aux[ch]) : 0;  // the winner is its lane's best entry
       if (own) live[ch] &= ~(1u << slot);
     }
     if (sigmoid) SEMMOE_ROW_REDUCE("v_or_b32_dpp", abits);  // the owner's s reaches every lane of the row
@@ -520,11 +527,19 @@ __device__ __forceinline__ void select_tokens_by_rows(const semmoe_config& cfg, 
     idp[ch] = ok ? topk_ids + size_t(tok_global0 + tl) * cfg.k : nullptr;
     wp[ch] = ok ? topk_w + size_t(tok_global0 + tl) * cfg.k : nullptr;
   }
-  if (cfg.E <= 16) select_rows16<1, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
-  else if (cfg.E <= 32) select_rows16<2, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
-  else if (cfg.E <= 64) select_rows16<4, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
-  else if (cfg.E <= 128) select_rows16<8, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
-  else select_rows16<16, kRowChains>(cfg, rowp, sel_bias, lane, idp, wp);
+  if (cfg.score == SEMMOE_SIGMOID) {
+    if (cfg.E <= 16) select_rows16<1, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 32) select_rows16<2, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 64) select_rows16<4, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 128) select_rows16<8, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
+    else select_rows16<16, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
+  } else {
+    if (cfg.E <= 16) select_rows16<1, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 32) select_rows16<2, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 64) select_rows16<4, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 128) select_rows16<8, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
+    else select_rows16<16, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
+  }
 }
 
 constexpr int kSelTokens = 2;  // tokens a wave selects for at a time (four gain nothing: the selection is bound by instruction issue)
