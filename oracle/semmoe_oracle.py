@@ -27,6 +27,9 @@ Which passage each function follows
   request_schedule / request_assignment
                                Alg. 2 `get_dp_rank` + `schedule` (Attention-DP scenario), with
                                S_r = argmax_j sum_{i in r} R_ij of Sec. 3.3
+  expert_place_affinity / unit_schedule / coschedule_score / coschedule / token_labels
+                               Alg. 1 whole (App. B): `expert_place` with its request term, `req_sched`,
+                               the alternation and its score, the token labels T / T_p it ends with
   reshuffle_exact              the ILP's communication term (Sec. 3.3) solved exactly
                                for fixed placement: min-cost flow
   dispatch / combine           the two all2all of expert parallelism (Sec. 1) as
@@ -44,7 +47,10 @@ greedy, greedy <= rounds <= optimum; table-driven rebatch - counts, hand example
 threshold extremes, one key per token = the rebatch on the actual top-k; request
 scheduling - hand example with mask and reset, the request-to-cluster rule where
 the mask cannot bite, every round reaches every rank, brute force over the unmasked
-set.  Parity unpinned (the paper gives nothing to check against): the
+set; co-scheduling solver - without the request term it is `place`, hand examples of every
+term and of the swap gain, planted topics recovered, remote mass = remote pair count when
+every token is a unit, never below the brute-force optimum, labels = `lookup_tables` of the
+count table.  Parity unpinned (the paper gives nothing to check against): the
 values of alpha, gamma, ft_steps; the behaviour of `align`; Fig. 3's example.
 """
 from __future__ import annotations
@@ -545,6 +551,193 @@ def request_assignment(req_offsets, req_rank, D: int):
     inv_shf[shf] = np.arange(T)
     return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
             np.bincount(token_rank, minlength=D).astype(np.int32))
+
+
+# --------------------------------------------------------------------------------------------
+# the co-scheduling solver in full (Alg. 1 with its request half; App. B)
+# --------------------------------------------------------------------------------------------
+
+
+def expert_place_affinity(load, coact, D: int, unit_act=None, unit_rank=None, alpha_e: int = 1, beta_e: int = 0,
+                          gamma_e: int = 0, ft_passes: int = 8):
+    """`expert_place` of Alg. 1 with its request term.  A unit is a request (or a token key standing for all its
+    occurrences); unit_act[u,e] is the activation mass of unit u on expert e, unit_rank[u] the cluster the unit is
+    scheduled to at the moment (fixed during the call).
+        EAfE[e,c] = sum of coact[e,e'] over experts e' already on c
+        EAfR[e,c] = sum of unit_act[u,e] over units u scheduled to c
+        score     = alpha_e*EAfE[e,c] + beta_e*EAfR[e,c] - gamma_e*loads_cls[c]
+    Experts hottest first (equal -> lower id); arg-max over the clusters not yet full (equal -> smaller loads_cls,
+    then smaller c); a cluster is full at E/D experts.  Fine-tuning as in `place`: first-improvement sweeps over
+    pairs e1 < e2 on different clusters, gain = alpha_e*(change of the intra-cluster co-activation mass)
+    + beta_e*(change of the activation mass that is local, sum_e EAfR[e, cluster(e)]); swap when gain > 0.
+    With beta_e = 0 and alpha_e > 0 this is `place`.  Returns expert_to_rank[E] int32."""
+    load = np.asarray(load, dtype=np.int64)
+    A = np.asarray(coact, dtype=np.int64)
+    E = load.shape[0]
+    assert A.shape == (E, E) and E % D == 0
+    m = E // D
+    R = [[0] * D for _ in range(E)]                 # EAfR
+    if unit_act is not None and unit_rank is not None:
+        Q = np.asarray(unit_act, dtype=np.int64)
+        for u in range(Q.shape[0]):
+            c = int(unit_rank[u])
+            for e in range(E):
+                R[e][c] += int(Q[u, e])
+    order = sorted(range(E), key=lambda e: (-int(load[e]), e))
+    rank_of = [-1] * E
+    members = [[] for _ in range(D)]
+    loads_cls = [0] * D
+    for e in order:
+        best = None
+        for c in range(D):
+            if len(members[c]) >= m:
+                continue
+            eafe = sum(int(A[e, e2]) for e2 in members[c])
+            score = alpha_e * eafe + beta_e * R[e][c] - gamma_e * loads_cls[c]
+            key = (-score, loads_cls[c], c)
+            if best is None or key < best[0]:
+                best = (key, c)
+        c = best[1]
+        rank_of[e] = c
+        members[c].append(e)
+        loads_cls[c] += int(load[e])
+
+    def aff(e, c, excl):
+        return sum(int(A[e, x]) for x in range(E) if rank_of[x] == c and x != e and x != excl)
+
+    for _ in range(ft_passes):
+        swapped = False
+        for e1 in range(E):
+            for e2 in range(e1 + 1, E):
+                c1, c2 = rank_of[e1], rank_of[e2]
+                if c1 == c2:
+                    continue
+                g_e = aff(e1, c2, e2) + aff(e2, c1, e1) - aff(e1, c1, e1) - aff(e2, c2, e2)
+                g_r = R[e1][c2] + R[e2][c1] - R[e1][c1] - R[e2][c2]
+                if alpha_e * g_e + beta_e * g_r > 0:
+                    rank_of[e1], rank_of[e2] = c2, c1
+                    swapped = True
+        if not swapped:
+            break
+    return np.array(rank_of, dtype=np.int32)
+
+
+def placement_order(expert_to_rank, D: int):
+    """physical order of a placement: rank-major, ascending original id inside a rank.
+    Returns (phys_of_expert, expert_of_phys) int32."""
+    r = np.asarray(expert_to_rank)
+    E = r.shape[0]
+    m = E // D
+    phys = np.zeros(E, dtype=np.int32)
+    seen = [0] * D
+    for e in range(E):
+        phys[e] = int(r[e]) * m + seen[int(r[e])]
+        seen[int(r[e])] += 1
+    inv = np.zeros(E, dtype=np.int32)
+    inv[phys] = np.arange(E, dtype=np.int32)
+    return phys, inv
+
+
+def unit_schedule(unit_act, unit_len, expert_to_rank, D: int, alpha_r: int = 0, beta_r: int = 1) -> np.ndarray:
+    """`req_sched` of Alg. 1: units longest first (equal -> lower index); for unit u and every cluster c that is
+    not full
+        RAfR[u,c] = sum over units u' already on c of sum_e unit_act[u,e]*unit_act[u',e]   (request-request)
+        RAfE[u,c] = sum of unit_act[u,e] over experts e placed on c                          (request-expert)
+        score     = alpha_r*RAfR[u,c] + beta_r*RAfE[u,c]
+    u goes to the arg-max (equal -> the cluster holding fewer tokens so far, then smaller c); a cluster is full
+    at ceil(U/D) units.  Returns unit_rank[U] int32."""
+    Q = np.asarray(unit_act, dtype=np.int64)
+    U, E = Q.shape
+    ln = [int(x) for x in np.asarray(unit_len)]
+    e2r = [int(x) for x in np.asarray(expert_to_rank)]
+    cap = -(-U // D)
+    order = sorted(range(U), key=lambda u: (-ln[u], u))
+    on = [[] for _ in range(D)]
+    tokens_cls = [0] * D
+    unit_rank = np.zeros(U, dtype=np.int32)
+    for u in order:
+        best = None
+        for c in range(D):
+            if len(on[c]) >= cap:
+                continue
+            rafr = sum(int(Q[u, e]) * int(Q[u2, e]) for u2 in on[c] for e in range(E))
+            rafe = sum(int(Q[u, e]) for e in range(E) if e2r[e] == c)
+            score = alpha_r * rafr + beta_r * rafe
+            key = (-score, tokens_cls[c], c)
+            if best is None or key < best[0]:
+                best = (key, c)
+        c = best[1]
+        unit_rank[u] = c
+        on[c].append(u)
+        tokens_cls[c] += ln[u]
+    return unit_rank
+
+
+def coschedule_score(unit_act, unit_len, expert_to_rank, unit_rank, D: int, w_load: int = 1, w_comm: int = 1):
+    """what Alg. 1's outer loop compares: w_load * (the most tokens any cluster holds) + w_comm * (activation
+    mass whose expert sits on another cluster than its unit: the all2all term of the Sec. 3.3 objective).
+    Returns (score, max_tokens, remote_mass) as Python ints."""
+    Q = np.asarray(unit_act, dtype=np.int64)
+    U, E = Q.shape
+    tokens = [0] * D
+    remote = 0
+    for u in range(U):
+        tokens[int(unit_rank[u])] += int(unit_len[u])
+        for e in range(E):
+            if int(expert_to_rank[e]) != int(unit_rank[u]):
+                remote += int(Q[u, e])
+    return w_load * max(tokens) + w_comm * remote, max(tokens), remote
+
+
+def coschedule(load, coact, unit_act, unit_len, D: int, alpha_e: int = 1, beta_e: int = 1, gamma_e: int = 0,
+               alpha_r: int = 0, beta_r: int = 1, ft_passes: int = 8, n_steps: int = 4, w_load: int = 1,
+               w_comm: int = 1):
+    """The alternating co-clustering of Alg. 1 (App. B).  Start: the experts are placed with no unit scheduled
+    (the request term is zero) and the units are clustered by their affinity to those experts (`unit_schedule`).
+    Then n_steps times: place the experts for the current unit schedule, schedule the units for the new
+    placement, score the pair; the pair of the lowest score is kept (equal -> the earlier step).
+    Returns (expert_to_rank[E], unit_rank[U], step_score list of n_steps ints, best_step)."""
+    assert n_steps >= 1
+    e2r = expert_place_affinity(load, coact, D, None, None, alpha_e, 0, gamma_e, ft_passes)
+    ur = unit_schedule(unit_act, unit_len, e2r, D, alpha_r, beta_r)
+    best = None
+    scores = []
+    for step in range(n_steps):
+        e2r = expert_place_affinity(load, coact, D, unit_act, ur, alpha_e, beta_e, gamma_e, ft_passes)
+        ur = unit_schedule(unit_act, unit_len, e2r, D, alpha_r, beta_r)
+        sc = coschedule_score(unit_act, unit_len, e2r, ur, D, w_load, w_comm)[0]
+        scores.append(sc)
+        if best is None or sc < best[0]:
+            best = (sc, e2r.copy(), ur.copy(), step)
+    return best[1], best[2], scores, best[3]
+
+
+def token_labels(req_offsets, keys, req_rank, V: int, D: int, k: int):
+    """The last lines of Alg. 1: count, per token id, how many of its occurrences sit in requests scheduled to
+    each cluster; the token's label is the cluster of the highest count (equal -> smallest) and its confidence
+    that count's share.  Same integer forms as `lookup_tables`: conf_q16 = floor(65536*share),
+    level = round-half-up(k*share); an id that never occurs has dev = -1, conf_q16 = 0, level = 0.
+    Returns (dev[V], conf_q16[V], level[V]) int32."""
+    off = np.asarray(req_offsets)
+    keys = np.asarray(keys)
+    cnt = [[0] * D for _ in range(V)]
+    for q in range(off.shape[0] - 1):
+        for i in range(int(off[q]), int(off[q + 1])):
+            v = int(keys[i])
+            if 0 <= v < V:
+                cnt[v][int(req_rank[q])] += 1
+    dev = np.full(V, -1, dtype=np.int32)
+    conf = np.zeros(V, dtype=np.int32)
+    level = np.zeros(V, dtype=np.int32)
+    for v in range(V):
+        tot = sum(cnt[v])
+        if tot == 0:
+            continue
+        best = max(range(D), key=lambda r: (cnt[v][r], -r))
+        dev[v] = best
+        conf[v] = (65536 * cnt[v][best]) // tot
+        level[v] = (2 * k * cnt[v][best] + tot) // (2 * tot)
+    return dev, conf, level
 
 
 def home_assignment(T: int, D: int):
