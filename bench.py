@@ -211,7 +211,6 @@ def main():
     sched_dev, sched_conf, sched_level = m.lookup_tables(table.cpu().numpy().view(np.uint32), e2r_h)
     t_lookup = time.perf_counter() - t0
     e2r, phys, inv = up(e2r_h), up(phys_h), up(inv_h)
-    del Xp, mp
 
     if args.balance_study:
         m.route(X, W_r, ids, tw, token_class=tc, class_bias=cb)
@@ -424,6 +423,44 @@ def main():
                                  "remote_pair_fraction": round(int(rpr.item()) / P, 4),
                                  "tokens_per_rank_max_over_mean": round(float(rch.max() / max(rch.mean(), 1)), 3)}
 
+    # ---------------- next row: the co-scheduling solver (Alg. 1 whole): profiling requests -> expert placement and
+    # token labels together; judged by the remote-pair fraction of the measured batch's requests scheduled by Alg. 2
+    pq_off_h, pq_cls_h, pq_key_h = WL.requests(w, profile=True)
+    n_pq = len(pq_off_h) - 1
+    idq = torch.empty(Tp, k, **i32)
+    twq = torch.empty(Tp, k, dtype=torch.float32, device=dev)
+    mp.route(Xp, W_r, idq, twq, token_class=up(pq_cls_h), class_bias=cb)
+    unit_of = up(np.repeat(np.arange(n_pq), np.diff(pq_off_h)).astype(np.int32))
+    unit_act = torch.zeros(n_pq, E, **i32)
+    mp.token_expert_hist(unit_of, idq, Tp, n_pq, unit_act)
+    load_q, coact_q, table_q = torch.zeros(E, **i32), torch.zeros(E, E, **i32), torch.zeros(V, E, **i32)
+    mp.coact_hist(idq, Tp, load_q, coact_q)
+    mp.token_expert_hist(up(pq_key_h), idq, Tp, V, table_q)
+    torch.cuda.synchronize()
+    load_qh, coact_qh = load_q.cpu().numpy().astype(np.uint64), coact_q.cpu().numpy().astype(np.uint64)
+    act_h, table_qh = unit_act.cpu().numpy().astype(np.uint64), table_q.cpu().numpy().view(np.uint32)
+    len_h = np.diff(pq_off_h).astype(np.uint64)
+    pl_a = m.place(load_qh, coact_qh)
+    t0 = time.perf_counter()
+    cs = m.coschedule(load_qh, coact_qh, act_h, len_h, alpha_e=1, beta_e=1, gamma_e=0, alpha_r=0, beta_r=1,
+                      ft_passes=8, n_steps=4, w_load=1, w_comm=1)
+    t_cosched = time.perf_counter() - t0
+    lab = m.token_labels(pq_off_h, pq_key_h, cs[3], V)
+    cosched_report = {"profiling_requests": n_pq, "host_ms": round(t_cosched * 1e3, 3),
+                      "step_score": [int(x) for x in cs[4]], "best_step": cs[5]}
+    for label, pl, dev_tab in (("place+lookup_tables", pl_a, m.lookup_tables(table_qh, pl_a[0])[0]),
+                               ("coschedule+lookup_tables", cs, m.lookup_tables(table_qh, cs[0])[0]),
+                               ("coschedule+token_labels", cs, lab[0])):
+        m.request_schedule(req_off, n_req, req_key, V, up(dev_tab), req_rank, tr2, shf2, ish2, rc2)
+        rpr = torch.empty(1, dtype=torch.int64, device=dev)
+        m.dispatch_index(ids_r, tr2, shf2, up(pl[1]), tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                         torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rpr)
+        torch.cuda.synchronize()
+        rch = rc2.cpu().numpy()
+        cosched_report[label] = {"remote_pair_fraction": round(int(rpr.item()) / P, 4),
+                                 "tokens_per_rank_max_over_mean": round(float(rch.max() / max(rch.mean(), 1)), 3)}
+    del Xp, mp
+
     # ---------------- algorithmic bytes / flops per launch
     alg = {
         # the bf16 router is one fused kernel (logits never leave the chip); fp32 writes and re-reads them
@@ -474,6 +511,7 @@ def main():
         "reshuffle_with_spill_rounds": rounds_report,
         "reshuffle_from_schedule_table": lookup_report,
         "request_schedule": request_report,
+        "coschedule": cosched_report,
         "load_imbalance_max_over_median": round(float(col.max() / max(np.median(col), 1)), 4),
         "offline_ms": {"route+coact_hist(profile batch of %d)" % Tp: round(t_hist * 1e3, 3),
                        "place(host)": round(t_place * 1e3, 3),

@@ -157,6 +157,52 @@ int32_t semmoe_place(const semmoe_config* cfg, const uint64_t* load, const uint6
                      int32_t* expert_of_phys);
 
 /*
+ * coschedule - the model-data co-scheduling solver, Alg. 1 whole (App. B): the alternation of `expert_place` with its
+ * request term and `req_sched`, for the co-clustering objective of Sec. 3.3.  HOST function, synchronous.
+ * A unit is a request of the profiling set (or a token key standing for all its occurrences): unit_act[u,e] is its
+ * activation mass on expert e (e.g. `semmoe_token_expert_hist` keyed by request number), unit_len[u] its tokens.
+ *   expert_place(unit_rank): as `semmoe_place`, with score = alpha_e*EAfE[e,c] + beta_e*EAfR[e,c] - gamma_e*loads_cls[c],
+ *     EAfR[e,c] = sum of unit_act[u,e] over the units scheduled to c; a fine-tuning swap is taken when
+ *     alpha_e*(gain of intra-cluster co-activation mass) + beta_e*(gain of local activation mass) > 0.
+ *   req_sched(placement): units longest first (equal -> lower index); unit u goes to the not-yet-full cluster c
+ *     maximising alpha_r*RAfR[u,c] + beta_r*RAfE[u,c], RAfR = sum over units u' already on c of
+ *     sum_e unit_act[u,e]*unit_act[u',e], RAfE = sum of unit_act[u,e] over c's experts (equal -> the cluster with fewer
+ *     tokens so far, then smaller c); a cluster is full at ceil(U/D) units.
+ *   Start: expert_place with no unit scheduled, then req_sched.  Then n_steps times expert_place, req_sched and
+ *     score = w_load*(most tokens on a cluster) + w_comm*(activation mass whose expert is on another cluster than its
+ *     unit); the pair of the lowest score is returned (equal -> the earlier step).
+ * Exact integer arithmetic; total mass and total length must stay below 2^40 and every weight within +-2^20
+ * (SEMMOE_EUNSUPPORTED otherwise).
+ * host in : load[E], coact[E*E], unit_act[U*E], unit_len[U] u64; params.  host out: expert_to_rank[E],
+ *           phys_of_expert[E], expert_of_phys[E], unit_rank[U] i32; step_score[n_steps] i64 and best_step (both may
+ *           be NULL).
+ */
+typedef struct semmoe_cosched_params {
+  int64_t alpha_e, beta_e, gamma_e; /* weights of expert_place */
+  int64_t alpha_r, beta_r;          /* weights of req_sched */
+  int64_t w_load, w_comm;           /* weights of the score, >= 0 */
+  int32_t ft_passes;                /* fine-tuning sweeps per expert_place, >= 0 */
+  int32_t n_steps;                  /* alternations, >= 1 */
+} semmoe_cosched_params;
+
+int32_t semmoe_coschedule(const semmoe_config* cfg, const uint64_t* load, const uint64_t* coact,
+                          const uint64_t* unit_act, const uint64_t* unit_len, int32_t U,
+                          const semmoe_cosched_params* params, int32_t* expert_to_rank, int32_t* phys_of_expert,
+                          int32_t* expert_of_phys, int32_t* unit_rank, int64_t* step_score, int32_t* best_step);
+
+/*
+ * token_labels - the last lines of Alg. 1: per token key, the number of its occurrences in requests scheduled to each
+ * cluster; label dev[v] = the cluster of the highest count (equal -> smallest), conf_q16[v] = floor(65536 * share of
+ * that count), level[v] = share * k rounded half up (same forms as `semmoe_lookup_tables`, and usable in its place);
+ * a key that never occurs gets dev = -1, conf_q16 = level = 0.  Keys outside [0,V) are skipped.  HOST function.
+ * host in : req_offsets[n_req+1] (starts at 0, non-decreasing), token_key[req_offsets[n_req]], req_rank[n_req] in
+ *           [0,D).  host out: dev[V], conf_q16[V], level[V] i32.
+ */
+int32_t semmoe_token_labels(const semmoe_config* cfg, const int32_t* req_offsets, int32_t n_req,
+                            const int32_t* token_key, const int32_t* req_rank, int32_t V, int32_t* dev,
+                            int32_t* conf_q16, int32_t* level);
+
+/*
  * token_expert_hist - the token-to-expert activation table of Sec. 3.2, built while profiling:
  * table[v,e] += #{(i,j): token_key[i] = v and ids[i,j] = e}.  ACCUMULATES over batches: the caller zeroes the table
  * before the first one.  Pairs whose key lies outside [0,V) or whose expert lies outside [0,E) are skipped.

@@ -34,6 +34,13 @@ class _CConfig(C.Structure):
                 ("cap", C.c_int32), ("num_classes", C.c_int32)]
 
 
+class CoschedParams(C.Structure):
+    """semmoe_cosched_params of the C header, field for field"""
+    _fields_ = [("alpha_e", C.c_int64), ("beta_e", C.c_int64), ("gamma_e", C.c_int64), ("alpha_r", C.c_int64),
+                ("beta_r", C.c_int64), ("w_load", C.c_int64), ("w_comm", C.c_int64), ("ft_passes", C.c_int32),
+                ("n_steps", C.c_int32)]
+
+
 @dataclass
 class Config:
     T: int
@@ -81,6 +88,8 @@ _SIGS = {
     "semmoe_token_expert_hist": ([_P, _P, _P, _P, C.c_int32, C.c_int32, _P], C.c_int32),
     "semmoe_lookup_tables": ([_P, _P, _P, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_place": ([_P, _P, _P, C.c_int64, C.c_int64, C.c_int32, _P, _P, _P], C.c_int32),
+    "semmoe_coschedule": ([_P, _P, _P, _P, _P, C.c_int32, _P, _P, _P, _P, _P, _P, _P], C.c_int32),
+    "semmoe_token_labels": ([_P, _P, C.c_int32, _P, _P, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_lookup": ([_P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
@@ -211,6 +220,48 @@ class SemMoE:
             C.byref(c), _ptr(load_u64), _ptr(coact_u64), int(alpha), int(gamma), int(ft_passes), _ptr(e2r),
             _ptr(phys), _ptr(inv)))
         return e2r, phys, inv
+
+    def coschedule(self, load_u64, coact_u64, unit_act_u64, unit_len_u64, alpha_e=1, beta_e=1, gamma_e=0, alpha_r=0,
+                   beta_r=1, ft_passes=8, n_steps=4, w_load=1, w_comm=1):
+        """host call: numpy uint64 in; (expert_to_rank, phys_of_expert, expert_of_phys, unit_rank, step_score,
+        best_step) out"""
+        import numpy as np
+        load_u64 = np.ascontiguousarray(load_u64, dtype=np.uint64)
+        coact_u64 = np.ascontiguousarray(coact_u64, dtype=np.uint64)
+        unit_act_u64 = np.ascontiguousarray(unit_act_u64, dtype=np.uint64)
+        unit_len_u64 = np.ascontiguousarray(unit_len_u64, dtype=np.uint64)
+        E = self.cfg.E
+        U = unit_len_u64.shape[0]
+        if unit_act_u64.shape != (U, E) or load_u64.shape != (E,) or coact_u64.shape != (E, E):
+            raise SemMoEError("coschedule: shapes must be load[E], coact[E,E], unit_act[U,E], unit_len[U]", -2)
+        e2r, phys, inv = (np.zeros(E, dtype=np.int32) for _ in range(3))
+        unit_rank = np.zeros(max(U, 1), dtype=np.int32)
+        step_score = np.zeros(max(int(n_steps), 1), dtype=np.int64)
+        best = C.c_int32(-1)
+        prm = CoschedParams(int(alpha_e), int(beta_e), int(gamma_e), int(alpha_r), int(beta_r), int(w_load),
+                            int(w_comm), int(ft_passes), int(n_steps))
+        c = self._cfg()
+        self._check("semmoe_coschedule", self.lib.semmoe_coschedule(
+            C.byref(c), _ptr(load_u64), _ptr(coact_u64), _ptr(unit_act_u64), _ptr(unit_len_u64), int(U),
+            C.cast(C.byref(prm), C.c_void_p), _ptr(e2r), _ptr(phys), _ptr(inv), _ptr(unit_rank), _ptr(step_score),
+            C.cast(C.byref(best), C.c_void_p)))
+        return e2r, phys, inv, unit_rank[:U], step_score, int(best.value)
+
+    def token_labels(self, req_offsets, token_key, req_rank, V):
+        """host call: numpy int32 in, three numpy int32 [V] arrays out"""
+        import numpy as np
+        req_offsets = np.ascontiguousarray(req_offsets, dtype=np.int32)
+        token_key = np.ascontiguousarray(token_key, dtype=np.int32)
+        req_rank = np.ascontiguousarray(req_rank, dtype=np.int32)
+        n_req = req_offsets.shape[0] - 1
+        if n_req < 0 or req_rank.shape[0] != n_req or token_key.shape[0] < int(req_offsets[-1]):
+            raise SemMoEError("token_labels: req_offsets[n_req+1], req_rank[n_req], token_key[req_offsets[-1]]", -2)
+        dev, conf, level = (np.zeros(max(int(V), 1), dtype=np.int32) for _ in range(3))
+        c = self._cfg()
+        self._check("semmoe_token_labels", self.lib.semmoe_token_labels(
+            C.byref(c), _ptr(req_offsets), int(n_req), _ptr(token_key), _ptr(req_rank), int(V), _ptr(dev), _ptr(conf),
+            _ptr(level)))
+        return dev, conf, level
 
     def reshuffle(self, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count, cap=None):
         c = self._cfg(**({"cap": cap} if cap is not None else {}))

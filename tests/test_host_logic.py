@@ -206,3 +206,99 @@ def test_host_place_rejects_bad_arguments():
     with pytest.raises(S.SemMoEError) as ei:
         m.place(np.ones(15), np.eye(15))
     assert ei.value.status == -2
+
+
+# ------------------------------------------------------------------ host co-scheduling solver == oracle
+def _units(T, E, D, k, U, seed, noise):
+    """units = runs of tokens (requests) of one topic over clustered routing; returns load, coact, unit_act, unit_len"""
+    r = np.random.default_rng(seed)
+    ids = _clustered_ids(T, E, D, k, seed, noise)
+    cuts = np.sort(r.choice(np.arange(1, T), size=U - 1, replace=False))
+    off = np.concatenate([[0], cuts, [T]])
+    unit_of = np.repeat(np.arange(U), np.diff(off))
+    load, co = O.coact_hist(ids, E)
+    return load, co, O.token_expert_table(unit_of, ids, U, E), np.diff(off), off
+
+
+@pytest.mark.parametrize("E,D,k,U,noise,prm", [
+    (16, 4, 2, 10, 0.3, dict(alpha_e=1, beta_e=1, gamma_e=0, alpha_r=0, beta_r=1, ft_passes=4, n_steps=3, w_load=1, w_comm=1)),
+    (32, 8, 4, 37, 0.5, dict(alpha_e=2, beta_e=3, gamma_e=1, alpha_r=1, beta_r=50, ft_passes=2, n_steps=4, w_load=2, w_comm=1)),
+    (24, 3, 3, 7, 0.7, dict(alpha_e=1, beta_e=0, gamma_e=0, alpha_r=1, beta_r=0, ft_passes=0, n_steps=1, w_load=0, w_comm=1)),
+    (16, 1, 2, 5, 0.5, dict(alpha_e=1, beta_e=1, gamma_e=0, alpha_r=0, beta_r=1, ft_passes=8, n_steps=2, w_load=1, w_comm=1)),
+    (16, 16, 2, 3, 0.5, dict(alpha_e=1, beta_e=2, gamma_e=0, alpha_r=1, beta_r=1, ft_passes=8, n_steps=2, w_load=1, w_comm=0)),
+    (64, 8, 8, 24, 0.4, dict(alpha_e=0, beta_e=1, gamma_e=0, alpha_r=0, beta_r=1, ft_passes=1, n_steps=2, w_load=1, w_comm=4)),
+])
+def test_host_coschedule_equals_oracle(E, D, k, U, noise, prm):
+    load, co, act, ln, _ = _units(500, E, D, k, U, seed=E + 3 * D + U, noise=noise)
+    want_e2r, want_ur, want_scores, want_best = O.coschedule(load, co, act, ln, D, **prm)
+    m = S.SemMoE(S.Config(T=1, d=8, E=E, k=k, F=8, D=D, cap=1), allocate_workspace=False)
+    e2r, phys, inv, ur, scores, best = m.coschedule(load, co, act, ln, **prm)
+    assert e2r.tolist() == want_e2r.tolist()
+    assert ur.tolist() == want_ur.tolist()
+    assert scores.tolist() == want_scores and best == want_best
+    want_phys, want_inv = O.placement_order(want_e2r, D)
+    assert phys.tolist() == want_phys.tolist() and inv.tolist() == want_inv.tolist()
+
+
+def test_host_coschedule_with_no_request_weight_and_one_step_places_like_place():
+    """beta_e = 0: the placement of every step is `place`'s, whatever the units are"""
+    load, co, act, ln, _ = _units(400, 32, 4, 4, 9, seed=5, noise=0.4)
+    m = S.SemMoE(S.Config(T=1, d=8, E=32, k=4, F=8, D=4, cap=1), allocate_workspace=False)
+    e2r, phys, inv, _, _, _ = m.coschedule(load, co, act, ln, alpha_e=1, beta_e=0, gamma_e=0, n_steps=2)
+    want = m.place(load, co, 1, 0, 8)
+    assert e2r.tolist() == want[0].tolist() and phys.tolist() == want[1].tolist() and inv.tolist() == want[2].tolist()
+
+
+def test_host_coschedule_rejects_bad_arguments():
+    m = S.SemMoE(S.Config(T=1, d=8, E=8, k=2, F=8, D=4, cap=1), allocate_workspace=False)
+    load, co = np.ones(8), np.ones((8, 8))
+    act, ln = np.ones((3, 8)), np.ones(3)
+    for bad, status in [(dict(n_steps=0), -1), (dict(ft_passes=-1), -1), (dict(w_load=-1), -1),
+                        (dict(beta_e=1 << 21), -5)]:
+        with pytest.raises(S.SemMoEError) as ei:
+            m.coschedule(load, co, act, ln, **bad)
+        assert ei.value.status == status, bad
+    with pytest.raises(S.SemMoEError) as ei:
+        m.coschedule(load, co, np.full((3, 8), 1 << 38, dtype=np.uint64), ln)          # total mass >= 2^40
+    assert ei.value.status == -5
+    m15 = S.SemMoE(S.Config(T=1, d=8, E=15, k=2, F=8, D=4, cap=1), allocate_workspace=False)
+    with pytest.raises(S.SemMoEError) as ei:
+        m15.coschedule(np.ones(15), np.ones((15, 15)), np.ones((3, 15)), ln)
+    assert ei.value.status == -2
+
+
+@pytest.mark.parametrize("V,D,k,n_req,seed", [(30, 4, 2, 9, 0), (200, 8, 8, 40, 1), (5, 1, 3, 2, 2), (64, 32, 4, 100, 3)])
+def test_host_token_labels_equal_oracle(V, D, k, n_req, seed):
+    r = np.random.default_rng(seed)
+    lens = r.integers(0, 30, size=n_req)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    keys = r.integers(-1, V + 1, size=int(off[-1])).astype(np.int32)          # some keys outside the table
+    keys[keys == V - 1] = 0                                                   # the last id never occurs
+    rr = r.integers(0, D, size=n_req).astype(np.int32)
+    want = O.token_labels(off, keys, rr, V, D, k)
+    m = S.SemMoE(S.Config(T=1, d=8, E=max(D, k), k=k, F=8, D=D, cap=1), allocate_workspace=False)
+    got = m.token_labels(off, keys, rr, V)
+    for g, w_, name in zip(got, want, ("dev", "conf_q16", "level")):
+        assert g.dtype == np.int32 and g.tolist() == w_.tolist(), name
+    assert got[0][V - 1] == -1
+
+
+def test_host_token_labels_reject_bad_arguments():
+    m = S.SemMoE(S.Config(T=1, d=8, E=8, k=2, F=8, D=4, cap=1), allocate_workspace=False)
+    with pytest.raises(S.SemMoEError) as ei:
+        m.token_labels(np.array([0, 2, 1]), np.zeros(2), np.array([0, 0]), 4)      # offsets decrease
+    assert ei.value.status == -1
+    with pytest.raises(S.SemMoEError) as ei:
+        m.token_labels(np.array([0, 1, 2]), np.zeros(2), np.array([0, 4]), 4)      # rank out of range
+    assert ei.value.status == -1
+
+
+def test_host_coschedule_equals_oracle_at_config2_shape():
+    """128 experts on 8 clusters, 34 requests cut from 8192 tokens of clustered top-8 routing"""
+    load, co, act, ln, _ = _units(8192, 128, 8, 8, 34, seed=11, noise=0.5)
+    prm = dict(alpha_e=1, beta_e=1, gamma_e=0, alpha_r=0, beta_r=1, ft_passes=1, n_steps=2, w_load=1, w_comm=1)
+    want_e2r, want_ur, want_scores, want_best = O.coschedule(load, co, act, ln, 8, **prm)
+    m = S.SemMoE(S.Config(T=1, d=8, E=128, k=8, F=8, D=8, cap=1), allocate_workspace=False)
+    e2r, _, _, ur, scores, best = m.coschedule(load, co, act, ln, **prm)
+    assert e2r.tolist() == want_e2r.tolist() and ur.tolist() == want_ur.tolist()
+    assert scores.tolist() == want_scores and best == want_best
