@@ -24,6 +24,9 @@ Which passage each function follows
   token_expert_table / lookup_tables / reshuffle_lookup
                                token-to-expert activation table and confidence (Sec. 3.2), the
                                schedule table T / T_p, and Alg. 3 `rebatch_tokens` driven by it
+  device_sequence / reshuffle_cond
+                               the inter-layer device-sequence table A / A_p (App. B) and Alg. 3's
+                               cond(T_p > A_p, T, A) with both tables
   request_schedule / request_assignment
                                Alg. 2 `get_dp_rank` + `schedule` (Attention-DP scenario), with
                                S_r = argmax_j sum_{i in r} R_ij of Sec. 3.3
@@ -50,7 +53,9 @@ the mask cannot bite, every round reaches every rank, brute force over the unmas
 set; co-scheduling solver - without the request term it is `place`, hand examples of every
 term and of the swap gain, planted topics recovered, remote mass = remote pair count when
 every token is a unit, never below the brute-force optimum, labels = `lookup_tables` of the
-count table.  Parity unpinned (the paper gives nothing to check against): the
+count table; device sequences and cond(T_p > A_p, T, A) - hand examples, the device is the first
+arg-max of the gain matrix, one table missing = the rebatch from the other, per token the table
+of higher confidence.  Parity unpinned (the paper gives nothing to check against): the
 values of alpha, gamma, ft_steps; the behaviour of `align`; Fig. 3's example.
 """
 from __future__ import annotations
@@ -504,6 +509,80 @@ def reshuffle_lookup(keys, dev, conf_q16, level, thr_q16: int, D: int, cap: int)
     inv_shf[shf] = np.arange(T)
     return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
             np.bincount(token_rank, minlength=D).astype(np.int32))
+
+
+def device_sequence(ids, expert_to_rank, D: int, seq_in=None) -> np.ndarray:
+    """The device a token selects at a layer, appended to the sequence of the layers before (App. B, inter-layer
+    activation conjugacy: the rows of the sequence table are the devices selected at the previous l layers).  With
+    k experts per token the device selected is read as the one holding most of the token's k experts (equal ->
+    the smallest).  seq_out[i] = seq_in[i]*D + device(i): chaining the call over l layers numbers the D^l rows,
+    oldest layer most significant.  A token whose history is unknown (seq_in[i] < 0) stays unknown (-1).
+    The sequence table itself is `token_expert_table` keyed by these numbers, and A / A_p are its `lookup_tables`."""
+    ids = np.asarray(ids)
+    e2r = np.asarray(expert_to_rank)
+    T = ids.shape[0]
+    out = np.zeros(T, dtype=np.int32)
+    for i in range(T):
+        cnt = [0] * D
+        for e in ids[i]:
+            cnt[int(e2r[int(e)])] += 1
+        dev = max(range(D), key=lambda r: (cnt[r], -r))
+        prev = 0 if seq_in is None else int(seq_in[i])
+        out[i] = -1 if prev < 0 else prev * D + dev
+    return out
+
+
+def _rebatch_from_preferences(pref, conf, D: int, cap: int):
+    """steps 2-4 of `reshuffle` for given preferences: keep by (conf desc, i asc) up to cap, spill the rest into the
+    free slots in rank order, shuffle = stable argsort of the final ranks"""
+    T = len(pref)
+    token_rank = np.full(T, -1, dtype=np.int64)
+    kept = [0] * D
+    for r in range(D):
+        cand = sorted((i for i in range(T) if pref[i] == r), key=lambda i: (-conf[i], i))
+        for i in cand[:cap]:
+            token_rank[i] = r
+        kept[r] = min(len(cand), cap)
+    free_slots = [r for r in range(D) for _ in range(cap - kept[r])]
+    for s_, i in enumerate([i for i in range(T) if token_rank[i] < 0]):
+        token_rank[i] = free_slots[s_]
+    shf = np.argsort(token_rank, kind="stable")
+    inv_shf = np.zeros(T, dtype=np.int64)
+    inv_shf[shf] = np.arange(T)
+    return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
+            np.bincount(token_rank, minlength=D).astype(np.int32))
+
+
+def reshuffle_cond(keys, dev, conf_q16, level, seq_keys, dev_a, conf_a_q16, level_a, thr_q16: int, D: int, cap: int):
+    """`rebatch_tokens` of Alg. 3 with both of its tables: dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).  T is
+    indexed by the token's key, the inter-layer table A by the token's device sequence (`device_sequence`); an
+    entry that does not exist (index outside the table, or never profiled: dev < 0) has confidence -1, so the
+    other table wins and, when neither exists, the token stays home.  The chosen entry is followed when its
+    confidence exceeds thr_q16 (-1: always): pref = its device, conf = its level; otherwise pref = home, conf = 0.
+    Then keep / spill / shuffle as in `reshuffle`.  Returns (token_rank, shf, inv_shf, rank_count) int32."""
+    keys = np.asarray(keys)
+    seq_keys = np.asarray(seq_keys)
+    T = keys.shape[0]
+    assert cap * D >= T
+    home = home_rank(T, D)
+    pref = [0] * T
+    conf = [0] * T
+
+    def entry(v, dv, cf, lv):
+        v = int(v)
+        if 0 <= v < len(dv) and 0 <= int(dv[v]) < D:
+            return int(cf[v]), int(dv[v]), int(lv[v])
+        return -1, -1, 0
+
+    for i in range(T):
+        ct, dt, lt = entry(keys[i], dev, conf_q16, level)
+        ca, da, la = entry(seq_keys[i], dev_a, conf_a_q16, level_a)
+        c, d_, l_ = (ct, dt, lt) if ct > ca else (ca, da, la)
+        if c >= 0 and c > thr_q16:
+            pref[i], conf[i] = d_, l_
+        else:
+            pref[i], conf[i] = int(home[i]), 0
+    return _rebatch_from_preferences(pref, conf, D, cap)
 
 
 def request_schedule(req_offsets, keys, dev, D: int) -> np.ndarray:
