@@ -393,6 +393,68 @@ def main():
             "ms": round(e0.elapsed_time(e1) / 20, 4), "remote_pair_fraction": round(int(rpr.item()) / P, 4),
             "tokens_moved_off_home": int((tr2 != home).sum().item())}
 
+    # ---------------- next row: Alg. 3 with both tables: the inter-layer device-sequence table A next to T.  The two
+    # MoE layers before this one route the same tokens by their own router weights and class clusters; their
+    # placements come from their own profile routing.  30 % of the tokens carry a key that all classes share.
+    seq_p, seq_m = None, None
+    t_seq = 0.0
+    for layer in (2, 1):
+        W_l, cb_l = up(WL.router_weight(w, layer), True), up(WL.class_bias(w, layer))
+        id_l = torch.empty(Tp, k, **i32)
+        mp.route(Xp, W_l, id_l, twp, token_class=tcp, class_bias=cb_l)
+        ld_l, co_l = torch.zeros(E, **i32), torch.zeros(E, E, **i32)
+        mp.coact_hist(id_l, Tp, ld_l, co_l)
+        e2r_l = up(m.place(ld_l.cpu().numpy().astype(np.uint64), co_l.cpu().numpy().astype(np.uint64))[0])
+        nxt = torch.empty(Tp, **i32)
+        mp.device_sequence(id_l, e2r_l, Tp, seq_p, nxt)
+        seq_p = nxt
+        id_m = torch.empty(T, k, **i32)
+        m.route(X, W_l, id_m, torch.empty_like(tw), token_class=tc, class_bias=cb_l)
+        nxt = torch.empty(T, **i32)
+        for _ in range(3):
+            m.device_sequence(id_m, e2r_l, T, seq_m, nxt)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            m.device_sequence(id_m, e2r_l, T, seq_m, nxt)
+        e1.record()
+        torch.cuda.synchronize()
+        t_seq = e0.elapsed_time(e1) / 20
+        seq_m = nxt
+    VA, VS = D * D, WL.vocab_size(w, shared=True)
+    keys_sp, keys_sm = up(WL.token_key(w, profile=True, shared_frac=0.3)), up(WL.token_key(w, shared_frac=0.3))
+    tab_t, tab_a = torch.zeros(VS, E, **i32), torch.zeros(VA, E, **i32)
+    mp.token_expert_hist(keys_sp, idp, Tp, VS, tab_t)
+    mp.token_expert_hist(seq_p, idp, Tp, VA, tab_a)
+    torch.cuda.synchronize()
+    tt = [up(t) for t in m.lookup_tables(tab_t.cpu().numpy().view(np.uint32), e2r_h)]
+    ta = [up(t) for t in m.lookup_tables(tab_a.cpu().numpy().view(np.uint32), e2r_h)]
+    none = [torch.full((1,), -1, **i32), torch.zeros(1, **i32), torch.zeros(1, **i32)]
+    seq_report = {"look_back_layers": 2, "sequence_rows": VA, "rows_seen_in_profile": int((ta[0] >= 0).sum().item()),
+                  "shared_key_share": 0.3, "device_sequence_ms": round(t_seq, 4)}
+    for label, a_t, a_a in (("T_only", tt, none), ("A_only", none, ta), ("cond(T_p>A_p,T,A)", tt, ta)):
+        tr2, shf2, ish2 = (torch.empty(T, **i32) for _ in range(3))
+        rc2 = torch.empty(D, **i32)
+        call = lambda: m.reshuffle_cond(keys_sm, a_t[0].shape[0], a_t[0], a_t[1], a_t[2], seq_m, a_a[0].shape[0],
+                                        a_a[0], a_a[1], a_a[2], 0, tr2, shf2, ish2, rc2)
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        rpr = torch.empty(1, dtype=torch.int64, device=dev)
+        m.dispatch_index(ids, tr2, shf2, phys, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                         torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rpr)
+        torch.cuda.synchronize()
+        seq_report[label] = {"ms": round(e0.elapsed_time(e1) / 20, 4),
+                             "remote_pair_fraction": round(int(rpr.item()) / P, 4),
+                             "tokens_moved_off_home": int((tr2 != home).sum().item())}
+
     # ---------------- next row: request-level scheduling (Attention-DP): requests = runs of tokens of one topic
     req_off_h, req_cls_h, req_key_h = WL.requests(w)
     n_req = len(req_off_h) - 1
@@ -510,6 +572,7 @@ def main():
                                  "semmoe_placement_reshuffle": round(remote / P, 4)},
         "reshuffle_with_spill_rounds": rounds_report,
         "reshuffle_from_schedule_table": lookup_report,
+        "reshuffle_with_sequence_table": seq_report,
         "request_schedule": request_report,
         "coschedule": cosched_report,
         "load_imbalance_max_over_median": round(float(col.max() / max(np.median(col), 1)), 4),

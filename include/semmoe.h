@@ -254,8 +254,9 @@ int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const in
 
 /*
  * reshuffle from the schedule table - Alg. 3 `rebatch_tokens` as it runs before the gate: the device id of a token is
- * looked up by its key, dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).  The inter-layer table A is not built here: its
- * device is the token's home shard and its confidence A_p the constant thr_q16 (in 1/65536).  So
+ * looked up by its key, dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).  This form has no inter-layer table A: its
+ * device is the token's home shard and its confidence A_p the constant thr_q16 (in 1/65536);
+ * `semmoe_reshuffle_cond` is the form with both tables.  So
  *   pref(i) = dev[key_i], conf(i) = level[key_i]  if key_i in [0,V), dev[key_i] in [0,D) and conf_q16[key_i] > thr_q16,
  *   pref(i) = home(i),    conf(i) = 0             otherwise;
  * keep, spill and shuffle then exactly as in `semmoe_reshuffle`.  Two launches.
@@ -265,6 +266,37 @@ int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* stream, const in
                                 const int32_t* dev, const int32_t* conf_q16, const int32_t* level, int32_t thr_q16,
                                 int32_t* token_rank, int32_t* shf, int32_t* inv_shf, int32_t* rank_count, void* ws,
                                 size_t ws_bytes);
+
+/*
+ * device_sequence - the row index of the inter-layer table of App. B ("modeling inter-layer activation conjugacy":
+ * the rows are the sequences of devices selected at the previous l layers).  The device a token selects at a layer is
+ * read as the rank holding most of its k experts (equal -> the smallest rank); seq_out[i] = seq_in[i] * D + device(i),
+ * or just device(i) when seq_in is NULL, so chaining the call over l layers numbers the D^l rows with the oldest layer
+ * most significant.  seq_in[i] < 0 (history unknown) gives -1.  The caller keeps D^l below 2^31.  Pairs whose expert or
+ * rank is out of range are not counted.  The table itself is `semmoe_token_expert_hist` keyed by these numbers
+ * (V = D^l) and A / A_p are its `semmoe_lookup_tables`.  One launch; cfg->T is ignored.
+ * dev in : topk_ids[T_batch,k], expert_to_rank[E], seq_in[T_batch] or NULL.  dev out: seq_out[T_batch] (may alias
+ *          seq_in).
+ */
+int32_t semmoe_device_sequence(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                               const int32_t* expert_to_rank, int32_t T_batch, const int32_t* seq_in, int32_t* seq_out);
+
+/*
+ * reshuffle with both schedule tables - Alg. 3 `rebatch_tokens` as printed: dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).
+ * T / T_p / level are indexed by token_key (as in `semmoe_reshuffle_lookup`), A / A_p / level_a by seq_key (the
+ * device sequence of `semmoe_device_sequence`).  An entry that does not exist - index outside its table, device outside
+ * [0,D), negative confidence - counts as confidence -1: the other table wins, and with neither the token stays home.
+ * Per token the entry of the strictly higher confidence is T's, otherwise A's; it is followed when its confidence
+ * exceeds thr_q16 (-1: always): pref = its device, conf = its level; else pref = home, conf = 0.  Keep, spill and
+ * shuffle then exactly as in `semmoe_reshuffle`.  Two launches.
+ * dev in : token_key[T], dev[V], conf_q16[V], level[V], seq_key[T], dev_a[VA], conf_a_q16[VA], level_a[VA] i32.
+ * dev out: token_rank[T], shf[T], inv_shf[T], rank_count[D].
+ */
+int32_t semmoe_reshuffle_cond(const semmoe_config* cfg, void* stream, const int32_t* token_key, int32_t V,
+                              const int32_t* dev, const int32_t* conf_q16, const int32_t* level,
+                              const int32_t* seq_key, int32_t VA, const int32_t* dev_a, const int32_t* conf_a_q16,
+                              const int32_t* level_a, int32_t thr_q16, int32_t* token_rank, int32_t* shf,
+                              int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes);
 
 /*
  * request_schedule - online request scheduling of the Attention-DP scenario: Alg. 2 `get_dp_rank` and `schedule`,

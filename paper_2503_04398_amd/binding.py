@@ -93,6 +93,9 @@ _SIGS = {
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_lookup": ([_P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
+    "semmoe_reshuffle_cond": ([_P, _P, _P, C.c_int32, _P, _P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5
+                              + [C.c_size_t], C.c_int32),
+    "semmoe_device_sequence": ([_P, _P, _P, _P, C.c_int32, _P, _P], C.c_int32),
     "semmoe_request_schedule": ([_P, _P, _P, C.c_int32, _P, C.c_int32] + [_P] * 7 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch": ([_P] * 15 + [C.c_size_t], C.c_int32),
     "semmoe_dispatch_index": ([_P] * 13 + [C.c_size_t], C.c_int32),
@@ -281,6 +284,19 @@ class SemMoE:
         self._check("semmoe_reshuffle_lookup", self.lib.semmoe_reshuffle_lookup(
             C.byref(c), _stream(), _ptr(token_key), int(V), _ptr(dev), _ptr(conf_q16), _ptr(level), int(thr_q16),
             _ptr(token_rank), _ptr(shf), _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def reshuffle_cond(self, token_key, V, dev, conf_q16, level, seq_key, VA, dev_a, conf_a_q16, level_a, thr_q16,
+                       token_rank, shf, inv_shf, rank_count, cap=None):
+        c = self._cfg(**({"cap": cap} if cap is not None else {}))
+        self._check("semmoe_reshuffle_cond", self.lib.semmoe_reshuffle_cond(
+            C.byref(c), _stream(), _ptr(token_key), int(V), _ptr(dev), _ptr(conf_q16), _ptr(level), _ptr(seq_key),
+            int(VA), _ptr(dev_a), _ptr(conf_a_q16), _ptr(level_a), int(thr_q16), _ptr(token_rank), _ptr(shf),
+            _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def device_sequence(self, topk_ids, expert_to_rank, T_batch, seq_in, seq_out):
+        c = self._cfg()
+        self._check("semmoe_device_sequence", self.lib.semmoe_device_sequence(
+            C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), int(T_batch), _ptr(seq_in), _ptr(seq_out)))
 
     def request_schedule(self, req_offsets, n_req, token_key, V, dev, req_rank, token_rank, shf, inv_shf, rank_count):
         c = self._cfg()

@@ -109,6 +109,97 @@ __global__ __launch_bounds__(kTokBlock) void rs_lookup_kernel(int T, int k, int 
   for (int x = threadIdx.x; x < nkeys; x += blockDim.x) w.cnt[size_t(blockIdx.x) * nkeys + x] = hist[x];
 }
 
+// K1 of Alg. 3 with both tables, dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]): T is indexed by the token's key, the
+// inter-layer table A by the token's device sequence.  An entry that does not exist (index outside the table, device
+// outside [0,D), negative confidence) has confidence -1, so the other table wins; the chosen entry is followed when it exists and its
+// confidence exceeds the threshold, otherwise the token stays home with priority 0.
+__global__ __launch_bounds__(kTokBlock) void rs_cond_kernel(int T, int k, int D, int V, int VA, int per_home,
+                                                            int thr_q16, const int32_t* __restrict__ keys,
+                                                            const int32_t* __restrict__ dev,
+                                                            const int32_t* __restrict__ conf_q16,
+                                                            const int32_t* __restrict__ level,
+                                                            const int32_t* __restrict__ seq_keys,
+                                                            const int32_t* __restrict__ dev_a,
+                                                            const int32_t* __restrict__ conf_a_q16,
+                                                            const int32_t* __restrict__ level_a, ReshuffleWs w) {
+  extern __shared__ int32_t hist[];  // D*(k+1)
+  const int nkeys = D * (k + 1);
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) hist[x] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  if (i < T) {
+    int ct = -1, dt = -1, lt = 0, ca = -1, da = -1, la = 0;
+    const int v = keys[i], q = seq_keys[i];
+    if ((unsigned)v < (unsigned)V) {
+      const int d = dev[v];
+      const int c = conf_q16[v];
+      if ((unsigned)d < (unsigned)D && c >= 0) {
+        dt = d;
+        ct = c;
+        lt = level[v];
+      }
+    }
+    if ((unsigned)q < (unsigned)VA) {
+      const int d = dev_a[q];
+      const int c = conf_a_q16[q];
+      if ((unsigned)d < (unsigned)D && c >= 0) {
+        da = d;
+        ca = c;
+        la = level_a[q];
+      }
+    }
+    const bool take_t = ct > ca;
+    const int c = take_t ? ct : ca, d = take_t ? dt : da, l = take_t ? lt : la;
+    int pref = i / per_home, conf = 0;
+    if (c >= 0 && c > thr_q16) {
+      pref = d;
+      conf = min(max(l, 0), k);
+    }
+    w.pc[i] = pref | (conf << 8);
+    atomicAdd(&hist[pref * (k + 1) + conf], 1);
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) w.cnt[size_t(blockIdx.x) * nkeys + x] = hist[x];
+}
+
+// The device a token selects at a layer - the one holding most of its k experts, equal -> the smallest - appended to
+// the sequence number of the layers before: seq_out = seq_in * D + device (seq_in < 0: unknown history stays -1).
+// Pairs whose expert or rank is out of range are not counted.
+__global__ __launch_bounds__(kTokBlock) void device_sequence_kernel(int T, int k, int D, int E,
+                                                                    const int32_t* __restrict__ ids,
+                                                                    const int32_t* __restrict__ e2r,
+                                                                    const int32_t* __restrict__ seq_in,
+                                                                    int32_t* __restrict__ seq_out) {
+  const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  if (i >= T) return;
+  int r[SEMMOE_MAX_K];
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+    r[j] = -1;
+    if (j < k) {
+      const int e = ids[size_t(i) * k + j];
+      if ((unsigned)e < (unsigned)E) {
+        const int rr = e2r[e];
+        if ((unsigned)rr < (unsigned)D) r[j] = rr;
+      }
+    }
+  }
+  int best_r = 0, best_c = 0;
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+    if (r[j] < 0) continue;
+    int c = 0;
+#pragma unroll
+    for (int j2 = 0; j2 < SEMMOE_MAX_K; ++j2) c += (r[j2] == r[j]);
+    if (c > best_c || (c == best_c && r[j] < best_r)) {
+      best_c = c;
+      best_r = r[j];
+    }
+  }
+  const int prev = seq_in ? seq_in[i] : 0;
+  seq_out[i] = prev < 0 ? -1 : prev * D + best_r;
+}
+
 // K2: thresholds per rank, free-slot prefix, borderline prefix over blocks (one workgroup)
 __global__ __launch_bounds__(kScanThreads) void rs_threshold_kernel(int NB, int k, int D, int cap, ReshuffleWs w) {
   __shared__ int32_t tot[SEMMOE_MAX_D * (SEMMOE_MAX_K + 1)];
@@ -985,6 +1076,69 @@ extern "C" int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* strea
   return SEMMOE_OK;
 }
 
+// keep / spill / shuffle from the (pref, conf) words and per-block tables a K1 kernel has written
+static int32_t finish_from_preferences(const semmoe_config* cfg, hipStream_t s, int NB, int32_t* token_rank,
+                                       int32_t* shf, int32_t* inv_shf, int32_t* rank_count, const ReshuffleWs& w) {
+  const int T = cfg->T, D = cfg->D, k = cfg->k;
+  if (NB <= kFusedMaxNB && D <= 64) {
+    hipLaunchKernelGGL(rs_fused_kernel, dim3(NB), dim3(kTokBlock), rs_fused_lds(D, k), s, T, NB, k, D, cfg->cap,
+                       token_rank, shf, inv_shf, rank_count, w);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, k, D, cfg->cap, w);
+  hipLaunchKernelGGL(rs_keep_kernel, dim3(NB), dim3(kTokBlock), (D * kWords + 1) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D + 1) * 4, s, T, D, token_rank, w);
+  hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, D, rank_count, w);
+  hipLaunchKernelGGL(rs_scatter_kernel, dim3(NB), dim3(kTokBlock), D * kWords * 4, s, T, D, token_rank, shf, inv_shf,
+                     w);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_reshuffle_cond(const semmoe_config* cfg, void* stream, const int32_t* token_key, int32_t V,
+                                         const int32_t* dev, const int32_t* conf_q16, const int32_t* level,
+                                         const int32_t* seq_key, int32_t VA, const int32_t* dev_a,
+                                         const int32_t* conf_a_q16, const int32_t* level_a, int32_t thr_q16,
+                                         int32_t* token_rank, int32_t* shf, int32_t* inv_shf, int32_t* rank_count,
+                                         void* ws, size_t ws_bytes) {
+  int32_t st = validate_config(cfg, true, false, false);
+  if (st != SEMMOE_OK) return st;
+  if (!token_key || !dev || !conf_q16 || !level || !seq_key || !dev_a || !conf_a_q16 || !level_a || !token_rank ||
+      !shf || !inv_shf || !rank_count)
+    return SEMMOE_EINVAL;
+  if (cfg->cap < 0 || V <= 0 || VA <= 0) return SEMMOE_EINVAL;
+  if ((long long)cfg->cap * cfg->D < cfg->T) return SEMMOE_ESHAPE;
+  if (cfg->k >= 128) return SEMMOE_EUNSUPPORTED;
+  ReshuffleWs w;
+  if (!carve_reshuffle(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int T = cfg->T, D = cfg->D, k = cfg->k;
+  const int NB = cdiv(T, kTokBlock);
+  if (T == 0) {
+    hipLaunchKernelGGL(rs_zero_kernel, dim3(1), dim3(64), 0, s, D, rank_count);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  hipLaunchKernelGGL(rs_cond_kernel, dim3(NB), dim3(kTokBlock), D * (k + 1) * 4, s, T, k, D, V, VA, cdiv(T, D), thr_q16,
+                     token_key, dev, conf_q16, level, seq_key, dev_a, conf_a_q16, level_a, w);
+  return finish_from_preferences(cfg, s, NB, token_rank, shf, inv_shf, rank_count, w);
+}
+
+extern "C" int32_t semmoe_device_sequence(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                          const int32_t* expert_to_rank, int32_t T_batch, const int32_t* seq_in,
+                                          int32_t* seq_out) {
+  if (!cfg || !topk_ids || !expert_to_rank || !seq_out) return SEMMOE_EINVAL;
+  if (cfg->E <= 0 || cfg->D <= 0 || cfg->k <= 0 || T_batch < 0) return SEMMOE_EINVAL;
+  if (cfg->k > SEMMOE_MAX_K || cfg->k > cfg->E) return SEMMOE_ESHAPE;
+  if (T_batch == 0) return SEMMOE_OK;
+  hipLaunchKernelGGL(device_sequence_kernel, dim3(cdiv(T_batch, kTokBlock)), dim3(kTokBlock), 0,
+                     static_cast<hipStream_t>(stream), T_batch, cfg->k, cfg->D, cfg->E, topk_ids, expert_to_rank, seq_in,
+                     seq_out);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
 extern "C" int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* stream, const int32_t* token_key, int32_t V,
                                            const int32_t* dev, const int32_t* conf_q16, const int32_t* level,
                                            int32_t thr_q16, int32_t* token_rank, int32_t* shf, int32_t* inv_shf,
@@ -1009,18 +1163,5 @@ extern "C" int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* strea
   const int nkeys = D * (k + 1);
   hipLaunchKernelGGL(rs_lookup_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, V, per_home, thr_q16,
                      token_key, dev, conf_q16, level, w);
-  if (NB <= kFusedMaxNB && D <= 64) {
-    hipLaunchKernelGGL(rs_fused_kernel, dim3(NB), dim3(kTokBlock), rs_fused_lds(D, k), s, T, NB, k, D, cfg->cap,
-                       token_rank, shf, inv_shf, rank_count, w);
-    SEMMOE_LAUNCH_CHECK();
-    return SEMMOE_OK;
-  }
-  hipLaunchKernelGGL(rs_threshold_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, k, D, cfg->cap, w);
-  hipLaunchKernelGGL(rs_keep_kernel, dim3(NB), dim3(kTokBlock), (D * kWords + 1) * 4, s, T, D, token_rank, w);
-  hipLaunchKernelGGL(rs_assign_kernel, dim3(NB), dim3(kTokBlock), (kWords + D + 1) * 4, s, T, D, token_rank, w);
-  hipLaunchKernelGGL(rs_rank_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, D, rank_count, w);
-  hipLaunchKernelGGL(rs_scatter_kernel, dim3(NB), dim3(kTokBlock), D * kWords * 4, s, T, D, token_rank, shf, inv_shf,
-                     w);
-  SEMMOE_LAUNCH_CHECK();
-  return SEMMOE_OK;
+  return finish_from_preferences(cfg, s, NB, token_rank, shf, inv_shf, rank_count, w);
 }

@@ -140,6 +140,25 @@ class Layer:
         torch.cuda.synchronize()
         return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
 
+    def reshuffle_cond(self, keys, tabs_t, seq_keys, tabs_a, thr_q16, cap=None):
+        keys_d = to_dev(np.asarray(keys, dtype=np.int32))
+        seq_d = to_dev(np.asarray(seq_keys, dtype=np.int32))
+        tt = [to_dev(np.asarray(t, dtype=np.int32)) for t in tabs_t]
+        ta = [to_dev(np.asarray(t, dtype=np.int32)) for t in tabs_a]
+        self.m.reshuffle_cond(keys_d, tt[0].shape[0], tt[0], tt[1], tt[2], seq_d, ta[0].shape[0], ta[0], ta[1], ta[2],
+                              thr_q16, self.token_rank, self.shf, self.inv_shf, self.rank_count, cap=cap)
+        torch.cuda.synchronize()
+        return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
+
+    def device_sequence(self, ids, e2r, seq_in=None):
+        ids_d = to_dev(np.asarray(ids, dtype=np.int32))
+        n = ids_d.shape[0]
+        out = torch.full((max(n, 1),), -9, dtype=torch.int32, device=DEV)
+        seq_d = None if seq_in is None else to_dev(np.asarray(seq_in, dtype=np.int32))
+        self.m.device_sequence(ids_d, to_dev(np.asarray(e2r, dtype=np.int32)), n, seq_d, out)
+        torch.cuda.synchronize()
+        return to_np(out)[:n]
+
     def request_schedule(self, req_offsets, keys, dev):
         off_d = to_dev(np.asarray(req_offsets, dtype=np.int32))
         keys_d = to_dev(np.asarray(keys, dtype=np.int32))

@@ -59,8 +59,20 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
     sched = play.m.lookup_tables(table.astype(np.uint32), e2r)
     for g, x, nm in zip(sched, O.lookup_tables(table, e2r, w.D, w.k), ("dev", "conf_q16", "level")):
         assert (g == x).all(), nm
+    # the inter-layer table: device sequences of two stand-in earlier layers (this layer's experts shifted by the
+    # layer number, so the history is informative), activation table keyed by them, A / A_p from it
+    VA = w.D * w.D
+    pseq = None
+    for layer in (2, 1):
+        pseq = play.device_sequence((pids + layer) % w.E, e2r, pseq)
+    table_a = H.to_np(play.token_expert_hist(pseq, pids, VA)).astype(np.int64)
+    assert (table_a == O.token_expert_table(pseq, pids, VA, w.E)).all()
+    sched_a = play.m.lookup_tables(table_a.astype(np.uint32), e2r)
+    for g, x, nm in zip(sched_a, O.lookup_tables(table_a, e2r, w.D, w.k), ("dev_a", "conf_a_q16", "level_a")):
+        assert (g == x).all(), nm
     del play, pinp
-    _say("  [%5.1fs] coact_hist, place, token-expert table and schedule table bit-exact" % (time.time() - t0))
+    _say("  [%5.1fs] coact_hist, place, token-expert table, sequence table and schedule tables bit-exact"
+         % (time.time() - t0))
     # ---- reshuffle, dispatch
     lay.set_placement(e2r, phys, inv)
     got = lay.reshuffle()
@@ -83,6 +95,19 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
             assert (g == x).all(), "lookup: " + nm
         _say("  [%5.1fs] reshuffle from the schedule table (thr %.3f) bit-exact; remote-pair fraction %.4f"
              % (time.time() - t0, thr / 65536, O.remote_fraction(ids, e2r, wantl[0])))
+    # Alg. 3 with both tables at the full size; 30 % of the keys are shared by all classes and lie outside T
+    seq, wseq = None, None
+    for layer in (2, 1):
+        seq = lay.device_sequence((ids + layer) % w.E, e2r, seq)
+        wseq = O.device_sequence((ids + layer) % w.E, e2r, w.D, wseq)
+    assert (seq == wseq).all()
+    skeys = WL.token_key(w, shared_frac=0.3)
+    gotc = lay.reshuffle_cond(skeys, sched, seq, sched_a, 0)
+    wantc = O.reshuffle_cond(skeys, *sched, seq, *sched_a, 0, w.D, w.cap)
+    for g, x, nm in zip(gotc, wantc, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == x).all(), "cond: " + nm
+    _say("  [%5.1fs] device sequences and reshuffle from both tables bit-exact; remote-pair fraction %.4f"
+         % (time.time() - t0, O.remote_fraction(ids, e2r, wantc[0])))
     # the request-level row at the full size: requests = runs of tokens of one topic, ranks from the schedule table
     roff, _, rkeys = WL.requests(w)
     gotq = lay.request_schedule(roff, rkeys, sched[0])

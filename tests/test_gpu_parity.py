@@ -256,6 +256,78 @@ def test_reshuffle_lookup_bit_exact(T, E, D, k, cf, V, thr):
             assert (g_ == w_).all()
 
 
+@pytest.mark.parametrize("T,E,D,k", [(256, 16, 4, 2), (1000, 128, 8, 8), (777, 64, 16, 4), (300, 32, 32, 2),
+                                     (5, 16, 4, 2), (3000, 48, 3, 16), (40000, 64, 16, 4), (513, 8, 8, 1)])
+def test_device_sequence_bit_exact(T, E, D, k):
+    """the device a token selects (most of its k experts, equal -> smallest), alone and chained over two layers
+    with unknown histories in between"""
+    _say("device sequence", T, E, D, k)
+    r = np.random.default_rng(T + E)
+    ids, e2r = _planted(T, E, D, k, seed=T + D, noise=0.5)
+    ids2, e2r2 = _planted(T, E, D, k, seed=T + D + 1, noise=0.5)
+    lay = H.Layer(WL.small(T=T, E=E, D=D, k=k))
+    one = lay.device_sequence(ids, e2r)
+    assert (one == O.device_sequence(ids, e2r, D)).all()
+    prev = one.copy()
+    prev[r.random(T) < 0.1] = -1
+    two = lay.device_sequence(ids2, e2r2, prev)
+    assert (two == O.device_sequence(ids2, e2r2, D, prev)).all()
+    assert ((two == -1) == (prev == -1)).all() and two.max() < D * D
+
+
+@pytest.mark.parametrize("T,E,D,k,cf,V,thr", [
+    (256, 16, 4, 2, 1.0, 64, -1), (1000, 128, 8, 8, 1.0, 200, 20000), (777, 64, 16, 4, 1.0, 33, 30000),
+    (300, 32, 32, 2, 1.0, 100, 0), (513, 16, 4, 4, 1.25, 50, 40000), (100, 8, 1, 2, 1.0, 10, 0),
+    (2049, 64, 64, 1, 1.0, 300, 10000), (5, 16, 4, 2, 1.0, 4, -1), (4000, 256, 32, 8, 1.0, 700, 16384),
+    (3000, 48, 3, 16, 1.0, 256, 65536), (40000, 64, 16, 4, 1.0, 320, -1)])
+def test_reshuffle_cond_bit_exact(T, E, D, k, cf, V, thr):
+    """Alg. 3 with both tables against the oracle, bit for bit.  Both tables come from the library's own profile
+    pass: T keyed by token keys of which a third say nothing about the token's cluster, A keyed by the device
+    sequence of two earlier layers (library kernel), some histories unknown, some keys outside the table"""
+    _say("reshuffle cond", T, E, D, k, cf, V, thr)
+    r = np.random.default_rng(T + V + 1)
+    ids, e2r = _planted(T, E, D, k, seed=T + D, noise=0.3)
+    g = O.gain_matrix(ids, e2r, D).argmax(axis=1)
+    keys = (g + D * r.integers(0, max(V // D, 1), size=T)).astype(np.int32) % V
+    vague = r.random(T) < 0.33
+    keys[vague] = r.integers(0, V, size=int(vague.sum()))
+    cap = int(math.ceil(cf * T / D))
+    lay = H.Layer(WL.small(T=T, E=E, D=D, k=k), cap=cap)
+    # two earlier layers whose routing follows the same clusters with other noise
+    prev = None
+    for layer in (2, 1):
+        ids_l = ids.copy()
+        flip = r.random(T) < 0.3
+        ids_l[flip] = _planted(T, E, D, k, seed=T + D + layer, noise=1.0)[0][flip]
+        prev = lay.device_sequence(ids_l, e2r, prev)
+    seq = prev.copy()
+    seq[r.random(T) < 0.05] = -1
+    VA = D * D
+    seen = r.random(T) < 0.9
+    tab_t = H.to_np(lay.token_expert_hist(keys[seen], ids[seen], V)).astype(np.uint32)
+    ok = seen & (seq >= 0)
+    tab_a = H.to_np(lay.token_expert_hist(seq[ok], ids[ok], VA)).astype(np.uint32)
+    tt = lay.m.lookup_tables(tab_t, e2r)
+    ta = lay.m.lookup_tables(tab_a, e2r)
+    keys2 = keys.copy()
+    if T > 8:
+        keys2[::11] = V + 3
+        keys2[5::11] = -2
+    got = lay.reshuffle_cond(keys2, tt, seq, ta, thr, cap=cap)
+    want = O.reshuffle_cond(keys2, *tt, seq, *ta, thr, D, cap)
+    for g_, w_, name in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g_ == w_).all(), (name, np.flatnonzero(g_ != w_)[:8])
+    assert (got[3] <= cap).all()
+    if thr >= 65536:
+        assert (got[0] == O.home_rank(T, D)).all()
+    # one table empty: the call equals the single-table entry point
+    none = tuple(np.array(x, dtype=np.int32) for x in ([-1], [0], [0]))
+    a = lay.reshuffle_cond(keys2, tt, seq, none, thr, cap=cap)
+    b = lay.reshuffle_lookup(keys2, *tt, thr, cap=cap)
+    for g_, w_ in zip(a, b):
+        assert (g_ == w_).all()
+
+
 @pytest.mark.parametrize("T,D,V,n_req,seed", [
     (256, 4, 64, 7, 0), (1000, 8, 500, 40, 1), (777, 16, 33, 100, 2), (5, 4, 7, 5, 3), (4000, 32, 1000, 64, 4),
     (3000, 3, 128, 1, 5), (2049, 64, 300, 200, 6), (100, 1, 10, 9, 7), (100000, 8, 1088, 3000, 8),
@@ -524,6 +596,14 @@ def test_empty_and_degenerate_inputs():
     lay.m.reshuffle_lookup(one, 8, one, one, one, 0, one, one, one, rc_d, cap=0)
     torch.cuda.synchronize()
     assert (H.to_np(rc_d) == 0).all()
+    rc_d.fill_(7)
+    lay.m.reshuffle_cond(one, 8, one, one, one, one, 8, one, one, one, 0, one, one, one, rc_d, cap=0)
+    torch.cuda.synchronize()
+    assert (H.to_np(rc_d) == 0).all()
+    seq = torch.full((8,), 5, **i32)
+    lay.m.device_sequence(one, lay.e2r, 0, None, seq)                           # no token: nothing written
+    torch.cuda.synchronize()
+    assert (H.to_np(seq) == 5).all()
     rc_d.fill_(7)
     lay.m.request_schedule(one, 0, one, 8, one, one, one, one, one, rc_d)       # no request, no token
     torch.cuda.synchronize()

@@ -110,6 +110,14 @@ def test_next_row_calls_reject_bad_arguments_without_a_gpu():
     c.cap = 15
     assert lib.semmoe_reshuffle_lookup(C.byref(c), None, p, 8, p, p, p, 0, p, p, p, p, p, big) == -2  # cap * D < T
     c.cap = 16
+    # both tables
+    assert lib.semmoe_reshuffle_cond(C.byref(c), None, p, 8, p, p, p, p, 0, p, p, p, 0, p, p, p, p, p, big) == -1  # VA <= 0
+    assert lib.semmoe_reshuffle_cond(C.byref(c), None, p, 8, p, p, p, None, 8, p, p, p, 0, p, p, p, p, p, big) == -1
+    assert lib.semmoe_reshuffle_cond(C.byref(c), None, p, 8, p, p, p, p, 8, p, p, p, 0, p, p, p, p, p, 8) == -3
+    assert lib.semmoe_device_sequence(C.byref(c), None, None, p, 4, None, p) == -1
+    assert lib.semmoe_device_sequence(C.byref(c), None, p, p, -1, None, p) == -1
+    assert lib.semmoe_device_sequence(C.byref(c), None, p, p, 4, None, None) == -1
+    assert lib.semmoe_device_sequence(C.byref(c), None, p, p, 0, None, p) == 0                       # nothing to do
     # request scheduling
     assert lib.semmoe_request_schedule(C.byref(c), None, None, 3, p, 8, p, p, p, p, p, p, p, big) == -1
     assert lib.semmoe_request_schedule(C.byref(c), None, p, -1, p, 8, p, p, p, p, p, p, p, big) == -1

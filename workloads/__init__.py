@@ -22,7 +22,7 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 # stream ids (one per tensor kind)
-_S_X, _S_WR, _S_PERM, _S_CLASS, _S_BIAS, _S_WGU, _S_WDOWN, _S_FREE, _S_SH, _S_KEY, _S_REQ = range(11)
+_S_X, _S_WR, _S_PERM, _S_CLASS, _S_BIAS, _S_WGU, _S_WDOWN, _S_FREE, _S_SH, _S_KEY, _S_REQ, _S_SHARED = range(12)
 PROFILE_SEED_OFFSET = 1000
 
 
@@ -145,32 +145,34 @@ def hidden(w: Workload, profile: bool = False, n: Optional[int] = None) -> np.nd
     return _normal(w, _rng(w, _S_X, 0, profile), (n, w.d), 1.0)
 
 
-def router_weight(w: Workload) -> np.ndarray:
-    """W_r[E,d] ~ N(0, 0.02): one row per expert (the paper's gate-matrix column)"""
-    return _normal(w, _rng(w, _S_WR), (w.E, w.d), w.weight_std)
+def router_weight(w: Workload, layer: int = 0) -> np.ndarray:
+    """W_r[E,d] ~ N(0, 0.02): one row per expert (the paper's gate-matrix column).  layer 0 is the layer the path
+    runs; layer 1, 2, ... are the MoE layers before it (their own weights, scramble and clusters), used only to
+    give tokens a routing history for the inter-layer table."""
+    return _normal(w, _rng(w, _S_WR, layer), (w.E, w.d), w.weight_std)
 
 
-def expert_scramble(w: Workload) -> np.ndarray:
+def expert_scramble(w: Workload, layer: int = 0) -> np.ndarray:
     """Seeded permutation pi of expert ids, so that contiguous (vanilla) placement does not
     already match the semantic clusters."""
-    return _rng(w, _S_PERM).permutation(w.E).astype(np.int32)
+    return _rng(w, _S_PERM, layer).permutation(w.E).astype(np.int32)
 
 
-def class_clusters(w: Workload) -> np.ndarray:
+def class_clusters(w: Workload, layer: int = 0) -> np.ndarray:
     """cluster[c, j] = pi[(c * E/C + j) mod E], j < m.  Disjoint when E/C == m, overlapping otherwise."""
-    pi = expert_scramble(w)
+    pi = expert_scramble(w, layer)
     stride = max(w.E // w.C, 1)
     idx = (np.arange(w.C)[:, None] * stride + np.arange(w.m)[None, :]) % w.E
     return pi[idx]
 
 
-def class_bias(w: Workload) -> np.ndarray:
+def class_bias(w: Workload, layer: int = 0) -> np.ndarray:
     """class_bias[C,E] fp32: beta_c on the class's cluster, 0 elsewhere."""
-    cl = class_clusters(w)
+    cl = class_clusters(w, layer)
     if w.bias_lo == w.bias_hi:
         beta = np.full(w.C, w.bias_lo, dtype=np.float32)
     else:
-        beta = _rng(w, _S_BIAS).uniform(w.bias_lo, w.bias_hi, size=w.C).astype(np.float32)
+        beta = _rng(w, _S_BIAS, layer).uniform(w.bias_lo, w.bias_hi, size=w.C).astype(np.float32)
     b = np.zeros((w.C, w.E), dtype=np.float32)
     for c in range(w.C):
         b[c, cl[c]] = beta[c]
@@ -197,18 +199,25 @@ def token_class(w: Workload, profile: bool = False, n: Optional[int] = None) -> 
 KEYS_PER_CLASS = 64
 
 
-def vocab_size(w: Workload) -> int:
-    """size of the synthetic vocabulary: KEYS_PER_CLASS keys per latent class + as many class-free keys"""
-    return (w.C + 1) * KEYS_PER_CLASS
+def vocab_size(w: Workload, shared: bool = False) -> int:
+    """size of the synthetic vocabulary: KEYS_PER_CLASS keys per latent class + as many class-free keys
+    (+ as many keys shared by all classes when `shared`)"""
+    return (w.C + 1 + (1 if shared else 0)) * KEYS_PER_CLASS
 
 
-def token_key(w: Workload, profile: bool = False, n: Optional[int] = None) -> np.ndarray:
+def token_key(w: Workload, profile: bool = False, n: Optional[int] = None, shared_frac: float = 0.0) -> np.ndarray:
     """token_key[T] int32 in [0, vocab_size): a synthetic token id.  Every class owns KEYS_PER_CLASS keys
-    (the tokens of a class are uniform over them); class-free tokens draw from the last KEYS_PER_CLASS keys.
-    Stands in for the vocabulary ids the paper's lookup tables are indexed by."""
+    (the tokens of a class are uniform over them); class-free tokens draw from the next KEYS_PER_CLASS keys.
+    Stands in for the vocabulary ids the paper's lookup tables are indexed by.
+    shared_frac > 0: that share of the tokens, of whatever class, carries one of KEYS_PER_CLASS further keys that all
+    classes share (ids from vocab_size(w) on; the vocabulary is then vocab_size(w, shared=True)): token ids whose
+    routing depends on the context and not on the id, which is what the inter-layer table is there for."""
     cls = token_class(w, profile, n)
     sub = _rng(w, _S_KEY, 0, profile).integers(0, KEYS_PER_CLASS, size=cls.shape[0])
     base = np.where(cls >= 0, cls, w.C).astype(np.int64) * KEYS_PER_CLASS
+    if shared_frac > 0:
+        amb = _rng(w, _S_SHARED, 0, profile).random(cls.shape[0]) < shared_frac
+        base[amb] = (w.C + 1) * KEYS_PER_CLASS
     return (base + sub).astype(np.int32)
 
 
