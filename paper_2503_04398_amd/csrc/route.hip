@@ -297,28 +297,35 @@ __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const fl
   constexpr bool sigmoid = SIG;  // compile-time: the softmax form carries none of the sigmoid form's bookkeeping
   const int NEGK = to_key(-__builtin_inff());
 
+  // rowp[ch] is always readable (the callers point the rows of absent tokens at a present one) and the expert index
+  // is clamped, so the loads carry no branch and go out together; what is absent is masked afterwards.  A token is
+  // present when it has somewhere to write (idp[ch]).
   int val[NCH][NS];    // key of the selection score
   float aux[NCH][NS];  // sigmoid: s (softmax reads the logit back from the key)
   uint32_t live[NCH];
+  float x[NCH][NS], sb[NS];
+#pragma unroll
+  for (int c = 0; c < NS; ++c) {
+    const int e = min(c * 16 + l16, E - 1);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) x[ch][c] = rowp[ch][e];
+    sb[c] = (SIG && sel_bias) ? sel_bias[e] : 0.0f;
+  }
 #pragma unroll
   for (int ch = 0; ch < NCH; ++ch) {
     live[ch] = 0;
 #pragma unroll
     for (int c = 0; c < NS; ++c) {
-      const int e = c * 16 + l16;
-      val[ch][c] = NEGK;
-      aux[ch][c] = 0.0f;
-      if (e < E && rowp[ch]) {
-        const float x = rowp[ch][e];
-        if (sigmoid) {
-          const float sg = sigmoid_exact_seq(x);
-          aux[ch][c] = sg;
-          val[ch][c] = to_key(__fadd_rn(sg, sel_bias ? sel_bias[e] : 0.0f));
-        } else {
-          val[ch][c] = to_key(x);
-        }
-        live[ch] |= 1u << c;
+      const bool there = c * 16 + l16 < E && idp[ch] != nullptr;
+      if (sigmoid) {
+        const float sg = sigmoid_exact_seq(x[ch][c]);
+        aux[ch][c] = there ? sg : 0.0f;
+        val[ch][c] = there ? to_key(__fadd_rn(sg, sb[c])) : NEGK;
+      } else {
+        aux[ch][c] = 0.0f;
+        val[ch][c] = there ? to_key(x[ch][c]) : NEGK;
       }
+      live[ch] |= there ? (1u << c) : 0u;
     }
   }
 
@@ -467,17 +474,21 @@ __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const fl
 
   float w[NCH];
   if (!sigmoid) {
-    float part[NCH];
 #pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) {
-      part[ch] = 0.0f;
+    for (int ch = 0; ch < NCH; ++ch) w[ch] = (l16 < k) ? expf(my_val[ch] - mx[ch]) : 0.0f;
+    if (!cfg.renorm) {  // softmax over all experts; with renormalisation its denominator cancels and is not formed
+      float part[NCH];
 #pragma unroll
-      for (int c = 0; c < NS; ++c)
-        if (c * 16 + l16 < E && rowp[ch]) part[ch] += expf(from_key(val[ch][c]) - mx[ch]);  // key -> logit
+      for (int ch = 0; ch < NCH; ++ch) {
+        part[ch] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NS; ++c)
+          if (c * 16 + l16 < E) part[ch] += expf(x[ch][c] - mx[ch]);
+      }
+      SEMMOE_ROW_REDUCE("v_add_f32_dpp", part);
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) w[ch] = w[ch] / part[ch];
     }
-    SEMMOE_ROW_REDUCE("v_add_f32_dpp", part);
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) w[ch] = (l16 < k) ? expf(my_val[ch] - mx[ch]) / part[ch] : 0.0f;
   } else {
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) w[ch] = (l16 < k) ? my_val[ch] : 0.0f;
@@ -493,7 +504,7 @@ __device__ __forceinline__ void select_rows16(const semmoe_config& cfg, const fl
 #pragma unroll
   for (int ch = 0; ch < NCH; ++ch) {
     if (sigmoid) w[ch] *= cfg.routed_scale;
-    if (l16 < k && rowp[ch]) {
+    if (l16 < k && idp[ch]) {
       idp[ch][l16] = my_id[ch];
       wp[ch][l16] = w[ch];
     }
@@ -510,12 +521,22 @@ __host__ __device__ inline bool select_by_rows(const semmoe_config& cfg) {
   return cfg.E <= 256 && cfg.k <= 16 && (cfg.score != SEMMOE_SIGMOID || cfg.n_group <= 16);
 }
 
+// Which selection code a kernel instantiation carries.  The host picks it from E, k, the score function and the group
+// count, so that a kernel holds one form instead of all of them (a fused router with every form in it was 150 KB of
+// code: its prologue alone, hoisted set-up of forms it never ran, took 3 us of instruction fetch per workgroup).
+enum : int { kSelAny = 0, kSelSmall = 1, kSel8 = 2, kSel16 = 3 };  // any E / row form with <= 4, 8, 16 slots per lane
+inline int select_form(const semmoe_config& cfg) {
+  if (!select_by_rows(cfg)) return kSelAny;
+  return cfg.E <= 64 ? kSelSmall : (cfg.E <= 128 ? kSel8 : kSel16);
+}
+
 // Tokens base .. base + kRowTokens - 1 (those below n_tok) by one wave: token = base + ch*4 + row.
 // row_of(token) -> pointer to its E logits; ids / weights are written to topk_ids / topk_w at tok_global0 + token.
-template <typename RowOf>
+template <int FORM, bool SIG, typename RowOf>
 __device__ __forceinline__ void select_tokens_by_rows(const semmoe_config& cfg, int base, int n_tok, RowOf row_of,
                                                       int tok_global0, const float* __restrict__ sel_bias, int lane,
                                                       int32_t* __restrict__ topk_ids, float* __restrict__ topk_w) {
+  static_assert(FORM == kSelSmall || FORM == kSel8 || FORM == kSel16, "a row form");
   const float* rowp[kRowChains];
   int32_t* idp[kRowChains];
   float* wp[kRowChains];
@@ -523,22 +544,18 @@ __device__ __forceinline__ void select_tokens_by_rows(const semmoe_config& cfg, 
   for (int ch = 0; ch < kRowChains; ++ch) {
     const int tl = base + ch * 4 + (lane >> 4);
     const bool ok = tl < n_tok && tok_global0 + tl < cfg.T;
-    rowp[ch] = ok ? row_of(tl) : nullptr;
+    rowp[ch] = row_of(min(tl, n_tok - 1));  // an absent token reads a present one's row and writes nothing
     idp[ch] = ok ? topk_ids + size_t(tok_global0 + tl) * cfg.k : nullptr;
     wp[ch] = ok ? topk_w + size_t(tok_global0 + tl) * cfg.k : nullptr;
   }
-  if (cfg.score == SEMMOE_SIGMOID) {
-    if (cfg.E <= 16) select_rows16<1, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 32) select_rows16<2, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 64) select_rows16<4, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 128) select_rows16<8, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
-    else select_rows16<16, kRowChains, true>(cfg, rowp, sel_bias, lane, idp, wp);
+  if constexpr (FORM == kSel16) {
+    select_rows16<16, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+  } else if constexpr (FORM == kSel8) {
+    select_rows16<8, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
   } else {
-    if (cfg.E <= 16) select_rows16<1, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 32) select_rows16<2, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 64) select_rows16<4, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 128) select_rows16<8, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
-    else select_rows16<16, kRowChains, false>(cfg, rowp, sel_bias, lane, idp, wp);
+    if (cfg.E <= 16) select_rows16<1, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 32) select_rows16<2, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    else select_rows16<4, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
   }
 }
 
@@ -585,7 +602,7 @@ struct RouteCfg {
   static_assert((NSTAGE - 1) * IPW < 64, "vmcnt range");
 };
 
-template <int TF, int TT, int NSTAGE>
+template <int TF, int TT, int NSTAGE, int FORM, bool SIG>
 __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, const bf16_t* __restrict__ X,
                                                           const bf16_t* __restrict__ W_r,
                                                           const float* __restrict__ b_g,
@@ -657,6 +674,13 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
           acc2[i][j][r] = 0.0f;
         }
 
+    // the tokens' classes are requested before the ring: they have arrived long before the logits need them
+    int cls_of[TT];
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+      const int tok = tok0 + j * 32 + lrow;
+      cls_of[j] = (token_class && !partial && tok < T) ? token_class[tok] : -1;
+    }
 #pragma unroll
     for (int s0 = 0; s0 < NSTAGE - 1; ++s0)
       if (s0 < n_it) issue(s0);
@@ -720,12 +744,46 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
     }
     __syncthreads();  // every wave is done with the ring: its first bytes now hold the logits
 
+    // A lane holds, per 32 x 32 block, four groups of four consecutive experts of one token.  With E a multiple of
+    // four and 16-byte aligned bias arrays a group's bias terms are one 16-byte load each, all requested before the
+    // first is used (one exposed latency per token tile instead of one per element), and a group's logits are
+    // one 16-byte LDS write and one 16-byte store.
+    const bool vec4 = (E & 3) == 0 && ((reinterpret_cast<size_t>(b_g) | reinterpret_cast<size_t>(class_bias) |
+                                        reinterpret_cast<size_t>(logits_out)) & 15) == 0;
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
       const int tl = j * 32 + lrow;
       const int tok = tok0 + tl;
-      const int cls = (token_class && tok < T) ? token_class[tok] : -1;
+      const int cls = cls_of[j];
       const float* cb = (cls >= 0 && cls < cfg.num_classes && class_bias) ? class_bias + size_t(cls) * E : nullptr;
+      if (vec4) {
+        f32x4_t add[TF][4];
+#pragma unroll
+        for (int i = 0; i < TF; ++i)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int e0 = (wave * TF + i) * 32 + g * 8 + half * 4;
+            f32x4_t a = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (e0 < E) {
+              if (b_g) a = *reinterpret_cast<const f32x4_t*>(b_g + e0);
+              if (cb) a += *reinterpret_cast<const f32x4_t*>(cb + e0);
+            }
+            add[i][g] = a;
+          }
+#pragma unroll
+        for (int i = 0; i < TF; ++i)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int e0 = (wave * TF + i) * 32 + g * 8 + half * 4;
+            if (e0 < E) {
+              f32x4_t v = {acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+              v += add[i][g];
+              *reinterpret_cast<f32x4_t*>(lg + tl * ldl + e0) = v;
+              if (logits_out && tok < T) *reinterpret_cast<f32x4_t*>(logits_out + size_t(tok) * E + e0) = v;
+            }
+          }
+        continue;
+      }
 #pragma unroll
       for (int i = 0; i < TF; ++i) {
 #pragma unroll
@@ -742,9 +800,9 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
       }
     }
     __syncthreads();
-    if (select_by_rows(cfg)) {
+    if constexpr (FORM != kSelAny) {
       for (int base = wave * kRowTokens; base < C::BT; base += 4 * kRowTokens)
-        select_tokens_by_rows(
+        select_tokens_by_rows<FORM, SIG>(
             cfg, base, C::BT, [&](int tl) { return lg + tl * ldl; }, tok0, sel_bias, lane, topk_ids, topk_w);
     } else {
       for (int tl0 = wave; tl0 < C::BT; tl0 += 4 * kSelTokens) {
@@ -767,6 +825,7 @@ __global__ __launch_bounds__(256) void route_fused_kernel(semmoe_config cfg, con
   }
 }
 
+template <int FORM, bool SIG>
 __global__ __launch_bounds__(256) void select_topk_rows_kernel(semmoe_config cfg, const float* __restrict__ logits,
                                                                const float* __restrict__ sel_bias,
                                                                int32_t* __restrict__ topk_ids,
@@ -774,7 +833,7 @@ __global__ __launch_bounds__(256) void select_topk_rows_kernel(semmoe_config cfg
   const int lane = threadIdx.x & 63;
   const int base = (blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * kRowTokens;
   if (base >= cfg.T) return;  // whole wave leaves together
-  select_tokens_by_rows(
+  select_tokens_by_rows<FORM, SIG>(
       cfg, base, cfg.T, [&](int tl) { return logits + size_t(tl) * cfg.E; }, 0, sel_bias, lane, topk_ids, topk_w);
 }
 
@@ -835,9 +894,23 @@ static int32_t launch_select(const semmoe_config* cfg, hipStream_t stream, const
                              const float* sel_bias, int32_t* topk_ids, float* topk_w) {
   if (cfg->T == 0) return SEMMOE_OK;
   const int waves_per_block = 4;
-  if (select_by_rows(*cfg)) {
-    hipLaunchKernelGGL(select_topk_rows_kernel, dim3(cdiv(cfg->T, waves_per_block * kRowTokens)),
-                       dim3(64 * waves_per_block), 0, stream, *cfg, logits, sel_bias, topk_ids, topk_w);
+  const int form = select_form(*cfg);
+  if (form != kSelAny) {
+    const dim3 grid(cdiv(cfg->T, waves_per_block * kRowTokens)), block(64 * waves_per_block);
+    const bool sig = cfg->score == SEMMOE_SIGMOID;
+#define SEMMOE_SELECT_LAUNCH(FORM_)                                                                                \
+  do {                                                                                                             \
+    if (sig)                                                                                                       \
+      hipLaunchKernelGGL((select_topk_rows_kernel<FORM_, true>), grid, block, 0, stream, *cfg, logits, sel_bias,   \
+                         topk_ids, topk_w);                                                                        \
+    else                                                                                                           \
+      hipLaunchKernelGGL((select_topk_rows_kernel<FORM_, false>), grid, block, 0, stream, *cfg, logits, sel_bias,  \
+                         topk_ids, topk_w);                                                                        \
+  } while (0)
+    if (form == kSelSmall) SEMMOE_SELECT_LAUNCH(kSelSmall);
+    else if (form == kSel8) SEMMOE_SELECT_LAUNCH(kSel8);
+    else SEMMOE_SELECT_LAUNCH(kSel16);
+#undef SEMMOE_SELECT_LAUNCH
     SEMMOE_LAUNCH_CHECK();
     return SEMMOE_OK;
   }
@@ -896,7 +969,9 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     SEMMOE_HIP(hipGetDevice(&dev));
     SEMMOE_HIP(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     const int n_tiles = cdiv(cfg->T, bt);
-#define SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_)                                                                          \
+    const int form = select_form(*cfg);
+    const bool sig = cfg->score == SEMMOE_SIGMOID;
+#define SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, FORM_, SIG_)                                                             \
   do {                                                                                                              \
     using RC = RouteCfg<TF_, TT_, NS_>;                                                                             \
     size_t lds = size_t(NS_) * RC::kStageBytes;                                                                     \
@@ -906,18 +981,42 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     const int items = n_tiles * n_parts;                                                                            \
     const int grid = items < ncu * per_cu ? items : ncu * per_cu;                                                   \
     if (lds > 48 * 1024)                                                                                            \
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_fused_kernel<TF_, TT_, NS_>),              \
+      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_fused_kernel<TF_, TT_, NS_, FORM_, SIG_>), \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));                        \
-    hipLaunchKernelGGL((route_fused_kernel<TF_, TT_, NS_>), dim3(grid), dim3(256), lds, s, *cfg, Xb, Wb, b_g,       \
-                       token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w, n_parts, partial);          \
+    hipLaunchKernelGGL((route_fused_kernel<TF_, TT_, NS_, FORM_, SIG_>), dim3(grid), dim3(256), lds, s, *cfg, Xb,   \
+                       Wb, b_g, token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w, n_parts, partial); \
+  } while (0)
+// the selection forms a shape can need: with E <= 128 the small and the 8-slot row forms, with E <= 256 the 16-slot one
+#define SEMMOE_ROUTE_FORMS_128(TF_, TT_, NS_)                                                                       \
+  do {                                                                                                              \
+    if (form == kSelSmall) {                                                                                        \
+      if (sig) SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSelSmall, true);                                                 \
+      else SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSelSmall, false);                                                    \
+    } else if (form == kSel8) {                                                                                     \
+      if (sig) SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSel8, true);                                                     \
+      else SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSel8, false);                                                        \
+    } else {                                                                                                        \
+      SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSelAny, false);                                                           \
+    }                                                                                                               \
+  } while (0)
+#define SEMMOE_ROUTE_FORMS_256(TF_, TT_, NS_)                                                                       \
+  do {                                                                                                              \
+    if (form == kSel16) {                                                                                           \
+      if (sig) SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSel16, true);                                                    \
+      else SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSel16, false);                                                       \
+    } else {                                                                                                        \
+      SEMMOE_ROUTE_LAUNCH(TF_, TT_, NS_, kSelAny, false);                                                           \
+    }                                                                                                               \
   } while (0)
     if (tf == 1) {
-      if (wide) SEMMOE_ROUTE_LAUNCH(1, 2, 5); else SEMMOE_ROUTE_LAUNCH(1, 1, 6);
+      if (wide) SEMMOE_ROUTE_FORMS_128(1, 2, 5); else SEMMOE_ROUTE_FORMS_128(1, 1, 6);
     } else if (tf == 2) {
-      if (wide) SEMMOE_ROUTE_LAUNCH(2, 2, 3); else SEMMOE_ROUTE_LAUNCH(2, 1, 4);
+      if (wide) SEMMOE_ROUTE_FORMS_256(2, 2, 3); else SEMMOE_ROUTE_FORMS_256(2, 1, 4);
     } else {
-      SEMMOE_ROUTE_LAUNCH(4, 1, 2);
+      SEMMOE_ROUTE_LAUNCH(4, 1, 2, kSelAny, false);
     }
+#undef SEMMOE_ROUTE_FORMS_128
+#undef SEMMOE_ROUTE_FORMS_256
 #undef SEMMOE_ROUTE_LAUNCH
     SEMMOE_LAUNCH_CHECK();
     if (n_parts > 1) {
