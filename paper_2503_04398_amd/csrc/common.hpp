@@ -78,4 +78,38 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
 }
 
+// The k experts of a token mapped through a table (expert -> rank, or expert -> physical position):
+//   r[j] = map[row[j]] for j < k when the token is there, the expert lies in [0,E) and the mapped value in [0,limit),
+//   else -1 (also for j >= k).
+// No load sits behind a branch: indices are clamped and the result is masked afterwards, so the k id loads go out
+// together and then the k table loads - two exposed latencies.  Written per element with a test in front of each load,
+// the compiler waits for every load before it issues the next: 2k latencies, 3-4 us of an index kernel.
+// `row` must be readable for k entries even when `have` is false (callers pass the row of a token that exists).
+template <int KU>
+__device__ __forceinline__ void load_mapped_ids_n(const int32_t* __restrict__ row, bool have, int k, int E,
+                                                  const int32_t* __restrict__ map, int limit,
+                                                  int (&r)[SEMMOE_MAX_K]) {
+  int e[KU], m[KU];
+#pragma unroll
+  for (int j = 0; j < KU; ++j) e[j] = row[min(j, k - 1)];
+#pragma unroll
+  for (int j = 0; j < KU; ++j) {
+    const bool ok = have && j < k && (unsigned)e[j] < (unsigned)E;
+    e[j] = ok ? e[j] : -1;
+  }
+#pragma unroll
+  for (int j = 0; j < KU; ++j) m[j] = map[max(e[j], 0)];
+#pragma unroll
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) r[j] = -1;
+#pragma unroll
+  for (int j = 0; j < KU; ++j) r[j] = (e[j] >= 0 && (unsigned)m[j] < (unsigned)limit) ? m[j] : -1;
+}
+
+__device__ __forceinline__ void load_mapped_ids(const int32_t* __restrict__ row, bool have, int k, int E,
+                                                const int32_t* __restrict__ map, int limit, int (&r)[SEMMOE_MAX_K]) {
+  static_assert(SEMMOE_MAX_K == 16, "the two widths below");
+  if (k <= 8) load_mapped_ids_n<8>(row, have, k, E, map, limit, r);  // k is uniform: a scalar branch
+  else load_mapped_ids_n<16>(row, have, k, E, map, limit, r);
+}
+
 }  // namespace semmoe

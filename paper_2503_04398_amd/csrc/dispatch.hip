@@ -36,17 +36,10 @@ __device__ __forceinline__ int load_pairs(int T, int k, int E, const int32_t* __
     tok = shf[pos];
     if ((unsigned)tok >= (unsigned)T) tok = -1;
   }
-  int e[SEMMOE_MAX_K];
+  int q[SEMMOE_MAX_K];
+  load_mapped_ids(ids + size_t(max(tok, 0)) * k, tok >= 0, k, E, phys, E, q);
 #pragma unroll
-  for (int j = 0; j < SEMMOE_MAX_K; ++j) e[j] = (j < k && tok >= 0) ? ids[size_t(tok) * k + j] : -1;
-#pragma unroll
-  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
-    q_out[j] = -1;
-    if ((unsigned)e[j] < (unsigned)E) {
-      const int q = phys[e[j]];
-      if ((unsigned)q < (unsigned)E) q_out[j] = q;
-    }
-  }
+  for (int j = 0; j < SEMMOE_MAX_K; ++j) q_out[j] = q[j];
   return tok;
 }
 
@@ -328,20 +321,10 @@ __global__ __launch_bounds__(kChunk) void dp_single_kernel(int T, int k, int E, 
       if ((unsigned)tok >= (unsigned)T) tok = -1;
     }
     int q[SEMMOE_MAX_K];
+    load_mapped_ids(ids + size_t(max(tok, 0)) * k, tok >= 0, k, E, phys, E, q);
 #pragma unroll
-    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
-      q[j] = -1;
-      if (j < k && tok >= 0) {
-        const int e = ids[size_t(tok) * k + j];
-        if ((unsigned)e < (unsigned)E) {
-          const int qq = phys[e];
-          if ((unsigned)qq < (unsigned)E) {
-            q[j] = qq;
-            atomicOr(&bm[qq * 32 + (t >> 5)], 1u << (t & 31));
-          }
-        }
-      }
-    }
+    for (int j = 0; j < SEMMOE_MAX_K; ++j)
+      if (q[j] >= 0) atomicOr(&bm[q[j] * 32 + (t >> 5)], 1u << (t & 31));
     __syncthreads();
     for (int key = hw; key < E; key += kChunk / 32) {  // 32-word popcount prefix per expert, one half-wave each
       const int v = __popc(bm[key * 32 + w]);

@@ -42,19 +42,9 @@ __global__ __launch_bounds__(kTokBlock) void rs_pref_kernel(int T, int k, int D,
   for (int x = threadIdx.x; x < nkeys; x += blockDim.x) hist[x] = 0;
   __syncthreads();
   const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  int r[SEMMOE_MAX_K];
+  load_mapped_ids(ids + size_t(min(i, T - 1)) * k, i < T, k, E, e2r, D, r);
   if (i < T) {
-    int r[SEMMOE_MAX_K];
-#pragma unroll
-    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
-      r[j] = -1;
-      if (j < k) {
-        const int e = ids[size_t(i) * k + j];
-        if ((unsigned)e < (unsigned)E) {
-          const int rr = e2r[e];
-          if ((unsigned)rr < (unsigned)D) r[j] = rr;
-        }
-      }
-    }
     const int home = i / per_home;
     int best_r = home, best_c = 0;  // g[i, home] first: it wins every tie
 #pragma unroll
@@ -173,17 +163,7 @@ __global__ __launch_bounds__(kTokBlock) void device_sequence_kernel(int T, int k
   const int i = blockIdx.x * kTokBlock + threadIdx.x;
   if (i >= T) return;
   int r[SEMMOE_MAX_K];
-#pragma unroll
-  for (int j = 0; j < SEMMOE_MAX_K; ++j) {
-    r[j] = -1;
-    if (j < k) {
-      const int e = ids[size_t(i) * k + j];
-      if ((unsigned)e < (unsigned)E) {
-        const int rr = e2r[e];
-        if ((unsigned)rr < (unsigned)D) r[j] = rr;
-      }
-    }
-  }
+  load_mapped_ids(ids + size_t(i) * k, true, k, E, e2r, D, r);
   int best_r = 0, best_c = 0;
 #pragma unroll
   for (int j = 0; j < SEMMOE_MAX_K; ++j) {
@@ -670,17 +650,10 @@ __global__ __launch_bounds__(kTokBlock) void rs_round_kernel(int T, int NB, int 
         // propose again: best rank with room after this round; equal gains -> home if it is one of them, else
         // the smallest; no rank of the token has room -> gain 0 (home if it has room, else the smallest with room)
         int rr[SEMMOE_MAX_K];
+        load_mapped_ids(ids + size_t(i) * k, true, k, E, e2r, D, rr);
 #pragma unroll
-        for (int j = 0; j < SEMMOE_MAX_K; ++j) {
-          rr[j] = -1;
-          if (j < k) {
-            const int e = ids[size_t(i) * k + j];
-            if ((unsigned)e < (unsigned)E) {
-              const int x = e2r[e];
-              if ((unsigned)x < (unsigned)D && free_nx[x] > 0) rr[j] = x;
-            }
-          }
-        }
+        for (int j = 0; j < SEMMOE_MAX_K; ++j)
+          if (rr[j] >= 0 && free_nx[rr[j]] <= 0) rr[j] = -1;  // a rank without room is no candidate
         const int home = i / per_home;
         const bool home_room = free_nx[home] > 0;
         int best_r = -1, best_c = 0;
@@ -815,17 +788,7 @@ __global__ __launch_bounds__(kChunk) void rs_single_kernel(int T, int k, int D, 
   // pref / conf per token and the (pref, conf) histogram
   for (int i = t; i < T; i += kChunk) {
     int r[SEMMOE_MAX_K];
-#pragma unroll
-    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
-      r[j] = -1;
-      if (j < k) {
-        const int e = ids[size_t(i) * k + j];
-        if ((unsigned)e < (unsigned)E) {
-          const int rr = e2r[e];
-          if ((unsigned)rr < (unsigned)D) r[j] = rr;
-        }
-      }
-    }
+    load_mapped_ids(ids + size_t(i) * k, true, k, E, e2r, D, r);
     const int home = i / per_home;
     int best_r = home, best_c = 0;
 #pragma unroll
