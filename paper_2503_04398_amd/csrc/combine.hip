@@ -1,7 +1,7 @@
 // combine: the combine all2all of expert parallelism (Sec. 1) plus `resume_tokens` (Alg. 3) on one
 // device: Out[i] = sum_j topk_w[i,j] * Y[slot_of_pair[i*k+j]] (+ Y_shared[i]), fp32 accumulation in
-// ascending j.  One workgroup per token, 16-byte chunks per thread; all k row loads of a chunk are
-// issued before the first use.
+// ascending j.  One workgroup per token, 16-byte chunks per thread; the row loads of a chunk are issued
+// (up to eight at a time) before the first use.  KU = k rounded up to 1, 2, 4, 8 or 16.
 #include "common.hpp"
 
 namespace semmoe {
@@ -20,7 +20,9 @@ __global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int
                                                       const float* __restrict__ topk_w,
                                                       const uint4* __restrict__ Y_shared, uint4* __restrict__ Out) {
   const int tok = blockIdx.x;
-  constexpr int KMAX = KU > 0 ? KU : SEMMOE_MAX_K;
+  constexpr int KMAX = KU;
+  constexpr int G = KU < 8 ? KU : 8;  // rows in flight per thread
+  static_assert(KU == 1 || KU == 2 || KU == 4 || KU == 8 || KU == 16, "k rounded up");
   int sl[KMAX];
   float wt[KMAX];
 #pragma unroll
@@ -34,10 +36,6 @@ __global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int
     }
   }
   for (int c = threadIdx.x; c < row_chunks; c += blockDim.x) {
-    uint4 v[KMAX];
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j)
-      v[j] = (sl[j] >= 0) ? load_stream16(&Y[size_t(sl[j]) * row_chunks + c]) : make_uint4(0, 0, 0, 0);
     uint4 sh = make_uint4(0, 0, 0, 0);
     if (Y_shared) sh = Y_shared[size_t(tok) * row_chunks + c];
     if constexpr (BF16) {
@@ -45,13 +43,20 @@ __global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int
 #pragma unroll
       for (int x = 0; x < 8; ++x) acc[x] = 0.0f;
 #pragma unroll
-      for (int j = 0; j < KMAX; ++j) {
-        if (j >= k) break;
-        const uint32_t u[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+      for (int g0 = 0; g0 < KMAX; g0 += G) {
+        uint4 v[G];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          acc[2 * x] = fmaf(wt[j], __uint_as_float(u[x] << 16), acc[2 * x]);
-          acc[2 * x + 1] = fmaf(wt[j], __uint_as_float(u[x] & 0xffff0000u), acc[2 * x + 1]);
+        for (int j = 0; j < G; ++j)
+          v[j] = (sl[g0 + j] >= 0) ? load_stream16(&Y[size_t(sl[g0 + j]) * row_chunks + c]) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          if (g0 + j >= k) break;
+          const uint32_t u[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            acc[2 * x] = fmaf(wt[g0 + j], __uint_as_float(u[x] << 16), acc[2 * x]);
+            acc[2 * x + 1] = fmaf(wt[g0 + j], __uint_as_float(u[x] & 0xffff0000u), acc[2 * x + 1]);
+          }
         }
       }
       if (Y_shared) {
@@ -67,12 +72,19 @@ __global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int
     } else {
       float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-      for (int j = 0; j < KMAX; ++j) {
-        if (j >= k) break;
-        acc[0] = fmaf(wt[j], __uint_as_float(v[j].x), acc[0]);
-        acc[1] = fmaf(wt[j], __uint_as_float(v[j].y), acc[1]);
-        acc[2] = fmaf(wt[j], __uint_as_float(v[j].z), acc[2]);
-        acc[3] = fmaf(wt[j], __uint_as_float(v[j].w), acc[3]);
+      for (int g0 = 0; g0 < KMAX; g0 += G) {
+        uint4 v[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j)
+          v[j] = (sl[g0 + j] >= 0) ? load_stream16(&Y[size_t(sl[g0 + j]) * row_chunks + c]) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          if (g0 + j >= k) break;
+          acc[0] = fmaf(wt[g0 + j], __uint_as_float(v[j].x), acc[0]);
+          acc[1] = fmaf(wt[g0 + j], __uint_as_float(v[j].y), acc[1]);
+          acc[2] = fmaf(wt[g0 + j], __uint_as_float(v[j].z), acc[2]);
+          acc[3] = fmaf(wt[g0 + j], __uint_as_float(v[j].w), acc[3]);
+        }
       }
       if (Y_shared) {
         acc[0] += __uint_as_float(sh.x); acc[1] += __uint_as_float(sh.y);
@@ -88,13 +100,12 @@ template <bool BF16>
 static void launch_combine(int k, int T, int row_chunks, hipStream_t s, const uint4* Y, const int32_t* slot,
                            const float* w, const uint4* Ysh, uint4* Out) {
   const int P = T * k;
-  switch (k) {
-    case 1: hipLaunchKernelGGL((combine_kernel<BF16, 1>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out); break;
-    case 2: hipLaunchKernelGGL((combine_kernel<BF16, 2>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out); break;
-    case 4: hipLaunchKernelGGL((combine_kernel<BF16, 4>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out); break;
-    case 8: hipLaunchKernelGGL((combine_kernel<BF16, 8>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out); break;
-    default: hipLaunchKernelGGL((combine_kernel<BF16, 0>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out); break;
-  }
+  // k rounded up to the next unrolled width; the kernel skips the slots beyond k
+  if (k <= 1) hipLaunchKernelGGL((combine_kernel<BF16, 1>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else if (k <= 2) hipLaunchKernelGGL((combine_kernel<BF16, 2>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else if (k <= 4) hipLaunchKernelGGL((combine_kernel<BF16, 4>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else if (k <= 8) hipLaunchKernelGGL((combine_kernel<BF16, 8>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else hipLaunchKernelGGL((combine_kernel<BF16, 16>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
 }
 
 }  // namespace semmoe

@@ -530,7 +530,7 @@ def test_layer_output_is_independent_of_placement_and_shuffle(placed, shuffle, c
 
 
 @pytest.mark.parametrize("dtype,k", [("bf16", 1), ("bf16", 2), ("bf16", 4), ("bf16", 8), ("fp32", 1), ("fp32", 2),
-                                     ("bf16", 3)])
+                                     ("bf16", 3), ("bf16", 6), ("bf16", 16), ("fp32", 5), ("fp32", 12)])
 def test_combine_after_dispatch_is_identity_for_unit_weights(dtype, k):
     _say("combine identity", dtype, k)
     T, E, D, d = 500, 16, 4, 72
