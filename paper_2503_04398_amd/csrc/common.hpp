@@ -112,4 +112,70 @@ __device__ __forceinline__ void load_mapped_ids(const int32_t* __restrict__ row,
   else load_mapped_ids_n<16>(row, have, k, E, map, limit, r);
 }
 
+// Column sums of a [n_rows][n_cols] table of counts: tot[c] += all rows, pre[c] += the rows before `b` (both in LDS,
+// zeroed by the caller, who also places the barriers).  A thread owns one column and every (threads / n_cols)-th
+// row, eight loads in flight: no division per element and two LDS atomics per thread (element by element, with a
+// division and up to two atomics each, a 32 x 128 table took twice as long).  The first eight loads can be requested
+// ahead of time (`column_sums_first`), before other work that has its own chain of dependent loads.
+struct ColumnBatch {
+  int v[8];
+};
+
+__device__ __forceinline__ ColumnBatch column_sums_first(const int32_t* __restrict__ table, int n_rows, int n_cols) {
+  ColumnBatch f;
+  const int t = threadIdx.x, nt = blockDim.x;
+  const int rpp = n_cols <= nt ? nt / n_cols : 1;
+  const int c = t % n_cols, r0 = t / n_cols;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int bb = r0 + u * rpp;
+    f.v[u] = (n_cols <= nt && r0 < rpp && bb < n_rows) ? table[size_t(bb) * n_cols + c] : 0;
+  }
+  return f;
+}
+
+__device__ __forceinline__ void column_sums_before(const int32_t* __restrict__ table, int n_rows, int n_cols, int b,
+                                                   int32_t* tot, int32_t* pre, const ColumnBatch* first = nullptr) {
+  const int t = threadIdx.x, nt = blockDim.x;
+  if (n_cols <= nt) {
+    const int rpp = nt / n_cols;  // rows covered per pass
+    const int c = t % n_cols, r0 = t / n_cols;
+    if (r0 >= rpp) return;
+    int s = 0, sb = 0;
+    for (int bb0 = r0; bb0 < n_rows; bb0 += 8 * rpp) {
+      int v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int bb = bb0 + u * rpp;
+        if (first && bb0 == r0) v[u] = first->v[u];
+        else v[u] = bb < n_rows ? table[size_t(bb) * n_cols + c] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        s += v[u];
+        sb += (bb0 + u * rpp < b) ? v[u] : 0;
+      }
+    }
+    if (s) atomicAdd(&tot[c], s);  // integer sums: the order does not matter
+    if (sb) atomicAdd(&pre[c], sb);
+    return;
+  }
+  for (int base = t; base < n_rows * n_cols; base += 8 * nt) {  // more columns than threads
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * nt;
+      v[u] = idx < n_rows * n_cols ? table[idx] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (v[u] == 0) continue;
+      const int idx = base + u * nt;
+      const int bb = idx / n_cols, c = idx - bb * n_cols;
+      atomicAdd(&tot[c], v[u]);
+      if (bb < b) atomicAdd(&pre[c], v[u]);
+    }
+  }
+}
+
 }  // namespace semmoe

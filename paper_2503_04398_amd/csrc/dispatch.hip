@@ -179,41 +179,22 @@ __global__ __launch_bounds__(kTokBlock) void dp_fused_kernel(int T, int k, int E
   unsigned long long* remote_sh = reinterpret_cast<unsigned long long*>(
       (reinterpret_cast<uintptr_t>(pre + E) + 7) & ~uintptr_t(7));
   const int t = threadIdx.x, b = blockIdx.x;
+  // the first rows of the count table are requested before the chain of three dependent loads (shf -> ids -> phys)
+  const ColumnBatch first = column_sums_first(w.cnt, NB, E);
   int q[SEMMOE_MAX_K];
-  const int tok = load_pairs(T, k, E, ids, shf, phys, q);  // three dependent loads: under way while the table is summed
+  const int tok = load_pairs(T, k, E, ids, shf, phys, q);
   for (int x = t; x < 2 * E + 1; x += kTokBlock) off[x] = 0;
   if (t == 0) *remote_sh = 0ull;
   __syncthreads();
-  for (int base = t; base < NB * E; base += 8 * kTokBlock) {  // eight loads in flight per thread
-    int v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int idx = base + u * kTokBlock;
-      v[u] = idx < NB * E ? w.cnt[idx] : 0;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (v[u] == 0) continue;
-      const int idx = base + u * kTokBlock;
-      const int bb = idx / E, e = idx - bb * E;
-      atomicAdd(&off[e], v[u]);  // integer sums: the order does not matter
-      if (bb < b) atomicAdd(&pre[e], v[u]);
-    }
-  }
-  // send matrix: entry x is summed over the workgroups' partial matrices by workgroup x % NB
+  column_sums_before(w.cnt, NB, E, b, off, pre, &first);
+  // send matrix: entry x is summed over the workgroups' partial matrices by workgroup x % NB, one wave per entry
   const int DD = D * D;
-  for (int x = b; x < DD; x += NB) {
+  for (int x = b + (t >> 6) * NB; x < DD; x += (kTokBlock >> 6) * NB) {
     uint32_t part = 0;
-    for (int bb = t; bb < NB; bb += kTokBlock) part += w.send_part[size_t(bb) * DD + x];
+    for (int bb = t & 63; bb < NB; bb += 64) part += w.send_part[size_t(bb) * DD + x];
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
-    if ((t & 63) == 0 && part) atomicAdd(remote_sh, (unsigned long long)part);  // reused as the entry's accumulator
-    __syncthreads();
-    if (t == 0) {
-      send_matrix[x] = (uint32_t)*remote_sh;
-      *remote_sh = 0ull;
-    }
-    __syncthreads();
+    if ((t & 63) == 0) send_matrix[x] = part;
   }
   if (b == 0) {  // remote pairs: sum of the workgroups' counts
     unsigned long long part = 0;

@@ -365,22 +365,7 @@ __global__ __launch_bounds__(kTokBlock) void rs_fused_kernel(int T, int NB, int 
   for (int x = t; x < 2 * nkeys; x += kTokBlock) tot[x] = 0;
   for (int x = t; x < D * kWords + kWords; x += kTokBlock) bm[x] = 0;
   __syncthreads();
-  for (int base = t; base < NB * nkeys; base += 8 * kTokBlock) {  // eight loads in flight per thread
-    int v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int idx = base + u * kTokBlock;
-      v[u] = idx < NB * nkeys ? w.cnt[idx] : 0;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (v[u] == 0) continue;
-      const int idx = base + u * kTokBlock;
-      const int bb = idx / nkeys, key = idx - bb * nkeys;
-      atomicAdd(&tot[key], v[u]);  // integer sums: the order does not matter
-      if (bb < b) atomicAdd(&pre[key], v[u]);
-    }
-  }
+  column_sums_before(w.cnt, NB, nkeys, b, tot, pre);
   __syncthreads();
   if (t < D) {
     const int r = t;
@@ -532,22 +517,7 @@ __global__ __launch_bounds__(kTokBlock) void rs_round_kernel(int T, int NB, int 
   for (int x = t; x < 3 * nkeys; x += kTokBlock) tot[x] = 0;
   for (int x = t; x < D * kWords + kWords; x += kTokBlock) bm[x] = 0;
   __syncthreads();
-  for (int base = t; base < NB * nkeys; base += 8 * kTokBlock) {  // eight loads in flight per thread
-    int v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int idx = base + u * kTokBlock;
-      v[u] = idx < NB * nkeys ? table_in[idx] : 0;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (v[u] == 0) continue;
-      const int idx = base + u * kTokBlock;
-      const int bb = idx / nkeys, key = idx - bb * nkeys;
-      atomicAdd(&tot[key], v[u]);
-      if (bb < b) atomicAdd(&pre[key], v[u]);
-    }
-  }
+  column_sums_before(table_in, NB, nkeys, b, tot, pre);
   __syncthreads();
   if (t < D) {
     const int r = t;
