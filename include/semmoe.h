@@ -79,9 +79,11 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *   SEMMOE_TUNE_HEAD_TAIL: with the 256 x 256 tile shapes (16, 20, 21, 22) a GEMM runs as two launches: the tiles that
  *     fill whole rounds of the persistent grid, then the rest as quarter tiles over the whole chip, when at most
  *     value/16 of a round is left over (default 8); 0 = always one launch
- *   SEMMOE_TUNE_TAIL_RING: kernel of that second launch.  Default: 128 x 128 pieces, one workgroup per compute unit,
- *     loads placed between the MFMAs (K a multiple of 64, else the next).  3 or 6: 128 x 64 pieces with the loads of a
- *     slice issued in a burst and an LDS ring of 3 (two workgroups per compute unit) or 6 (one)
+ *   SEMMOE_TUNE_TAIL_RING: how the rest is run.  Default: 128 x 128 pieces with the loads placed between the MFMAs, in
+ *     the same launch as the big tiles (a workgroup takes pieces once its tiles are done; K a multiple of 64 with at
+ *     least three slices, else the next).  1: the same pieces as a second launch.  3 or 6: a second launch of
+ *     128 x 64 pieces with the loads of a slice issued in a burst and an LDS ring of 3 (two workgroups per compute
+ *     unit) or 6 (one)
  *   SEMMOE_TUNE_ROUTE_SPLIT: bf16 router with at most 512 tokens: parts the K dimension is split into over workgroups
  *     (partial sums added in order by a second kernel, then the selection kernel); 0 = always the fused kernel,
  *     default: as many parts as fill the chip, at most 16
@@ -96,7 +98,7 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
 #define SEMMOE_TUNE_BLOCKS_PER_CU 2
 #define SEMMOE_TUNE_INDEX_PATH 3 /* reshuffle / dispatch index: 1 = one kernel per phase, 2 = single workgroup, 3 = two launches */
 #define SEMMOE_TUNE_HEAD_TAIL 5  /* 0: one launch per GEMM; default: big tiles for the full rounds + quarter tiles */
-#define SEMMOE_TUNE_TAIL_RING 6  /* tail launch: default 128 x 128 pieces; 3 or 6: 128 x 64 pieces, that ring depth */
+#define SEMMOE_TUNE_TAIL_RING 6  /* tail: default 128 x 128 pieces in the head's launch; 1: as a second launch; 3, 6: 128 x 64 pieces */
 #define SEMMOE_TUNE_ROUTE_SPLIT 7 /* parts of K in the few-token router; 0 = fused kernel */
 #define SEMMOE_TUNE_GRID_CAP 4   /* upper limit of the persistent GEMM grids (tests: many tiles per workgroup) */
 int32_t semmoe_set_tuning(int32_t key, int32_t value);

@@ -159,11 +159,45 @@ static int32_t launch_tail_pieces(GemmArgs a, int max_rows, int head_grid, hipSt
   return SEMMOE_OK;
 }
 
+// Head (four-wave 256 x 256 tiles, K slices of 64, ring of 2) and tail (128 x 128 pieces, ring of 3) in one launch.
+// SEMMOE_EUNSUPPORTED when either half does not take the shape: the caller then launches them one after the other.
+template <int MODE>
+static int32_t launch_w4_split(const GemmArgs& h, int max_rows, hipStream_t stream) {
+  using CH = W4Cfg<MODE, 64, 2, 2>;
+  using CP = DmaCfg<MODE, 2, 2, 2, 2, 64, 3>;
+  const int w_rows = (MODE == kModeSwiglu) ? 2 * h.N : h.N;
+  if (h.K % 64 != 0 || h.K / 64 < 3) return SEMMOE_EUNSUPPORTED;
+  if ((unsigned long long)w_rows * h.ldw * 2 >= (1ull << 32) || (unsigned long long)CH::BT * h.ldx * 2 >= (1ull << 32))
+    return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
+  const size_t lds = CH::kLdsBytes > CP::kLdsBytes ? CH::kLdsBytes : CP::kLdsBytes;
+  if (lds > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  const int n_ftiles = cdiv(h.N, CH::FEAT);
+  const long long bound = (long long)(max_rows / CH::BT + h.nq) * n_ftiles;
+  if (bound <= 0) return SEMMOE_OK;
+  const int grid = grid_for(bound, num_cu());
+  GemmArgs t = h;  // the tail's view of the same problem: the tiles the head's `grid` workgroups leave over, in pieces
+  t.sched_mode = 2;
+  t.sched_g = grid;
+  t.sched_sub_t = 256 / CP::BT;
+  t.sched_sub_f = 256 / CP::BW;
+  auto kern = gemm_bf16_w4_split_kernel<MODE, 64, 2, 2, 3>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(lds)));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, h, t);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
 template <int MODE>
 static int32_t launch_tail(const GemmArgs& a, int max_rows, int head_grid, hipStream_t stream) {
   const int ring = g_tune[SEMMOE_TUNE_TAIL_RING];
   if (ring == 6) return launch_tail_as<MODE, 6, 1>(a, max_rows, head_grid, stream);
   if (ring == 3) return launch_tail_as<MODE, 3, 2>(a, max_rows, head_grid, stream);
+  // 128 x 128 pieces as a launch of their own (the default runs them inside the head's launch: launch_w4_split)
   const int32_t st = launch_tail_pieces<MODE, 3>(a, max_rows, head_grid, stream);  // a ring of 4 gains nothing
   if (st != SEMMOE_EUNSUPPORTED) return st;
   return launch_tail_as<MODE, 3, 2>(a, max_rows, head_grid, stream);
@@ -259,6 +293,10 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         GemmArgs h = a;
         h.sched_mode = 1;
         h.sched_thr = split_threshold();
+        if (id == 22 && g_tune[SEMMOE_TUNE_TAIL_RING] < 0) {  // default shape and tail: both halves in one launch
+          const int32_t sm = launch_w4_split<kModeSwiglu>(h, max_rows, stream);
+          if (sm != SEMMOE_EUNSUPPORTED) return sm;
+        }
         const int32_t st = launch_bf16_tile<kModeSwiglu>(id, h, max_rows, 1, stream);
         if (st != SEMMOE_OK) return st;
         return launch_tail<kModeSwiglu>(h, max_rows, big_tile_grid(a, max_rows, 128), stream);
@@ -270,6 +308,10 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         GemmArgs h = a;
         h.sched_mode = 1;
         h.sched_thr = split_threshold();
+        if (id == 22 && g_tune[SEMMOE_TUNE_TAIL_RING] < 0) {
+          const int32_t sm = launch_w4_split<kModeStore>(h, max_rows, stream);
+          if (sm != SEMMOE_EUNSUPPORTED) return sm;
+        }
         const int32_t st = launch_bf16_tile<kModeStore>(id, h, max_rows, 1, stream);
         if (st != SEMMOE_OK) return st;
         return launch_tail<kModeStore>(h, max_rows, big_tile_grid(a, max_rows, 256), stream);

@@ -123,10 +123,9 @@ __device__ __forceinline__ TileRef locate_tile(const GemmArgs& a, const int* pre
 }
 
 template <int MODE, int BK, int NSTAGE, int DMA_EVERY>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
+__device__ __forceinline__ void gemm_bf16_w4_body(const GemmArgs& a, unsigned char* lds_raw) {
   using C = W4Cfg<MODE, BK, NSTAGE, DMA_EVERY>;
   static_assert(MODE != kModeLogits, "the router has its own kernel");
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
 
   const int tid = threadIdx.x;
@@ -405,10 +404,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
 // staged through the ring's LDS.  Needs K % 64 == 0 and K / 64 >= NSTAGE.
 // ------------------------------------------------------------------------------------------------
 template <int MODE, int NSTAGE>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
+__device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned char* lds_raw) {
   using C = DmaCfg<MODE, 2, 2, 2, 2, 64, NSTAGE>;
   static_assert(C::IPW == 8 && C::KS == 4 && C::RB == 128, "geometry the loop below is written for");
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   int* pre = reinterpret_cast<int*>(lds_raw + C::kTileBytes);
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
 
@@ -563,6 +561,30 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
     store_tile_via_lds<MODE, 2, 2, 2, 2>(acc, lds_raw, a, at.row_lo, at.n_tok, at.f0, wf, wt);
     __syncthreads();   // the next piece's loads overwrite the staged piece
   }
+}
+
+template <int MODE, int BK, int NSTAGE, int DMA_EVERY>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  gemm_bf16_w4_body<MODE, BK, NSTAGE, DMA_EVERY>(a, lds_raw);
+}
+
+template <int MODE, int NSTAGE>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  gemm_bf16_piece_body<MODE, NSTAGE>(a, lds_raw);
+}
+
+// Head and tail of a split in one launch: every workgroup first works through its 256 x 256 tiles of the full rounds,
+// then takes pieces of the left-over tiles.  Pieces and head tiles write disjoint outputs, so nothing has to be waited
+// for in between except this workgroup's own LDS.  Saves the second launch (also when nothing is left over, which
+// only the device knows) and lets a workgroup that is done early start on the pieces.
+template <int MODE, int BK, int NSTAGE, int DMA_EVERY, int PIECE_RING>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_w4_split_kernel(GemmArgs head, GemmArgs tail) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  gemm_bf16_w4_body<MODE, BK, NSTAGE, DMA_EVERY>(head, lds_raw);
+  __syncthreads();  // the head's last output staging has been read
+  gemm_bf16_piece_body<MODE, PIECE_RING>(tail, lds_raw);
 }
 
 }  // namespace semmoe

@@ -684,9 +684,10 @@ def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
 
 
 @pytest.mark.parametrize("grid_cap,split,ring", [(1, 16, 6), (4, 8, 6), (-1, 16, 6), (1, 16, 3), (-1, 8, 3),
-                                                  (2, 16, -1), (-1, 16, -1)])
+                                                  (2, 16, -1), (-1, 16, -1), (1, 8, -1), (1, 16, 1), (-1, 8, 1)])
 def test_tail_launch_kernels(grid_cap, split, ring):
-    """the tail launch of a split GEMM: 128 x 128 pieces (default) and the 128 x 64 pieces with a ring of 3 or 6"""
+    """the tail of a split GEMM: 128 x 128 pieces in the head's launch (default) or as a second launch (1), and the
+    128 x 64 pieces with a ring of 3 or 6"""
     _say("tail ring", ring, "grid cap", grid_cap, "split", split)
     w = WL.small(T=2500, d=512, E=4, k=2, F=192, D=2, dtype="bf16", C=2)
     m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
