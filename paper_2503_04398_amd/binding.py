@@ -58,6 +58,17 @@ class Config:
     cap: int = 0
     num_classes: int = 0
 
+    def __post_init__(self):
+        # the names of the workload descriptions are accepted for the two enumerations
+        if isinstance(self.dtype, str):
+            if self.dtype not in ("bf16", "fp32"):
+                raise ValueError("dtype must be 'bf16' or 'fp32' (or the BF16 / FP32 constants)")
+            self.dtype = BF16 if self.dtype == "bf16" else FP32
+        if isinstance(self.score, str):
+            if self.score not in ("softmax", "sigmoid"):
+                raise ValueError("score must be 'softmax' or 'sigmoid' (or the SOFTMAX / SIGMOID constants)")
+            self.score = SIGMOID if self.score == "sigmoid" else SOFTMAX
+
     def c(self) -> _CConfig:
         return _CConfig(self.T, self.d, self.E, self.k, self.F, self.D, self.dtype, self.score, int(self.renorm),
                         self.n_group, self.topk_group, self.routed_scale, self.cap, self.num_classes)

@@ -310,3 +310,12 @@ def test_host_coschedule_equals_oracle_at_config2_shape():
     e2r, _, _, ur, scores, best = m.coschedule(load, co, act, ln, **prm)
     assert e2r.tolist() == want_e2r.tolist() and ur.tolist() == want_ur.tolist()
     assert scores.tolist() == want_scores and best == want_best
+
+
+def test_config_accepts_the_names_of_its_enumerations():
+    c = S.Config(T=8, d=8, E=8, k=2, F=8, D=2, score="sigmoid", dtype="fp32")
+    assert c.score == B.SIGMOID and c.dtype == B.FP32 and c.c().score == B.SIGMOID
+    assert S.Config(T=8, d=8, E=8, k=2, F=8, D=2, score="softmax", dtype="bf16").c().dtype == B.BF16
+    for bad in (dict(score="tanh"), dict(dtype="fp16")):
+        with pytest.raises(ValueError):
+            S.Config(T=8, d=8, E=8, k=2, F=8, D=2, **bad)
