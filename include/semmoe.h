@@ -80,8 +80,9 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *     fill whole rounds of the persistent grid, then the rest as quarter tiles over the whole chip, when at most
  *     value/16 of a round is left over (default 8); 0 = always one launch
  *   SEMMOE_TUNE_TAIL_RING: how the rest is run.  Default: 128 x 128 pieces with the loads placed between the MFMAs, in
- *     the same launch as the big tiles (a workgroup takes pieces once its tiles are done; K a multiple of 64 with at
- *     least three slices, else the next).  1: the same pieces as a second launch.  3 or 6: a second launch of
+ *     the same launch as the big tiles (a workgroup takes pieces once its tiles are done; 128 x 64 pieces instead when
+ *     so few tiles are left over that they fit the grid once; K a multiple of 64 with at least three slices, else
+ *     the next).  2: the same without the smaller pieces.  1: 128 x 128 pieces as a second launch.  3 or 6: a second launch of
  *     128 x 64 pieces with the loads of a slice issued in a burst and an LDS ring of 3 (two workgroups per compute
  *     unit) or 6 (one)
  *   SEMMOE_TUNE_ROUTE_SPLIT: bf16 router with at most 512 tokens: parts the K dimension is split into over workgroups

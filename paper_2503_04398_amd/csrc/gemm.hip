@@ -180,6 +180,7 @@ static int32_t launch_w4_split(const GemmArgs& h, int max_rows, hipStream_t stre
   t.sched_g = grid;
   t.sched_sub_t = 256 / CP::BT;
   t.sched_sub_f = 256 / CP::BW;
+  t.sched_fine = g_tune[SEMMOE_TUNE_TAIL_RING] == 2 ? 0 : 1;
   auto kern = gemm_bf16_w4_split_kernel<MODE, 64, 2, 2, 3>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -293,7 +294,7 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         GemmArgs h = a;
         h.sched_mode = 1;
         h.sched_thr = split_threshold();
-        if (id == 22 && g_tune[SEMMOE_TUNE_TAIL_RING] < 0) {  // default shape and tail: both halves in one launch
+        if (id == 22 && (g_tune[SEMMOE_TUNE_TAIL_RING] < 0 || g_tune[SEMMOE_TUNE_TAIL_RING] == 2)) {  // both halves in one launch
           const int32_t sm = launch_w4_split<kModeSwiglu>(h, max_rows, stream);
           if (sm != SEMMOE_EUNSUPPORTED) return sm;
         }
@@ -308,7 +309,7 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         GemmArgs h = a;
         h.sched_mode = 1;
         h.sched_thr = split_threshold();
-        if (id == 22 && g_tune[SEMMOE_TUNE_TAIL_RING] < 0) {
+        if (id == 22 && (g_tune[SEMMOE_TUNE_TAIL_RING] < 0 || g_tune[SEMMOE_TUNE_TAIL_RING] == 2)) {
           const int32_t sm = launch_w4_split<kModeStore>(h, max_rows, stream);
           if (sm != SEMMOE_EUNSUPPORTED) return sm;
         }

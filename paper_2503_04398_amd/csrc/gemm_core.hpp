@@ -40,6 +40,7 @@ struct GemmArgs {
   int sched_g;            // tail: grid size of the head launch
   int sched_thr;          // the split happens when at most sched_thr / 16 of a round is left over
   int sched_sub_t, sched_sub_f;  // tail: pieces per parent tile along tokens and along features
+  int sched_fine;         // tail inside the head's launch: 1 = halve the pieces along the tokens when few tiles are left
 };
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -130,10 +131,10 @@ struct TileWalk {
   int n_ftiles_list, bt_list, cutoff, total;
 };
 
-__device__ __forceinline__ TileWalk make_walk(const GemmArgs& a, int* pre, int BT, int FEAT) {
+__device__ __forceinline__ TileWalk make_walk(const GemmArgs& a, int* pre, int BT, int FEAT, int sub_t = 0) {
   TileWalk w;
   w.tail = a.sched_mode == 2;
-  w.sub_t = w.tail ? a.sched_sub_t : 1;
+  w.sub_t = w.tail ? (sub_t > 0 ? sub_t : a.sched_sub_t) : 1;  // sub_t: the kernel's own cut along the tokens
   w.sub_f = w.tail ? a.sched_sub_f : 1;
   w.n_ftiles_list = (a.N + w.sub_f * FEAT - 1) / (w.sub_f * FEAT);
   w.bt_list = w.sub_t * BT;

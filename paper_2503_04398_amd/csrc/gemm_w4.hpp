@@ -403,10 +403,16 @@ __device__ __forceinline__ void gemm_bf16_w4_body(const GemmArgs& a, unsigned ch
 // slice to land.  Pieces are independent (no stream across pieces: most workgroups get one); the output piece is
 // staged through the ring's LDS.  Needs K % 64 == 0 and K / 64 >= NSTAGE.
 // ------------------------------------------------------------------------------------------------
-template <int MODE, int NSTAGE>
-__device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned char* lds_raw) {
-  using C = DmaCfg<MODE, 2, 2, 2, 2, 64, NSTAGE>;
-  static_assert(C::IPW == 8 && C::KS == 4 && C::RB == 128, "geometry the loop below is written for");
+// TT = 2: 128 x 128 pieces (four per parent tile).  TT = 1: 128 weight rows x 64 tokens (eight per parent tile), for
+// when so few parent tiles are left over that the bigger pieces would leave most compute units idle; sub_t is then
+// the number of pieces along the tokens of a parent tile (4) in place of the launch's value.
+template <int MODE, int NSTAGE, int TT>
+__device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned char* lds_raw, int sub_t = 0) {
+  using C = DmaCfg<MODE, 2, 2, 2, TT, 64, NSTAGE>;
+  static_assert(C::KS == 4 && C::RB == 128 && C::BW == 128 && (TT == 1 || TT == 2), "geometry the loop below is written for");
+  constexpr int kIpwW = 8;       // load instructions per slice of a wave that loads weight rows (waves 0, 1: 64 rows each)
+  constexpr int kIpwX = 4 * TT;  // ... of a wave that loads token rows (waves 2, 3: 32 * TT rows each)
+  constexpr int kMfma = 2 * TT;  // MFMAs per k-step and wave
   int* pre = reinterpret_cast<int*>(lds_raw + C::kTileBytes);
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
 
@@ -415,15 +421,18 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wf = wave & 1;
   const int wt = wave >> 1;
-  const TileWalk walk = make_walk(a, pre, C::BT, C::FEAT);
+  const TileWalk walk = make_walk(a, pre, C::BT, C::FEAT, sub_t);
   const int nk = a.K / 64;
 
   const int frag_swz = ((lane & 31) / C::RPB) % C::CPR;
   const unsigned frag_w = (wf * 64 + (lane & 31)) * C::RB;
-  const unsigned frag_x = (C::BW + wt * 64 + (lane & 31)) * C::RB;
+  const unsigned frag_x = (C::BW + wt * 32 * TT + (lane & 31)) * C::RB;
   const int d_row = lane / C::CPR;
   const int d_pos = lane % C::CPR;
-  const bool loads_w = wave < 2;  // waves 0, 1: the 128 weight rows of a slice; waves 2, 3: the 128 token rows
+  const bool loads_w = wave < 2;  // waves 0, 1: the 128 weight rows of a slice; waves 2, 3: the token rows
+  const int n_my = loads_w ? kIpwW : kIpwX;  // this wave's load instructions per slice
+  // first LDS byte of this wave's rows inside a stage (an instruction fills 8 rows = 1 KB)
+  const unsigned my_rows_lds = loads_w ? wave * kIpwW * 1024 : (C::BW / 8 + (wave - 2) * kIpwX) * 1024;
 
   for (int item = xcd_worker_index(); item < walk.total; item += gridDim.x) {
     TileAt at;
@@ -432,12 +441,12 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
 
     // ---- load stream of this piece
     const unsigned char* i_base;
-    uint32_t i_off[C::IPW];
+    uint32_t i_off[kIpwW];
     if (loads_w) {
       i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.W) + size_t(widx) * a.w_group_stride);
 #pragma unroll
-      for (int i = 0; i < C::IPW; ++i) {
-        const int sr = (wave * C::IPW + i) * C::RPI + d_row;
+      for (int i = 0; i < kIpwW; ++i) {
+        const int sr = (wave * kIpwW + i) * C::RPI + d_row;
         const int c = d_pos ^ ((sr / C::RPB) % C::CPR);
         int grow;
         if constexpr (MODE == kModeSwiglu) {
@@ -452,10 +461,10 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
     } else {
       i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.X) + size_t(at.row_lo) * a.ldx);
 #pragma unroll
-      for (int i = 0; i < C::IPW; ++i) {
-        const int sr = (wave * C::IPW + i) * C::RPI + d_row;
-        const int c = d_pos ^ ((sr / C::RPB) % C::CPR);
-        i_off[i] = uint32_t(min(sr - C::BW, at.n_tok - 1)) * uint32_t(a.ldx) * 2u + uint32_t(c) * 16u;
+      for (int i = 0; i < kIpwW; ++i) {
+        const int xr = ((wave - 2) * kIpwX + min(i, kIpwX - 1)) * C::RPI + d_row;  // token row of the piece
+        const int c = d_pos ^ (((C::BW + xr) / C::RPB) % C::CPR);
+        i_off[i] = uint32_t(min(xr, at.n_tok - 1)) * uint32_t(a.ldx) * 2u + uint32_t(c) * 16u;
       }
     }
     int i_slice = 0, i_stage = 0;
@@ -469,45 +478,53 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
       ++i_slice;
       i_base += C::RB;
       i_stage = (i_stage + 1 == NSTAGE) ? 0 : i_stage + 1;
-      i_dst = lds_base + i_stage * C::kStageBytes + wave * C::IPW * 1024;
+      i_dst = lds_base + i_stage * C::kStageBytes + my_rows_lds;
     };
     auto i_issue = [&](auto idx) __attribute__((always_inline)) {
       constexpr int i = decltype(idx)::value;
-      lds_dma16_imm<i * 1024>(i_base, i_off[i], i_dst);
-      if constexpr (i == C::IPW - 1) i_next_slice();
+      if constexpr (i < kIpwX) {  // every wave
+        lds_dma16_imm<i * 1024>(i_base, i_off[i], i_dst);
+        if constexpr (i == kIpwW - 1) i_next_slice();
+        else if (i == n_my - 1) i_next_slice();
+      } else {  // only the waves that load weight rows have this many (uniform branch)
+        if (loads_w) {
+          lds_dma16_imm<i * 1024>(i_base, i_off[i], i_dst);
+          if constexpr (i == kIpwW - 1) i_next_slice();
+        }
+      }
     };
 
-    bf16x8_t af[2][2], bfr[2][2];
-    auto frag = [&](int stage, int ks, bf16x8_t(&fa)[2], bf16x8_t(&fb)[2]) __attribute__((always_inline)) {
+    bf16x8_t af[2][2], bfr[2][TT];
+    auto frag = [&](int stage, int ks, bf16x8_t(&fa)[2], bf16x8_t(&fb)[TT]) __attribute__((always_inline)) {
       const unsigned char* S = lds_raw + stage * C::kStageBytes;
       const int off = ((ks * 2 + (lane >> 5)) ^ frag_swz) * 16;
 #pragma unroll
       for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(S + frag_w + i * 32 * C::RB + off);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(S + frag_x + j * 32 * C::RB + off);
+      for (int j = 0; j < TT; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(S + frag_x + j * 32 * C::RB + off);
     };
 
     // prologue: the first NSTAGE slices; the stream then stands on slice NSTAGE-1, whose last loads are fetched
     // once more by the k-steps before the first barrier, after which it moves on
     for (int s0 = 0; s0 < NSTAGE; ++s0) {
 #pragma unroll
-      for (int i = 0; i < C::IPW; ++i)
-        lds_dma16_s(i_base + s0 * C::RB, i_off[i], lds_base + s0 * C::kStageBytes + (wave * C::IPW + i) * 1024);
+      for (int i = 0; i < kIpwW; ++i)
+        if (i < n_my) lds_dma16_s(i_base + s0 * C::RB, i_off[i], lds_base + s0 * C::kStageBytes + my_rows_lds + i * 1024);
     }
     i_base += (NSTAGE - 1) * C::RB;
     i_slice = NSTAGE - 1;
     i_stage = NSTAGE - 1;
-    i_dst = lds_base + i_stage * C::kStageBytes + wave * C::IPW * 1024;
-    wait_vmcnt<(NSTAGE - 1) * C::IPW>();
+    i_dst = lds_base + i_stage * C::kStageBytes + my_rows_lds;
+    if (loads_w) wait_vmcnt<(NSTAGE - 1) * kIpwW>(); else wait_vmcnt<(NSTAGE - 1) * kIpwX>();
     __syncthreads();
     frag(0, 0, af[0], bfr[0]);
     int c_stage = 0;
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[2][TT];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TT; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
@@ -518,7 +535,9 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
         constexpr int cur = ks & 1;
         if constexpr (ks == 3) {
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-          if (!i_done) wait_vmcnt<(NSTAGE - 2) * C::IPW>(); else wait_vmcnt<0>();
+          if (i_done) wait_vmcnt<0>();
+          else if (loads_w) wait_vmcnt<(NSTAGE - 2) * kIpwW>();
+          else wait_vmcnt<(NSTAGE - 2) * kIpwX>();
           __syncthreads();
         }
         // the four fragment reads of the next k-step go out one by one behind the MFMAs
@@ -526,19 +545,22 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
         const int off_next = ((((ks == 3) ? 0 : ks + 1) * 2 + (lane >> 5)) ^ frag_swz) * 16;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < TT; ++j) {
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
             {
+              // the 2 + TT fragment reads of the next k-step, spread over this k-step's 2 * TT MFMAs
               const int p = j * 2 + i;  // constant after unrolling
               if (p < 2)
                 af[cur ^ 1][p] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_w + p * 32 * C::RB + off_next);
               else
                 bfr[cur ^ 1][p - 2] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_x + (p - 2) * 32 * C::RB + off_next);
+              if (TT == 1 && p == 1)  // two MFMAs, three reads: the token fragment goes with the second
+                bfr[cur ^ 1][0] = *reinterpret_cast<const bf16x8_t*>(S_next + frag_x + off_next);
             }
             // window position = MFMAs since the barrier; a load after each of the first eight
-            const int m = ((ks == 3) ? 0 : (ks + 1) * 4) + j * 2 + i;  // constant after unrolling
+            const int m = ((ks == 3) ? 0 : (ks + 1) * kMfma) + j * 2 + i;  // constant after unrolling
             switch (m) {
 #define SEMMOE_PIECE_CASE(n) case n: i_issue(std::integral_constant<int, n>{}); break;
               SEMMOE_PIECE_CASE(0) SEMMOE_PIECE_CASE(1) SEMMOE_PIECE_CASE(2) SEMMOE_PIECE_CASE(3)
@@ -558,7 +580,7 @@ __device__ __forceinline__ void gemm_bf16_piece_body(const GemmArgs& a, unsigned
     }
     wait_vmcnt<0>();   // the standing stream's last loads: nothing may write into the ring any more
     __syncthreads();   // every wave has left the ring: it now takes the output piece
-    store_tile_via_lds<MODE, 2, 2, 2, 2>(acc, lds_raw, a, at.row_lo, at.n_tok, at.f0, wf, wt);
+    store_tile_via_lds<MODE, 2, 2, 2, TT>(acc, lds_raw, a, at.row_lo, at.n_tok, at.f0, wf, wt);
     __syncthreads();   // the next piece's loads overwrite the staged piece
   }
 }
@@ -572,7 +594,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
 template <int MODE, int NSTAGE>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  gemm_bf16_piece_body<MODE, NSTAGE>(a, lds_raw);
+  gemm_bf16_piece_body<MODE, NSTAGE, 2>(a, lds_raw);
 }
 
 // Head and tail of a split in one launch: every workgroup first works through its 256 x 256 tiles of the full rounds,
@@ -584,7 +606,14 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_split_kernel(GemmArgs hea
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   gemm_bf16_w4_body<MODE, BK, NSTAGE, DMA_EVERY>(head, lds_raw);
   __syncthreads();  // the head's last output staging has been read
-  gemm_bf16_piece_body<MODE, PIECE_RING>(tail, lds_raw);
+  // few parent tiles left over: 128 x 64 pieces, eight per parent tile, so that twice as many compute units take part
+  // (a piece walks all of K however few there are: its time does not shrink with their number)
+  const TileWalk probe = make_walk(tail, reinterpret_cast<int*>(lds_raw), 128, (MODE == kModeSwiglu) ? 64 : 128);
+  __syncthreads();
+  if (tail.sched_fine && probe.total > 0 && probe.total * 2 <= int(gridDim.x))
+    gemm_bf16_piece_body<MODE, PIECE_RING, 1>(tail, lds_raw, 4);
+  else
+    gemm_bf16_piece_body<MODE, PIECE_RING, 2>(tail, lds_raw);
 }
 
 }  // namespace semmoe
