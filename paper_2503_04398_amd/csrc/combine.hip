@@ -15,7 +15,7 @@ __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
 }
 
 template <bool BF16, int KU>
-__global__ __launch_bounds__(256) void combine_kernel(int k, int row_chunks, int P, const uint4* __restrict__ Y,
+__global__ __launch_bounds__(512) void combine_kernel(int k, int row_chunks, int P, const uint4* __restrict__ Y,
                                                       const int32_t* __restrict__ slot_of_pair,
                                                       const float* __restrict__ topk_w,
                                                       const uint4* __restrict__ Y_shared, uint4* __restrict__ Out) {
@@ -100,12 +100,13 @@ template <bool BF16>
 static void launch_combine(int k, int T, int row_chunks, hipStream_t s, const uint4* Y, const int32_t* slot,
                            const float* w, const uint4* Ysh, uint4* Out) {
   const int P = T * k;
+  const int threads = row_walk_threads(row_chunks);
   // k rounded up to the next unrolled width; the kernel skips the slots beyond k
-  if (k <= 1) hipLaunchKernelGGL((combine_kernel<BF16, 1>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
-  else if (k <= 2) hipLaunchKernelGGL((combine_kernel<BF16, 2>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
-  else if (k <= 4) hipLaunchKernelGGL((combine_kernel<BF16, 4>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
-  else if (k <= 8) hipLaunchKernelGGL((combine_kernel<BF16, 8>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
-  else hipLaunchKernelGGL((combine_kernel<BF16, 16>), dim3(T), dim3(256), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  if (k <= 1) hipLaunchKernelGGL((combine_kernel<BF16, 1>), dim3(T), dim3(threads), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else if (k <= 2) hipLaunchKernelGGL((combine_kernel<BF16, 2>), dim3(T), dim3(threads), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else if (k <= 4) hipLaunchKernelGGL((combine_kernel<BF16, 4>), dim3(T), dim3(threads), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else if (k <= 8) hipLaunchKernelGGL((combine_kernel<BF16, 8>), dim3(T), dim3(threads), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
+  else hipLaunchKernelGGL((combine_kernel<BF16, 16>), dim3(T), dim3(threads), 0, s, k, row_chunks, P, Y, slot, w, Ysh, Out);
 }
 
 }  // namespace semmoe

@@ -31,6 +31,24 @@ int32_t validate_config(const semmoe_config* cfg, bool need_T, bool need_rows, b
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Threads of a workgroup that walks one row of `row_chunks` 16-byte chunks, a chunk per thread and pass: whole waves,
+// at most 512 threads, and the count that leaves the fewest lanes without a chunk (896 chunks: 448 threads x 2 passes
+// instead of 256 x 3.5; 360 chunks: 384 x 1 instead of 256 x 1.4).
+inline int row_walk_threads(int row_chunks) {
+  int best = 256, best_waste = 1 << 30;
+  for (int passes = 1; passes <= 8; ++passes) {
+    int th = cdiv(cdiv(row_chunks, passes), 64) * 64;
+    if (th > 512) continue;
+    if (th < 64) th = 64;
+    const int waste = th * passes - row_chunks;
+    if (waste < best_waste) {
+      best_waste = waste;
+      best = th;
+    }
+  }
+  return best;
+}
 inline size_t act_bytes(const semmoe_config* cfg) { return cfg->dtype == SEMMOE_BF16 ? 2 : 4; }
 
 // Sequential carving of the caller's workspace.

@@ -341,7 +341,7 @@ static size_t dp_single_lds(int E, int D) {
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int K_UNROLL>
-__global__ __launch_bounds__(256) void dp_rows_kernel(int k, int row_chunks, int P, const u32x4_t* __restrict__ X,
+__global__ __launch_bounds__(512) void dp_rows_kernel(int k, int row_chunks, int P, const u32x4_t* __restrict__ X,
                                                       const int32_t* __restrict__ slot_of_pair,
                                                       u32x4_t* __restrict__ X_perm) {
   const int tok = blockIdx.x;
@@ -435,12 +435,13 @@ static int32_t dispatch_rows_impl(const semmoe_config* cfg, hipStream_t s, const
   const u32x4_t* Xv = static_cast<const u32x4_t*>(X);
   u32x4_t* Xp = static_cast<u32x4_t*>(X_perm);
   const int P = T * k;
+  const int threads = row_walk_threads(row_chunks);
   switch (k) {
-    case 1: hipLaunchKernelGGL(dp_rows_kernel<1>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-    case 2: hipLaunchKernelGGL(dp_rows_kernel<2>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-    case 4: hipLaunchKernelGGL(dp_rows_kernel<4>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-    case 8: hipLaunchKernelGGL(dp_rows_kernel<8>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
-    default: hipLaunchKernelGGL(dp_rows_kernel<0>, dim3(T), dim3(256), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 1: hipLaunchKernelGGL(dp_rows_kernel<1>, dim3(T), dim3(threads), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 2: hipLaunchKernelGGL(dp_rows_kernel<2>, dim3(T), dim3(threads), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 4: hipLaunchKernelGGL(dp_rows_kernel<4>, dim3(T), dim3(threads), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    case 8: hipLaunchKernelGGL(dp_rows_kernel<8>, dim3(T), dim3(threads), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
+    default: hipLaunchKernelGGL(dp_rows_kernel<0>, dim3(T), dim3(threads), 0, s, k, row_chunks, P, Xv, slot_of_pair, Xp); break;
   }
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
