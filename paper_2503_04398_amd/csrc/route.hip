@@ -963,8 +963,11 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
       logits_ws = c.take<float>(size_t(cfg->T) * cfg->E);
       if (!c.ok) return SEMMOE_EWORKSPACE;
     }
+    // tokens per workgroup: as many as still give every compute unit a tile (every workgroup streams all of W_r past its
+    // tokens, so W_r traffic per token falls with the tile): 128 (up to 128 experts), 64 (up to 256), else 32
     const bool wide = n_parts == 1 && cdiv(cfg->T, 64) >= 256 && tf <= 2;
-    const int bt = wide ? 64 : 32;
+    const bool wider = wide && tf == 1 && cdiv(cfg->T, 128) >= 256;
+    const int bt = wider ? 128 : (wide ? 64 : 32);
     int dev = 0, ncu = 256;
     SEMMOE_HIP(hipGetDevice(&dev));
     SEMMOE_HIP(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
@@ -1009,7 +1012,9 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     }                                                                                                               \
   } while (0)
     if (tf == 1) {
-      if (wide) SEMMOE_ROUTE_FORMS_128(1, 2, 5); else SEMMOE_ROUTE_FORMS_128(1, 1, 6);
+      if (wider) SEMMOE_ROUTE_FORMS_128(1, 4, 4);
+      else if (wide) SEMMOE_ROUTE_FORMS_128(1, 2, 5);
+      else SEMMOE_ROUTE_FORMS_128(1, 1, 6);
     } else if (tf == 2) {
       if (wide) SEMMOE_ROUTE_FORMS_256(2, 2, 3); else SEMMOE_ROUTE_FORMS_256(2, 1, 4);
     } else {

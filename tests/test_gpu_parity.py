@@ -84,10 +84,12 @@ def test_route_from_logits_sigmoid_group_limited(E, k, T, ng, tg, scale, bias):
     ("fp32", 200, 72, 16, 2, -1), ("bf16", 333, 200, 128, 8, -1), ("bf16", 333, 200, 128, 8, 0),
     ("bf16", 130, 64, 24, 3, -1), ("fp32", 64, 512, 16, 2, -1), ("bf16", 257, 1032, 256, 8, -1),
     ("bf16", 257, 1032, 256, 8, 0), ("bf16", 100, 4096, 128, 8, 5), ("bf16", 40, 512, 384, 6, 3),
-    ("bf16", 700, 256, 64, 4, -1), ("bf16", 512, 2048, 128, 8, 16)])
+    ("bf16", 700, 256, 64, 4, -1), ("bf16", 512, 2048, 128, 8, 16), ("bf16", 16400, 136, 64, 4, -1),
+    ("bf16", 16390, 72, 256, 8, -1), ("bf16", 32800, 72, 128, 8, -1)])
 def test_route_gemm_and_selection(dtype, T, d, E, k, split):
     """router GEMM + selection; split: the few-token router's parts of K (-1 the library's choice, 0 the fused
-    kernel, n forced; T = 700 is above the few-token limit and always fused)"""
+    kernel, n forced; T = 700 is above the few-token limit and always fused).  From 16384 tokens on a workgroup
+    takes 64 tokens, from 32768 on (up to 128 experts) 128: the last three cases, with ragged last tiles"""
     _say("route", dtype, T, d, E, k, "split", split)
     w = WL.small(T=T, d=d, E=E, k=k, D=1, C=4, dtype=dtype)
     inp = H.make_inputs(w)
