@@ -331,6 +331,18 @@ def main():
     stage_ms = {name: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps
                 for i, name in enumerate(stages)}
 
+    # ---------------- the FFN of every rank's experts in one call (the whole device's expert work, not one rank's share)
+    for _ in range(2):
+        m.expert_ffn(-1, X_perm, expert_offsets, inv, W_gu, W_down, Y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        m.expert_ffn(-1, X_perm, expert_offsets, inv, W_gu, W_down, Y)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_ffn_all = e0.elapsed_time(e1) / 10
+
     # ---------------- what the batch looked like
     ro = rank_offsets.cpu().numpy()
     rows_ffn = int(ro[D] - ro[0]) if args.all_ranks else int(ro[1] - ro[0])
@@ -569,6 +581,10 @@ def main():
                    "cap": w.cap, "ffn_rows": rows_ffn},
         "roofline": roofline,
         "stages": roof,
+        "expert_ffn_all_ranks": {"ms": round(ms_ffn_all, 4), "rows": P,
+                                 ("TFLOP/s" if w.dtype == "bf16" else "TFLOP/s_fp32"): round(6.0 * d * F * P / (ms_ffn_all * 1e-3) / 1e12, 2),
+                                 "frac": round(6.0 * d * F * P / (ms_ffn_all * 1e-3) / 1e12 /
+                                               (MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS), 4)},
         "ms_per_step_with_stage_events": round(ms_evented, 4),
         "ms_per_step_graph_replay": None if ms_graph is None else round(ms_graph, 4),
         "remote_pair_fraction": {"vanilla_placement_home_ranks": round(int(rp2.item()) / P, 4),
