@@ -97,6 +97,14 @@ def achievable_peaks(m, torch, dev):
             flops[0] = m.probe_mfma(ops, iters, sink)
         t = timed(run, 5)
         out["mfma_only_%s_operands_TFLOPs" % name] = round(flops[0] / t / 1e12, 1)
+    # the vendor library's plain square bf16 GEMM on random data (torch.matmul -> hipBLASLt / rocBLAS): a reference
+    # for what a dense GEMM sustains on this chip, not part of the path
+    n = 8192
+    a = (torch.randn(n, n, device=dev) * 0.02).to(torch.bfloat16)
+    b = torch.randn(n, n, device=dev).to(torch.bfloat16)
+    c = torch.empty(n, n, dtype=torch.bfloat16, device=dev)
+    t = timed(lambda: torch.matmul(a, b, out=c), 5)
+    out["library_square_bf16_gemm_8192_TFLOPs"] = round(2.0 * n ** 3 / t / 1e12, 1)
     return out
 
 
