@@ -21,6 +21,7 @@ Which passage each function follows
   place                        Alg. 1 `expert_place` (+ App. B text), request term dropped
   reshuffle                    Alg. 3 `rebatch_tokens` (argsort, group, align, concat)
   reshuffle_rounds             the same with gain-aware spill rounds (towards the Sec. 3.3 optimum)
+  reshuffle_refine             the same followed by moves of placed tokens until the Sec. 3.3 optimum is reached
   token_expert_table / lookup_tables / reshuffle_lookup
                                token-to-expert activation table and confidence (Sec. 3.2), the
                                schedule table T / T_p, and Alg. 3 `rebatch_tokens` driven by it
@@ -46,7 +47,9 @@ Pins (tests/test_oracle_*.py): brute force on tiny inputs, closed forms,
 library argsort / matmul special cases, the 1/D local-activation rate of
 class-free routing (the ~25 % baseline of Tables 3-4 at D = 4), planted-cluster
 recovery; for the rows built on top: spill rounds - hand example, round one = the
-greedy, greedy <= rounds <= optimum; table-driven rebatch - counts, hand example,
+greedy, greedy <= rounds <= optimum; moves of placed tokens - hand examples of an exchange, a rotation over
+three ranks, a move into free room and of which walk and tokens are taken, the optimum of the
+min-cost flow and of brute force, the budget of cycles; table-driven rebatch - counts, hand example,
 threshold extremes, one key per token = the rebatch on the actual top-k; request
 scheduling - hand example with mask and reset, the request-to-cluster rule where
 the mask cannot bite, every round reaches every rank, brute force over the unmasked
@@ -423,6 +426,101 @@ def reshuffle_rounds(ids, expert_to_rank, D: int, cap: int, rounds: int):
     rank_count = np.bincount(token_rank, minlength=D)
     return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
             rank_count.astype(np.int32))
+
+
+def reshuffle_refine(ids, expert_to_rank, D: int, cap: int, max_cycles: int = 1 << 30, rounds: int = 1, start=None):
+    """`reshuffle_rounds` (rounds = 1: `reshuffle`), then moves of already placed tokens until no
+    assignment under the capacity bound has more local pairs (the communication term of the
+    Sec. 3.3 objective for a fixed placement; `align` of Alg. 3 as the bound).  An assignment is
+    optimal exactly when its residual graph has no closed walk of positive gain, so such walks
+    are cancelled one by one.  `start`, if given, is the assignment to begin with instead.
+
+    Nodes: the D ranks and a node Z that stands for free room.  Arcs, for the current assignment:
+      a -> b (ranks, a != b)  w = max over the tokens i on a of g[i,b] - g[i,a]  (absent if a is empty)
+      a -> Z                  w = 0, present when a holds fewer than cap tokens
+      Z -> b                  w = 0
+    best_1 = w;  best_L[u][v] = max_x best_{L-1}[u][x] + w[x][v]  (walks of exactly L arcs).
+    One cycle: take the smallest L in 2 .. D+1 for which some best_L[u][u] > 0 (a closed walk
+    of that least length visits no node twice); u0 = the smallest u with the largest
+    best_L[u][u]; walk back from u0, at every step to the smallest x with
+    best_{l-1}[u0][x] + w[x][v] = best_l[u0][v].  n(a -> b) = number of tokens on a that attain
+    w[a][b]; n(a -> Z) = cap - tokens on a; m = the least n over the arcs of the walk that leave
+    a rank.  On every arc a -> b between ranks the m tokens of smallest index among those that
+    attain w[a][b] move to b.  Every cycle adds at least m >= 1 local pairs, so the loop ends.
+
+    Stops when no such walk is left (converged) or after `max_cycles` cycles.  Returns
+    (token_rank, shf, inv_shf, rank_count) int32, cycles applied, converged (bool)."""
+    ids = np.asarray(ids)
+    T = ids.shape[0]
+    assert cap * D >= T and max_cycles >= 0
+    if start is None:
+        token_rank = reshuffle_rounds(ids, expert_to_rank, D, cap, rounds)[0].astype(np.int64)
+    else:
+        token_rank = np.array(start, dtype=np.int64)
+        assert token_rank.shape == (T,) and np.bincount(token_rank, minlength=D).max() <= cap
+    g = gain_matrix(ids, expert_to_rank, D)
+    N, Z = D + 1, D
+    cycles, converged = 0, False
+    while True:
+        on = [np.flatnonzero(token_rank == a) for a in range(D)]
+        w = [[None] * N for _ in range(N)]
+        for a in range(D):
+            for b in range(D):
+                if a != b and len(on[a]) > 0:
+                    w[a][b] = int((g[on[a], b] - g[on[a], a]).max())
+            if len(on[a]) < cap:
+                w[a][Z] = 0
+            w[Z][a] = 0
+        best = {1: w}
+        found, u0 = None, None
+        for L in range(2, N + 1):
+            cur = [[None] * N for _ in range(N)]
+            for u in range(N):
+                for v in range(N):
+                    sums = [best[L - 1][u][x] + w[x][v] for x in range(N)
+                            if best[L - 1][u][x] is not None and w[x][v] is not None]
+                    if sums:
+                        cur[u][v] = max(sums)
+            best[L] = cur
+            diag = [cur[u][u] for u in range(N)]
+            have = [d for d in diag if d is not None]
+            if have and max(have) > 0:
+                found, u0 = L, diag.index(max(have))
+                break
+        if found is None:
+            converged = True
+            break
+        if cycles == max_cycles:
+            break
+        walk, v = [u0], u0
+        for l in range(found, 1, -1):
+            x = min(x for x in range(N)
+                    if best[l - 1][u0][x] is not None and w[x][v] is not None
+                    and best[l - 1][u0][x] + w[x][v] == best[l][u0][v])
+            walk.append(x)
+            v = x
+        walk.append(u0)
+        walk.reverse()
+        movers, m = [], None
+        for a, b in zip(walk[:-1], walk[1:]):
+            if a == Z:
+                continue
+            if b == Z:
+                n = cap - len(on[a])
+            else:
+                sel = on[a][(g[on[a], b] - g[on[a], a]) == w[a][b]]
+                movers.append((b, sel))
+                n = len(sel)
+            m = n if m is None else min(m, n)
+        for b, sel in movers:
+            token_rank[sel[:m]] = b
+        cycles += 1
+    shf = np.argsort(token_rank, kind="stable")
+    inv_shf = np.zeros(T, dtype=np.int64)
+    inv_shf[shf] = np.arange(T)
+    rank_count = np.bincount(token_rank, minlength=D)
+    return (token_rank.astype(np.int32), shf.astype(np.int32), inv_shf.astype(np.int32),
+            rank_count.astype(np.int32)), cycles, converged
 
 
 # --------------------------------------------------------------------------------------------
