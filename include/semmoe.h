@@ -256,6 +256,28 @@ int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const in
                                 int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes);
 
 /*
+ * reshuffle refined to the optimum - `semmoe_reshuffle_rounds`, then moves of already placed tokens until no
+ * assignment under the capacity bound has more local pairs: the communication term of the Sec. 3.3 objective for a
+ * fixed placement, with `align` of Alg. 3 as the bound.  An assignment is optimal exactly when its residual graph has
+ * no closed walk of positive gain; the graph has the D ranks and a node Z for free room as nodes and
+ *   a -> b (ranks)  w = max over the tokens i on a of g[i,b] - g[i,a];   a -> Z  w = 0 while a holds fewer than cap
+ *   tokens;   Z -> b  w = 0.
+ * One cycle: best_L[u][v] = the best walk of exactly L arcs; the smallest L in 2 .. D+1 with some best_L[u][u] > 0 (a
+ * closed walk of least length visits no node twice), u0 = the smallest u with the largest best_L[u][u], walked back
+ * through the smallest predecessor that attains the best at every step; m = the least, over the arcs that leave a
+ * rank, of the number of tokens that attain the arc (free slots for an arc into Z); on every arc between ranks the m
+ * tokens of smallest index that attain it move.  Stops when no such walk is left or after `max_cycles` cycles.
+ * One workgroup holds all tokens in registers, so T <= 32768, D <= 8, k <= 15 (SEMMOE_EUNSUPPORTED beyond); five
+ * launches on top of the starting assignment's.  rounds >= 1, max_cycles >= 0 (0: the starting assignment).
+ * dev in / out as `semmoe_reshuffle`; dev out: info[2] i32 = cycles applied, 1 if no walk of positive gain is left
+ * (the assignment is optimal) else 0.
+ */
+int32_t semmoe_reshuffle_refine(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                const int32_t* expert_to_rank, int32_t rounds, int32_t max_cycles, int32_t* token_rank,
+                                int32_t* shf, int32_t* inv_shf, int32_t* rank_count, int32_t* info, void* ws,
+                                size_t ws_bytes);
+
+/*
  * reshuffle from the schedule table - Alg. 3 `rebatch_tokens` as it runs before the gate: the device id of a token is
  * looked up by its key, dev_ids = cond(T_p[B] > A_p[B], T[B], A[B]).  This form has no inter-layer table A: its
  * device is the token's home shard and its confidence A_p the constant thr_q16 (in 1/65536);

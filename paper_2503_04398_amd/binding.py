@@ -103,6 +103,7 @@ _SIGS = {
     "semmoe_token_labels": ([_P, _P, C.c_int32, _P, _P, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
+    "semmoe_reshuffle_refine": ([_P] * 4 + [C.c_int32, C.c_int32] + [_P] * 6 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_lookup": ([_P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_cond": ([_P, _P, _P, C.c_int32, _P, _P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5
                               + [C.c_size_t], C.c_int32),
@@ -288,6 +289,13 @@ class SemMoE:
         self._check("semmoe_reshuffle_rounds", self.lib.semmoe_reshuffle_rounds(
             C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), int(rounds), _ptr(token_rank), _ptr(shf),
             _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def reshuffle_refine(self, topk_ids, expert_to_rank, rounds, max_cycles, token_rank, shf, inv_shf, rank_count,
+                         info, cap=None):
+        c = self._cfg(**({"cap": cap} if cap is not None else {}))
+        self._check("semmoe_reshuffle_refine", self.lib.semmoe_reshuffle_refine(
+            C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), int(rounds), int(max_cycles),
+            _ptr(token_rank), _ptr(shf), _ptr(inv_shf), _ptr(rank_count), _ptr(info), _ptr(self.ws), self.ws_bytes))
 
     def reshuffle_lookup(self, token_key, V, dev, conf_q16, level, thr_q16, token_rank, shf, inv_shf, rank_count,
                          cap=None):

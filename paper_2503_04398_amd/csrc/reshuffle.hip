@@ -871,6 +871,298 @@ __global__ __launch_bounds__(kChunk) void rs_single_kernel(int T, int k, int D, 
   }
 }
 
+// ---- moves of placed tokens until the assignment has the most local pairs the capacity bound allows ----------------
+// (communication term of the Sec. 3.3 objective for a fixed placement; `align` of Alg. 3 as the bound.)  An assignment
+// is optimal exactly when its residual graph has no closed walk of positive gain.  The graph is tiny: the D ranks and a
+// node Z for free room; arc a -> b carries the best gain g[i,b] - g[i,a] of a token on a, a -> Z exists while a has
+// room, Z -> b always.  One workgroup holds every token in registers (its gains as one nibble per rank, its rank) and
+// a histogram hist[a][b][gain] in LDS that is updated only for the tokens that move.  Per cycle: arcs from the
+// histogram, walks of exactly L arcs by max-plus products until a diagonal entry is positive (such a closed walk of
+// least length visits no rank twice), the walk back, a workgroup-wide count of the tokens that attain each arc in
+// token order, and the move of the first m of them on every arc.  All integer, no atomic's order reaches an output.
+constexpr int kRefThreads = 1024;
+constexpr int kRefMaxD = 8;
+constexpr int kRefMaxK = 15;
+constexpr int kRefNodes = kRefMaxD + 1;
+constexpr int kRefNone = -(1 << 28);  // arc or walk that does not exist
+constexpr int kRefMaxT = kRefThreads * 32;
+
+__global__ __launch_bounds__(kTokBlock) void rs_gain_kernel(int T, int k, int D, int E,
+                                                            const int32_t* __restrict__ ids,
+                                                            const int32_t* __restrict__ e2r,
+                                                            int32_t* __restrict__ gain_word) {
+  const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  int r[SEMMOE_MAX_K];
+  load_mapped_ids(ids + size_t(min(i, T - 1)) * k, i < T, k, E, e2r, D, r);
+  if (i < T) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int j = 0; j < SEMMOE_MAX_K; ++j)
+      if (r[j] >= 0) w += 1u << (4 * r[j]);
+    gain_word[i] = int32_t(w);
+  }
+}
+
+struct RefineLds {
+  int32_t hist[kRefMaxD * kRefMaxD * (2 * kRefMaxK + 1)];  // [a][b][gain + k]: tokens on a by their gain of moving to b
+  int32_t cnt[kRefMaxD];                                   // tokens per rank
+  int32_t w[kRefNodes * kRefNodes];                        // arcs
+  int32_t n[kRefNodes * kRefNodes];                        // tokens that attain the arc (a -> Z: free slots of a)
+  int32_t best[kRefNodes + 1][kRefNodes * kRefNodes];      // best[L][u][v]: walks of exactly L arcs
+  int32_t walk[kRefNodes + 1];
+  int32_t m, n_arcs;
+  int32_t arc_a[kRefNodes], arc_b[kRefNodes];
+  uint32_t tgt_of, arc_of;       // per rank (nibble): target of the arc that leaves it (15: none), its index
+  unsigned long long gain_of;    // per rank (byte): gain + k of that arc
+  unsigned long long wave_tot[2][kRefThreads / 64];
+};
+
+__device__ __forceinline__ int gain_nibble(uint32_t g, int r) { return int((g >> (4 * r)) & 15u); }
+
+template <int TPT>
+__global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, int D, int cap, int max_cycles,
+                                                                const int32_t* __restrict__ gain_word,
+                                                                int32_t* __restrict__ token_rank,
+                                                                int32_t* __restrict__ info) {
+  __shared__ RefineLds L;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int N = D + 1, Z = D, NG = 2 * k + 1;
+  static_assert(TPT % 8 == 0 && TPT <= 32, "ranks are kept eight to a register, the movers of a thread in one mask");
+  uint32_t g[TPT];        // gains, one nibble per rank
+  uint32_t rkp[TPT / 8];  // ranks, one nibble per token (15: no token)
+#pragma unroll
+  for (int t8 = 0; t8 < TPT / 8; ++t8) rkp[t8] = 0;
+#pragma unroll
+  for (int t = 0; t < TPT; ++t) {
+    const int i = tid * TPT + t;
+    const int ii = min(i, T - 1);
+    const uint32_t gv = uint32_t(gain_word[ii]);
+    const int rv = token_rank[ii];
+    g[t] = i < T ? gv : 0u;
+    rkp[t >> 3] |= ((i < T && (unsigned)rv < (unsigned)D) ? uint32_t(rv) : 15u) << (4 * (t & 7));
+  }
+  auto rank_of = [&](int t) __attribute__((always_inline)) { return int((rkp[t >> 3] >> (4 * (t & 7))) & 15u); };
+  for (int x = tid; x < D * D * NG; x += kRefThreads) L.hist[x] = 0;
+  if (tid < kRefMaxD) L.cnt[tid] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < TPT; ++t) {
+    const int a = rank_of(t);
+    if (a == 15) continue;
+    atomicAdd(&L.cnt[a], 1);
+    const int ga = gain_nibble(g[t], a);
+#pragma unroll
+    for (int b = 0; b < kRefMaxD; ++b)
+      if (b < D && b != a) atomicAdd(&L.hist[(a * D + b) * NG + gain_nibble(g[t], b) - ga + k], 1);
+  }
+  __syncthreads();
+
+  int cycles = 0, converged = 0;
+  for (;;) {
+    // The gains never change, so the compiler would extract every nibble of every token once, in front of this
+    // loop, and keep them all in registers: eight values per token.  Make the words opaque once per cycle.
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) asm volatile("" : "+v"(g[t]));
+    // arcs of the residual graph
+    if (tid < N * N) {
+      const int a = tid / N, b = tid % N;
+      int wv = kRefNone, nv = 0;
+      if (a < D && b < D && a != b) {
+        for (int d = NG - 1; d >= 0; --d) {
+          const int c = L.hist[(a * D + b) * NG + d];
+          if (c > 0) {
+            wv = d - k;
+            nv = c;
+            break;
+          }
+        }
+      } else if (a < D && b == Z) {
+        const int c = L.cnt[a];
+        if (c < cap) {
+          wv = 0;
+          nv = cap - c;
+        }
+      } else if (a == Z && b < D) {
+        wv = 0;
+        nv = 0x7fffffff;
+      }
+      L.w[tid] = wv;
+      L.n[tid] = nv;
+      L.best[1][tid] = wv;
+    }
+    __syncthreads();
+    // shortest closed walk of positive gain
+    int found = 0, u0 = 0;
+    for (int len = 2; len <= N; ++len) {
+      if (tid < N * N) {
+        const int u = tid / N, v = tid % N;
+        int bv = kRefNone;
+        for (int x = 0; x < N; ++x) {
+          const int p = L.best[len - 1][u * N + x], q = L.w[x * N + v];
+          if (p > kRefNone / 2 && q > kRefNone / 2) bv = max(bv, p + q);
+        }
+        L.best[len][tid] = bv;
+      }
+      __syncthreads();
+      int top = 0;  // every thread reads the same diagonal: the decision is uniform
+      for (int u = 0; u < N; ++u) {
+        const int d = L.best[len][u * N + u];
+        if (d > top) {
+          top = d;
+          u0 = u;
+        }
+      }
+      if (top > 0) {
+        found = len;
+        break;
+      }
+    }
+    found = __builtin_amdgcn_readfirstlane(found);
+    u0 = __builtin_amdgcn_readfirstlane(u0);
+    if (found == 0) {
+      converged = 1;
+      break;
+    }
+    if (cycles >= max_cycles || cycles > T * k) break;  // every cycle adds a local pair: T*k bounds them
+    if (tid == 0) {
+      // walk back from u0: at every step the smallest predecessor that attains the best walk
+      int v = u0;
+      L.walk[found] = u0;
+      for (int l = found; l >= 2; --l) {
+        int pick = 0;
+        for (int x = N - 1; x >= 0; --x) {
+          const int p = L.best[l - 1][u0 * N + x], q = L.w[x * N + v];
+          if (p > kRefNone / 2 && q > kRefNone / 2 && p + q == L.best[l][u0 * N + v]) pick = x;
+        }
+        L.walk[l - 1] = pick;
+        v = pick;
+      }
+      L.walk[0] = u0;
+      int m = 0x7fffffff, na = 0;
+      uint32_t tgt_of = 0xffffffffu, arc_of = 0;
+      unsigned long long gain_of = 0;
+      for (int s = 0; s < found; ++s) {
+        const int a = L.walk[s], b = L.walk[s + 1];
+        if (a == Z) continue;
+        m = min(m, L.n[a * N + b]);
+        if (b != Z) {
+          L.arc_a[na] = a;
+          L.arc_b[na] = b;
+          tgt_of = (tgt_of & ~(15u << (4 * a))) | (uint32_t(b) << (4 * a));
+          arc_of |= uint32_t(na) << (4 * a);
+          gain_of |= (unsigned long long)(L.w[a * N + b] + k) << (8 * a);
+          ++na;
+        }
+      }
+      L.m = m;
+      L.n_arcs = na;
+      L.tgt_of = tgt_of;
+      L.arc_of = arc_of;
+      L.gain_of = gain_of;
+    }
+    __syncthreads();
+    const int m = L.m, na = L.n_arcs;
+    if (m <= 0) {  // cannot happen while the histogram matches the tokens; never spin on it
+      converged = -1;
+      break;
+    }
+    const uint32_t tgt_of = L.tgt_of, arc_of = L.arc_of;
+    const unsigned long long gain_of = L.gain_of;
+    // the tokens that attain the arc leaving their rank; per arc a 16-bit count (at most 32768 tokens)
+    uint32_t mine = 0;
+    unsigned long long c_lo = 0, c_hi = 0;
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) {
+      const int a = rank_of(t) & 7;
+      const int b = int((tgt_of >> (4 * a)) & 15u);
+      const int want = int((gain_of >> (8 * a)) & 255ull) - k;
+      const bool hit = rank_of(t) != 15 && b != 15 && gain_nibble(g[t], b & 7) - gain_nibble(g[t], a) == want;
+      if (hit) {
+        const int e = int((arc_of >> (4 * a)) & 15u);
+        const unsigned long long one = 1ull << (16 * (e & 3));
+        mine |= 1u << t;
+        if (e < 4) c_lo += one;
+        else c_hi += one;
+      }
+    }
+    unsigned long long i_lo = c_lo, i_hi = c_hi;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const unsigned long long t_lo = __shfl_up(i_lo, off);
+      const unsigned long long t_hi = __shfl_up(i_hi, off);
+      if (lane >= off) {
+        i_lo += t_lo;
+        i_hi += t_hi;
+      }
+    }
+    if (lane == 63) {
+      L.wave_tot[0][wave] = i_lo;
+      L.wave_tot[1][wave] = i_hi;
+    }
+    __syncthreads();
+    unsigned long long o_lo = i_lo - c_lo, o_hi = i_hi - c_hi;  // tokens before this thread's, per arc
+    for (int w2 = 0; w2 < wave; ++w2) {
+      o_lo += L.wave_tot[0][w2];
+      o_hi += L.wave_tot[1][w2];
+    }
+#pragma unroll
+    for (int t = 0; t < TPT; ++t) {
+      if (!((mine >> t) & 1u)) continue;
+      const int a = rank_of(t);
+      const int b = int((tgt_of >> (4 * a)) & 15u);
+      const int e = int((arc_of >> (4 * a)) & 15u);
+      const int sh = 16 * (e & 3);
+      const int ord = int(((e < 4 ? o_lo : o_hi) >> sh) & 0xffffull);
+      if (e < 4) o_lo += 1ull << sh;
+      else o_hi += 1ull << sh;
+      if (ord >= m) continue;
+      const int ga = gain_nibble(g[t], a), gb = gain_nibble(g[t], b);
+#pragma unroll
+      for (int s = 0; s < kRefMaxD; ++s) {
+        if (s >= D) continue;
+        const int gs = gain_nibble(g[t], s);
+        if (s != a) atomicSub(&L.hist[(a * D + s) * NG + gs - ga + k], 1);
+        if (s != b) atomicAdd(&L.hist[(b * D + s) * NG + gs - gb + k], 1);
+      }
+      rkp[t >> 3] = (rkp[t >> 3] & ~(15u << (4 * (t & 7)))) | (uint32_t(b) << (4 * (t & 7)));
+    }
+    if (tid < na) {
+      atomicSub(&L.cnt[L.arc_a[tid]], m);
+      atomicAdd(&L.cnt[L.arc_b[tid]], m);
+    }
+    ++cycles;
+    __syncthreads();
+  }
+#pragma unroll
+  for (int t = 0; t < TPT; ++t) {
+    const int i = tid * TPT + t;
+    if (i < T && rank_of(t) != 15) token_rank[i] = rank_of(t);
+  }
+  if (tid == 0) {
+    info[0] = cycles;
+    info[1] = converged;
+  }
+}
+
+// (pref, conf) words and per-block table of an assignment that already respects the capacity bound: every token
+// proposes its rank, so the keep phase keeps everything and the shuffle follows from it
+__global__ __launch_bounds__(kTokBlock) void rs_from_rank_kernel(int T, int k, int D,
+                                                                 const int32_t* __restrict__ token_rank,
+                                                                 ReshuffleWs w) {
+  extern __shared__ int32_t hist[];  // D*(k+1)
+  const int nkeys = D * (k + 1);
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) hist[x] = 0;
+  __syncthreads();
+  const int i = blockIdx.x * kTokBlock + threadIdx.x;
+  if (i < T) {
+    const int r = min(max(token_rank[i], 0), D - 1);
+    w.pc[i] = r;
+    atomicAdd(&hist[r * (k + 1)], 1);
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < nkeys; x += blockDim.x) w.cnt[size_t(blockIdx.x) * nkeys + x] = hist[x];
+}
+
 __global__ void rs_zero_kernel(int n, int32_t* __restrict__ v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) v[i] = 0;
@@ -1096,5 +1388,38 @@ extern "C" int32_t semmoe_reshuffle_lookup(const semmoe_config* cfg, void* strea
   const int nkeys = D * (k + 1);
   hipLaunchKernelGGL(rs_lookup_kernel, dim3(NB), dim3(kTokBlock), nkeys * 4, s, T, k, D, V, per_home, thr_q16,
                      token_key, dev, conf_q16, level, w);
+  return finish_from_preferences(cfg, s, NB, token_rank, shf, inv_shf, rank_count, w);
+}
+
+extern "C" int32_t semmoe_reshuffle_refine(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                           const int32_t* expert_to_rank, int32_t rounds, int32_t max_cycles,
+                                           int32_t* token_rank, int32_t* shf, int32_t* inv_shf, int32_t* rank_count,
+                                           int32_t* info, void* ws, size_t ws_bytes) {
+  if (!info) return SEMMOE_EINVAL;
+  if (max_cycles < 0) return SEMMOE_EINVAL;
+  if (cfg && (cfg->D > kRefMaxD || cfg->k > kRefMaxK || cfg->T > kRefMaxT)) return SEMMOE_EUNSUPPORTED;
+  // the starting assignment (all other argument checks are the ones of that call)
+  int32_t st = semmoe_reshuffle_rounds(cfg, stream, topk_ids, expert_to_rank, rounds, token_rank, shf, inv_shf,
+                                       rank_count, ws, ws_bytes);
+  if (st != SEMMOE_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int T = cfg->T, D = cfg->D, k = cfg->k;
+  if (T == 0) {
+    hipLaunchKernelGGL(rs_zero_kernel, dim3(1), dim3(64), 0, s, 2, info);
+    SEMMOE_LAUNCH_CHECK();
+    return SEMMOE_OK;
+  }
+  ReshuffleWs w;
+  if (!carve_reshuffle(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
+  const int NB = cdiv(T, kTokBlock);
+  // the (pref, conf) words are free once the starting assignment stands: they hold the gain words meanwhile
+  hipLaunchKernelGGL(rs_gain_kernel, dim3(NB), dim3(kTokBlock), 0, s, T, k, D, cfg->E, topk_ids, expert_to_rank, w.pc);
+  if (T <= kRefThreads * 8)
+    hipLaunchKernelGGL(rs_refine_kernel<8>, dim3(1), dim3(kRefThreads), 0, s, T, k, D, cfg->cap, max_cycles, w.pc,
+                       token_rank, info);
+  else
+    hipLaunchKernelGGL(rs_refine_kernel<32>, dim3(1), dim3(kRefThreads), 0, s, T, k, D, cfg->cap, max_cycles, w.pc,
+                       token_rank, info);
+  hipLaunchKernelGGL(rs_from_rank_kernel, dim3(NB), dim3(kTokBlock), D * (k + 1) * 4, s, T, k, D, token_rank, w);
   return finish_from_preferences(cfg, s, NB, token_rank, shf, inv_shf, rank_count, w);
 }

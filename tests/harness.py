@@ -122,6 +122,15 @@ class Layer:
         torch.cuda.synchronize()
         return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count))
 
+    def reshuffle_refine(self, rounds=1, max_cycles=1 << 30, cap=None):
+        """returns ((token_rank, shf, inv_shf, rank_count), cycles, converged)"""
+        info = torch.full((2,), -7, dtype=torch.int32, device=DEV)
+        self.m.reshuffle_refine(self.ids, self.e2r, rounds, max_cycles, self.token_rank, self.shf, self.inv_shf,
+                                self.rank_count, info, cap=cap)
+        torch.cuda.synchronize()
+        cyc, conv = (int(v) for v in to_np(info))
+        return tuple(to_np(t) for t in (self.token_rank, self.shf, self.inv_shf, self.rank_count)), cyc, conv
+
     def token_expert_hist(self, keys, ids, V, table=None):
         """accumulate one batch into the activation table; returns the device table (int32 storage of the u32 counts)"""
         if table is None:

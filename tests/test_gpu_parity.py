@@ -188,6 +188,56 @@ def test_reshuffle_rounds_bit_exact(T, E, D, k, cf, noise, rounds):
             assert (g == w_).all()
 
 
+@pytest.mark.parametrize("T,E,D,k,cf,noise", [
+    (256, 16, 4, 2, 1.0, 0.2), (1000, 128, 8, 8, 1.0, 0.5), (513, 16, 4, 4, 1.25, 0.4), (100, 8, 1, 2, 1.0, 0.5),
+    (5, 16, 4, 2, 1.0, 0.5), (3000, 48, 3, 15, 1.0, 0.3), (777, 64, 8, 4, 1.0, 0.3), (8192, 64, 8, 4, 1.0, 0.4),
+    (8193, 32, 4, 2, 1.0, 0.3), (20000, 128, 8, 8, 1.0, 0.6), (32768, 64, 8, 6, 1.0, 0.5), (700, 14, 7, 2, 1.1, 0.2)])
+@pytest.mark.parametrize("rounds,max_cycles", [(1, 1 << 30), (3, 1 << 30), (1, 0), (1, 3)])
+def test_reshuffle_refine_bit_exact(T, E, D, k, cf, noise, rounds, max_cycles):
+    """moves of placed tokens until the assignment is optimal, against the oracle's cycle by cycle: same tokens,
+    same number of cycles, same verdict; both workgroup forms (8 and 32 tokens per thread)"""
+    _say("reshuffle refine", T, E, D, k, cf, "rounds", rounds, "max_cycles", max_cycles)
+    ids, e2r = _planted(T, E, D, k, seed=T + D, noise=noise)
+    cap = int(math.ceil(cf * T / D))
+    w = WL.small(T=T, E=E, D=D, k=k)
+    lay = H.Layer(w, cap=cap)
+    lay.set_routing(ids)
+    lay.e2r = H.to_dev(e2r)
+    got, cycles, conv = lay.reshuffle_refine(rounds, max_cycles)
+    want, wcycles, wconv = O.reshuffle_refine(ids, e2r, D, cap, max_cycles, rounds=min(rounds, D))
+    assert (cycles, conv) == (wcycles, int(wconv))
+    for g, w_, name in zip(got, want, ("token_rank", "shf", "inv_shf", "rank_count")):
+        assert (g == w_).all(), (name, np.flatnonzero(g != w_)[:8])
+    assert (got[3] <= cap).all()
+    start = O.reshuffle_rounds(ids, e2r, D, cap, min(rounds, D))[0]
+    assert O.local_pairs(ids, e2r, got[0]) >= O.local_pairs(ids, e2r, start) + cycles
+    if max_cycles == 0:
+        assert (got[0] == start).all()
+
+
+def test_reshuffle_refine_reaches_the_min_cost_flow_optimum():
+    """the end state against the exact optimum of the assignment problem (a different algorithm)"""
+    _say("reshuffle refine vs min-cost flow")
+    for T, E, D, k in ((160, 16, 4, 2), (200, 32, 8, 4)):
+        ids, e2r = _planted(T, E, D, k, seed=3 * T, noise=0.3)
+        cap = T // D
+        lay = H.Layer(WL.small(T=T, E=E, D=D, k=k), cap=cap)
+        lay.set_routing(ids)
+        lay.e2r = H.to_dev(e2r)
+        got, cycles, conv = lay.reshuffle_refine()
+        assert conv == 1
+        assert O.local_pairs(ids, e2r, got[0]) == O.reshuffle_exact(ids, e2r, D, cap)[1]
+
+
+def test_reshuffle_refine_refuses_what_one_workgroup_cannot_hold():
+    lay = H.Layer(WL.small(T=64, E=32, D=16, k=2), cap=4)
+    i32 = dict(dtype=torch.int32, device=H.DEV)
+    one = torch.zeros(256, **i32)
+    with pytest.raises(Exception) as ei:
+        lay.m.reshuffle_refine(one, one, 1, 10, one, one, one, one, one, cap=4)
+    assert getattr(ei.value, "status", None) == -5
+
+
 @pytest.mark.parametrize("T,E,D,k,V,batches", [
     (256, 16, 4, 2, 64, 1), (1000, 128, 8, 8, 500, 3), (777, 64, 16, 4, 33, 2), (5, 16, 4, 2, 7, 1),
     (4000, 256, 32, 8, 1000, 2), (3000, 48, 3, 16, 128, 1), (70000, 32, 4, 2, 9, 1)])
@@ -594,6 +644,11 @@ def test_empty_and_degenerate_inputs():
     lay.m.reshuffle_rounds(one, lay.e2r, 3, one, one, one, rc_d, cap=0)
     torch.cuda.synchronize()
     assert (H.to_np(rc_d) == 0).all()
+    rc_d.fill_(7)
+    info = torch.full((2,), 9, **i32)
+    lay.m.reshuffle_refine(one, lay.e2r, 1, 10, one, one, one, rc_d, info, cap=0)
+    torch.cuda.synchronize()
+    assert (H.to_np(rc_d) == 0).all() and (H.to_np(info) == 0).all()
     rc_d.fill_(7)
     lay.m.reshuffle_lookup(one, 8, one, one, one, 0, one, one, one, rc_d, cap=0)
     torch.cuda.synchronize()

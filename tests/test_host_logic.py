@@ -98,6 +98,17 @@ def test_next_row_calls_reject_bad_arguments_without_a_gpu():
     assert lib.semmoe_reshuffle_rounds(C.byref(c), None, p, p, 0, p, p, p, p, p, big) == -1          # rounds < 1
     assert lib.semmoe_reshuffle_rounds(C.byref(c), None, None, p, 2, p, p, p, p, p, big) == -1
     assert lib.semmoe_reshuffle_rounds(C.byref(c), None, p, p, 2, p, p, p, p, None, 0) == -3
+    # reshuffle refined to the optimum
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 1, 10, p, p, p, p, None, p, big) == -1   # no info
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 1, -1, p, p, p, p, p, p, big) == -1      # max_cycles < 0
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 0, 10, p, p, p, p, p, p, big) == -1      # rounds < 1
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, None, 1, 10, p, p, p, p, p, p, big) == -1
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 1, 10, p, p, p, p, p, None, 0) == -3
+    assert lib.semmoe_reshuffle_refine(None, None, p, p, 1, 10, p, p, p, p, p, p, big) == -1
+    keep = (c.T, c.D, c.cap)
+    c.T, c.cap = 32769, 32769
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 1, 10, p, p, p, p, p, p, big) == -5      # T > 32768
+    c.T, c.D, c.cap = keep
     # activation table, schedule tables, table-driven reshuffle
     assert lib.semmoe_token_expert_hist(C.byref(c), None, None, p, 4, 8, p) == -1
     assert lib.semmoe_token_expert_hist(C.byref(c), None, p, p, -1, 8, p) == -1
