@@ -393,6 +393,31 @@ def main():
         rounds_report[str(R)] = {"ms": round(e0.elapsed_time(e1) / 20, 4),
                                  "remote_pair_fraction": round(int(rpr.item()) / P, 4)}
 
+    # ---------------- the same refined to the optimum by moves of placed tokens (not part of the timed step)
+    refine_report = {}
+    if D <= 8 and w.k <= 15 and T <= 32768:
+        info = torch.empty(2, **i32)
+        for R in (1, 3):
+            tr2, shf2, ish2 = (torch.empty(T, **i32) for _ in range(3))
+            rc2 = torch.empty(D, **i32)
+            for _ in range(2):
+                m.reshuffle_refine(ids, e2r, R, 1 << 30, tr2, shf2, ish2, rc2, info)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                m.reshuffle_refine(ids, e2r, R, 1 << 30, tr2, shf2, ish2, rc2, info)
+            e1.record()
+            torch.cuda.synchronize()
+            rpr = torch.empty(1, dtype=torch.int64, device=dev)
+            m.dispatch_index(ids, tr2, shf2, phys, tmp[0], tmp[1], torch.empty_like(expert_offsets),
+                             torch.empty_like(rank_offsets), torch.empty_like(send_matrix), rpr)
+            torch.cuda.synchronize()
+            cyc, conv = (int(v) for v in info.cpu())
+            refine_report["after_%d_round%s" % (R, "" if R == 1 else "s")] = {
+                "ms": round(e0.elapsed_time(e1) / 10, 4), "cycles": cyc, "optimal": bool(conv),
+                "remote_pair_fraction": round(int(rpr.item()) / P, 4)}
+
     # ---------------- next row: reshuffle from the schedule table, by token key alone (not part of the timed step)
     keys = up(WL.token_key(w))
     tabs = [up(t) for t in (sched_dev, sched_conf, sched_level)]
@@ -599,6 +624,7 @@ def main():
                                  "semmoe_placement_home_ranks": round(int(rp3.item()) / P, 4),
                                  "semmoe_placement_reshuffle": round(remote / P, 4)},
         "reshuffle_with_spill_rounds": rounds_report,
+        "reshuffle_refined_to_optimum": refine_report,
         "reshuffle_from_schedule_table": lookup_report,
         "reshuffle_with_sequence_table": seq_report,
         "request_schedule": request_report,

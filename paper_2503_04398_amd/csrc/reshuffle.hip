@@ -909,11 +909,7 @@ struct RefineLds {
   int32_t w[kRefNodes * kRefNodes];                        // arcs
   int32_t n[kRefNodes * kRefNodes];                        // tokens that attain the arc (a -> Z: free slots of a)
   int32_t best[kRefNodes + 1][kRefNodes * kRefNodes];      // best[L][u][v]: walks of exactly L arcs
-  int32_t walk[kRefNodes + 1];
-  int32_t m, n_arcs;
-  int32_t arc_a[kRefNodes], arc_b[kRefNodes];
-  uint32_t tgt_of, arc_of;       // per rank (nibble): target of the arc that leaves it (15: none), its index
-  unsigned long long gain_of;    // per rank (byte): gain + k of that arc
+  int32_t pred[kRefNodes + 1][kRefNodes * kRefNodes];      // the smallest x that attains best[L][u][v] as best[L-1][u][x] + w[x][v]
   unsigned long long wave_tot[2][kRefThreads / 64];
 };
 
@@ -953,7 +949,7 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
     const int ga = gain_nibble(g[t], a);
 #pragma unroll
     for (int b = 0; b < kRefMaxD; ++b)
-      if (b < D && b != a) atomicAdd(&L.hist[(a * D + b) * NG + gain_nibble(g[t], b) - ga + k], 1);
+      if (b < D) atomicAdd(&L.hist[(a * D + b) * NG + gain_nibble(g[t], b) - ga + k], 1);  // b = a: a row nobody reads
   }
   __syncthreads();
 
@@ -968,13 +964,17 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
       const int a = tid / N, b = tid % N;
       int wv = kRefNone, nv = 0;
       if (a < D && b < D && a != b) {
-        for (int d = NG - 1; d >= 0; --d) {
-          const int c = L.hist[(a * D + b) * NG + d];
-          if (c > 0) {
-            wv = d - k;
-            nv = c;
-            break;
-          }
+        // all buckets requested at once (a loop that stops at the first non-empty one waits for every read in turn)
+        for (int d0 = 0; d0 < NG; d0 += 16) {
+          int c[16];
+#pragma unroll
+          for (int d = 0; d < 16; ++d) c[d] = L.hist[(a * D + b) * NG + min(d0 + d, NG - 1)];
+#pragma unroll
+          for (int d = 0; d < 16; ++d)
+            if (d0 + d < NG && c[d] > 0) {
+              wv = d0 + d - k;
+              nv = c[d];
+            }
         }
       } else if (a < D && b == Z) {
         const int c = L.cnt[a];
@@ -993,25 +993,36 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
     __syncthreads();
     // shortest closed walk of positive gain
     int found = 0, u0 = 0;
+    int wcol[kRefNodes];  // arcs into this thread's end node
+#pragma unroll
+    for (int x = 0; x < kRefNodes; ++x) wcol[x] = (tid < N * N && x < N) ? L.w[x * N + tid % N] : kRefNone;
     for (int len = 2; len <= N; ++len) {
       if (tid < N * N) {
-        const int u = tid / N, v = tid % N;
-        int bv = kRefNone;
-        for (int x = 0; x < N; ++x) {
-          const int p = L.best[len - 1][u * N + x], q = L.w[x * N + v];
-          if (p > kRefNone / 2 && q > kRefNone / 2) bv = max(bv, p + q);
-        }
+        const int u = tid / N;
+        int prow[kRefNodes];
+#pragma unroll
+        for (int x = 0; x < kRefNodes; ++x) prow[x] = L.best[len - 1][u * N + min(x, N - 1)];
+        int bv = kRefNone, bx = 0;
+#pragma unroll
+        for (int x = kRefNodes - 1; x >= 0; --x)
+          if (prow[x] > kRefNone / 2 && wcol[x] > kRefNone / 2 && prow[x] + wcol[x] >= bv) {
+            bv = prow[x] + wcol[x];
+            bx = x;  // descending x with >=: the smallest x that attains the best
+          }
         L.best[len][tid] = bv;
+        L.pred[len][tid] = bx;
       }
       __syncthreads();
       int top = 0;  // every thread reads the same diagonal: the decision is uniform
-      for (int u = 0; u < N; ++u) {
-        const int d = L.best[len][u * N + u];
-        if (d > top) {
-          top = d;
+      int diag[kRefNodes];
+#pragma unroll
+      for (int u = 0; u < kRefNodes; ++u) diag[u] = L.best[len][min(u, N - 1) * (N + 1)];
+#pragma unroll
+      for (int u = 0; u < kRefNodes; ++u)
+        if (u < N && diag[u] > top) {
+          top = diag[u];
           u0 = u;
         }
-      }
       if (top > 0) {
         found = len;
         break;
@@ -1024,50 +1035,33 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
       break;
     }
     if (cycles >= max_cycles || cycles > T * k) break;  // every cycle adds a local pair: T*k bounds them
-    if (tid == 0) {
-      // walk back from u0: at every step the smallest predecessor that attains the best walk
+    // Walk back from u0 through the recorded predecessors; every thread does it for itself (the same LDS words
+    // for all: no table to write, no barrier).  Arcs come out last to first; their numbering only labels counters.
+    int m = 0x7fffffff, na = 0;
+    uint32_t tgt_of = 0xffffffffu, arc_of = 0;  // per rank (nibble): target of the arc that leaves it (15: none), its index
+    unsigned long long gain_of = 0;             // per rank (byte): gain + k of that arc
+    {
       int v = u0;
-      L.walk[found] = u0;
-      for (int l = found; l >= 2; --l) {
-        int pick = 0;
-        for (int x = N - 1; x >= 0; --x) {
-          const int p = L.best[l - 1][u0 * N + x], q = L.w[x * N + v];
-          if (p > kRefNone / 2 && q > kRefNone / 2 && p + q == L.best[l][u0 * N + v]) pick = x;
-        }
-        L.walk[l - 1] = pick;
-        v = pick;
-      }
-      L.walk[0] = u0;
-      int m = 0x7fffffff, na = 0;
-      uint32_t tgt_of = 0xffffffffu, arc_of = 0;
-      unsigned long long gain_of = 0;
-      for (int s = 0; s < found; ++s) {
-        const int a = L.walk[s], b = L.walk[s + 1];
+      for (int l = found; l >= 1; --l) {
+        const int a = (l >= 2) ? L.pred[l][u0 * N + v] : u0;
+        const int b = v;
+        v = a;
         if (a == Z) continue;
         m = min(m, L.n[a * N + b]);
         if (b != Z) {
-          L.arc_a[na] = a;
-          L.arc_b[na] = b;
           tgt_of = (tgt_of & ~(15u << (4 * a))) | (uint32_t(b) << (4 * a));
           arc_of |= uint32_t(na) << (4 * a);
           gain_of |= (unsigned long long)(L.w[a * N + b] + k) << (8 * a);
           ++na;
         }
       }
-      L.m = m;
-      L.n_arcs = na;
-      L.tgt_of = tgt_of;
-      L.arc_of = arc_of;
-      L.gain_of = gain_of;
     }
-    __syncthreads();
-    const int m = L.m, na = L.n_arcs;
+    m = __builtin_amdgcn_readfirstlane(m);
+    na = __builtin_amdgcn_readfirstlane(na);
     if (m <= 0) {  // cannot happen while the histogram matches the tokens; never spin on it
       converged = -1;
       break;
     }
-    const uint32_t tgt_of = L.tgt_of, arc_of = L.arc_of;
-    const unsigned long long gain_of = L.gain_of;
     // the tokens that attain the arc leaving their rank; per arc a 16-bit count (at most 32768 tokens)
     uint32_t mine = 0;
     unsigned long long c_lo = 0, c_hi = 0;
@@ -1089,10 +1083,13 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
       const unsigned long long t_lo = __shfl_up(i_lo, off);
-      const unsigned long long t_hi = __shfl_up(i_hi, off);
-      if (lane >= off) {
-        i_lo += t_lo;
-        i_hi += t_hi;
+      if (lane >= off) i_lo += t_lo;
+    }
+    if (na > 4) {  // uniform
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long t_hi = __shfl_up(i_hi, off);
+        if (lane >= off) i_hi += t_hi;
       }
     }
     if (lane == 63) {
@@ -1101,9 +1098,18 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
     }
     __syncthreads();
     unsigned long long o_lo = i_lo - c_lo, o_hi = i_hi - c_hi;  // tokens before this thread's, per arc
-    for (int w2 = 0; w2 < wave; ++w2) {
-      o_lo += L.wave_tot[0][w2];
-      o_hi += L.wave_tot[1][w2];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      if (half == 1 && na <= 4) break;  // uniform
+      unsigned long long tot[kRefThreads / 64];  // requested together, not one by one
+#pragma unroll
+      for (int w2 = 0; w2 < kRefThreads / 64; ++w2) tot[w2] = L.wave_tot[half][w2];
+      unsigned long long sum = 0;
+#pragma unroll
+      for (int w2 = 0; w2 < kRefThreads / 64; ++w2)
+        if (w2 < wave) sum += tot[w2];
+      if (half == 0) o_lo += sum;
+      else o_hi += sum;
     }
 #pragma unroll
     for (int t = 0; t < TPT; ++t) {
@@ -1119,16 +1125,19 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
       const int ga = gain_nibble(g[t], a), gb = gain_nibble(g[t], b);
 #pragma unroll
       for (int s = 0; s < kRefMaxD; ++s) {
-        if (s >= D) continue;
+        if (s >= D) continue;  // uniform
         const int gs = gain_nibble(g[t], s);
-        if (s != a) atomicSub(&L.hist[(a * D + s) * NG + gs - ga + k], 1);
-        if (s != b) atomicAdd(&L.hist[(b * D + s) * NG + gs - gb + k], 1);
+        atomicSub(&L.hist[(a * D + s) * NG + gs - ga + k], 1);  // s = a, s = b: the rows (a, a), (b, b) nobody reads
+        atomicAdd(&L.hist[(b * D + s) * NG + gs - gb + k], 1);
       }
       rkp[t >> 3] = (rkp[t >> 3] & ~(15u << (4 * (t & 7)))) | (uint32_t(b) << (4 * (t & 7)));
     }
-    if (tid < na) {
-      atomicSub(&L.cnt[L.arc_a[tid]], m);
-      atomicAdd(&L.cnt[L.arc_b[tid]], m);
+    if (tid < D) {  // a rank with an arc out loses m tokens, one with an arc in gains m
+      int delta = ((tgt_of >> (4 * tid)) & 15u) != 15u ? -m : 0;
+#pragma unroll
+      for (int a = 0; a < kRefMaxD; ++a)
+        if (int((tgt_of >> (4 * a)) & 15u) == tid) delta += m;
+      L.cnt[tid] += delta;
     }
     ++cycles;
     __syncthreads();
