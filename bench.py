@@ -395,7 +395,7 @@ def main():
 
     # ---------------- the same refined to the optimum by moves of placed tokens (not part of the timed step)
     refine_report = {}
-    if D <= 8 and w.k <= 15 and T <= 32768:
+    if D <= 16 and w.k <= 15 and T <= 32768:
         info = torch.empty(2, **i32)
         for R in (1, 3):
             tr2, shf2, ish2 = (torch.empty(T, **i32) for _ in range(3))

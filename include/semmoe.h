@@ -267,7 +267,7 @@ int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const in
  * through the smallest predecessor that attains the best at every step; m = the least, over the arcs that leave a
  * rank, of the number of tokens that attain the arc (free slots for an arc into Z); on every arc between ranks the m
  * tokens of smallest index that attain it move.  Stops when no such walk is left or after `max_cycles` cycles.
- * One workgroup holds all tokens in registers, so T <= 32768, D <= 8, k <= 15 (SEMMOE_EUNSUPPORTED beyond); five
+ * One workgroup holds all tokens in registers, so T <= 32768, D <= 16, k <= 15 (SEMMOE_EUNSUPPORTED beyond); five
  * launches on top of the starting assignment's.  rounds >= 1, max_cycles >= 0 (0: the starting assignment).
  * dev in / out as `semmoe_reshuffle`; dev out: info[2] i32 = cycles applied, 1 if no walk of positive gain is left
  * (the assignment is optimal) else 0.

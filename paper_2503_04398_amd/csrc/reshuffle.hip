@@ -880,75 +880,94 @@ __global__ __launch_bounds__(kChunk) void rs_single_kernel(int T, int k, int D, 
 // histogram, walks of exactly L arcs by max-plus products until a diagonal entry is positive (such a closed walk of
 // least length visits no rank twice), the walk back, a workgroup-wide count of the tokens that attain each arc in
 // token order, and the move of the first m of them on every arc.  All integer, no atomic's order reaches an output.
+// Two forms: up to 8 ranks (a nibble per rank fills a 32-bit word) and up to 16 (a 64-bit word).
 constexpr int kRefThreads = 1024;
-constexpr int kRefMaxD = 8;
+constexpr int kRefMaxD = 16;
 constexpr int kRefMaxK = 15;
-constexpr int kRefNodes = kRefMaxD + 1;
-constexpr int kRefNone = -(1 << 28);  // arc or walk that does not exist
+constexpr int kRefNone = -30000;  // arc or walk that does not exist (walk gains lie within +-15 * 17; stored as 16 bits)
 constexpr int kRefMaxT = kRefThreads * 32;
 
+// gain word of a token: nibble r = g[i][r]; ranks 8 .. 15 go to a second word
 __global__ __launch_bounds__(kTokBlock) void rs_gain_kernel(int T, int k, int D, int E,
                                                             const int32_t* __restrict__ ids,
                                                             const int32_t* __restrict__ e2r,
-                                                            int32_t* __restrict__ gain_word) {
+                                                            int32_t* __restrict__ gain_lo,
+                                                            int32_t* __restrict__ gain_hi) {
   const int i = blockIdx.x * kTokBlock + threadIdx.x;
   int r[SEMMOE_MAX_K];
   load_mapped_ids(ids + size_t(min(i, T - 1)) * k, i < T, k, E, e2r, D, r);
   if (i < T) {
-    uint32_t w = 0;
+    uint32_t lo = 0, hi = 0;
 #pragma unroll
-    for (int j = 0; j < SEMMOE_MAX_K; ++j)
-      if (r[j] >= 0) w += 1u << (4 * r[j]);
-    gain_word[i] = int32_t(w);
+    for (int j = 0; j < SEMMOE_MAX_K; ++j) {
+      if (r[j] >= 0 && r[j] < 8) lo += 1u << (4 * r[j]);
+      if (r[j] >= 8) hi += 1u << (4 * (r[j] - 8));
+    }
+    gain_lo[i] = int32_t(lo);
+    if (D > 8) gain_hi[i] = int32_t(hi);
   }
 }
 
+template <int MD>
 struct RefineLds {
-  int32_t hist[kRefMaxD * kRefMaxD * (2 * kRefMaxK + 1)];  // [a][b][gain + k]: tokens on a by their gain of moving to b
-  int32_t cnt[kRefMaxD];                                   // tokens per rank
-  int32_t w[kRefNodes * kRefNodes];                        // arcs
-  int32_t n[kRefNodes * kRefNodes];                        // tokens that attain the arc (a -> Z: free slots of a)
-  int32_t best[kRefNodes + 1][kRefNodes * kRefNodes];      // best[L][u][v]: walks of exactly L arcs
-  int32_t pred[kRefNodes + 1][kRefNodes * kRefNodes];      // the smallest x that attains best[L][u][v] as best[L-1][u][x] + w[x][v]
-  unsigned long long wave_tot[2][kRefThreads / 64];
+  static constexpr int kNodes = MD + 1;
+  int32_t hist[MD * MD * (2 * kRefMaxK + 1)];        // [a][b][gain + k]: tokens on a by their gain of moving to b
+  int32_t cnt[MD];                                   // tokens per rank
+  int32_t w[kNodes * kNodes];                        // arcs
+  int32_t n[kNodes * kNodes];                        // tokens that attain the arc (a -> Z: free slots of a)
+  int16_t best[kNodes + 1][kNodes * kNodes];         // best[L][u][v]: walks of exactly L arcs
+  uint8_t pred[kNodes + 1][kNodes * kNodes];         // the smallest x with best[L][u][v] = best[L-1][u][x] + w[x][v]
+  unsigned long long wave_tot[MD / 4][kRefThreads / 64];
 };
 
-__device__ __forceinline__ int gain_nibble(uint32_t g, int r) { return int((g >> (4 * r)) & 15u); }
+template <class GW>
+__device__ __forceinline__ int gain_nibble(GW g, int r) {
+  return int((g >> (4 * r)) & GW(15));
+}
 
-template <int TPT, int NT>
-__global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int cap, int max_cycles,
-                                                                const int32_t* __restrict__ gain_word,
+template <int TPT, int MD>
+__global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, int D, int cap, int max_cycles,
+                                                                const int32_t* __restrict__ gain_lo,
+                                                                const int32_t* __restrict__ gain_hi,
                                                                 int32_t* __restrict__ token_rank,
                                                                 int32_t* __restrict__ info) {
-  __shared__ RefineLds L;
+  static_assert(TPT % 8 == 0 && TPT <= 32, "ranks are kept eight to a register, the movers of a thread in one mask");
+  static_assert(MD == 8 || MD == 16, "a nibble per rank in a 32- or a 64-bit word");
+  using GW = typename std::conditional<MD == 8, uint32_t, unsigned long long>::type;
+  constexpr int kNodes = MD + 1;
+  constexpr int kWords = MD / 4;  // 64-bit words of four 16-bit counters, one counter per arc
+  __shared__ RefineLds<MD> L;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int N = D + 1, Z = D, NG = 2 * k + 1;
-  static_assert(TPT % 8 == 0 && TPT <= 32, "ranks are kept eight to a register, the movers of a thread in one mask");
-  uint32_t g[TPT];        // gains, one nibble per rank
-  uint32_t rkp[TPT / 8];  // ranks, one nibble per token (15: no token)
+  GW g[TPT];              // gains, one nibble per rank
+  uint32_t rkp[TPT / 8];  // ranks, one nibble per token
+  uint32_t valid = 0;     // bit t: the thread's token t exists
 #pragma unroll
   for (int t8 = 0; t8 < TPT / 8; ++t8) rkp[t8] = 0;
 #pragma unroll
   for (int t = 0; t < TPT; ++t) {
     const int i = tid * TPT + t;
     const int ii = min(i, T - 1);
-    const uint32_t gv = uint32_t(gain_word[ii]);
+    GW gv = GW(uint32_t(gain_lo[ii]));
+    if constexpr (MD == 16) gv |= GW(uint32_t(gain_hi[ii])) << 32;
     const int rv = token_rank[ii];
-    g[t] = i < T ? gv : 0u;
-    rkp[t >> 3] |= ((i < T && (unsigned)rv < (unsigned)D) ? uint32_t(rv) : 15u) << (4 * (t & 7));
+    const bool have = i < T && (unsigned)rv < (unsigned)D;
+    g[t] = have ? gv : GW(0);
+    rkp[t >> 3] |= (have ? uint32_t(rv) : 0u) << (4 * (t & 7));
+    valid |= (have ? 1u : 0u) << t;
   }
   auto rank_of = [&](int t) __attribute__((always_inline)) { return int((rkp[t >> 3] >> (4 * (t & 7))) & 15u); };
-  for (int x = tid; x < D * D * NG; x += NT) L.hist[x] = 0;
-  if (tid < kRefMaxD) L.cnt[tid] = 0;
+  for (int x = tid; x < D * D * NG; x += kRefThreads) L.hist[x] = 0;
+  if (tid < MD) L.cnt[tid] = 0;
   __syncthreads();
 #pragma unroll
   for (int t = 0; t < TPT; ++t) {
+    if (!((valid >> t) & 1u)) continue;
     const int a = rank_of(t);
-    if (a == 15) continue;
     atomicAdd(&L.cnt[a], 1);
     const int ga = gain_nibble(g[t], a);
 #pragma unroll
-    for (int b = 0; b < kRefMaxD; ++b)
+    for (int b = 0; b < MD; ++b)
       if (b < D) atomicAdd(&L.hist[(a * D + b) * NG + gain_nibble(g[t], b) - ga + k], 1);  // b = a: a row nobody reads
   }
   __syncthreads();
@@ -956,7 +975,7 @@ __global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int 
   int cycles = 0, converged = 0;
   for (;;) {
     // The gains never change, so the compiler would extract every nibble of every token once, in front of this
-    // loop, and keep them all in registers: eight values per token.  Make the words opaque once per cycle.
+    // loop, and keep them all in registers: a value per token and rank.  Make the words opaque once per cycle.
 #pragma unroll
     for (int t = 0; t < TPT; ++t) asm volatile("" : "+v"(g[t]));
     // arcs of the residual graph
@@ -988,37 +1007,37 @@ __global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int 
       }
       L.w[tid] = wv;
       L.n[tid] = nv;
-      L.best[1][tid] = wv;
+      L.best[1][tid] = int16_t(wv);
     }
     __syncthreads();
     // shortest closed walk of positive gain
     int found = 0, u0 = 0;
-    int wcol[kRefNodes];  // arcs into this thread's end node
+    int wcol[kNodes];  // arcs into this thread's end node
 #pragma unroll
-    for (int x = 0; x < kRefNodes; ++x) wcol[x] = (tid < N * N && x < N) ? L.w[x * N + tid % N] : kRefNone;
+    for (int x = 0; x < kNodes; ++x) wcol[x] = (tid < N * N && x < N) ? L.w[x * N + tid % N] : kRefNone;
     for (int len = 2; len <= N; ++len) {
       if (tid < N * N) {
         const int u = tid / N;
-        int prow[kRefNodes];
+        int prow[kNodes];
 #pragma unroll
-        for (int x = 0; x < kRefNodes; ++x) prow[x] = L.best[len - 1][u * N + min(x, N - 1)];
+        for (int x = 0; x < kNodes; ++x) prow[x] = L.best[len - 1][u * N + min(x, N - 1)];
         int bv = kRefNone, bx = 0;
 #pragma unroll
-        for (int x = kRefNodes - 1; x >= 0; --x)
+        for (int x = kNodes - 1; x >= 0; --x)
           if (prow[x] > kRefNone / 2 && wcol[x] > kRefNone / 2 && prow[x] + wcol[x] >= bv) {
             bv = prow[x] + wcol[x];
             bx = x;  // descending x with >=: the smallest x that attains the best
           }
-        L.best[len][tid] = bv;
-        L.pred[len][tid] = bx;
+        L.best[len][tid] = int16_t(bv);
+        L.pred[len][tid] = uint8_t(bx);
       }
       __syncthreads();
       int top = 0;  // every thread reads the same diagonal: the decision is uniform
-      int diag[kRefNodes];
+      int diag[kNodes];
 #pragma unroll
-      for (int u = 0; u < kRefNodes; ++u) diag[u] = L.best[len][min(u, N - 1) * (N + 1)];
+      for (int u = 0; u < kNodes; ++u) diag[u] = L.best[len][min(u, N - 1) * (N + 1)];
 #pragma unroll
-      for (int u = 0; u < kRefNodes; ++u)
+      for (int u = 0; u < kNodes; ++u)
         if (u < N && diag[u] > top) {
           top = diag[u];
           u0 = u;
@@ -1038,20 +1057,27 @@ __global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int 
     // Walk back from u0 through the recorded predecessors; every thread does it for itself (the same LDS words
     // for all: no table to write, no barrier).  Arcs come out last to first; their numbering only labels counters.
     int m = 0x7fffffff, na = 0;
-    uint32_t tgt_of = 0xffffffffu, arc_of = 0;  // per rank (nibble): target of the arc that leaves it (15: none), its index
-    unsigned long long gain_of = 0;             // per rank (byte): gain + k of that arc
+    uint32_t out_mask = 0;                 // bit a: an arc of the walk leaves rank a
+    GW tgt_of = 0, arc_of = 0;             // per rank (nibble): target of that arc, its index
+    unsigned long long gain_of[MD / 8];    // per rank (byte): gain + k of that arc
+#pragma unroll
+    for (int h = 0; h < MD / 8; ++h) gain_of[h] = 0;
     {
       int v = u0;
       for (int l = found; l >= 1; --l) {
-        const int a = (l >= 2) ? L.pred[l][u0 * N + v] : u0;
+        const int a = (l >= 2) ? int(L.pred[l][u0 * N + v]) : u0;
         const int b = v;
         v = a;
         if (a == Z) continue;
         m = min(m, L.n[a * N + b]);
         if (b != Z) {
-          tgt_of = (tgt_of & ~(15u << (4 * a))) | (uint32_t(b) << (4 * a));
-          arc_of |= uint32_t(na) << (4 * a);
-          gain_of |= (unsigned long long)(L.w[a * N + b] + k) << (8 * a);
+          out_mask |= 1u << a;
+          tgt_of |= GW(b) << (4 * a);
+          arc_of |= GW(na) << (4 * a);
+          const unsigned long long gb = (unsigned long long)(L.w[a * N + b] + k) << (8 * (a & 7));
+#pragma unroll
+          for (int h = 0; h < MD / 8; ++h)
+            if ((a >> 3) == h) gain_of[h] |= gb;
           ++na;
         }
       }
@@ -1064,67 +1090,71 @@ __global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int 
     }
     // the tokens that attain the arc leaving their rank; per arc a 16-bit count (at most 32768 tokens)
     uint32_t mine = 0;
-    unsigned long long c_lo = 0, c_hi = 0;
+    unsigned long long c[kWords];
+#pragma unroll
+    for (int wi = 0; wi < kWords; ++wi) c[wi] = 0;
 #pragma unroll
     for (int t = 0; t < TPT; ++t) {
-      const int a = rank_of(t) & 7;
-      const int b = int((tgt_of >> (4 * a)) & 15u);
-      const int want = int((gain_of >> (8 * a)) & 255ull) - k;
-      const bool hit = rank_of(t) != 15 && b != 15 && gain_nibble(g[t], b & 7) - gain_nibble(g[t], a) == want;
+      const int a = rank_of(t);
+      const int b = gain_nibble(tgt_of, a);
+      unsigned long long gword = gain_of[0];
+      if constexpr (MD == 16) gword = (a & 8) ? gain_of[1] : gain_of[0];
+      const int want = int((gword >> (8 * (a & 7))) & 255ull) - k;
+      const bool hit = ((valid >> t) & 1u) && ((out_mask >> a) & 1u) &&
+                       gain_nibble(g[t], b) - gain_nibble(g[t], a) == want;
       if (hit) {
-        const int e = int((arc_of >> (4 * a)) & 15u);
+        const int e = gain_nibble(arc_of, a);
         const unsigned long long one = 1ull << (16 * (e & 3));
         mine |= 1u << t;
-        if (e < 4) c_lo += one;
-        else c_hi += one;
+#pragma unroll
+        for (int wi = 0; wi < kWords; ++wi)
+          if ((e >> 2) == wi) c[wi] += one;
       }
     }
-    unsigned long long i_lo = c_lo, i_hi = c_hi;
+    unsigned long long incl[kWords];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const unsigned long long t_lo = __shfl_up(i_lo, off);
-      if (lane >= off) i_lo += t_lo;
-    }
-    if (na > 4) {  // uniform
+    for (int wi = 0; wi < kWords; ++wi) {
+      incl[wi] = c[wi];
+      if (wi * 4 < na) {  // uniform
 #pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const unsigned long long t_hi = __shfl_up(i_hi, off);
-        if (lane >= off) i_hi += t_hi;
+        for (int off = 1; off < 64; off <<= 1) {
+          const unsigned long long up = __shfl_up(incl[wi], off);
+          if (lane >= off) incl[wi] += up;
+        }
       }
-    }
-    if (lane == 63) {
-      L.wave_tot[0][wave] = i_lo;
-      L.wave_tot[1][wave] = i_hi;
+      if (lane == 63) L.wave_tot[wi][wave] = incl[wi];
     }
     __syncthreads();
-    unsigned long long o_lo = i_lo - c_lo, o_hi = i_hi - c_hi;  // tokens before this thread's, per arc
-    {
-      // totals of the waves before this one: lane w holds wave w's total, a sum over the first lanes of the wave
-      const int w2 = lane & (kRefThreads / 64 - 1);
-      unsigned long long p_lo = (lane < wave) ? L.wave_tot[0][w2] : 0ull;
-      unsigned long long p_hi = (lane < wave && na > 4) ? L.wave_tot[1][w2] : 0ull;
+    unsigned long long before[kWords];  // tokens before this thread's, per arc
 #pragma unroll
-      for (int off = 1; off < kRefThreads / 64; off <<= 1) {
-        p_lo += __shfl_xor(p_lo, off);
-        if (na > 4) p_hi += __shfl_xor(p_hi, off);  // uniform
+    for (int wi = 0; wi < kWords; ++wi) {
+      before[wi] = incl[wi] - c[wi];
+      if (wi * 4 < na) {
+        // totals of the waves before this one: lane w holds wave w's total, a sum over the first lanes of the wave
+        unsigned long long p = (lane < wave) ? L.wave_tot[wi][lane & (kRefThreads / 64 - 1)] : 0ull;
+#pragma unroll
+        for (int off = 1; off < kRefThreads / 64; off <<= 1) p += __shfl_xor(p, off);
+        before[wi] += __shfl(p, 0);
       }
-      o_lo += __shfl(p_lo, 0);
-      if (na > 4) o_hi += __shfl(p_hi, 0);
     }
 #pragma unroll
     for (int t = 0; t < TPT; ++t) {
       if (!((mine >> t) & 1u)) continue;
       const int a = rank_of(t);
-      const int b = int((tgt_of >> (4 * a)) & 15u);
-      const int e = int((arc_of >> (4 * a)) & 15u);
+      const int b = gain_nibble(tgt_of, a);
+      const int e = gain_nibble(arc_of, a);
       const int sh = 16 * (e & 3);
-      const int ord = int(((e < 4 ? o_lo : o_hi) >> sh) & 0xffffull);
-      if (e < 4) o_lo += 1ull << sh;
-      else o_hi += 1ull << sh;
+      int ord = 0;
+#pragma unroll
+      for (int wi = 0; wi < kWords; ++wi)
+        if ((e >> 2) == wi) {
+          ord = int((before[wi] >> sh) & 0xffffull);
+          before[wi] += 1ull << sh;
+        }
       if (ord >= m) continue;
       const int ga = gain_nibble(g[t], a), gb = gain_nibble(g[t], b);
 #pragma unroll
-      for (int s = 0; s < kRefMaxD; ++s) {
+      for (int s = 0; s < MD; ++s) {
         if (s >= D) continue;  // uniform
         const int gs = gain_nibble(g[t], s);
         atomicSub(&L.hist[(a * D + s) * NG + gs - ga + k], 1);  // s = a, s = b: the rows (a, a), (b, b) nobody reads
@@ -1133,10 +1163,10 @@ __global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int 
       rkp[t >> 3] = (rkp[t >> 3] & ~(15u << (4 * (t & 7)))) | (uint32_t(b) << (4 * (t & 7)));
     }
     if (tid < D) {  // a rank with an arc out loses m tokens, one with an arc in gains m
-      int delta = ((tgt_of >> (4 * tid)) & 15u) != 15u ? -m : 0;
+      int delta = ((out_mask >> tid) & 1u) ? -m : 0;
 #pragma unroll
-      for (int a = 0; a < kRefMaxD; ++a)
-        if (int((tgt_of >> (4 * a)) & 15u) == tid) delta += m;
+      for (int a = 0; a < MD; ++a)
+        if (((out_mask >> a) & 1u) && gain_nibble(tgt_of, a) == tid) delta += m;
       L.cnt[tid] += delta;
     }
     ++cycles;
@@ -1145,7 +1175,7 @@ __global__ __launch_bounds__(NT) void rs_refine_kernel(int T, int k, int D, int 
 #pragma unroll
   for (int t = 0; t < TPT; ++t) {
     const int i = tid * TPT + t;
-    if (i < T && rank_of(t) != 15) token_rank[i] = rank_of(t);
+    if (i < T && ((valid >> t) & 1u)) token_rank[i] = rank_of(t);
   }
   if (tid == 0) {
     info[0] = cycles;
@@ -1421,19 +1451,25 @@ extern "C" int32_t semmoe_reshuffle_refine(const semmoe_config* cfg, void* strea
   ReshuffleWs w;
   if (!carve_reshuffle(cfg, ws, ws_bytes, &w)) return SEMMOE_EWORKSPACE;
   const int NB = cdiv(T, kTokBlock);
-  // the (pref, conf) words are free once the starting assignment stands: they hold the gain words meanwhile
-  hipLaunchKernelGGL(rs_gain_kernel, dim3(NB), dim3(kTokBlock), 0, s, T, k, D, cfg->E, topk_ids, expert_to_rank, w.pc);
+  // the (pref, conf) words are free once the starting assignment stands: they hold the gain words meanwhile, and
+  // inv_shf, which is written last, the second word of more than 8 ranks
+  hipLaunchKernelGGL(rs_gain_kernel, dim3(NB), dim3(kTokBlock), 0, s, T, k, D, cfg->E, topk_ids, expert_to_rank, w.pc,
+                     inv_shf);
   // tokens per thread by batch size; fewer, longer threads were slower (8192 tokens: 512 x 16 against 1024 x 8, +13 %):
   // what a cycle waits for is latency, and more waves hide more of it
-  if (T <= kRefThreads * 8)
-    hipLaunchKernelGGL((rs_refine_kernel<8, kRefThreads>), dim3(1), dim3(kRefThreads), 0, s, T, k, D, cfg->cap,
-                       max_cycles, w.pc, token_rank, info);
-  else if (T <= kRefThreads * 16)
-    hipLaunchKernelGGL((rs_refine_kernel<16, kRefThreads>), dim3(1), dim3(kRefThreads), 0, s, T, k, D, cfg->cap,
-                       max_cycles, w.pc, token_rank, info);
-  else
-    hipLaunchKernelGGL((rs_refine_kernel<32, kRefThreads>), dim3(1), dim3(kRefThreads), 0, s, T, k, D, cfg->cap,
-                       max_cycles, w.pc, token_rank, info);
+#define SEMMOE_REFINE_LAUNCH(TPT, MD)                                                                                \
+  hipLaunchKernelGGL((rs_refine_kernel<TPT, MD>), dim3(1), dim3(kRefThreads), 0, s, T, k, D, cfg->cap, max_cycles,   \
+                     w.pc, inv_shf, token_rank, info)
+  if (D <= 8) {
+    if (T <= kRefThreads * 8) SEMMOE_REFINE_LAUNCH(8, 8);
+    else if (T <= kRefThreads * 16) SEMMOE_REFINE_LAUNCH(16, 8);
+    else SEMMOE_REFINE_LAUNCH(32, 8);
+  } else {
+    if (T <= kRefThreads * 8) SEMMOE_REFINE_LAUNCH(8, 16);
+    else if (T <= kRefThreads * 16) SEMMOE_REFINE_LAUNCH(16, 16);
+    else SEMMOE_REFINE_LAUNCH(32, 16);
+  }
+#undef SEMMOE_REFINE_LAUNCH
   hipLaunchKernelGGL(rs_from_rank_kernel, dim3(NB), dim3(kTokBlock), D * (k + 1) * 4, s, T, k, D, token_rank, w);
   return finish_from_preferences(cfg, s, NB, token_rank, shf, inv_shf, rank_count, w);
 }

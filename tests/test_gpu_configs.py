@@ -100,19 +100,20 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
         assert (g == x).all(), "rounds: " + nm
     _say("  [%5.1fs] reshuffle with 3 spill rounds bit-exact; remote-pair fraction %.4f (1 round: %.4f)"
          % (time.time() - t0, O.remote_fraction(ids, e2r, want3[0]), O.remote_fraction(ids, e2r, want[0])))
-    # moves of placed tokens after the three rounds, until nothing is left to gain (one workgroup: D <= 8 only)
-    if w.D <= 8 and w.k <= 15 and w.T <= 32768:
+    # moves of placed tokens after the three rounds, until nothing is left to gain (one workgroup: up to 16 ranks)
+    if w.D <= 16 and w.k <= 15 and w.T <= 32768:
         gotr, cycles, conv = lay.reshuffle_refine(3)
         wantr, wcycles, wconv = O.reshuffle_refine(ids, e2r, w.D, w.cap, rounds=3)
         assert (cycles, conv) == (wcycles, 1) and wconv
         for g, x, nm in zip(gotr, wantr, ("token_rank", "shf", "inv_shf", "rank_count")):
             assert (g == x).all(), "refine: " + nm
         # the optimum of the assignment problem from a library solver (the LP of a transportation problem is integral)
-        g_all = O.gain_matrix(ids, e2r, w.D)
-        best = _lp_optimum(g_all, w.D, w.cap)
-        assert O.local_pairs(ids, e2r, gotr[0]) == best
-        _say("  [%5.1fs] reshuffle refined to the optimum in %d cycles, bit-exact; remote-pair fraction %.4f = LP optimum"
-             % (time.time() - t0, cycles, O.remote_fraction(ids, e2r, gotr[0])))
+        lp = ""
+        if w.T * w.D <= 70000:
+            assert O.local_pairs(ids, e2r, gotr[0]) == _lp_optimum(O.gain_matrix(ids, e2r, w.D), w.D, w.cap)
+            lp = " = LP optimum"
+        _say("  [%5.1fs] reshuffle refined to the optimum in %d cycles, bit-exact; remote-pair fraction %.4f%s"
+             % (time.time() - t0, cycles, O.remote_fraction(ids, e2r, gotr[0]), lp))
     # the table-driven row at the full size: rebatch from token keys alone, two thresholds
     keys = WL.token_key(w)
     for thr in (0, 24576):

@@ -191,11 +191,13 @@ def test_reshuffle_rounds_bit_exact(T, E, D, k, cf, noise, rounds):
 @pytest.mark.parametrize("T,E,D,k,cf,noise", [
     (256, 16, 4, 2, 1.0, 0.2), (1000, 128, 8, 8, 1.0, 0.5), (513, 16, 4, 4, 1.25, 0.4), (100, 8, 1, 2, 1.0, 0.5),
     (5, 16, 4, 2, 1.0, 0.5), (3000, 48, 3, 15, 1.0, 0.3), (777, 64, 8, 4, 1.0, 0.3), (8192, 64, 8, 4, 1.0, 0.4),
-    (8193, 32, 4, 2, 1.0, 0.3), (20000, 128, 8, 8, 1.0, 0.6), (32768, 64, 8, 6, 1.0, 0.5), (700, 14, 7, 2, 1.1, 0.2)])
+    (8193, 32, 4, 2, 1.0, 0.3), (20000, 128, 8, 8, 1.0, 0.6), (32768, 64, 8, 6, 1.0, 0.5), (700, 14, 7, 2, 1.1, 0.2),
+    (900, 64, 16, 4, 1.0, 0.4), (3000, 36, 9, 4, 1.0, 0.3), (10000, 128, 16, 8, 1.0, 0.5), (20000, 60, 12, 5, 1.0, 0.4),
+    (32768, 128, 16, 4, 1.0, 0.5), (400, 13, 13, 1, 1.0, 0.0)])
 @pytest.mark.parametrize("rounds,max_cycles", [(1, 1 << 30), (3, 1 << 30), (1, 0), (1, 3)])
 def test_reshuffle_refine_bit_exact(T, E, D, k, cf, noise, rounds, max_cycles):
     """moves of placed tokens until the assignment is optimal, against the oracle's cycle by cycle: same tokens,
-    same number of cycles, same verdict; both workgroup forms (8 and 32 tokens per thread)"""
+    same number of cycles, same verdict; every form of the workgroup (8, 16, 32 tokens per thread; up to 8 and up to 16 ranks)"""
     _say("reshuffle refine", T, E, D, k, cf, "rounds", rounds, "max_cycles", max_cycles)
     ids, e2r = _planted(T, E, D, k, seed=T + D, noise=noise)
     cap = int(math.ceil(cf * T / D))
@@ -230,11 +232,11 @@ def test_reshuffle_refine_reaches_the_min_cost_flow_optimum():
 
 
 def test_reshuffle_refine_refuses_what_one_workgroup_cannot_hold():
-    lay = H.Layer(WL.small(T=64, E=32, D=16, k=2), cap=4)
+    lay = H.Layer(WL.small(T=64, E=64, D=32, k=2), cap=2)
     i32 = dict(dtype=torch.int32, device=H.DEV)
     one = torch.zeros(256, **i32)
     with pytest.raises(Exception) as ei:
-        lay.m.reshuffle_refine(one, one, 1, 10, one, one, one, one, one, cap=4)
+        lay.m.reshuffle_refine(one, one, 1, 10, one, one, one, one, one, cap=2)
     assert getattr(ei.value, "status", None) == -5
 
 

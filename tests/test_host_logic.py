@@ -109,6 +109,9 @@ def test_next_row_calls_reject_bad_arguments_without_a_gpu():
     c.T, c.cap = 32769, 32769
     assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 1, 10, p, p, p, p, p, p, big) == -5      # T > 32768
     c.T, c.D, c.cap = keep
+    c.D, c.E, c.cap = 32, 32, 2
+    assert lib.semmoe_reshuffle_refine(C.byref(c), None, p, p, 1, 10, p, p, p, p, p, p, big) == -5      # D > 16
+    c.D, c.E, c.cap = keep[1], 16, keep[2]
     # activation table, schedule tables, table-driven reshuffle
     assert lib.semmoe_token_expert_hist(C.byref(c), None, None, p, 4, 8, p) == -1
     assert lib.semmoe_token_expert_hist(C.byref(c), None, p, p, -1, 8, p) == -1
