@@ -1012,36 +1012,44 @@ __global__ __launch_bounds__(kRefThreads) void rs_refine_kernel(int T, int k, in
     __syncthreads();
     // shortest closed walk of positive gain
     int found = 0, u0 = 0;
-    int wcol[kNodes];  // arcs into this thread's end node
-#pragma unroll
-    for (int x = 0; x < kNodes; ++x) wcol[x] = (tid < N * N && x < N) ? L.w[x * N + tid % N] : kRefNone;
+    // LDS words requested together: a whole row of 9 nodes at once, but a row of 17 in three parts - its registers
+    // are paid for by every thread of the workgroup, and the 16-rank form with 32 tokens per thread has none to spare
+    constexpr int kChunk = (MD == 8) ? kNodes : 6;
     for (int len = 2; len <= N; ++len) {
       if (tid < N * N) {
-        const int u = tid / N;
-        int prow[kNodes];
-#pragma unroll
-        for (int x = 0; x < kNodes; ++x) prow[x] = L.best[len - 1][u * N + min(x, N - 1)];
+        const int u = tid / N, v = tid % N;
         int bv = kRefNone, bx = 0;
+        for (int x0 = (kNodes - 1) / kChunk * kChunk; x0 >= 0; x0 -= kChunk) {
+          int p[kChunk], q[kChunk];
 #pragma unroll
-        for (int x = kNodes - 1; x >= 0; --x)
-          if (prow[x] > kRefNone / 2 && wcol[x] > kRefNone / 2 && prow[x] + wcol[x] >= bv) {
-            bv = prow[x] + wcol[x];
-            bx = x;  // descending x with >=: the smallest x that attains the best
+          for (int j = 0; j < kChunk; ++j) {
+            const int x = min(x0 + j, N - 1);
+            p[j] = L.best[len - 1][u * N + x];
+            q[j] = L.w[x * N + v];
           }
+#pragma unroll
+          for (int j = kChunk - 1; j >= 0; --j)
+            if (x0 + j < N && p[j] > kRefNone / 2 && q[j] > kRefNone / 2 && p[j] + q[j] >= bv) {
+              bv = p[j] + q[j];
+              bx = x0 + j;  // descending x with >=: the smallest x that attains the best
+            }
+        }
         L.best[len][tid] = int16_t(bv);
         L.pred[len][tid] = uint8_t(bx);
       }
       __syncthreads();
       int top = 0;  // every thread reads the same diagonal: the decision is uniform
-      int diag[kNodes];
+      for (int x0 = 0; x0 < N; x0 += kChunk) {
+        int diag[kChunk];
 #pragma unroll
-      for (int u = 0; u < kNodes; ++u) diag[u] = L.best[len][min(u, N - 1) * (N + 1)];
+        for (int j = 0; j < kChunk; ++j) diag[j] = L.best[len][min(x0 + j, N - 1) * (N + 1)];
 #pragma unroll
-      for (int u = 0; u < kNodes; ++u)
-        if (u < N && diag[u] > top) {
-          top = diag[u];
-          u0 = u;
-        }
+        for (int j = 0; j < kChunk; ++j)
+          if (x0 + j < N && diag[j] > top) {
+            top = diag[j];
+            u0 = x0 + j;
+          }
+      }
       if (top > 0) {
         found = len;
         break;
