@@ -269,8 +269,8 @@ int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const in
  * tokens of smallest index that attain it move.  Stops when no such walk is left or after `max_cycles` cycles.
  * One workgroup holds all tokens in registers, so T <= 32768, D <= 16, k <= 15 (SEMMOE_EUNSUPPORTED beyond); five
  * launches on top of the starting assignment's.  rounds >= 1, max_cycles >= 0 (0: the starting assignment).
- * dev in / out as `semmoe_reshuffle`; dev out: info[2] i32 = cycles applied, 1 if no walk of positive gain is left
- * (the assignment is optimal) else 0.
+ * dev in / out as `semmoe_reshuffle` (the output arrays also serve as scratch while the call runs); dev out:
+ * info[2] i32 = cycles applied, 1 if no walk of positive gain is left (the assignment is optimal) else 0.
  */
 int32_t semmoe_reshuffle_refine(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
                                 const int32_t* expert_to_rank, int32_t rounds, int32_t max_cycles, int32_t* token_rank,
