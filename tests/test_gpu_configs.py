@@ -38,6 +38,31 @@ def _lp_optimum(g, D, cap):
     return int(round(-res.fun))
 
 
+def _no_gainful_closed_walk(g, token_rank, D, cap):
+    """Optimality certificate of an assignment at any size: its residual graph on the ranks (+ a node for free
+    room) has no closed walk of positive gain.  Checked with a library routine: an arc of gain w gets the weight
+    1 - (D + 2) * w (never zero, which scipy would drop); a simple closed walk of L <= D + 1 arcs and total gain G
+    weighs L - (D + 2) * G, negative exactly when G >= 1, and scipy's Bellman-Ford reports negative cycles."""
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import bellman_ford, NegativeCycleError
+    N, scale = D + 1, D + 2
+    W = np.zeros((N, N))
+    cnt = np.bincount(token_rank, minlength=D)
+    for a in range(D):
+        on = np.flatnonzero(token_rank == a)
+        for b in range(D):
+            if a != b and len(on):
+                W[a, b] = -scale * int((g[on, b] - g[on, a]).max()) + 1
+        if cnt[a] < cap:
+            W[a, D] = 1
+        W[D, a] = 1
+    try:
+        bellman_ford(csr_matrix(W), directed=True)
+    except NegativeCycleError:
+        return False
+    return True
+
+
 def _full_config(name, n_tok_sample, n_slot_sample, rank):
     w = WL.CONFIGS[name]
     t0 = time.time()
@@ -108,9 +133,12 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
         for g, x, nm in zip(gotr, wantr, ("token_rank", "shf", "inv_shf", "rank_count")):
             assert (g == x).all(), "refine: " + nm
         # the optimum of the assignment problem from a library solver (the LP of a transportation problem is integral)
+        g_all = O.gain_matrix(ids, e2r, w.D)
+        assert _no_gainful_closed_walk(g_all, gotr[0], w.D, w.cap)
+        assert not _no_gainful_closed_walk(g_all, got3[0], w.D, w.cap) or cycles == 0   # the certificate can fail
         lp = ""
         if w.T * w.D <= 70000:
-            assert O.local_pairs(ids, e2r, gotr[0]) == _lp_optimum(O.gain_matrix(ids, e2r, w.D), w.D, w.cap)
+            assert O.local_pairs(ids, e2r, gotr[0]) == _lp_optimum(g_all, w.D, w.cap)
             lp = " = LP optimum"
         _say("  [%5.1fs] reshuffle refined to the optimum in %d cycles, bit-exact; remote-pair fraction %.4f%s"
              % (time.time() - t0, cycles, O.remote_fraction(ids, e2r, gotr[0]), lp))
