@@ -39,8 +39,9 @@ Which passage each function follows
   dispatch / combine           the two all2all of expert parallelism (Sec. 1) as
                                single-device permutations; `resume_tokens` of Alg. 3
   expert_ffn                   the expert FFN (Sec. 2), SwiGLU form
-  moe_definition               the plain MoE layer: what the whole path must equal
-                               ("losslessly", Sec. 5)
+  moe_definition / moe_definition_by_expert
+                               the plain MoE layer: what the whole path must equal
+                               ("losslessly", Sec. 5), token by token / expert by expert
   remote volume                alpha*k*B*S/G all2all volume model (Sec. 3.1)
 
 Pins (tests/test_oracle_*.py): brute force on tiny inputs, closed forms,
@@ -1132,6 +1133,28 @@ def moe_definition(X, ids, topk_w, weight_of, shared=None, tokens=None) -> np.nd
             out[n] += w[i, j] * swiglu_ffn(X[i:i + 1], *cache[e])[0]
         if shared is not None:
             out[n] += swiglu_ffn(X[i:i + 1], *shared)[0]
+    return out
+
+
+def moe_definition_by_expert(X, ids, topk_w, weight_of, shared=None, tokens=None) -> np.ndarray:
+    """The same sum as `moe_definition`, taken expert by expert instead of token by token:
+    Out[i] = sum over the experts e of (sum_j [ids[i,j] = e] topk_w[i,j]) * FFN_e(X[i]) (+ FFN_shared(X[i])),
+    experts in ascending id, every expert's weights asked for exactly once (`weight_of(e)` is called for each
+    expert some sampled token uses, in ascending order).  For layers whose experts do not fit host memory
+    together.  Still no placement, shuffle or permutation; pinned to `moe_definition`."""
+    X = np.asarray(X)
+    ids = np.asarray(ids)
+    w = np.asarray(topk_w, dtype=np.float64)
+    toks = np.arange(X.shape[0]) if tokens is None else np.asarray(tokens)
+    out = np.zeros((len(toks), X.shape[1]), dtype=np.float64)
+    sub_ids = ids[toks]
+    for e in np.unique(sub_ids):
+        hit = sub_ids == e                                   # [n, k]
+        rows = np.flatnonzero(hit.any(axis=1))
+        coef = (w[toks[rows]] * hit[rows]).sum(axis=1)       # a token's experts are distinct: one term
+        out[rows] += coef[:, None] * swiglu_ffn(X[toks[rows]], *weight_of(int(e)))
+    if shared is not None:
+        out += swiglu_ffn(X[toks], *shared)
     return out
 
 

@@ -214,6 +214,36 @@ def test_path_equals_plain_moe_definition(placed, shuffle, cf):
     np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-13)
 
 
+@pytest.mark.parametrize("with_shared,sample", [(True, None), (False, [3, 17, 17, 40, 0]), (True, [59])])
+def test_expert_major_definition_equals_token_major_definition(with_shared, sample):
+    """`moe_definition_by_expert` is the same sum in another order; every expert's weights are asked for once,
+    in ascending id, and only those of experts a sampled token uses"""
+    w = WL.small(T=60, d=16, E=8, k=3, F=12, D=4, dtype="fp32")
+    X = WL.hidden(w)
+    L = O.route_logits(X, WL.router_weight(w), None, WL.token_class(w), WL.class_bias(w))
+    ids, tw = O.select_topk(L, w.k, "softmax", False)
+    weights = {e: WL.expert_weight(w, e) for e in range(w.E)}
+    shared = WL.shared_weight(w) if with_shared else None
+    asked = []
+
+    def weight_of(e):
+        asked.append(e)
+        return weights[e]
+
+    got = O.moe_definition_by_expert(X, ids, tw, weight_of, shared, tokens=sample)
+    ref = O.moe_definition(X, ids, tw, lambda e: weights[e], shared, tokens=sample)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-15)
+    used = sorted(set(ids.ravel().tolist())) if sample is None else sorted(set(ids[sample].ravel().tolist()))
+    assert asked == used
+    # a dropped weight, a wrong expert or a doubled term cannot hide: one token, by hand
+    i = 7
+    by_hand = sum(tw[i, j] * O.swiglu_ffn(X[i:i + 1], *weights[int(ids[i, j])])[0] for j in range(w.k))
+    if shared is not None:
+        by_hand = by_hand + O.swiglu_ffn(X[i:i + 1], *shared)[0]
+    np.testing.assert_allclose(O.moe_definition_by_expert(X, ids, tw, lambda e: weights[e], shared, tokens=[i])[0],
+                               by_hand, rtol=1e-12, atol=1e-15)
+
+
 def test_semantic_placement_and_reshuffle_raise_local_rate_on_config1():
     """the method's point (Sec. 4.5): co-scheduling raises the local activation rate over vanilla"""
     w = WL.CONFIGS["c1_tiny_fp32"]
