@@ -763,6 +763,71 @@ def test_tail_launch_kernels(grid_cap, split, ring):
             m.set_tuning(key, -1)
 
 
+def _split_plan(rows_per_group, n_feat, feat_per_tile, grid, thr16=8):
+    """the tile arithmetic of a split grouped GEMM, as the launcher and the kernel do it: 256-row token tiles per
+    group x feature tiles, the head takes the full rounds of `grid` workgroups unless more than thr16/16 of a round
+    is left over; returns (listed, head, left_over)"""
+    listed = sum(-(-r // 256) for r in rows_per_group) * -(-n_feat // feat_per_tile)
+    rem = listed % grid
+    head = listed if 16 * rem > thr16 * grid else listed - rem
+    return listed, head, listed - head
+
+
+@pytest.mark.parametrize("ring", [-1, 2])
+@pytest.mark.parametrize("rows", [(9 * 256 + 100, 7 * 256 - 30), (10 * 256, 6 * 256 + 100)])
+def test_in_launch_tail_pieces_of_the_split_gemm(rows, ring):
+    """The tail of the default split launch (tile 22): pieces of the left-over 256 x 256 tiles inside the head's
+    launch.  The kernel takes 128 x 64 pieces (eight per parent tile) when twice the number of 128 x 128 pieces
+    still fits the grid, else 128 x 128 pieces; with the tail knob at 2 always the latter.  The shape is chosen with
+    the kernel's own arithmetic so that the 128 x 64 branch provably runs, in both GEMMs:
+      two groups of 10 + 7 token tiles (the last one ragged: 226 or 100 rows, so with 100 rows two of the four
+      64-token pieces of a parent tile lie outside the group and are skipped, one is partly filled);
+      gate/up: F = 192 against 128 features per tile -> 2 feature tiles (the second half filled), K = d = 320 = 5 slices;
+      down:    N = d = 320 against 256 per tile -> 2 feature tiles (the second a quarter filled), K = F = 192 = 3
+               slices, the fewest the pieces' ring of 3 takes;
+      either way 17 x 2 = 34 tiles on a grid capped at 16 workgroups: 2 full rounds = 32 tiles for the head
+      (2/16 of a round is left over, below the threshold of 8/16), 2 parent tiles left over = 8 pieces of
+      128 x 128, and 2 x 8 = 16 <= 16 workgroups -> sixteen 128 x 64 pieces."""
+    _say("in-launch tail pieces", rows, "tail knob", ring)
+    d, F, grid = 320, 192, 16
+    for n_feat, per_tile in ((F, 128), (d, 256)):
+        listed, head, left = _split_plan(rows, n_feat, per_tile, grid)
+        assert (listed, head, left) == (34, 32, 2)
+        assert left * 4 > 0 and left * 4 * 2 <= grid          # the kernel's condition for the 128 x 64 pieces
+    T = sum(rows)
+    w = WL.small(T=T, d=d, E=2, k=1, F=F, D=1, dtype="bf16", C=1)
+    assert T // 2 >= 192                                     # the launcher's estimate of rows per group picks tile 22
+    ids = np.repeat(np.arange(2, dtype=np.int32), rows)[:, None]
+    r = np.random.default_rng(5)
+    ids = ids[r.permutation(T)]                              # dispatch has to gather the groups
+    e2r, phys, inv = O.vanilla_placement(2, 1)
+    m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
+    try:
+        m.set_tuning(4, grid)
+        m.set_tuning(6, ring)
+        lay = H.Layer(w)
+        X = WL.hidden(w)
+        lay.X = H.to_dev(X, w)
+        lay.set_routing(ids, np.ones((T, 1), dtype=np.float32))
+        lay.set_placement(e2r, phys, inv)
+        tr, shf, ishf, rc = lay.reshuffle()
+        dg = lay.dispatch()
+        assert tuple(np.diff(dg["expert_offsets"])) == tuple(rows)
+        dw = O.dispatch(X, ids, tr, ishf, phys, 1)
+        weights = {e: WL.expert_weight(w, e) for e in range(2)}
+        lay.load_experts(range(2))
+        Y = H.to_np(lay.expert_ffn(0, poison=512.0))
+        Yo = O.expert_ffn(dw["X_perm"], dw["expert_offsets"], inv, lambda e: weights[e], 1)
+        assert not (Y == 512.0).all(axis=1).any()            # every row was written
+        H.assert_close(Y, Yo, "bf16", "Y")
+        # per-row check as well: the pieces' rows are few, a global maximum alone would be lenient for them
+        lo = dw["expert_offsets"][1] + (len(range(0, rows[1], 256)) - 1) * 256
+        H.assert_close(Y[lo:], Yo[lo:], "bf16", "Y rows of the left-over tiles")
+    finally:
+        for key in (4, 6):
+            m.set_tuning(key, -1)
+
+
 def test_probes_copy_and_mfma_loop():
     """the two probes bench.py reads achievable rates from: the copy copies, the MFMA loop's checksum is the exact sum"""
     m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
