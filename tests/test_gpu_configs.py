@@ -237,6 +237,8 @@ def _full_config(name, n_tok_sample, n_slot_sample, rank):
         a, b = np.searchsorted(samp, [lo, hi])
         if b > a:
             Yo_samp[a:b] = O.swiglu_ffn(inp.X[pos[samp[a:b]] // w.k], wgu, wdn)
+        if (e + 1) % 32 == 0:
+            _say("  [%5.1fs] ... %d experts" % (time.time() - t0, e + 1))
         return wgu, wdn
 
     used = set(int(e) for e in np.unique(ids[toks]))
