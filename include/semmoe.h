@@ -242,6 +242,24 @@ int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* 
                          int32_t* rank_count, void* ws, size_t ws_bytes);
 
 /*
+ * reshuffle_static - semmoe_reshuffle for callers that cannot allocate or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without `ws`, same kernels,
+ * same results bit for bit; the scratch is a fixed array of SEMMOE_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (each GPU the library runs on holds its own copy until the process ends).  The call makes
+ * no allocation of any kind.  The first call on a device looks the array's address up (the device of `stream` must
+ * be the current device, as for every call here).
+ * Limits: semmoe_workspace_bytes()'s reshuffle share must fit the array, which covers T = 131072 tokens at
+ * D = 32, k = 8 and every workload of this library's benchmark; beyond, SEMMOE_EUNSUPPORTED is returned before
+ * anything is launched.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and give wrong results; calls in stream order on one stream are safe.  Nothing has to
+ * be cleared between calls: no kernel reads scratch it has not written in the same call.
+ */
+#define SEMMOE_STATIC_SCRATCH_BYTES (4u << 20)
+int32_t semmoe_reshuffle_static(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf, int32_t* inv_shf,
+                                int32_t* rank_count);
+
+/*
  * reshuffle with gain-aware spill rounds - the capacity-bounded assignment pushed towards the objective of Sec. 3.3
  * (the most local pairs for a fixed placement), which the keep/spill of `semmoe_reshuffle` only approximates when
  * capacity binds.  Round 0 is the keep phase of `semmoe_reshuffle`.  In each further round every token still unplaced

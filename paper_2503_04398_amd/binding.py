@@ -102,6 +102,7 @@ _SIGS = {
     "semmoe_coschedule": ([_P, _P, _P, _P, _P, C.c_int32, _P, _P, _P, _P, _P, _P, _P], C.c_int32),
     "semmoe_token_labels": ([_P, _P, C.c_int32, _P, _P, C.c_int32, _P, _P, _P], C.c_int32),
     "semmoe_reshuffle": ([_P] * 9 + [C.c_size_t], C.c_int32),
+    "semmoe_reshuffle_static": ([_P] * 8, C.c_int32),
     "semmoe_reshuffle_rounds": ([_P] * 4 + [C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_refine": ([_P] * 4 + [C.c_int32, C.c_int32] + [_P] * 6 + [C.c_size_t], C.c_int32),
     "semmoe_reshuffle_lookup": ([_P, _P, _P, C.c_int32, _P, _P, _P, C.c_int32] + [_P] * 5 + [C.c_size_t], C.c_int32),
@@ -283,6 +284,13 @@ class SemMoE:
         self._check("semmoe_reshuffle", self.lib.semmoe_reshuffle(
             C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), _ptr(token_rank), _ptr(shf),
             _ptr(inv_shf), _ptr(rank_count), _ptr(self.ws), self.ws_bytes))
+
+    def reshuffle_static(self, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count, cap=None):
+        """the reshuffle on the library's own fixed scratch array: no workspace argument, no allocation"""
+        c = self._cfg(**({"cap": cap} if cap is not None else {}))
+        self._check("semmoe_reshuffle_static", self.lib.semmoe_reshuffle_static(
+            C.byref(c), _stream(), _ptr(topk_ids), _ptr(expert_to_rank), _ptr(token_rank), _ptr(shf),
+            _ptr(inv_shf), _ptr(rank_count)))
 
     def reshuffle_rounds(self, topk_ids, expert_to_rank, rounds, token_rank, shf, inv_shf, rank_count, cap=None):
         c = self._cfg(**({"cap": cap} if cap is not None else {}))

@@ -3,6 +3,8 @@
 // inverse (`resume_tokens`).  Everything is integer and order-independent: stable ranks inside a
 // 256-token workgroup come from LDS bitmaps (rank = popcount of the key's bits below the token),
 // ranks across workgroups from small exclusive scans; no atomic's ordering reaches an output.
+#include <mutex>
+
 #include "common.hpp"
 #include "scan_util.hpp"
 
@@ -1249,9 +1251,9 @@ size_t ws_reshuffle(const semmoe_config* cfg) {
 
 using namespace semmoe;
 
-extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
-                                    const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf,
-                                    int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes) {
+static int32_t reshuffle_with_scratch(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                      const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf,
+                                      int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes) {
   int32_t st = validate_config(cfg, true, false, false);
   if (st != SEMMOE_OK) return st;
   if (!topk_ids || !expert_to_rank || !token_rank || !shf || !inv_shf || !rank_count) return SEMMOE_EINVAL;
@@ -1301,6 +1303,55 @@ extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, cons
                      w);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_reshuffle(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                    const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf,
+                                    int32_t* inv_shf, int32_t* rank_count, void* ws, size_t ws_bytes) {
+  return reshuffle_with_scratch(cfg, stream, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count, ws,
+                                ws_bytes);
+}
+
+// ---- the same call for callers that cannot allocate: the scratch is a fixed array in the code object ---------------
+// The array's name is a host-side stand-in for the symbol, not a device address: host code only ever uses the
+// address hipGetSymbolAddress returns for the current device (every device holds its own copy of the array).
+constexpr size_t kStaticScratchBytes = SEMMOE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxScratchDevices = 64;
+static void* g_scratch_ptr[kMaxScratchDevices];  // per device: address of its copy of `scratch`, null until asked for
+static std::mutex g_scratch_mutex;
+
+static int32_t static_scratch_of_current_device(void** out) {
+  int dev = 0;
+  SEMMOE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxScratchDevices) return SEMMOE_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    SEMMOE_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));  // the device `dev` is current
+    if (!p) return SEMMOE_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_reshuffle_static(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,
+                                           const int32_t* expert_to_rank, int32_t* token_rank, int32_t* shf,
+                                           int32_t* inv_shf, int32_t* rank_count) {
+  int32_t st = validate_config(cfg, true, false, false);
+  if (st != SEMMOE_OK) return st;
+  if (!topk_ids || !expert_to_rank || !token_rank || !shf || !inv_shf || !rank_count) return SEMMOE_EINVAL;
+  if (cfg->cap < 0) return SEMMOE_EINVAL;
+  if ((long long)cfg->cap * cfg->D < cfg->T) return SEMMOE_ESHAPE;
+  if (ws_reshuffle(cfg) > kStaticScratchBytes) return SEMMOE_EUNSUPPORTED;  // beyond the fixed array: before any HIP call
+  void* ws = nullptr;
+  st = static_scratch_of_current_device(&ws);
+  if (st != SEMMOE_OK) return st;
+  // No kernel of the reshuffle reads scratch it has not written in the same call, so nothing has to be cleared.
+  return reshuffle_with_scratch(cfg, stream, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count, ws,
+                                kStaticScratchBytes);
 }
 
 extern "C" int32_t semmoe_reshuffle_rounds(const semmoe_config* cfg, void* stream, const int32_t* topk_ids,

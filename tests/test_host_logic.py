@@ -76,6 +76,15 @@ def test_calls_reject_null_pointers_and_bad_capacity_without_a_gpu():
     c.cap = 16
     assert lib.semmoe_reshuffle(C.byref(c), None, p, p, p, p, p, p, None, 0) == -3      # no workspace
     assert lib.semmoe_reshuffle(C.byref(c), None, p, p, p, p, p, p, p, 8) == -3         # too small
+    # the allocation-free form checks the same things, and its size limit, before it touches a GPU
+    assert lib.semmoe_reshuffle_static(C.byref(c), None, p, p, p, p, p, None) == -1
+    c.cap = 15
+    assert lib.semmoe_reshuffle_static(C.byref(c), None, p, p, p, p, p, p) == -2
+    c.cap = 16
+    big = S.Config(T=1 << 21, d=64, E=64, k=8, F=32, D=32, cap=1 << 16).c()      # scratch need above the fixed array
+    assert S.SemMoE(S.Config(T=1 << 21, d=64, E=64, k=8, F=32, D=32, cap=1 << 16),
+                    allocate_workspace=False).workspace_bytes() > (4 << 20)
+    assert lib.semmoe_reshuffle_static(C.byref(big), None, p, p, p, p, p, p) == -5
     assert lib.semmoe_expert_ffn(C.byref(c), None, 4, p, p, p, p, p, p, p, 1 << 20) == -1   # rank >= D
     assert lib.semmoe_expert_ffn(C.byref(c), None, 0, p + 4, p, p, p, p, p, p, 1 << 20) == -1  # misaligned rows
     assert lib.semmoe_route(C.byref(c), None, p, p, None, p, None, None, None, p, p, p, 1 << 20) == -1  # class pair
