@@ -159,6 +159,37 @@ static int32_t launch_tail_pieces(GemmArgs a, int max_rows, int head_grid, hipSt
   return SEMMOE_OK;
 }
 
+// Every tile as 128 x 128 pieces with the loads placed between the MFMAs (the tail's piece kernel with nothing left
+// to a head launch): for problems whose 256 x 256 tiles would leave most compute units idle, such as the shared
+// expert on one rank's shard of tokens.
+template <int MODE>
+static int32_t launch_all_pieces(GemmArgs a, int max_rows, hipStream_t stream) {
+  using C = DmaCfg<MODE, 2, 2, 2, 2, 64, 3>;
+  const int w_rows = (MODE == kModeSwiglu) ? 2 * a.N : a.N;
+  if (a.K % 64 != 0 || a.K / 64 < 3) return SEMMOE_EUNSUPPORTED;
+  if ((unsigned long long)w_rows * a.ldw * 2 >= (1ull << 32) || (unsigned long long)C::BT * a.ldx * 2 >= (1ull << 32))
+    return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
+  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  const long long bound_p = (long long)(max_rows / 256 + a.nq) * cdiv(a.N, 2 * C::FEAT);  // parent tiles, at most
+  if (bound_p <= 0) return SEMMOE_OK;
+  a.sched_mode = 2;
+  a.sched_g = 1 << 24;  // no head launch: more workgroups than there can be tiles, so the cut falls at tile 0
+  a.sched_thr = 16;
+  a.sched_sub_t = 2;
+  a.sched_sub_f = 2;
+  const int grid = grid_for(bound_p * 4, num_cu());
+  auto kern = gemm_bf16_piece_kernel<MODE, 3>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   int(C::kLdsBytes)));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
 // Head (four-wave 256 x 256 tiles, K slices of 64, ring of 2) and tail (128 x 128 pieces, ring of 3) in one launch.
 // SEMMOE_EUNSUPPORTED when either half does not take the shape: the caller then launches them one after the other.
 template <int MODE>
@@ -242,6 +273,11 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
     case 25: return launch_dma<MODE, 4, 1, 2, 2, 64, 3>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 256 x 64, ring of 3
     case 26: return launch_dma<MODE, 2, 2, 2, 1, 64, 3>(a, max_rows, bpc > 0 ? bpc : 2, s);     // 128 x 64, ring of 3, two per CU
     case 27: return launch_dma<MODE, 2, 2, 2, 1, 64, 4>(a, max_rows, bpc > 0 ? bpc : 1, s);     // 128 x 64, ring of 4
+    case 28: {  // 128 x 128 pieces, loads between the MFMAs
+      const int32_t st = launch_all_pieces<MODE>(a, max_rows, s);
+      if (st != SEMMOE_EUNSUPPORTED) return st;
+      return launch_bf16<MODE, 2, 2, 2, 2, 64>(a, max_rows, bpc > 0 ? bpc : 2, s);  // K not a multiple of 64, or short
+    }
     default: break;
   }
   if (id >= 20 && id <= 22) {  // four waves, 256 x 256, loads interleaved with the MFMAs
@@ -259,8 +295,10 @@ static int32_t launch_bf16_tile(int id, const GemmArgs& a, int max_rows, int bpc
 
 // Default tile shape from the mean rows per group the caller expects (the true, ragged row counts live on
 // the device): big direct-to-LDS tiles when groups fill them, small register-staged tiles otherwise.
-static int default_tile(int est_rows_per_group) {
-  if (est_rows_per_group >= 192) return 22;
+static int default_tile(int est_rows_per_group, long long big_tiles_at_most) {
+  // big tiles only pay when they fill the chip: 512 rows of the shared expert give 48 of them for 256 compute units
+  // (measured, d 7168, F 2048: 171 us as 256 x 256 tiles, 84 us as 128 x 128 pieces; with 2048 rows 202 against 216)
+  if (est_rows_per_group >= 192) return big_tiles_at_most * 2 >= num_cu() ? 22 : 28;
   if (est_rows_per_group >= 96) return 0;
   return 26;  // few rows per group (decode): the weights stream through; narrow tiles, deep ring, two per CU
 }
@@ -288,8 +326,9 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
     switch (mode) {
       case kModeLogits: return launch_bf16<kModeLogits, 2, 2, 2, 1, 64>(a, max_rows, 2, stream);  // 128 experts x 64 tokens
       case kModeSwiglu: {
-        const int id = g_tune[SEMMOE_TUNE_GATEUP_TILE] >= 0 ? g_tune[SEMMOE_TUNE_GATEUP_TILE]
-                                                            : default_tile(est_rows_per_group);
+        const int id = g_tune[SEMMOE_TUNE_GATEUP_TILE] >= 0
+                           ? g_tune[SEMMOE_TUNE_GATEUP_TILE]
+                           : default_tile(est_rows_per_group, (long long)(max_rows / 256 + a.nq) * cdiv(a.N, 128));
         if (!split_launch(id)) return launch_bf16_tile<kModeSwiglu>(id, a, max_rows, bpc, stream);
         GemmArgs h = a;
         h.sched_mode = 1;
@@ -303,8 +342,9 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         return launch_tail<kModeSwiglu>(h, max_rows, big_tile_grid(a, max_rows, 128), stream);
       }
       default: {
-        const int id = g_tune[SEMMOE_TUNE_DOWN_TILE] >= 0 ? g_tune[SEMMOE_TUNE_DOWN_TILE]
-                                                          : default_tile(est_rows_per_group);
+        const int id = g_tune[SEMMOE_TUNE_DOWN_TILE] >= 0
+                           ? g_tune[SEMMOE_TUNE_DOWN_TILE]
+                           : default_tile(est_rows_per_group, (long long)(max_rows / 256 + a.nq) * cdiv(a.N, 256));
         if (!split_launch(id)) return launch_bf16_tile<kModeStore>(id, a, max_rows, bpc, stream);
         GemmArgs h = a;
         h.sched_mode = 1;

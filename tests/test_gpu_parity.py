@@ -698,7 +698,7 @@ def test_empty_and_degenerate_inputs():
     H.assert_close(Y, Yo, "bf16", "Y")
 
 
-@pytest.mark.parametrize("tile", [0, 3, 4, 6, 11, 12, 14, 15, 16, 17, 18, 19, 25, 26, 27])
+@pytest.mark.parametrize("tile", [0, 3, 4, 6, 11, 12, 14, 15, 16, 17, 18, 19, 25, 26, 27, 28])
 def test_every_gemm_tile_shape_on_a_ragged_problem(tile):
     """each tile shape of the bf16 grouped GEMMs (register-staged, direct-to-LDS ring, skinny), with ragged
     groups, partial K slices (d % 64 = 8, F % 32 = 8) and partial feature tiles"""
@@ -718,6 +718,7 @@ def test_every_gemm_tile_shape_on_a_ragged_problem(tile):
 
 
 @pytest.mark.parametrize("tile,grid_cap,split", [(20, -1, -1), (21, -1, -1), (22, -1, -1), (16, -1, -1), (20, 3, -1),
+                                                 (28, -1, -1), (28, 3, -1),
                                                  (22, 5, -1), (21, 1, 0), (16, 7, -1), (22, 4, 0), (16, 2, 0),
                                                  (22, 1, 16), (20, 6, 3)])
 def test_big_gemm_tiles_with_many_tiles_per_workgroup(tile, grid_cap, split):
@@ -796,13 +797,14 @@ def test_in_launch_tail_pieces_of_the_split_gemm(rows, ring):
         assert left * 4 > 0 and left * 4 * 2 <= grid          # the kernel's condition for the 128 x 64 pieces
     T = sum(rows)
     w = WL.small(T=T, d=d, E=2, k=1, F=F, D=1, dtype="bf16", C=1)
-    assert T // 2 >= 192                                     # the launcher's estimate of rows per group picks tile 22
     ids = np.repeat(np.arange(2, dtype=np.int32), rows)[:, None]
     r = np.random.default_rng(5)
     ids = ids[r.permutation(T)]                              # dispatch has to gather the groups
     e2r, phys, inv = O.vanilla_placement(2, 1)
     m = S.SemMoE(S.Config.from_workload(w), allocate_workspace=False)
     try:
+        m.set_tuning(0, 22)      # the 256 x 256 tiles of the full-size workloads (so few rows would take pieces throughout)
+        m.set_tuning(1, 22)
         m.set_tuning(4, grid)
         m.set_tuning(6, ring)
         lay = H.Layer(w)
@@ -824,7 +826,7 @@ def test_in_launch_tail_pieces_of_the_split_gemm(rows, ring):
         lo = dw["expert_offsets"][1] + (len(range(0, rows[1], 256)) - 1) * 256
         H.assert_close(Y[lo:], Yo[lo:], "bf16", "Y rows of the left-over tiles")
     finally:
-        for key in (4, 6):
+        for key in (0, 1, 4, 6):
             m.set_tuning(key, -1)
 
 
