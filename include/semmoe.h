@@ -10,9 +10,16 @@
  *   - Every function returns a status: SEMMOE_OK or a negative SEMMOE_E* code.  Arguments are
  *     validated before anything is launched, so argument errors need no GPU.
  *   - "dev" pointers are device memory, "host" pointers host memory.  The caller owns every
- *     buffer; the library allocates nothing and keeps no state between calls.  Scratch comes
- *     from the caller's workspace `ws` of at least semmoe_workspace_bytes() bytes, 256-byte
- *     aligned; calls on one stream may share it.
+ *     buffer and the library allocates nothing.  Scratch comes from the caller's workspace `ws`
+ *     of at least semmoe_workspace_bytes() bytes, 256-byte aligned; calls on one stream may
+ *     share it.
+ *   - No result depends on an earlier call.  What the library does keep between calls, all of it
+ *     safe to use from several threads: per device, its compute-unit count and LDS limit (looked
+ *     up once) and which kernels already had their LDS limit raised there; per thread, the last
+ *     HIP error; per process, the tuning knobs of semmoe_set_tuning (tests and sweeps: a knob set
+ *     by one thread changes the kernel choice of every thread); per device, the address of the
+ *     fixed scratch array of semmoe_reshuffle_static.  The current device must be the device of
+ *     `stream` and of the buffers.
  *   - Device calls enqueue on `stream` (a hipStream_t passed as void*; NULL = default stream)
  *     and return without synchronising.  Calls that share a workspace must not overlap.
  *   - Activations and weights ("act" type) are fp32 or bf16 as cfg->dtype says, row-major,
@@ -68,11 +75,14 @@ int32_t semmoe_last_hip_error(void);
 int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*host*/);
 
 /*
- * Tuning knobs for benchmarks (process-wide, not thread-safe).  value < 0 restores the default, which the
- * library picks per shape.  Results never depend on them beyond fp32 summation order inside a GEMM tile.
+ * Tuning knobs for tests and sweeps.  Process-wide state: a knob holds until it is set again and applies to every
+ * call of every thread (each knob is one atomic integer; a call reads the knobs it needs once, when it picks its
+ * kernels).  value < 0 restores the default, which the library picks per shape.  Results never depend on them beyond
+ * fp32 summation order inside a GEMM tile.  semmoe_get_tuning reads a knob back (-1: default).
  *   SEMMOE_TUNE_GATEUP_TILE / SEMMOE_TUNE_DOWN_TILE: tile-shape id of the bf16 grouped GEMMs
  *     (0, 3, 4, 6: register-staged; 11, 12, 14, 15, 16: direct-to-LDS ring; 17, 18: skinny register-staged tiles;
  *     19, 25, 26, 27: skinny tiles with a direct-to-LDS ring for decode;
+ *     28: 128 x 128 pieces throughout (the default when 256 x 256 tiles would fill less than half the compute units);
  *     20, 21, 22: four waves on a 256 x 256 tile with loads placed between the MFMAs; K must be a multiple of the
  *     K slice (32 for 20 and 21, 64 for 22) and hold at least a ring of slices (128); other K run as 16)
  *   SEMMOE_TUNE_BLOCKS_PER_CU: persistent workgroups per compute unit for those GEMMs
@@ -103,6 +113,7 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
 #define SEMMOE_TUNE_ROUTE_SPLIT 7 /* parts of K in the few-token router; 0 = fused kernel */
 #define SEMMOE_TUNE_GRID_CAP 4   /* upper limit of the persistent GEMM grids (tests: many tiles per workgroup) */
 int32_t semmoe_set_tuning(int32_t key, int32_t value);
+int32_t semmoe_get_tuning(int32_t key, int32_t* value_out /*host*/);
 
 /*
  * route - the gating function G(h) = top-k(softmax(W_g h + b_g)) of Sec. 3.2.

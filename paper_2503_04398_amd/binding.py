@@ -93,6 +93,7 @@ _SIGS = {
     "semmoe_last_hip_error": ([], C.c_int32),
     "semmoe_workspace_bytes": ([_P, C.POINTER(C.c_size_t)], C.c_int32),
     "semmoe_set_tuning": ([C.c_int32, C.c_int32], C.c_int32),
+    "semmoe_get_tuning": ([C.c_int32, _P], C.c_int32),
     "semmoe_route": ([_P] * 12 + [C.c_size_t], C.c_int32),
     "semmoe_route_from_logits": ([_P] * 6, C.c_int32),
     "semmoe_coact_hist": ([_P, _P, _P, C.c_int32, _P, _P], C.c_int32),
@@ -188,6 +189,11 @@ class SemMoE:
 
     def set_tuning(self, key: int, value: int):
         self._check("semmoe_set_tuning", self.lib.semmoe_set_tuning(int(key), int(value)))
+
+    def get_tuning(self, key: int) -> int:
+        v = C.c_int32(0)
+        self._check("semmoe_get_tuning", self.lib.semmoe_get_tuning(int(key), C.byref(v)))
+        return int(v.value)
 
     # -- entry points
     def route(self, X, W_r, topk_ids, topk_w, b_g=None, token_class=None, class_bias=None, sel_bias=None,

@@ -6,6 +6,48 @@ namespace semmoe {
 static thread_local int32_t g_last_hip_error = 0;
 void set_last_hip_error(hipError_t e) { g_last_hip_error = static_cast<int32_t>(e); }
 
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_info_state[kMaxDevices];  // 0: not looked up, 1: being written, 2: valid
+DeviceInfo g_info[kMaxDevices];
+}  // namespace
+
+int32_t device_info(DeviceInfo* out) {
+  int dev = 0;
+  SEMMOE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SEMMOE_EUNSUPPORTED;
+  if (g_info_state[dev].load(std::memory_order_acquire) != 2) {
+    DeviceInfo d{256, 65536};
+    SEMMOE_HIP(hipDeviceGetAttribute(&d.num_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    SEMMOE_HIP(hipDeviceGetAttribute(&d.max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    if (d.num_cu <= 0 || d.max_lds <= 0) return SEMMOE_EHIP;
+    int expect = 0;
+    if (g_info_state[dev].compare_exchange_strong(expect, 1, std::memory_order_acq_rel)) {
+      g_info[dev] = d;
+      g_info_state[dev].store(2, std::memory_order_release);
+    } else {
+      *out = d;  // another thread is writing the same values
+      return SEMMOE_OK;
+    }
+  }
+  *out = g_info[dev];
+  return SEMMOE_OK;
+}
+
+int32_t allow_max_dynamic_lds(std::atomic<uint64_t>* done, const void* kernel) {
+  int dev = 0;
+  SEMMOE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SEMMOE_EUNSUPPORTED;
+  const uint64_t bit = 1ull << dev;
+  if (done->load(std::memory_order_acquire) & bit) return SEMMOE_OK;
+  DeviceInfo d;
+  const int32_t st = device_info(&d);
+  if (st != SEMMOE_OK) return st;
+  SEMMOE_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, d.max_lds));
+  done->fetch_or(bit, std::memory_order_release);
+  return SEMMOE_OK;
+}
+
 int32_t validate_config(const semmoe_config* cfg, bool need_T, bool need_rows, bool need_ffn) {
   if (!cfg) return SEMMOE_EINVAL;
   if (cfg->E <= 0 || cfg->k <= 0 || cfg->D <= 0) return SEMMOE_EINVAL;

@@ -3,6 +3,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <atomic>
 #include <stddef.h>
 
 #include "semmoe.h"
@@ -24,6 +26,17 @@ void set_last_hip_error(hipError_t e);
   } while (0)
 
 #define SEMMOE_LAUNCH_CHECK() SEMMOE_HIP(hipGetLastError())
+
+// Facts about the current device, looked up once per device and kept (device ids below 64; thread-safe).
+struct DeviceInfo {
+  int num_cu;   // compute units
+  int max_lds;  // most LDS a workgroup can ask for, bytes
+};
+int32_t device_info(DeviceInfo* out);
+
+// Raises a kernel's dynamic-LDS limit to the device's maximum, once per device: `done` is the call site's own flag
+// word (bit = device id), so every kernel and every device is handled exactly once, from whichever thread comes first.
+int32_t allow_max_dynamic_lds(std::atomic<uint64_t>* done, const void* kernel);
 
 // Shape rules every call shares.  `need_ffn`: d and F are used; `need_T`: cfg->T is used.
 int32_t validate_config(const semmoe_config* cfg, bool need_T, bool need_rows, bool need_ffn);

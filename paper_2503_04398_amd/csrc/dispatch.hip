@@ -397,8 +397,11 @@ static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, cons
   if ((path != 1 && T <= kSingleAutoT) || path == 2) {
     if (T > kSingleMaxT) return SEMMOE_EUNSUPPORTED;
     const size_t lds = dp_single_lds(E, D);
-    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(dp_single_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+    static std::atomic<uint64_t> lds_allowed{0};
+    {
+      const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(dp_single_kernel));
+      if (as != SEMMOE_OK) return as;
+    }
     hipLaunchKernelGGL(dp_single_kernel, dim3(1), dim3(kChunk), lds, s, T, k, E, D, topk_ids, token_rank, shf,
                        phys_of_expert, slot_of_pair, pair_of_slot, expert_offsets, rank_offsets, send_matrix,
                        reinterpret_cast<unsigned long long*>(remote_pairs));

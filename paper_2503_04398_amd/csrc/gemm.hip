@@ -4,26 +4,23 @@
 
 namespace semmoe {
 
-static int g_num_cu = 0;
-static int g_max_lds = 0;
-static int g_tune[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
+// Tuning knobs (semmoe_set_tuning): process-wide, read by every call from every thread; meant for tests and sweeps.
+static std::atomic<int> g_tune[8] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 
+// compute units / LDS limit of the current device (looked up once per device; 256 / 64 KB if the lookup fails)
 static int num_cu() {
-  if (g_num_cu == 0) {
-    int dev = 0, n = 0, l = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    if (hipDeviceGetAttribute(&l, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || l <= 0) l = 65536;
-    g_num_cu = n;
-    g_max_lds = l;
-  }
-  return g_num_cu;
+  DeviceInfo d;
+  return device_info(&d) == SEMMOE_OK ? d.num_cu : 256;
+}
+static int max_lds() {
+  DeviceInfo d;
+  return device_info(&d) == SEMMOE_OK ? d.max_lds : 65536;
 }
 
-int tuning_value(int key) { return (key >= 0 && key < 8) ? g_tune[key] : -1; }
+int tuning_value(int key) { return (key >= 0 && key < 8) ? g_tune[key].load(std::memory_order_relaxed) : -1; }
 
 static int grid_for(long long tile_bound, long long cap) {
-  if (g_tune[SEMMOE_TUNE_GRID_CAP] > 0 && cap > g_tune[SEMMOE_TUNE_GRID_CAP]) cap = g_tune[SEMMOE_TUNE_GRID_CAP];
+  if (tuning_value(SEMMOE_TUNE_GRID_CAP) > 0 && cap > tuning_value(SEMMOE_TUNE_GRID_CAP)) cap = tuning_value(SEMMOE_TUNE_GRID_CAP);
   return (int)(tile_bound < cap ? tile_bound : cap);
 }
 
@@ -35,13 +32,12 @@ static int32_t launch_bf16(const GemmArgs& a, int max_rows, int blocks_per_cu, h
   if (bound <= 0) return SEMMOE_OK;
   const int grid = grid_for(bound, (long long)num_cu() * blocks_per_cu);
   auto kern = gemm_bf16_kernel<MODE, NWF, NWT, TF, TT, BK, MINW>;
-  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
   if (C::kLdsBytes > 48 * 1024) {
-    static bool attr_set = false;  // one flag per instantiation
-    if (!attr_set) {
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     int(C::kLdsBytes)));
-      attr_set = true;
+    static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+    {
+      const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+      if (as != SEMMOE_OK) return as;
     }
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
@@ -57,13 +53,12 @@ static int32_t launch_dma(const GemmArgs& a, int max_rows, int blocks_per_cu, hi
   if (bound <= 0) return SEMMOE_OK;
   const int grid = grid_for(bound, (long long)num_cu() * blocks_per_cu);
   auto kern = gemm_bf16_dma_kernel<MODE, NWF, NWT, TF, TT, BK, NSTAGE, MINW>;
-  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
   if (C::kLdsBytes > 48 * 1024) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     int(C::kLdsBytes)));
-      attr_set = true;
+    static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+    {
+      const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+      if (as != SEMMOE_OK) return as;
     }
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
@@ -79,17 +74,16 @@ static int32_t launch_w4(const GemmArgs& a, int max_rows, hipStream_t stream) {
   if (a.K % BK != 0 || a.K / BK < NSTAGE) return SEMMOE_EUNSUPPORTED;
   if ((unsigned long long)w_rows * a.ldw * 2 >= (1ull << 32) || (unsigned long long)C::BT * a.ldx * 2 >= (1ull << 32))
     return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
-  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
   const int n_ftiles = cdiv(a.N, C::FEAT);
   const long long bound = (long long)(max_rows / C::BT + a.nq) * n_ftiles;
   if (bound <= 0) return SEMMOE_OK;
   const int grid = grid_for(bound, num_cu());
   auto kern = gemm_bf16_w4_kernel<MODE, BK, NSTAGE, DMA_EVERY>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   int(C::kLdsBytes)));
-    attr_set = true;
+  static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+  {
+    const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+    if (as != SEMMOE_OK) return as;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
@@ -115,12 +109,11 @@ static int32_t launch_tail_as(GemmArgs a, int max_rows, int head_grid, hipStream
   a.sched_sub_f = kSubF;
   const int grid = grid_for(left_p * kSubT * kSubF, (long long)num_cu() * PER_CU);
   auto kern = gemm_bf16_dma_kernel<MODE, 2, 2, 2, 1, 64, RING, 1>;
-  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   int(C::kLdsBytes)));
-    attr_set = true;
+  if (C::kLdsBytes > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
+  static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+  {
+    const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+    if (as != SEMMOE_OK) return as;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
@@ -136,7 +129,7 @@ static int32_t launch_tail_pieces(GemmArgs a, int max_rows, int head_grid, hipSt
   if (a.K % 64 != 0 || a.K / 64 < NSTAGE) return SEMMOE_EUNSUPPORTED;
   if ((unsigned long long)w_rows * a.ldw * 2 >= (1ull << 32) || (unsigned long long)C::BT * a.ldx * 2 >= (1ull << 32))
     return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
-  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
   constexpr int kSubT = 256 / C::BT, kSubF = 256 / C::BW;
   const int n_ftiles_p = cdiv(a.N, kSubF * C::FEAT);
   const long long bound_p = (long long)(max_rows / 256 + a.nq) * n_ftiles_p;  // parent tiles, at most
@@ -148,11 +141,10 @@ static int32_t launch_tail_pieces(GemmArgs a, int max_rows, int head_grid, hipSt
   a.sched_sub_f = kSubF;
   const int grid = grid_for(left_p * kSubT * kSubF, num_cu());
   auto kern = gemm_bf16_piece_kernel<MODE, NSTAGE>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   int(C::kLdsBytes)));
-    attr_set = true;
+  static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+  {
+    const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+    if (as != SEMMOE_OK) return as;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
@@ -169,7 +161,7 @@ static int32_t launch_all_pieces(GemmArgs a, int max_rows, hipStream_t stream) {
   if (a.K % 64 != 0 || a.K / 64 < 3) return SEMMOE_EUNSUPPORTED;
   if ((unsigned long long)w_rows * a.ldw * 2 >= (1ull << 32) || (unsigned long long)C::BT * a.ldx * 2 >= (1ull << 32))
     return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
-  if (C::kLdsBytes > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (C::kLdsBytes > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
   const long long bound_p = (long long)(max_rows / 256 + a.nq) * cdiv(a.N, 2 * C::FEAT);  // parent tiles, at most
   if (bound_p <= 0) return SEMMOE_OK;
   a.sched_mode = 2;
@@ -179,11 +171,10 @@ static int32_t launch_all_pieces(GemmArgs a, int max_rows, hipStream_t stream) {
   a.sched_sub_f = 2;
   const int grid = grid_for(bound_p * 4, num_cu());
   auto kern = gemm_bf16_piece_kernel<MODE, 3>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   int(C::kLdsBytes)));
-    attr_set = true;
+  static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+  {
+    const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+    if (as != SEMMOE_OK) return as;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kLdsBytes, stream, a);
   SEMMOE_LAUNCH_CHECK();
@@ -201,7 +192,7 @@ static int32_t launch_w4_split(const GemmArgs& h, int max_rows, hipStream_t stre
   if ((unsigned long long)w_rows * h.ldw * 2 >= (1ull << 32) || (unsigned long long)CH::BT * h.ldx * 2 >= (1ull << 32))
     return SEMMOE_EUNSUPPORTED;  // per-lane row offsets are 32-bit
   const size_t lds = CH::kLdsBytes > CP::kLdsBytes ? CH::kLdsBytes : CP::kLdsBytes;
-  if (lds > size_t(g_max_lds)) return SEMMOE_EUNSUPPORTED;
+  if (lds > size_t(max_lds())) return SEMMOE_EUNSUPPORTED;
   const int n_ftiles = cdiv(h.N, CH::FEAT);
   const long long bound = (long long)(max_rows / CH::BT + h.nq) * n_ftiles;
   if (bound <= 0) return SEMMOE_OK;
@@ -211,13 +202,12 @@ static int32_t launch_w4_split(const GemmArgs& h, int max_rows, hipStream_t stre
   t.sched_g = grid;
   t.sched_sub_t = 256 / CP::BT;
   t.sched_sub_f = 256 / CP::BW;
-  t.sched_fine = g_tune[SEMMOE_TUNE_TAIL_RING] == 2 ? 0 : 1;
+  t.sched_fine = tuning_value(SEMMOE_TUNE_TAIL_RING) == 2 ? 0 : 1;
   auto kern = gemm_bf16_w4_split_kernel<MODE, 64, 2, 2, 3>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   int(lds)));
-    attr_set = true;
+  static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
+  {
+    const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(kern));
+    if (as != SEMMOE_OK) return as;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, h, t);
   SEMMOE_LAUNCH_CHECK();
@@ -226,7 +216,7 @@ static int32_t launch_w4_split(const GemmArgs& h, int max_rows, hipStream_t stre
 
 template <int MODE>
 static int32_t launch_tail(const GemmArgs& a, int max_rows, int head_grid, hipStream_t stream) {
-  const int ring = g_tune[SEMMOE_TUNE_TAIL_RING];
+  const int ring = tuning_value(SEMMOE_TUNE_TAIL_RING);
   if (ring == 6) return launch_tail_as<MODE, 6, 1>(a, max_rows, head_grid, stream);
   if (ring == 3) return launch_tail_as<MODE, 3, 2>(a, max_rows, head_grid, stream);
   // 128 x 128 pieces as a launch of their own (the default runs them inside the head's launch: launch_w4_split)
@@ -306,13 +296,13 @@ static int default_tile(int est_rows_per_group, long long big_tiles_at_most) {
 // Head/tail split: for the tile shapes of 256 x 256 with a persistent grid of one workgroup per compute unit.
 static bool split_launch(int id) {
   const bool big = id == 16 || (id >= 20 && id <= 22);
-  const int t = g_tune[SEMMOE_TUNE_HEAD_TAIL];
+  const int t = tuning_value(SEMMOE_TUNE_HEAD_TAIL);
   return big && t != 0;
 }
 
 // left-over share of a round (in sixteenths) up to which the split happens
 static int split_threshold() {
-  const int t = g_tune[SEMMOE_TUNE_HEAD_TAIL];
+  const int t = tuning_value(SEMMOE_TUNE_HEAD_TAIL);
   return (t >= 1 && t <= 16) ? t : 8;
 }
 
@@ -320,20 +310,19 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
                     hipStream_t stream) {
   if (a.nq <= 0 || max_rows <= 0) return SEMMOE_OK;
   if (a.nq > 512) return SEMMOE_EUNSUPPORTED;
-  num_cu();
   if (dtype == SEMMOE_BF16) {
-    const int bpc = g_tune[SEMMOE_TUNE_BLOCKS_PER_CU];
+    const int bpc = tuning_value(SEMMOE_TUNE_BLOCKS_PER_CU);
     switch (mode) {
       case kModeLogits: return launch_bf16<kModeLogits, 2, 2, 2, 1, 64>(a, max_rows, 2, stream);  // 128 experts x 64 tokens
       case kModeSwiglu: {
-        const int id = g_tune[SEMMOE_TUNE_GATEUP_TILE] >= 0
-                           ? g_tune[SEMMOE_TUNE_GATEUP_TILE]
+        const int id = tuning_value(SEMMOE_TUNE_GATEUP_TILE) >= 0
+                           ? tuning_value(SEMMOE_TUNE_GATEUP_TILE)
                            : default_tile(est_rows_per_group, (long long)(max_rows / 256 + a.nq) * cdiv(a.N, 128));
         if (!split_launch(id)) return launch_bf16_tile<kModeSwiglu>(id, a, max_rows, bpc, stream);
         GemmArgs h = a;
         h.sched_mode = 1;
         h.sched_thr = split_threshold();
-        if (id == 22 && (g_tune[SEMMOE_TUNE_TAIL_RING] < 0 || g_tune[SEMMOE_TUNE_TAIL_RING] == 2)) {  // both halves in one launch
+        if (id == 22 && (tuning_value(SEMMOE_TUNE_TAIL_RING) < 0 || tuning_value(SEMMOE_TUNE_TAIL_RING) == 2)) {  // both halves in one launch
           const int32_t sm = launch_w4_split<kModeSwiglu>(h, max_rows, stream);
           if (sm != SEMMOE_EUNSUPPORTED) return sm;
         }
@@ -342,14 +331,14 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
         return launch_tail<kModeSwiglu>(h, max_rows, big_tile_grid(a, max_rows, 128), stream);
       }
       default: {
-        const int id = g_tune[SEMMOE_TUNE_DOWN_TILE] >= 0
-                           ? g_tune[SEMMOE_TUNE_DOWN_TILE]
+        const int id = tuning_value(SEMMOE_TUNE_DOWN_TILE) >= 0
+                           ? tuning_value(SEMMOE_TUNE_DOWN_TILE)
                            : default_tile(est_rows_per_group, (long long)(max_rows / 256 + a.nq) * cdiv(a.N, 256));
         if (!split_launch(id)) return launch_bf16_tile<kModeStore>(id, a, max_rows, bpc, stream);
         GemmArgs h = a;
         h.sched_mode = 1;
         h.sched_thr = split_threshold();
-        if (id == 22 && (g_tune[SEMMOE_TUNE_TAIL_RING] < 0 || g_tune[SEMMOE_TUNE_TAIL_RING] == 2)) {
+        if (id == 22 && (tuning_value(SEMMOE_TUNE_TAIL_RING) < 0 || tuning_value(SEMMOE_TUNE_TAIL_RING) == 2)) {
           const int32_t sm = launch_w4_split<kModeStore>(h, max_rows, stream);
           if (sm != SEMMOE_EUNSUPPORTED) return sm;
         }
@@ -370,6 +359,12 @@ int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int es
 
 extern "C" int32_t semmoe_set_tuning(int32_t key, int32_t value) {
   if (key < 0 || key >= 8) return SEMMOE_EINVAL;
-  semmoe::g_tune[key] = value;
+  semmoe::g_tune[key].store(value, std::memory_order_relaxed);
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_get_tuning(int32_t key, int32_t* value_out) {
+  if (key < 0 || key >= 8 || !value_out) return SEMMOE_EINVAL;
+  *value_out = semmoe::tuning_value(key);
   return SEMMOE_OK;
 }

@@ -85,14 +85,14 @@ extern "C" int32_t semmoe_coact_hist(const semmoe_config* cfg, void* stream, con
   if (T_batch == 0) return SEMMOE_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t lds = size_t(cfg->E) * (cfg->E + 1) / 2 * 4;
-  int dev = 0, max_lds = 0;
-  SEMMOE_HIP(hipGetDevice(&dev));
-  SEMMOE_HIP(hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+  DeviceInfo di;
+  st = device_info(&di);
+  if (st != SEMMOE_OK) return st;
   const int grid = cdiv(T_batch, 256) < 256 ? cdiv(T_batch, 256) : 256;
-  if (lds <= size_t(max_lds)) {
-    if (lds > 48 * 1024)
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(coact_lds_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+  if (lds <= size_t(di.max_lds)) {
+    static std::atomic<uint64_t> lds_allowed{0};
+    st = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(coact_lds_kernel));
+    if (st != SEMMOE_OK) return st;
     hipLaunchKernelGGL(coact_lds_kernel, dim3(grid), dim3(256), lds, s, cfg->E, cfg->k, T_batch, topk_ids, load,
                        coact);
   } else {

@@ -1275,11 +1275,10 @@ static int32_t reshuffle_with_scratch(const semmoe_config* cfg, void* stream, co
   const int path = tuning_value(SEMMOE_TUNE_INDEX_PATH);
   if ((path != 1 && T <= kSingleAutoT && D < 255) || path == 2) {
     if (T > kSingleMaxT || D >= 255) return SEMMOE_EUNSUPPORTED;
-    static bool attr_set = false;
-    if (!attr_set) {
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rs_single_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(sizeof(SingleLds))));
-      attr_set = true;
+    static std::atomic<uint64_t> lds_allowed{0};
+    {
+      const int32_t as = allow_max_dynamic_lds(&lds_allowed, reinterpret_cast<const void*>(rs_single_kernel));
+      if (as != SEMMOE_OK) return as;
     }
     hipLaunchKernelGGL(rs_single_kernel, dim3(1), dim3(kChunk), sizeof(SingleLds), s, T, k, D, cfg->E, cfg->cap,
                        per_home, topk_ids, expert_to_rank, token_rank, shf, inv_shf, rank_count);

@@ -951,10 +951,11 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     const bf16_t* Xb = static_cast<const bf16_t*>(X);
     const bf16_t* Wb = static_cast<const bf16_t*>(W_r);
     const int tf = cfg->E <= 128 ? 1 : (cfg->E <= 256 ? 2 : 4);
-    int dev0 = 0, ncu0 = 256;
-    SEMMOE_HIP(hipGetDevice(&dev0));
-    SEMMOE_HIP(hipDeviceGetAttribute(&ncu0, hipDeviceAttributeMultiprocessorCount, dev0));
-    const int n_parts = route_parts(cfg, ncu0);
+    DeviceInfo di;
+    st = device_info(&di);
+    if (st != SEMMOE_OK) return st;
+    const int ncu = di.num_cu;
+    const int n_parts = route_parts(cfg, ncu);
     float* partial = nullptr;
     float* logits_ws = nullptr;
     if (n_parts > 1) {
@@ -968,9 +969,6 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     const bool wide = n_parts == 1 && cdiv(cfg->T, 64) >= 256 && tf <= 2;
     const bool wider = wide && tf == 1 && cdiv(cfg->T, 128) >= 256;
     const int bt = wider ? 128 : (wide ? 64 : 32);
-    int dev = 0, ncu = 256;
-    SEMMOE_HIP(hipGetDevice(&dev));
-    SEMMOE_HIP(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
     const int n_tiles = cdiv(cfg->T, bt);
     const int form = select_form(*cfg);
     const bool sig = cfg->score == SEMMOE_SIGMOID;
@@ -983,9 +981,10 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     const int per_cu = lds <= 80 * 1024 ? 2 : 1;                                                                    \
     const int items = n_tiles * n_parts;                                                                            \
     const int grid = items < ncu * per_cu ? items : ncu * per_cu;                                                   \
-    if (lds > 48 * 1024)                                                                                            \
-      SEMMOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(route_fused_kernel<TF_, TT_, NS_, FORM_, SIG_>), \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));                        \
+    static std::atomic<uint64_t> lds_allowed{0}; /* one per instantiation named below */                            \
+    st = allow_max_dynamic_lds(&lds_allowed,                                                                        \
+                               reinterpret_cast<const void*>(route_fused_kernel<TF_, TT_, NS_, FORM_, SIG_>));      \
+    if (st != SEMMOE_OK) return st;                                                                                 \
     hipLaunchKernelGGL((route_fused_kernel<TF_, TT_, NS_, FORM_, SIG_>), dim3(grid), dim3(256), lds, s, *cfg, Xb,   \
                        Wb, b_g, token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w, n_parts, partial); \
   } while (0)

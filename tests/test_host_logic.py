@@ -37,6 +37,25 @@ def _mk(**kw):
     return S.SemMoE(S.Config(**base), allocate_workspace=False)
 
 
+def test_tuning_knobs_are_process_state_that_reads_back():
+    """a knob holds its value until it is set again (from any SemMoE object: the state belongs to the process),
+    reads back, and is restored by a negative value; keys outside the table are refused"""
+    a, b = _mk(), _mk(T=128, cap=32)
+    for key in range(8):
+        assert a.get_tuning(key) == -1
+    try:
+        a.set_tuning(4, 13)
+        assert a.get_tuning(4) == 13 and b.get_tuning(4) == 13
+        b.set_tuning(4, 7)
+        assert a.get_tuning(4) == 7
+    finally:
+        a.set_tuning(4, -1)
+    assert b.get_tuning(4) == -1
+    assert a.lib.semmoe_set_tuning(8, 1) == -1 and a.lib.semmoe_set_tuning(-1, 1) == -1
+    v = C.c_int32(5)
+    assert a.lib.semmoe_get_tuning(8, C.byref(v)) == -1 and a.lib.semmoe_get_tuning(0, None) == -1
+
+
 def test_workspace_bytes_grows_with_the_hidden_activation():
     a = _mk().workspace_bytes()
     b = _mk(T=128, cap=32).workspace_bytes()

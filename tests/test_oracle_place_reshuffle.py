@@ -119,6 +119,35 @@ def test_place_finetune_never_lowers_mass_and_gain_formula_matches_mass_differen
         if w_prev is not None:
             assert W >= w_prev
         w_prev = W
+    # the swap gain of the sweeps, A(e1, c2 - e2) + A(e2, c1 - e1) - A(e1, c1 - e1) - A(e2, c2 - e2) with
+    # A(e, S) = sum of coact[e, e'] over e' in S, is exactly what a swap adds to the intra-rank mass
+    e2r0, _, _ = O.place(load, co, D, ft_passes=0)
+    W0 = O.intra_rank_mass(co, e2r0)
+    members = {c: [e for e in range(E) if e2r0[e] == c] for c in range(D)}
+    A = lambda e, S: int(sum(co[e, x] for x in S))
+    best = 0
+    for e1 in range(E):
+        for e2 in range(e1 + 1, E):
+            c1, c2 = int(e2r0[e1]), int(e2r0[e2])
+            if c1 == c2:
+                continue
+            s1 = [x for x in members[c1] if x != e1]
+            s2 = [x for x in members[c2] if x != e2]
+            gain = A(e1, s2) + A(e2, s1) - A(e1, s1) - A(e2, s2)
+            swapped = e2r0.copy()
+            swapped[e1], swapped[e2] = c2, c1
+            assert O.intra_rank_mass(co, swapped) - W0 == gain
+            best = max(best, gain)
+    # and the sweeps stop only where no swap gains: after enough passes every such gain is <= 0
+    e2r8, _, _ = O.place(load, co, D, ft_passes=64)
+    W8 = O.intra_rank_mass(co, e2r8)
+    for e1 in range(E):
+        for e2 in range(e1 + 1, E):
+            if e2r8[e1] != e2r8[e2]:
+                swapped = e2r8.copy()
+                swapped[e1], swapped[e2] = e2r8[e2], e2r8[e1]
+                assert O.intra_rank_mass(co, swapped) <= W8
+    assert (best > 0) == (W8 > W0)
 
 
 def test_place_greedy_order_hottest_first_and_gamma_balances_load():
