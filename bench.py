@@ -118,6 +118,19 @@ def achievable_peaks(m, torch, dev):
             flops[0] = m.probe_mfma(ops, iters, sink)
         t = timed(run, 5)
         out["mfma_only_%s_operands_TFLOPs" % name] = round(flops[0] / t / 1e12, 1)
+    # the K loop of the grouped GEMM's 256 x 256 tile alone (no tile list, epilogue or ragged edge; operands shared
+    # in L2), whole and with parts taken out: what the loads and the LDS reads cost the MFMA stream
+    n_panels, row_bytes, n_sl = 96, 16384, 2000
+    panels = torch.randn(n_panels * 256 * row_bytes // 2, device=dev).to(torch.bfloat16)
+    sink2 = torch.empty(256 * 512, dtype=torch.float32, device=dev)
+    for v, name in ((0, "tile_loop"), (1, "tile_loop_without_loads"), (2, "tile_loop_without_lds_reads"),
+                    (3, "tile_loop_mfma_and_barriers_only"), (4, "tile_loop_eight_waves")):
+        flops = [0.0]
+        def run():
+            flops[0] = m.probe_tile_loop(panels, n_panels, row_bytes, v, n_sl, sink2)
+        t = timed(run, 4)
+        out[name + "_TFLOPs"] = round(flops[0] / t / 1e12, 1)
+    del panels
     # the vendor library's plain square bf16 GEMM on random data (torch.matmul -> hipBLASLt / rocBLAS): a reference
     # for what a dense GEMM sustains on this chip, not part of the path
     n = 8192
@@ -327,10 +340,10 @@ def run_config(name, args, traffic_tab):
     ms_evented = (time.perf_counter() - t0) / args.steps * 1e3
     stage_ms = {nm: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps for i, nm in enumerate(stages)}
     if args.calib_copy:
-        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)    # 256 MiB read + 256 MiB written per copy
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)    # 256 MiB read + 256 MiB written per copy
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            m.probe_copy(dst, src, src.numel())
         torch.cuda.synchronize()
         del src, dst
     # W untimed warm-up steps, then the timed region: exactly K steps, nothing between the calls
@@ -369,16 +382,18 @@ def run_config(name, args, traffic_tab):
         torch.cuda.synchronize()
         ms_graph = (time.perf_counter() - t0) / args.steps * 1e3
     # ---------------- the FFN of every rank's experts in one call (the whole device's expert work, not one rank's share)
-    for _ in range(2):
-        m.expert_ffn(-1, X_perm, expert_offsets, inv, W_gu, W_down, Y)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        m.expert_ffn(-1, X_perm, expert_offsets, inv, W_gu, W_down, Y)
-    e1.record()
-    torch.cuda.synchronize()
-    ms_ffn_all = e0.elapsed_time(e1) / 5
+    ms_ffn_all = float("nan")
+    if not args.step_only:
+        for _ in range(2):
+            m.expert_ffn(-1, X_perm, expert_offsets, inv, W_gu, W_down, Y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            m.expert_ffn(-1, X_perm, expert_offsets, inv, W_gu, W_down, Y)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_ffn_all = e0.elapsed_time(e1) / 5
 
     # ---------------- what the batch looked like
     ro = rank_offsets.cpu().numpy()
@@ -403,7 +418,7 @@ def run_config(name, args, traffic_tab):
     torch.cuda.synchronize()
 
     next_rows = None
-    if name == NEXT_ROWS_ON and not args.no_next_rows:
+    if name == NEXT_ROWS_ON and not (args.no_next_rows or args.step_only):
         # ---------------- next row: reshuffle with gain-aware spill rounds (not part of the timed step)
         rounds_report = {}
         for R in (2, 3, D):
@@ -683,7 +698,9 @@ def run_config(name, args, traffic_tab):
     }
     if next_rows:
         rec.update(next_rows)
-    if not (args.no_cpu or args.zero_weights):
+    if args.step_only:
+        rec.pop("expert_ffn_all_ranks")
+    if not (args.no_cpu or args.zero_weights or args.step_only):
         t0 = time.time()
         rec["cpu_baseline"] = cpu_baseline(w, min(args.cpu_sample, T), (e2r_h, phys_h, inv_h), weights0, args.cpu_seconds)
         say("[%s] cpu baseline %.1f s" % (name, time.time() - t0))
@@ -704,6 +721,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the reports of the widened rows (spill rounds ...)")
     ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-peak probes")
+    ap.add_argument("--step-only", action="store_true",
+                    help="nothing but set-up and the layer steps (for profiler runs: every launch of a step kernel in "
+                         "the trace is then a launch of the step): no all-ranks FFN, widened rows, probes or CPU baseline")
     ap.add_argument("--all-ranks", action="store_true", help="FFN over every rank's experts instead of rank 0")
     ap.add_argument("--host-weights", action="store_true",
                     help="draw every expert's weights with the numpy generator (default: rank 0's experts and the shared "
@@ -714,7 +734,7 @@ def main():
                     help="diagnostic: expert weights all zero (same launches, tiles and bytes; shows how much of the GEMM "
                          "time depends on the data values, i.e. on power-limited clocks); the CPU baseline is skipped")
     ap.add_argument("--calib-copy", action="store_true",
-                    help="also run a plain 256 MiB device copy three times before the timed loops: under rocprofv3 "
+                    help="also run the library's copy probe on 256 MiB three times between the loops: under rocprofv3 "
                          "--pmc its FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
     ap.add_argument("--balance-study", action="store_true",
                     help="instead of the timed layer step: sweep the load weight gamma of the placement and the capacity "
@@ -758,7 +778,7 @@ def main():
             r.pop("_probe_handle", None)
             out["configs"][n] = r
     out["device"] = torch.cuda.get_device_name(0)
-    if not args.no_peaks:
+    if not (args.no_peaks or args.step_only):
         out["achievable"] = achievable_peaks(m, torch, "cuda:0")
     if cpu is not None:
         out["cpu_baseline"] = cpu

@@ -440,16 +440,27 @@ int32_t semmoe_combine(const semmoe_config* cfg, void* stream, const void* Y, co
 
 /*
  * Probes of what the chip sustains, for reading roofline fractions against (not part of the layer; no passage of
- * the paper).  Both enqueue one kernel on `stream`; the caller times it.
+ * the paper).  Each enqueues one kernel on `stream`; the caller times it.
  *   semmoe_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte aligned, bytes % 16 == 0; moves
  *     2*bytes through HBM.
  *   semmoe_probe_mfma: 256 workgroups of 4 waves, each wave 16 independent 32x32x16 bf16 MFMAs per iteration on operand
  *     fragments read once from `operands` (device, 64 sets x 8 fragments x 64 lanes x 16 bytes = 512 KiB, any finite
  *     bf16 values: the data decide the power drawn and so the clock); `sink` (device, 256*256 floats) receives
  *     checksums; *flops_out (host, may be NULL) = flops of the launch.
+ *   semmoe_probe_tile_loop: the steady-state K loop of the grouped GEMM's 256 x 256 tile and nothing else (no tile
+ *     list, no epilogue, no ragged edge): 256 workgroups, each `n_slices` (>= 2) K slices of 64 through two LDS stages
+ *     filled by direct global->LDS loads, on operand panels that neighbouring workgroups share, so the loads hit
+ *     in L2.  `panels` (device, 16-byte aligned): n_panels (>= 96) panels of 256 rows of row_bytes bytes
+ *     (row_bytes % 128 == 0) of finite bf16 values; the walk over K wraps around inside a row.  variant 0: the loop
+ *     as the GEMM runs it, four waves of 128 x 128; 1: without the loads inside the loop; 2: without the fragment
+ *     reads; 3: MFMAs and barriers only; 4 - 7: the same four with eight waves of 128 x 64 (two per SIMD).  The
+ *     differences say what the loads and the LDS reads cost the MFMA stream: the ceiling of this tile design.
+ *     `sink` (device, 256*512 floats) receives checksums; *flops_out (host, may be NULL) = flops of the launch.
  */
 int32_t semmoe_probe_copy(void* stream, void* dst, const void* src, size_t bytes);
 int32_t semmoe_probe_mfma(void* stream, const void* operands, int32_t iters, float* sink, double* flops_out);
+int32_t semmoe_probe_tile_loop(void* stream, const void* panels, int32_t n_panels, int32_t row_bytes, int32_t variant,
+                               int32_t n_slices, float* sink, double* flops_out);
 
 #ifdef __cplusplus
 }

@@ -119,6 +119,7 @@ _SIGS = {
     "semmoe_combine": ([_P] * 7, C.c_int32),
     "semmoe_probe_copy": ([_P, _P, _P, C.c_size_t], C.c_int32),
     "semmoe_probe_mfma": ([_P, _P, C.c_int32, _P, C.POINTER(C.c_double)], C.c_int32),
+    "semmoe_probe_tile_loop": ([_P, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double)], C.c_int32),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -378,6 +379,13 @@ class SemMoE:
         fl = C.c_double(0.0)
         self._check("semmoe_probe_mfma", self.lib.semmoe_probe_mfma(_stream(), _ptr(operands), int(iters), _ptr(sink),
                                                                     C.byref(fl)))
+        return fl.value
+
+    def probe_tile_loop(self, panels, n_panels, row_bytes, variant, n_slices, sink):
+        """returns the flops of the launch"""
+        fl = C.c_double(0.0)
+        self._check("semmoe_probe_tile_loop", self.lib.semmoe_probe_tile_loop(
+            _stream(), _ptr(panels), int(n_panels), int(row_bytes), int(variant), int(n_slices), _ptr(sink), C.byref(fl)))
         return fl.value
 
     def combine(self, Y, slot_of_pair, topk_w, Out, Y_shared=None):

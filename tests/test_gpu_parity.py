@@ -846,6 +846,30 @@ def test_probes_copy_and_mfma_loop():
     assert (H.to_np(sink) == 3 * 16.0 * 256).all()
 
 
+@pytest.mark.parametrize("variant", list(range(8)))
+def test_probe_tile_loop_checksum(variant):
+    """the steady-state tile loop probe: on all-ones operands every MFMA adds 16 to each accumulator element, so a
+    lane's checksum is (its accumulator elements) x 16 x 4 k-steps x slices, whatever parts of the loop are left out"""
+    m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
+    n_panels, row_bytes, n_slices = 96, 1024, 9
+    panels = torch.ones(n_panels * 256 * row_bytes // 2, dtype=torch.bfloat16, device=H.DEV)
+    sink = torch.zeros(256 * 512, dtype=torch.float32, device=H.DEV)
+    flops = m.probe_tile_loop(panels, n_panels, row_bytes, variant, n_slices, sink)
+    torch.cuda.synchronize()
+    assert flops == 256 * 2.0 * 256 * 256 * 64 * n_slices
+    threads = 256 if variant < 4 else 512
+    elems = 256 if variant < 4 else 128                      # 4 x 4 or 4 x 2 tiles of 16 elements per lane
+    got = H.to_np(sink)[:256 * threads]
+    assert (got == elems * 16.0 * 4 * n_slices).all()
+    # argument checks happen on the host: too few panels, rows that are not whole 128-byte slices, one slice
+    with pytest.raises(S.SemMoEError):
+        m.probe_tile_loop(panels, 95, row_bytes, variant, n_slices, sink)
+    with pytest.raises(S.SemMoEError):
+        m.probe_tile_loop(panels, n_panels, 192, variant, n_slices, sink)
+    with pytest.raises(S.SemMoEError):
+        m.probe_tile_loop(panels, n_panels, row_bytes, variant, 1, sink)
+
+
 @pytest.mark.parametrize("seed", list(range(10)))
 def test_whole_path_on_random_shapes_with_default_kernels(seed):
     """the whole layer on seeded random shapes with the library's own choice of kernels (tile shapes by rows per
