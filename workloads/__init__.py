@@ -79,11 +79,11 @@ CONFIGS: Dict[str, Workload] = {
     "c1_tiny_fp32": Workload("c1_tiny_fp32", T=256, d=512, E=16, k=2, F=1024, D=4, dtype="fp32",
                              score="softmax", renorm=False, C=4, bias_lo=2.0, bias_hi=2.0,
                              class_mix="uniform"),
-    # configs[1]: Qwen3-30B-A3B-shaped layer (the workload the metric is quoted on)
+    # configs[1]: Qwen3-30B-A3B-shaped layer
     "c2_qwen3_30b": Workload("c2_qwen3_30b", T=8192, d=2048, E=128, k=8, F=768, D=8, dtype="bf16",
                              score="softmax", renorm=True, C=16, bias_lo=1.5, bias_hi=1.5,
                              class_mix="zipf", zipf_s=1.1),
-    # configs[2]: DeepSeek-V3-shaped layer
+    # configs[2]: DeepSeek-V3-shaped layer (the largest of the five; it fits one GPU)
     "c3_deepseek_v3": Workload("c3_deepseek_v3", T=16384, d=7168, E=256, k=8, F=2048, D=32, dtype="bf16",
                                score="sigmoid", renorm=True, C=32, bias_lo=1.5, bias_hi=1.5,
                                class_mix="uniform", n_group=8, topk_group=4, n_shared=1),
