@@ -230,8 +230,13 @@ def place(load, coact, D: int, alpha: int = 1, gamma: int = 0, ft_passes: int = 
     loads_cls, then smaller c); a rank holding E/D experts is masked.
     Fine-tuning: the algorithm's random pair swaps "kept if the affinity gain is positive" are
     taken as deterministic first-improvement sweeps over pairs e1 < e2 on different ranks, at
-    most `ft_passes` sweeps, stopping after a sweep without a swap.  gain = change of the
-    intra-rank co-activation mass W = sum_c sum_{a<b on c} coact[a,b].
+    most `ft_passes` sweeps, stopping after a sweep without a swap.  The gain of a swap weighs
+    both terms of the Sec. 3.3 objective with the weights of the greedy pass:
+        gain = alpha * (change of the intra-rank co-activation mass W = sum_c sum_{a<b on c} coact[a,b])
+             + gamma * (max(L1, L2) - max(L1', L2')),
+    L1, L2 the loads of the two ranks before and L1', L2' after the swap (what the swap takes off
+    the larger of the two loads: the maximum load over all ranks never grows by a swap whose load
+    term is not negative).  With gamma = 0 this is the affinity gain alone.
     Physical order: rank-major, ascending original id inside a rank.
     Returns (expert_to_rank[E], phys_of_expert[E], expert_of_phys[E]) int32."""
     load = np.asarray(load, dtype=np.int64)
@@ -272,9 +277,13 @@ def place(load, coact, D: int, alpha: int = 1, gamma: int = 0, ft_passes: int = 
                 c1, c2 = rank_of[e1], rank_of[e2]
                 if c1 == c2:
                     continue
-                gain = aff(e1, c2, e2) + aff(e2, c1, e1) - aff(e1, c1, e1) - aff(e2, c2, e2)
-                if gain > 0:
+                g_e = aff(e1, c2, e2) + aff(e2, c1, e1) - aff(e1, c1, e1) - aff(e2, c2, e2)
+                l1 = loads_cls[c1] - int(load[e1]) + int(load[e2])
+                l2 = loads_cls[c2] - int(load[e2]) + int(load[e1])
+                g_l = max(loads_cls[c1], loads_cls[c2]) - max(l1, l2)
+                if alpha * g_e + gamma * g_l > 0:
                     rank_of[e1], rank_of[e2] = c2, c1
+                    loads_cls[c1], loads_cls[c2] = l1, l2
                     swapped = True
         if not swapped:
             break
@@ -747,8 +756,9 @@ def expert_place_affinity(load, coact, D: int, unit_act=None, unit_rank=None, al
     Experts hottest first (equal -> lower id); arg-max over the clusters not yet full (equal -> smaller loads_cls,
     then smaller c); a cluster is full at E/D experts.  Fine-tuning as in `place`: first-improvement sweeps over
     pairs e1 < e2 on different clusters, gain = alpha_e*(change of the intra-cluster co-activation mass)
-    + beta_e*(change of the activation mass that is local, sum_e EAfR[e, cluster(e)]); swap when gain > 0.
-    With beta_e = 0 and alpha_e > 0 this is `place`.  Returns expert_to_rank[E] int32."""
+    + beta_e*(change of the activation mass that is local, sum_e EAfR[e, cluster(e)])
+    + gamma_e*(what the swap takes off the larger of the two clusters' loads); swap when gain > 0.
+    With beta_e = 0 this is `place`.  Returns expert_to_rank[E] int32."""
     load = np.asarray(load, dtype=np.int64)
     A = np.asarray(coact, dtype=np.int64)
     E = load.shape[0]
@@ -792,8 +802,12 @@ def expert_place_affinity(load, coact, D: int, unit_act=None, unit_rank=None, al
                     continue
                 g_e = aff(e1, c2, e2) + aff(e2, c1, e1) - aff(e1, c1, e1) - aff(e2, c2, e2)
                 g_r = R[e1][c2] + R[e2][c1] - R[e1][c1] - R[e2][c2]
-                if alpha_e * g_e + beta_e * g_r > 0:
+                l1 = loads_cls[c1] - int(load[e1]) + int(load[e2])
+                l2 = loads_cls[c2] - int(load[e2]) + int(load[e1])
+                g_l = max(loads_cls[c1], loads_cls[c2]) - max(l1, l2)
+                if alpha_e * g_e + beta_e * g_r + gamma_e * g_l > 0:
                     rank_of[e1], rank_of[e2] = c2, c1
+                    loads_cls[c1], loads_cls[c2] = l1, l2
                     swapped = True
         if not swapped:
             break

@@ -150,6 +150,59 @@ def test_place_finetune_never_lowers_mass_and_gain_formula_matches_mass_differen
     assert (best > 0) == (W8 > W0)
 
 
+def test_place_swap_gain_weighs_affinity_and_load_hand_example():
+    """the fine-tuning gain with both terms of the Sec. 3.3 objective, worked by hand.
+    loads (4, 2, 4, 6); co-activations (0,1) = 1, (1,2) = (1,3) = (2,3) = 3; two ranks of two; alpha = gamma = 1.
+    Greedy, hottest first: e3 -> rank 0; e0: -6 on rank 0 against 0 -> rank 1; e2: 3 - 6 = -3 on rank 0 against
+    0 - 4 -> rank 0 (full); e1 -> rank 1: ranks {2, 3} and {0, 1}, loads 10 and 6, intra-rank mass 3 + 1 = 4.
+    Sweep: (0, 2): affinity gain 0 + 3 - 1 - 3 = -1, loads stay (6, 10): no.  (0, 3): affinity gain
+    0 + 3 - 1 - 3 = -1, loads become (8, 8): the larger falls by 2: gain -1 + 2 = 1 > 0: swap.  Ranks {0, 2} and
+    {1, 3}.  (1, 2): 1 + 3 - 3 - 0 = 1 but the loads would go to (10, 6): 1 - 2 < 0: no.  (2, 3): 0 - 2: no.
+    A second sweep changes nothing.  With gamma = 0 the swap (0, 3) loses 1 and nothing moves."""
+    load = np.array([4, 2, 4, 6])
+    co = np.diag(load).astype(np.int64)
+    for (a, b), v in {(0, 1): 1, (1, 2): 3, (1, 3): 3, (2, 3): 3}.items():
+        co[a, b] = co[b, a] = v
+    greedy, _, _ = O.place(load, co, 2, alpha=1, gamma=1, ft_passes=0)
+    assert greedy.tolist() == [1, 1, 0, 0] and O.intra_rank_mass(co, greedy) == 4
+    tuned, _, _ = O.place(load, co, 2, alpha=1, gamma=1, ft_passes=8)
+    assert tuned.tolist() == [0, 1, 0, 1] and O.intra_rank_mass(co, tuned) == 3
+    assert np.bincount(tuned, weights=load).tolist() == [8, 8]
+    one, _, _ = O.place(load, co, 2, alpha=1, gamma=1, ft_passes=1)
+    assert one.tolist() == tuned.tolist()                       # the first sweep already makes the swap
+    # the load weight is what decides: doubled affinity weight (2 * -1 + 2 = 0, not > 0) keeps the greedy's ranks
+    assert O.place(load, co, 2, alpha=2, gamma=1, ft_passes=8)[0].tolist() == O.place(load, co, 2, 2, 1, 0)[0].tolist()
+    # `expert_place_affinity` without units is the same algorithm
+    assert O.expert_place_affinity(load, co, 2, None, None, 1, 0, 1, 8).tolist() == tuned.tolist()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_place_swaps_are_stable_under_the_two_term_gain_and_load_only_never_raises_the_maximum(seed):
+    E, D, k = 12, 3, 3
+    ids, _, _ = _planted_ids(300, E, D, k, seed=40 + seed, noise=0.6)
+    load, co = O.coact_hist(ids, E)
+    alpha, gamma = (1, 2) if seed % 2 else (3, 1)
+    e2r, _, _ = O.place(load, co, D, alpha=alpha, gamma=gamma, ft_passes=64)
+    W = O.intra_rank_mass(co, e2r)
+    L = np.bincount(e2r, weights=load, minlength=D)
+    for a in range(E):                                          # no pair is left whose swap gains, terms recomputed here
+        for b in range(a + 1, E):
+            ca, cb = int(e2r[a]), int(e2r[b])
+            if ca == cb:
+                continue
+            sw = e2r.copy()
+            sw[a], sw[b] = cb, ca
+            L2 = np.bincount(sw, weights=load, minlength=D)
+            gain = alpha * (O.intra_rank_mass(co, sw) - W) + gamma * (max(L[ca], L[cb]) - max(L2[ca], L2[cb]))
+            assert gain <= 0
+    # load term alone: the sweeps can only lower the largest load of the greedy's placement
+    g0, _, _ = O.place(load, co, D, alpha=0, gamma=1, ft_passes=0)
+    g8, _, _ = O.place(load, co, D, alpha=0, gamma=1, ft_passes=8)
+    assert np.bincount(g8, weights=load, minlength=D).max() <= np.bincount(g0, weights=load, minlength=D).max()
+    # no weights at all: nothing gains, nothing moves
+    assert (O.place(load, co, D, 0, 0, 8)[0] == O.place(load, co, D, 0, 0, 0)[0]).all()
+
+
 def test_place_greedy_order_hottest_first_and_gamma_balances_load():
     # two hot experts (0, 1) never co-activated with anything: alpha-term is zero for them
     E, D = 4, 2
