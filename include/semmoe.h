@@ -160,7 +160,9 @@ int32_t semmoe_coact_hist(const semmoe_config* cfg, void* stream, const int32_t*
  *   Experts by load descending (equal -> lower id); expert e goes to the not-yet-full rank c maximising
  *   alpha*sum_{e' on c} coact[e,e'] - gamma*loads_cls[c] (equal -> smaller loads_cls, then smaller c);
  *   a rank is full at E/D experts.  Then at most ft_passes first-improvement sweeps over pairs e1<e2 on
- *   different ranks, swapping when the intra-rank co-activation mass rises; stops after a sweep with no swap.
+ *   different ranks, swapping when alpha*(rise of the intra-rank co-activation mass) + gamma*(what the swap
+ *   takes off the larger of the two ranks' loads) > 0 - both terms of the objective of Sec. 3.3 with the weights
+ *   of the greedy pass; gamma = 0: the affinity gain alone; stops after a sweep with no swap.
  *   Physical order: rank-major, ascending original id inside a rank (the transparent gate-column shuffle
  *   of Sec. 3.3 "Model scheduling" is phys_of_expert).
  * host in : load[E] u64, coact[E*E] u64 (symmetric).  host out: expert_to_rank[E], phys_of_expert[E],

@@ -17,7 +17,8 @@ typedef __int128 i128;
 
 // The greedy pass and the fine-tuning sweeps of `expert_place`.  req_aff[e*D + c] (may be null) is the request term
 // EAfR: the activation mass on expert e of the units scheduled to cluster c.  Scores are
-// alpha*EAfE + beta*EAfR - gamma*loads_cls; a swap is taken when w_e*(co-activation gain) + beta*(local mass gain) > 0.
+// alpha*EAfE + beta*EAfR - gamma*loads_cls; a swap is taken when w_e*(co-activation gain) + beta*(local mass gain)
+// + gamma*(what it takes off the larger of the two clusters' loads) > 0.
 static void expert_place_core(int E, int D, const uint64_t* load, const uint64_t* coact, const i64* req_aff, i64 alpha,
                               i64 beta, i64 gamma, i64 w_e, int ft_passes, std::vector<int>& rank_of) {
   const int m = E / D;
@@ -70,13 +71,18 @@ static void expert_place_core(int E, int D, const uint64_t* load, const uint64_t
                         (aff[static_cast<size_t>(e1) * D + c1] - A(e1, e1)) -
                         (aff[static_cast<size_t>(e2) * D + c2] - A(e2, e2));
         const i128 g_r = R(e1, c2) + R(e2, c1) - R(e1, c1) - R(e2, c2);
-        if (static_cast<i128>(w_e) * g_e + beta * g_r > 0) {
+        const i64 l1 = loads_cls[c1] - static_cast<i64>(load[e1]) + static_cast<i64>(load[e2]);
+        const i64 l2 = loads_cls[c2] - static_cast<i64>(load[e2]) + static_cast<i64>(load[e1]);
+        const i64 g_l = std::max(loads_cls[c1], loads_cls[c2]) - std::max(l1, l2);
+        if (static_cast<i128>(w_e) * g_e + beta * g_r + static_cast<i128>(gamma) * g_l > 0) {
           leave(e1, c1);
           leave(e2, c2);
           join(e1, c2);
           join(e2, c1);
           rank_of[e1] = c2;
           rank_of[e2] = c1;
+          loads_cls[c1] = l1;
+          loads_cls[c2] = l2;
           swapped = true;
         }
       }
@@ -106,7 +112,7 @@ extern "C" int32_t semmoe_place(const semmoe_config* cfg, const uint64_t* load, 
   if (E <= 0 || D <= 0 || ft_passes < 0) return SEMMOE_EINVAL;
   if (E % D != 0) return SEMMOE_ESHAPE;
   std::vector<int> rank_of;
-  expert_place_core(E, D, load, coact, nullptr, alpha, 0, gamma, 1, ft_passes, rank_of);
+  expert_place_core(E, D, load, coact, nullptr, alpha, 0, gamma, alpha, ft_passes, rank_of);
   placement_order(E, D, rank_of, expert_to_rank, phys_of_expert, expert_of_phys);
   return SEMMOE_OK;
 }

@@ -198,6 +198,7 @@ def _clustered_ids(T, E, D, k, seed, noise):
 @pytest.mark.parametrize("E,D,k,noise,alpha,gamma,ft", [
     (16, 4, 2, 0.2, 1, 0, 8), (32, 8, 4, 0.5, 1, 0, 8), (24, 3, 3, 0.7, 1, 0, 0), (32, 4, 4, 0.6, 2, 1, 3),
     (64, 8, 8, 0.4, 1, 0, 8), (16, 1, 2, 0.5, 1, 0, 8), (16, 16, 2, 0.5, 1, 0, 8),
+    (32, 4, 4, 0.6, 1, 2, 8), (48, 8, 4, 0.5, 4, 1, 8), (24, 3, 3, 0.7, 0, 1, 8), (64, 8, 8, 0.4, 16, 1, 4),
 ])
 def test_host_place_equals_oracle(E, D, k, noise, alpha, gamma, ft):
     ids = _clustered_ids(700, E, D, k, seed=E * 7 + D, noise=noise)
