@@ -169,7 +169,8 @@ static int32_t launch_all_pieces(GemmArgs a, int max_rows, hipStream_t stream) {
   a.sched_thr = 16;
   a.sched_sub_t = 2;
   a.sched_sub_f = 2;
-  const int grid = grid_for(bound_p * 4, num_cu());
+  a.sched_fine = 1;  // 128 x 64 pieces when the 128 x 128 ones would leave half the compute units idle
+  const int grid = grid_for(bound_p * 8, num_cu());
   auto kern = gemm_bf16_piece_kernel<MODE, 3>;
   static std::atomic<uint64_t> lds_allowed{0};  // one flag word per instantiation, a bit per device
   {

@@ -591,9 +591,19 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_w4_kernel(GemmArgs a) {
   gemm_bf16_w4_body<MODE, BK, NSTAGE, DMA_EVERY>(a, lds_raw);
 }
 
+// Pieces as a launch of their own.  With sched_fine set the kernel halves the pieces along the tokens (128 x 64)
+// when twice the number of 128 x 128 pieces still fits the grid, as the split kernel below does for its tail.
 template <int MODE, int NSTAGE>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_piece_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  if (a.sched_fine) {
+    const TileWalk probe = make_walk(a, reinterpret_cast<int*>(lds_raw), 128, (MODE == kModeSwiglu) ? 64 : 128);
+    __syncthreads();
+    if (probe.total > 0 && probe.total * 2 <= int(gridDim.x)) {
+      gemm_bf16_piece_body<MODE, NSTAGE, 1>(a, lds_raw, 4);
+      return;
+    }
+  }
   gemm_bf16_piece_body<MODE, NSTAGE, 2>(a, lds_raw);
 }
 

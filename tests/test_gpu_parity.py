@@ -830,6 +830,29 @@ def test_in_launch_tail_pieces_of_the_split_gemm(rows, ring):
             m.set_tuning(key, -1)
 
 
+@pytest.mark.parametrize("n_rows,d,F", [(300, 256, 192), (512, 320, 256), (100, 192, 200)])
+def test_shared_ffn_as_pieces(n_rows, d, F):
+    """the shared expert on a shard of tokens: so few rows that 256 x 256 tiles could not fill the chip, so the library
+    takes 128 x 128 pieces throughout, and 128 x 64 ones where twice as many still fit the grid (300 rows, F = 192:
+    2 x 2 parent tiles = 16 pieces, 32 <= the grid of 32; the last 64-token piece holds 44 rows, the two after it none);
+    F = 200 is no multiple of 64: the pieces' K loop does not take the down projection, the register-staged kernel does"""
+    _say("shared ffn as pieces", n_rows, d, F)
+    w = WL.small(T=max(n_rows, 512), d=d, E=4, k=1, F=F, D=1, dtype="bf16", C=1, n_shared=1)
+    lay = H.Layer(w)
+    X = WL.hidden(w)
+    lay.X = H.to_dev(X, w)
+    wgu, wdn = WL.shared_weight(w)
+    ysh = torch.full((w.T, d), 512.0, dtype=torch.bfloat16, device=H.DEV)
+    lay.m.shared_ffn(lay.X, n_rows, H.to_dev(wgu, w), H.to_dev(wdn, w), ysh)
+    torch.cuda.synchronize()
+    got = H.to_np(ysh)
+    assert (got[n_rows:] == 512.0).all()                       # rows beyond the shard untouched
+    want = O.swiglu_ffn(X[:n_rows], wgu, wdn)
+    H.assert_close(got[:n_rows], want, "bf16", "Y_shared")
+    if n_rows % 64:
+        H.assert_close(got[n_rows - n_rows % 64:n_rows], want[n_rows - n_rows % 64:], "bf16", "rows of the partly filled piece")
+
+
 def test_probes_copy_and_mfma_loop():
     """the two probes bench.py reads achievable rates from: the copy copies, the MFMA loop's checksum is the exact sum"""
     m = S.SemMoE(S.Config(T=1, d=8, E=2, k=1, F=8, D=1, cap=1), allocate_workspace=False)
