@@ -108,8 +108,12 @@ def achievable_peaks(m, torch, dev):
     src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     t_copy = timed(lambda: m.probe_copy(dst, src, nbytes), 10)
+    words = torch.empty(2048 * 256, dtype=torch.int32, device=dev)
+    t_read = timed(lambda: m.probe_stream(src, nbytes, 0, words), 10)
+    t_write = timed(lambda: m.probe_stream(dst, nbytes, 1, words), 10)
     sink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
-    out = {"hbm_copy_GBps": round(2 * nbytes / t_copy / 1e9, 1)}
+    out = {"hbm_copy_GBps": round(2 * nbytes / t_copy / 1e9, 1), "hbm_read_only_GBps": round(nbytes / t_read / 1e9, 1),
+           "hbm_write_only_GBps": round(nbytes / t_write / 1e9, 1)}
     iters = 20000
     for name, ops in (("constant", torch.ones(256 * 1024, dtype=torch.bfloat16, device=dev)),
                       ("random", torch.randn(256 * 1024, device=dev).to(torch.bfloat16))):

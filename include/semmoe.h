@@ -445,6 +445,9 @@ int32_t semmoe_combine(const semmoe_config* cfg, void* stream, const void* Y, co
  * the paper).  Each enqueues one kernel on `stream`; the caller times it.
  *   semmoe_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte aligned, bytes % 16 == 0; moves
  *     2*bytes through HBM.
+ *   semmoe_probe_stream: the same walk over buf[0..bytes) (device, 16-byte aligned, bytes a multiple of 16384)
+ *     reading only (write = 0; per-thread sums go to `sink`, device, 2048*256 words) or writing only (write != 0;
+ *     buf is overwritten): the rates of an all-read and an all-write stream.
  *   semmoe_probe_mfma: 256 workgroups of 4 waves, each wave 16 independent 32x32x16 bf16 MFMAs per iteration on operand
  *     fragments read once from `operands` (device, 64 sets x 8 fragments x 64 lanes x 16 bytes = 512 KiB, any finite
  *     bf16 values: the data decide the power drawn and so the clock); `sink` (device, 256*256 floats) receives
@@ -460,6 +463,7 @@ int32_t semmoe_combine(const semmoe_config* cfg, void* stream, const void* Y, co
  *     `sink` (device, 256*512 floats) receives checksums; *flops_out (host, may be NULL) = flops of the launch.
  */
 int32_t semmoe_probe_copy(void* stream, void* dst, const void* src, size_t bytes);
+int32_t semmoe_probe_stream(void* stream, void* buf, size_t bytes, int32_t write, uint32_t* sink);
 int32_t semmoe_probe_mfma(void* stream, const void* operands, int32_t iters, float* sink, double* flops_out);
 int32_t semmoe_probe_tile_loop(void* stream, const void* panels, int32_t n_panels, int32_t row_bytes, int32_t variant,
                                int32_t n_slices, float* sink, double* flops_out);

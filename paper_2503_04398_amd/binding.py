@@ -118,6 +118,7 @@ _SIGS = {
     "semmoe_shared_ffn": ([_P, _P, _P, C.c_int32, _P, _P, _P, _P, C.c_size_t], C.c_int32),
     "semmoe_combine": ([_P] * 7, C.c_int32),
     "semmoe_probe_copy": ([_P, _P, _P, C.c_size_t], C.c_int32),
+    "semmoe_probe_stream": ([_P, _P, C.c_size_t, C.c_int32, _P], C.c_int32),
     "semmoe_probe_mfma": ([_P, _P, C.c_int32, _P, C.POINTER(C.c_double)], C.c_int32),
     "semmoe_probe_tile_loop": ([_P, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P, C.POINTER(C.c_double)], C.c_int32),
 }
@@ -373,6 +374,10 @@ class SemMoE:
 
     def probe_copy(self, dst, src, nbytes):
         self._check("semmoe_probe_copy", self.lib.semmoe_probe_copy(_stream(), _ptr(dst), _ptr(src), int(nbytes)))
+
+    def probe_stream(self, buf, nbytes, write, sink):
+        self._check("semmoe_probe_stream", self.lib.semmoe_probe_stream(_stream(), _ptr(buf), int(nbytes), int(bool(write)),
+                                                                        _ptr(sink)))
 
     def probe_mfma(self, operands, iters, sink):
         """returns the flops of the launch"""

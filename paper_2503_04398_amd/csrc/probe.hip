@@ -30,6 +30,32 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4_t* __restrict__ d
     __builtin_nontemporal_store(src[i], dst + i);
 }
 
+// The same walk reading only (the sums go to `sink`) or writing only: what HBM gives a stream that is all reads or
+// all writes, the two ends between which the layer's row movers lie (combine reads 8 rows per row written,
+// dispatch writes 8 per row read).  MODE 0: read, 1: write.
+template <int MODE>
+__global__ __launch_bounds__(256) void probe_stream_kernel(u32x4_t* __restrict__ buf, size_t n16,
+                                                           unsigned* __restrict__ sink) {
+  const size_t n_chunks = n16 / 1024;  // whole 16 KB chunks only
+  u32x4_t acc = {0, 0, 0, 0};
+  for (size_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const size_t i = c * 1024 + threadIdx.x;
+    if (MODE == 0) {
+      acc += __builtin_nontemporal_load(buf + i);
+      acc += __builtin_nontemporal_load(buf + i + 256);
+      acc += __builtin_nontemporal_load(buf + i + 512);
+      acc += __builtin_nontemporal_load(buf + i + 768);
+    } else {
+      const u32x4_t v = {1u, 2u, 3u, unsigned(c)};
+      __builtin_nontemporal_store(v, buf + i);
+      __builtin_nontemporal_store(v, buf + i + 256);
+      __builtin_nontemporal_store(v, buf + i + 512);
+      __builtin_nontemporal_store(v, buf + i + 768);
+    }
+  }
+  if (MODE == 0) sink[size_t(blockIdx.x) * 256 + threadIdx.x] = acc.x + acc.y + acc.z + acc.w;
+}
+
 // Each wave keeps 4 x 4 accumulator tiles of 32 x 32 and multiplies the same 8 operand fragments (read once from
 // `operands`: 8 KB per wave) `iters` x 16 times: nothing but MFMAs in the loop.
 __global__ __launch_bounds__(256, 1) void probe_mfma_kernel(const bf16x8_t* __restrict__ operands, int iters,
@@ -196,6 +222,18 @@ extern "C" int32_t semmoe_probe_copy(void* stream, void* dst, const void* src, s
   if (bytes == 0) return SEMMOE_OK;
   hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<u32x4_t*>(dst), static_cast<const u32x4_t*>(src), bytes / 16);
+  SEMMOE_LAUNCH_CHECK();
+  return SEMMOE_OK;
+}
+
+extern "C" int32_t semmoe_probe_stream(void* stream, void* buf, size_t bytes, int32_t write, uint32_t* sink) {
+  if (!buf || !sink || bytes % 16384 != 0 || !aligned16(buf)) return SEMMOE_EINVAL;
+  if (bytes == 0) return SEMMOE_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (write)
+    hipLaunchKernelGGL(probe_stream_kernel<1>, dim3(2048), dim3(256), 0, s, static_cast<u32x4_t*>(buf), bytes / 16, sink);
+  else
+    hipLaunchKernelGGL(probe_stream_kernel<0>, dim3(2048), dim3(256), 0, s, static_cast<u32x4_t*>(buf), bytes / 16, sink);
   SEMMOE_LAUNCH_CHECK();
   return SEMMOE_OK;
 }

@@ -859,6 +859,16 @@ def test_probes_copy_and_mfma_loop():
     src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device=H.DEV)
     dst = torch.zeros_like(src)
     m.probe_copy(dst, src, src.numel())
+    words = torch.zeros(2048 * 256, dtype=torch.int32, device=H.DEV)
+    ones = torch.ones(1 << 18, dtype=torch.int32, device=H.DEV)                 # 1 MiB = 64 chunks of 16 KB
+    m.probe_stream(ones, ones.numel() * 4, 0, words)
+    filled = torch.zeros(1 << 18, dtype=torch.int32, device=H.DEV)
+    m.probe_stream(filled, filled.numel() * 4, 1, words[:1])                     # the write form never touches the sink
+    torch.cuda.synchronize()
+    assert int(words[:64 * 256].sum().item()) == (1 << 18) and int(words[64 * 256:].sum().item()) == 0
+    f = filled.view(-1, 4)
+    assert bool((f[:, 0] == 1).all()) and bool((f[:, 1] == 2).all()) and bool((f[:, 2] == 3).all())
+    assert torch.equal(f[:, 3], torch.arange(64, device=H.DEV, dtype=torch.int32).repeat_interleave(1024))
     ops = torch.ones(256 * 1024, dtype=torch.bfloat16, device=H.DEV)
     sink = torch.zeros(256 * 256, dtype=torch.float32, device=H.DEV)
     flops = m.probe_mfma(ops, 3, sink)
