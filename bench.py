@@ -165,8 +165,8 @@ def balance_study(args, w, m, up, X, W_r, tc, cb, ids, tw, load, coact, bufs, to
         return e0.elapsed_time(e1) / reps
 
     points = []
-    for alpha, gamma, ft in ((1, 0, 8), (1, 1, 8), (1, 0, 0), (64, 1, 0), (32, 1, 0), (16, 1, 0), (8, 1, 0), (4, 1, 0),
-                             (2, 1, 0), (1, 1, 0), (0, 1, 0)):
+    for alpha, gamma, ft in ((1, 0, 8), (1, 0, 0), (16, 1, 0), (8, 1, 0), (4, 1, 0), (4, 1, 8), (2, 1, 0), (2, 1, 8),
+                             (1, 1, 8), (1, 4, 8), (1, 16, 8), (1, 64, 8), (1, 256, 8), (0, 1, 0), (0, 1, 8)):
         e2r_s, phys_s, inv_s = (up(a) for a in m.place(load_h, coact_h, alpha, gamma, ft))
         rank_load = np.bincount(e2r_s.cpu().numpy(), weights=load_h.astype(np.float64), minlength=D)
         for cf in (1.0, 1.25, 1.5, 2.0, float(D)):
