@@ -745,6 +745,9 @@ def main():
                          "factor of the reshuffle, and print remote-pair fraction, per-rank load imbalance and the FFN "
                          "time of the slowest rank for each point (one JSON line; workload: --config, default the "
                          "Qwen3-30B-shaped one)")
+    ap.add_argument("--peaks-only", action="store_true",
+                    help="only the library's probes (copy / read / write streams, MFMA-only loops, the tile's K loop whole "
+                         "and in parts, the vendor GEMM): one JSON line; the command the counter profile of the probes runs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a one-GPU hot path (logical ranks are simulated on one device); "
@@ -758,6 +761,12 @@ def main():
     torch.cuda.set_device(0)
     if args.balance_study:
         run_config(args.config or NEXT_ROWS_ON, args, {})
+        return
+    if args.peaks_only:
+        import paper_2503_04398_amd as S
+        handle = S.SemMoE(S.Config(T=8, d=8, E=8, k=1, F=8, D=1, cap=8), allocate_workspace=False)
+        print(json.dumps({"achievable": achievable_peaks(handle, torch, "cuda:0"), "data": "synthetic",
+                          "device": torch.cuda.get_device_name(0)}))
         return
     traffic_tab = measured_traffic()
     names = [args.config] if args.config else [HEADLINE] + [n for n in WL.CONFIG_ORDER if n != HEADLINE]

@@ -72,7 +72,8 @@ int32_t validate_config(const semmoe_config* cfg, bool need_T, bool need_rows, b
 size_t ws_route(const semmoe_config* cfg) {
   const size_t logits = align_up(size_t(cfg->T) * cfg->E * 4, 256);
   // few tokens: the router splits K over workgroups and keeps up to 16 partial sums per logit
-  return (cfg->T <= 512 ? 17 * logits : logits) + 512;
+  // many tokens and more than 128 experts: K split of the 256 x 256 tile, up to 8 parts
+  return (cfg->T <= 512 ? 17 * logits : (cfg->E > 128 ? 9 * logits : logits)) + 512;
 }
 
 }  // namespace semmoe

@@ -307,6 +307,21 @@ static int split_threshold() {
   return (t >= 1 && t <= 16) ? t : 8;
 }
 
+int32_t launch_ksplit_gemm(const void* X, const void* W, int T, int N, int d, int n_parts, float* partial,
+                           hipStream_t stream) {
+  if (T <= 0 || N <= 0 || n_parts < 1 || n_parts > 64 || N % 4 != 0) return SEMMOE_EUNSUPPORTED;
+  if (d % (64 * n_parts) != 0 || (long long)T * n_parts > 0x3fffffffLL) return SEMMOE_EUNSUPPORTED;
+  GemmArgs a{};
+  a.X = X; a.ldx = d;
+  a.W = W; a.ldw = d; a.w_group_stride = size_t(d / n_parts);
+  a.N = N; a.K = d / n_parts;
+  a.offsets = nullptr; a.q_lo = 0; a.nq = n_parts; a.n_rows_single = T;
+  a.group_to_weight = nullptr;
+  a.out = partial; a.ldo = N;
+  a.ksplit_rows = T;
+  return launch_w4<kModeLogits, 64, 2, 2>(a, T * n_parts, stream);
+}
+
 int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int est_rows_per_group,
                     hipStream_t stream) {
   if (a.nq <= 0 || max_rows <= 0) return SEMMOE_OK;

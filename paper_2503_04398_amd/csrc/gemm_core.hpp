@@ -41,6 +41,10 @@ struct GemmArgs {
   int sched_thr;          // the split happens when at most sched_thr / 16 of a round is left over
   int sched_sub_t, sched_sub_f;  // tail: pieces per parent tile along tokens and along features
   int sched_fine;         // tail inside the head's launch: 1 = halve the pieces along the tokens when few tiles are left
+  // One GEMM with its K dimension split over workgroups (four-wave kernel, raw fp32 sums): ksplit_rows > 0 makes every
+  // group q the same ksplit_rows rows of X against columns [q*K, (q+1)*K) of X and of W (K = depth of a part, ldx and
+  // ldw the full depth, w_group_stride = K); group q writes output rows q*ksplit_rows ..., that is partial[q][row][n].
+  int ksplit_rows;
 };
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -59,7 +63,8 @@ __device__ __forceinline__ int build_tile_prefix(const GemmArgs& a, int n_ftiles
     const int lo = min(tid * per, a.nq), hi = min(lo + per, a.nq);
     int s = 0;
     for (int q = lo; q < hi; ++q) {
-      int rows = a.offsets ? (a.offsets[a.q_lo + q + 1] - a.offsets[a.q_lo + q]) : a.n_rows_single;
+      int rows = a.ksplit_rows ? a.ksplit_rows
+                               : (a.offsets ? (a.offsets[a.q_lo + q + 1] - a.offsets[a.q_lo + q]) : a.n_rows_single);
       s += ((rows + BT - 1) / BT) * n_ftiles;
     }
     int incl = s;
@@ -71,7 +76,8 @@ __device__ __forceinline__ int build_tile_prefix(const GemmArgs& a, int n_ftiles
     int run = incl - s;
     if (tid == 0) pre[0] = 0;
     for (int q = lo; q < hi; ++q) {
-      int rows = a.offsets ? (a.offsets[a.q_lo + q + 1] - a.offsets[a.q_lo + q]) : a.n_rows_single;
+      int rows = a.ksplit_rows ? a.ksplit_rows
+                               : (a.offsets ? (a.offsets[a.q_lo + q + 1] - a.offsets[a.q_lo + q]) : a.n_rows_single);
       run += ((rows + BT - 1) / BT) * n_ftiles;
       pre[q + 1] = run;
     }
@@ -724,5 +730,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
 
 // host-side launcher: picks the kernel for the dtype, sizes a persistent grid.
 int32_t launch_gemm(int mode, int dtype, const GemmArgs& a, int max_rows, int est_rows_per_group, hipStream_t stream);
+// X[T, d] . W[N, d]^T with d cut into n_parts equal parts of whole 64-element slices: partial[p][t][n] = raw fp32 sums
+// of part p (four-wave 256 x 256 kernel).  SEMMOE_EUNSUPPORTED when the shape does not fit that kernel.
+int32_t launch_ksplit_gemm(const void* X, const void* W, int T, int N, int d, int n_parts, float* partial,
+                           hipStream_t stream);
 
 }  // namespace semmoe

@@ -97,7 +97,7 @@ struct W4Cfg {
 };
 
 struct TileRef {
-  int row_lo, n_tok, f0, widx;
+  int row_lo, n_tok, f0, widx, q;
 };
 
 // gtab (LDS, filled once per workgroup): per group its first row, the row after its last, and its weight index.
@@ -119,13 +119,14 @@ __device__ __forceinline__ TileRef locate_tile(const GemmArgs& a, const int* pre
   t.n_tok = min(BT, row_hi - t.row_lo);
   t.f0 = ft * FEAT;
   t.widx = __builtin_amdgcn_readfirstlane(gtab[3 * q + 2]);
+  t.q = q;
   return t;
 }
 
 template <int MODE, int BK, int NSTAGE, int DMA_EVERY>
 __device__ __forceinline__ void gemm_bf16_w4_body(const GemmArgs& a, unsigned char* lds_raw) {
   using C = W4Cfg<MODE, BK, NSTAGE, DMA_EVERY>;
-  static_assert(MODE != kModeLogits, "the router has its own kernel");
+  // kModeLogits here: raw fp32 sums, no bias terms (the K-split router adds the parts and the biases afterwards)
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<size_t>(lds_raw));
 
   const int tid = threadIdx.x;
@@ -140,9 +141,15 @@ __device__ __forceinline__ void gemm_bf16_w4_body(const GemmArgs& a, unsigned ch
   const int n_ftiles = (a.N + C::FEAT - 1) / C::FEAT;
   const int G = gridDim.x;
   for (int q = tid; q < a.nq; q += C::kThreads) {
-    gtab[3 * q] = a.offsets ? a.offsets[a.q_lo + q] : 0;
-    gtab[3 * q + 1] = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
-    gtab[3 * q + 2] = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
+    if (a.ksplit_rows) {  // part q of K: the same rows of X, its own columns, its own block of output rows
+      gtab[3 * q] = q * a.ksplit_rows;
+      gtab[3 * q + 1] = (q + 1) * a.ksplit_rows;
+      gtab[3 * q + 2] = q;
+    } else {
+      gtab[3 * q] = a.offsets ? a.offsets[a.q_lo + q] : 0;
+      gtab[3 * q + 1] = a.offsets ? a.offsets[a.q_lo + q + 1] : a.n_rows_single;
+      gtab[3 * q + 2] = a.group_to_weight ? a.group_to_weight[a.q_lo + q] : (a.q_lo + q);
+    }
   }
   const int listed = __builtin_amdgcn_readfirstlane(build_tile_prefix(a, n_ftiles, pre, C::BT));  // ends with a barrier
   const int total = a.sched_mode == 1 ? head_tiles(listed, G, a.sched_thr) : listed;  // head launch of a split
@@ -200,6 +207,8 @@ __device__ __forceinline__ void gemm_bf16_w4_body(const GemmArgs& a, unsigned ch
       }
     } else {
       i_base = reinterpret_cast<const unsigned char*>(static_cast<const bf16_t*>(a.X) + size_t(t.row_lo) * a.ldx);
+      // K split: output row q * ksplit_rows + r is row r of X, columns from q * K on
+      if (a.ksplit_rows) i_base -= (size_t(t.q) * a.ksplit_rows * a.ldx - size_t(t.q) * a.K) * 2;
 #pragma unroll
       for (int i = 0; i < C::IPW; ++i) {
         const int sr = (wave * C::IPW + i) * C::RPI + d_row - C::BW;  // token row of the tile
@@ -338,6 +347,41 @@ __device__ __forceinline__ void gemm_bf16_w4_body(const GemmArgs& a, unsigned ch
     bf16_t* out = static_cast<bf16_t*>(a.out);
     const int tok_in = lane & 31, half = lane >> 5;
     const int r_row = lane >> 3, r_chunk = lane & 7;  // read-back: 8 lanes per staged row
+    if constexpr (MODE == kModeLogits) {
+      // fp32 sums: one MFMA tile (32 features x 32 tokens) per pass, a staged row = 32 floats = 8 chunks of 16 bytes.
+      // N is a multiple of 4 (checked by the host), so a chunk is inside the matrix or outside it as a whole.
+      float* outf = static_cast<float*>(a.out);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (j >= nj) break;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          __builtin_amdgcn_sched_barrier(0);
+          asm volatile("" : "+a"(acc[i][j]));
+          unsigned char* wp = stg + tok_in * C::kStgRow + half * 16;
+          const f32x16_t& c = acc[i][j];
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            f32x4_t v = {c[g4 * 4 + 0], c[g4 * 4 + 1], c[g4 * 4 + 2], c[g4 * 4 + 3]};
+            *reinterpret_cast<f32x4_t*>(wp + g4 * 32) = v;
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_wave_barrier();
+          const int feat = t.f0 + wf * 128 + i * 32 + r_chunk * 4;
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const int sr = p * 8 + r_row;
+            const int row = (j * 2 + wt) * 32 + sr;
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(stg + sr * C::kStgRow + r_chunk * 16);
+            if (row < t.n_tok && feat < a.N)  // read once, soon: not worth a place in the memory-side cache
+              __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(outf + (size_t(t.row_lo) + row) * a.ldo + feat));
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
+      continue;
+    }
     constexpr int kPasses = (MODE == kModeSwiglu) ? 1 : 2;  // 64 output features per pass
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -837,6 +837,65 @@ __global__ __launch_bounds__(256) void select_topk_rows_kernel(semmoe_config cfg
       cfg, base, cfg.T, [&](int tl) { return logits + size_t(tl) * cfg.E; }, 0, sel_bias, lane, topk_ids, topk_w);
 }
 
+// The two kernels below in one, for the row forms of the selection and E a multiple of four: a wave adds up the parts
+// of its kRowTokens tokens (ascending order, then b_g, then the class bias: the same sums as route_reduce_kernel)
+// into LDS with 16-byte loads and selects from there.  The partial sums are read once and never again.
+constexpr int kSumSelectMaxE = 256;
+template <int FORM, bool SIG>
+__global__ __launch_bounds__(256) void route_sum_select_kernel(semmoe_config cfg, int n_parts,
+                                                               const float* __restrict__ partial,
+                                                               const float* __restrict__ b_g,
+                                                               const int32_t* __restrict__ token_class,
+                                                               const float* __restrict__ class_bias,
+                                                               const float* __restrict__ sel_bias,
+                                                               float* __restrict__ logits_out,
+                                                               int32_t* __restrict__ topk_ids,
+                                                               float* __restrict__ topk_w) {
+  __shared__ __attribute__((aligned(16))) float lg_all[4 * kRowTokens * (kSumSelectMaxE + 4)];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int base = (blockIdx.x * 4 + wave) * kRowTokens;
+  if (base >= cfg.T) return;  // whole wave leaves together (no workgroup barrier below)
+  const int E = cfg.E, e4 = E / 4, ld = E + 4;
+  float* lg = lg_all + wave * kRowTokens * (kSumSelectMaxE + 4);
+  const int n_tok = min(kRowTokens, cfg.T - base);
+  const size_t n = size_t(cfg.T) * E;
+  const bool out16 = logits_out && (reinterpret_cast<size_t>(logits_out) & 15) == 0;
+  for (int idx = lane; idx < n_tok * e4; idx += 64) {
+    const int tl = idx / e4, e = (idx - tl * e4) * 4;
+    const size_t at = size_t(base + tl) * E + e;
+    f32x4_t v = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int p0 = 0; p0 < n_parts; p0 += 4) {  // four loads in flight
+      f32x4_t x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        x[u] = p0 + u < n_parts ? __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(partial + size_t(p0 + u) * n + at))
+                                : f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v += x[u];
+    }
+    if (b_g) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] += b_g[e + u];
+    }
+    const int cls = token_class ? token_class[base + tl] : -1;
+    if (cls >= 0 && cls < cfg.num_classes && class_bias) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] += class_bias[size_t(cls) * E + e + u];
+    }
+    *reinterpret_cast<f32x4_t*>(lg + tl * ld + e) = v;
+    if (out16) {
+      *reinterpret_cast<f32x4_t*>(logits_out + at) = v;
+    } else if (logits_out) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) logits_out[at + u] = v[u];
+    }
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+  select_tokens_by_rows<FORM, SIG>(
+      cfg, 0, n_tok, [&](int tl) { return lg + tl * ld; }, base, sel_bias, lane, topk_ids, topk_w);
+}
+
 // logits[tok][e] = sum over the parts of K, in ascending order, + b_g[e] + class_bias[token_class[tok]][e]
 __global__ __launch_bounds__(256) void route_reduce_kernel(semmoe_config cfg, int n_parts,
                                                            const float* __restrict__ partial,
@@ -852,7 +911,7 @@ __global__ __launch_bounds__(256) void route_reduce_kernel(semmoe_config cfg, in
   for (int p0 = 0; p0 < n_parts; p0 += 8) {  // eight loads in flight
     float x[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) x[u] = p0 + u < n_parts ? partial[size_t(p0 + u) * n + idx] : 0.0f;
+    for (int u = 0; u < 8; ++u) x[u] = p0 + u < n_parts ? __builtin_nontemporal_load(partial + size_t(p0 + u) * n + idx) : 0.0f;
 #pragma unroll
     for (int u = 0; u < 8; ++u) v += x[u];
   }
@@ -861,6 +920,28 @@ __global__ __launch_bounds__(256) void route_reduce_kernel(semmoe_config cfg, in
   if (cls >= 0 && cls < cfg.num_classes && class_bias) v += class_bias[size_t(cls) * cfg.E + e];
   logits[idx] = v;
   if (logits_out) logits_out[idx] = v;
+}
+
+// Many tokens and more than 128 experts: the fused kernel's workgroup (64 tokens) streams all of W_r past its tokens,
+// five rows of operands per token and slice.  The 256 x 256 tile of the grouped GEMM takes two, with K cut into as
+// many parts as fill the chip; the parts are then added in order and the selection runs as a kernel of its own.
+// tune (SEMMOE_TUNE_ROUTE_SPLIT): -1 automatic, 0 never, 100 + n this form with n parts whatever the token count.
+static int route_big_parts(const semmoe_config* cfg, int ncu) {
+  const int tune = tuning_value(SEMMOE_TUNE_ROUTE_SPLIT);
+  if (cfg->dtype != SEMMOE_BF16 || tune == 0 || cfg->E <= 128 || cfg->E % 4 != 0 || cfg->d % 64 != 0) return 0;
+  const int nk = cfg->d / 64;
+  if (tune >= 100) {
+    const int parts = tune - 100;
+    return (parts >= 1 && parts <= 8 && nk % parts == 0 && nk / parts >= 2) ? parts : 0;
+  }
+  if (tune > 0) return 0;  // a forced split of the fused kernel
+  const long long tiles = (long long)cdiv(cfg->T, 256) * cdiv(cfg->E, 256);
+  if (tiles * 8 < ncu) return 0;  // too few tokens to fill the chip with 256-token tiles and K parts of useful depth
+  int parts = int(ncu / tiles);
+  if (parts < 1) parts = 1;
+  if (parts > 8) parts = 8;
+  while (parts > 1 && (nk % parts != 0 || nk / parts < 8)) --parts;
+  return nk / parts >= 2 ? parts : 0;
 }
 
 constexpr int kRouteSplitMaxTiles = 16;  // up to this many token tiles of 32 the K dimension is split over workgroups
@@ -955,6 +1036,39 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
     st = device_info(&di);
     if (st != SEMMOE_OK) return st;
     const int ncu = di.num_cu;
+    if (const int big_parts = route_big_parts(cfg, ncu)) {
+      Carver c(ws, ws_bytes);
+      float* part = c.take<float>(size_t(big_parts) * cfg->T * cfg->E);
+      float* lg = c.take<float>(size_t(cfg->T) * cfg->E);
+      if (!c.ok) return SEMMOE_EWORKSPACE;
+      st = launch_ksplit_gemm(X, W_r, cfg->T, cfg->E, cfg->d, big_parts, part, s);
+      const int form = select_form(*cfg);
+      if (st == SEMMOE_OK && form == kSel16 && cfg->E <= kSumSelectMaxE) {  // more than 128 experts: the 16-slot form
+        const dim3 grid(cdiv(cfg->T, 4 * kRowTokens)), block(256);
+        const bool sig = cfg->score == SEMMOE_SIGMOID;
+#define SEMMOE_SUM_SELECT(FORM_)                                                                                    \
+  do {                                                                                                              \
+    if (sig)                                                                                                        \
+      hipLaunchKernelGGL((route_sum_select_kernel<FORM_, true>), grid, block, 0, s, *cfg, big_parts, part, b_g,     \
+                         token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                          \
+    else                                                                                                            \
+      hipLaunchKernelGGL((route_sum_select_kernel<FORM_, false>), grid, block, 0, s, *cfg, big_parts, part, b_g,    \
+                         token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                          \
+  } while (0)
+        SEMMOE_SUM_SELECT(kSel16);
+#undef SEMMOE_SUM_SELECT
+        SEMMOE_LAUNCH_CHECK();
+        return SEMMOE_OK;
+      }
+      if (st == SEMMOE_OK) {
+        const size_t n = size_t(cfg->T) * cfg->E;
+        hipLaunchKernelGGL(route_reduce_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, s, *cfg, big_parts, part,
+                           b_g, token_class, class_bias, lg, logits_out);
+        SEMMOE_LAUNCH_CHECK();
+        return launch_select(cfg, s, lg, sel_bias, topk_ids, topk_w);
+      }
+      if (st != SEMMOE_EUNSUPPORTED) return st;
+    }
     const int n_parts = route_parts(cfg, ncu);
     float* partial = nullptr;
     float* logits_ws = nullptr;
