@@ -428,7 +428,7 @@ int32_t semmoe_expert_ffn(const semmoe_config* cfg, void* stream, int32_t rank, 
 /*
  * shared_ffn - the same FFN with one set of weights applied to n_tokens rows (the always-active shared
  * expert of DeepSeek-style layers).  dev in: X[n_tokens,d]; W_gu_sh[2F,d]; W_down_sh[d,F].  dev out:
- * Y_shared[n_tokens,d].  n_tokens <= T*k.
+ * Y_shared[n_tokens,d].  n_tokens <= T*k.  ws: n_tokens*F activations + 512 bytes are enough.
  */
 int32_t semmoe_shared_ffn(const semmoe_config* cfg, void* stream, const void* X, int32_t n_tokens,
                           const void* W_gu_sh, const void* W_down_sh, void* Y_shared, void* ws,

@@ -167,6 +167,7 @@ class SemMoE:
         self.device = device
         self.ws = None
         self.ws_bytes = 0
+        self.ws_shared = None
         if allocate_workspace:
             import torch
             self.ws_bytes = self.workspace_bytes()
@@ -367,10 +368,16 @@ class SemMoE:
             _ptr(W_gu), _ptr(W_down), _ptr(Y), _ptr(self.ws), self.ws_bytes))
 
     def shared_ffn(self, X, n_tokens, W_gu_sh, W_down_sh, Y_shared):
+        """the shared expert has a workspace of its own (n_tokens x F activations), so that it may run on another
+        stream beside the routed path's calls, which share `self.ws`"""
         c = self._cfg()
+        need = int(n_tokens) * self.cfg.F * (2 if self.cfg.dtype == BF16 else 4) + 512
+        if self.ws_shared is None or self.ws_shared.numel() < need:
+            import torch
+            self.ws_shared = torch.empty(need, dtype=torch.uint8, device=X.device)
         self._check("semmoe_shared_ffn", self.lib.semmoe_shared_ffn(
             C.byref(c), _stream(), _ptr(X), int(n_tokens), _ptr(W_gu_sh), _ptr(W_down_sh), _ptr(Y_shared),
-            _ptr(self.ws), self.ws_bytes))
+            _ptr(self.ws_shared), self.ws_shared.numel()))
 
     def probe_copy(self, dst, src, nbytes):
         self._check("semmoe_probe_copy", self.lib.semmoe_probe_copy(_stream(), _ptr(dst), _ptr(src), int(nbytes)))
