@@ -411,6 +411,7 @@ static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, cons
   if (NB > 0) {
     hipLaunchKernelGGL(dp_count_kernel, dim3(NB), dim3(kTokBlock), (E * kWords + D * D + 1) * 4, s, T, k, E, D, topk_ids,
                        token_rank, shf, phys_of_expert, w);
+    SEMMOE_LAUNCH_CHECK();
   }
   if (NB > 0 && ((path != 1 && NB <= kFusedMaxNB) || path == 3)) {
     hipLaunchKernelGGL(dp_fused_kernel, dim3(NB), dim3(kTokBlock), dp_fused_lds(E), s, T, k, E, D, NB, topk_ids, shf,
@@ -421,6 +422,7 @@ static int32_t dispatch_index_impl(const semmoe_config* cfg, hipStream_t s, cons
   }
   hipLaunchKernelGGL(dp_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, NB, E, D, expert_offsets, rank_offsets, send_matrix,
                      reinterpret_cast<unsigned long long*>(remote_pairs), w);
+  SEMMOE_LAUNCH_CHECK();
   if (NB > 0) {
     hipLaunchKernelGGL(dp_slot_kernel, dim3(NB), dim3(kTokBlock), E * kWords * 4, s, T, k, E, topk_ids, shf,
                        phys_of_expert, slot_of_pair, pair_of_slot, expert_offsets, w);
