@@ -680,7 +680,8 @@ def run_config(name, args, traffic_tab):
                                % (w.name, T, d, E, k, F, D, w.dtype, w.score, k, w.C,
                                   "all ranks" if args.all_ranks else "rank 0's experts",
                                   " + the shared expert on rank 0's shard of %d tokens" % n_sh if w.n_shared else ""),
-                   "cap": w.cap, "ffn_rows": rows_ffn, "ffn_experts_with_rows": active},
+                   "cap": w.cap, "ffn_rows": rows_ffn, "ffn_experts_with_rows": active,
+                   "ffn_rows_per_expert": [int(x) for x in np.diff(eo[:q_hi + 1])] if q_hi <= 32 else None},
         "roofline": roofline,
         "stages": roof,
         "expert_ffn_all_ranks": {"ms": round(ms_ffn_all, 4), "rows": P,
