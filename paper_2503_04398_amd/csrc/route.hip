@@ -532,16 +532,16 @@ inline int select_form(const semmoe_config& cfg) {
 
 // Tokens base .. base + kRowTokens - 1 (those below n_tok) by one wave: token = base + ch*4 + row.
 // row_of(token) -> pointer to its E logits; ids / weights are written to topk_ids / topk_w at tok_global0 + token.
-template <int FORM, bool SIG, typename RowOf>
+template <int FORM, bool SIG, int NCH = kRowChains, typename RowOf>
 __device__ __forceinline__ void select_tokens_by_rows(const semmoe_config& cfg, int base, int n_tok, RowOf row_of,
                                                       int tok_global0, const float* __restrict__ sel_bias, int lane,
                                                       int32_t* __restrict__ topk_ids, float* __restrict__ topk_w) {
   static_assert(FORM == kSelSmall || FORM == kSel8 || FORM == kSel16, "a row form");
-  const float* rowp[kRowChains];
-  int32_t* idp[kRowChains];
-  float* wp[kRowChains];
+  const float* rowp[NCH];
+  int32_t* idp[NCH];
+  float* wp[NCH];
 #pragma unroll
-  for (int ch = 0; ch < kRowChains; ++ch) {
+  for (int ch = 0; ch < NCH; ++ch) {
     const int tl = base + ch * 4 + (lane >> 4);
     const bool ok = tl < n_tok && tok_global0 + tl < cfg.T;
     rowp[ch] = row_of(min(tl, n_tok - 1));  // an absent token reads a present one's row and writes nothing
@@ -549,13 +549,13 @@ __device__ __forceinline__ void select_tokens_by_rows(const semmoe_config& cfg, 
     wp[ch] = ok ? topk_w + size_t(tok_global0 + tl) * cfg.k : nullptr;
   }
   if constexpr (FORM == kSel16) {
-    select_rows16<16, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    select_rows16<16, NCH, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
   } else if constexpr (FORM == kSel8) {
-    select_rows16<8, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    select_rows16<8, NCH, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
   } else {
-    if (cfg.E <= 16) select_rows16<1, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
-    else if (cfg.E <= 32) select_rows16<2, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
-    else select_rows16<4, kRowChains, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    if (cfg.E <= 16) select_rows16<1, NCH, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    else if (cfg.E <= 32) select_rows16<2, NCH, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
+    else select_rows16<4, NCH, SIG>(cfg, rowp, sel_bias, lane, idp, wp);
   }
 }
 
@@ -838,9 +838,11 @@ __global__ __launch_bounds__(256) void select_topk_rows_kernel(semmoe_config cfg
 }
 
 // The two kernels below in one, for the row forms of the selection and E a multiple of four: a wave adds up the parts
-// of its kRowTokens tokens (ascending order, then b_g, then the class bias: the same sums as route_reduce_kernel)
+// of its four tokens (ascending order, then b_g, then the class bias: the same sums as route_reduce_kernel)
 // into LDS with 16-byte loads and selects from there.  The partial sums are read once and never again.
 constexpr int kSumSelectMaxE = 256;
+constexpr int kSumSelectChains = 1;                       // four tokens a wave: twice the waves to hide the latencies
+constexpr int kSumSelectTokens = 4 * kSumSelectChains;
 template <int FORM, bool SIG>
 __global__ __launch_bounds__(256) void route_sum_select_kernel(semmoe_config cfg, int n_parts,
                                                                const float* __restrict__ partial,
@@ -851,27 +853,27 @@ __global__ __launch_bounds__(256) void route_sum_select_kernel(semmoe_config cfg
                                                                float* __restrict__ logits_out,
                                                                int32_t* __restrict__ topk_ids,
                                                                float* __restrict__ topk_w) {
-  __shared__ __attribute__((aligned(16))) float lg_all[4 * kRowTokens * (kSumSelectMaxE + 4)];
+  __shared__ __attribute__((aligned(16))) float lg_all[4 * kSumSelectTokens * (kSumSelectMaxE + 4)];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int base = (blockIdx.x * 4 + wave) * kRowTokens;
+  const int base = (blockIdx.x * int(blockDim.x >> 6) + wave) * kSumSelectTokens;  // one to four waves per workgroup
   if (base >= cfg.T) return;  // whole wave leaves together (no workgroup barrier below)
   const int E = cfg.E, e4 = E / 4, ld = E + 4;
-  float* lg = lg_all + wave * kRowTokens * (kSumSelectMaxE + 4);
-  const int n_tok = min(kRowTokens, cfg.T - base);
+  float* lg = lg_all + wave * kSumSelectTokens * (kSumSelectMaxE + 4);
+  const int n_tok = min(kSumSelectTokens, cfg.T - base);
   const size_t n = size_t(cfg.T) * E;
   const bool out16 = logits_out && (reinterpret_cast<size_t>(logits_out) & 15) == 0;
   for (int idx = lane; idx < n_tok * e4; idx += 64) {
     const int tl = idx / e4, e = (idx - tl * e4) * 4;
     const size_t at = size_t(base + tl) * E + e;
     f32x4_t v = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int p0 = 0; p0 < n_parts; p0 += 4) {  // four loads in flight
-      f32x4_t x[4];
+    for (int p0 = 0; p0 < n_parts; p0 += 8) {  // eight loads in flight
+      f32x4_t x[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u)
         x[u] = p0 + u < n_parts ? __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(partial + size_t(p0 + u) * n + at))
                                 : f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-      for (int u = 0; u < 4; ++u) v += x[u];
+      for (int u = 0; u < 8; ++u) v += x[u];
     }
     if (b_g) {
 #pragma unroll
@@ -892,8 +894,34 @@ __global__ __launch_bounds__(256) void route_sum_select_kernel(semmoe_config cfg
   }
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_wave_barrier();
-  select_tokens_by_rows<FORM, SIG>(
+  select_tokens_by_rows<FORM, SIG, kSumSelectChains>(
       cfg, 0, n_tok, [&](int tl) { return lg + tl * ld; }, base, sel_bias, lane, topk_ids, topk_w);
+}
+
+// launches route_sum_select_kernel when the shape has a row form of the selection and E is a multiple of four;
+// false: nothing was launched (the caller runs the two kernels)
+static bool launch_sum_select(const semmoe_config* cfg, hipStream_t s, int n_parts, const float* partial,
+                              const float* b_g, const int32_t* token_class, const float* class_bias,
+                              const float* sel_bias, float* logits_out, int32_t* topk_ids, float* topk_w) {
+  const int form = select_form(*cfg);
+  if (form == kSelAny || cfg->E > kSumSelectMaxE || cfg->E % 4 != 0) return false;
+  const int waves = 4;
+  const dim3 grid(cdiv(cfg->T, waves * kSumSelectTokens)), block(64 * waves);
+  const bool sig = cfg->score == SEMMOE_SIGMOID;
+#define SEMMOE_SUM_SELECT(FORM_)                                                                                    \
+  do {                                                                                                              \
+    if (sig)                                                                                                        \
+      hipLaunchKernelGGL((route_sum_select_kernel<FORM_, true>), grid, block, 0, s, *cfg, n_parts, partial, b_g,    \
+                         token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                          \
+    else                                                                                                            \
+      hipLaunchKernelGGL((route_sum_select_kernel<FORM_, false>), grid, block, 0, s, *cfg, n_parts, partial, b_g,   \
+                         token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                          \
+  } while (0)
+  if (form == kSel16) SEMMOE_SUM_SELECT(kSel16);
+  else if (form == kSel8) SEMMOE_SUM_SELECT(kSel8);
+  else SEMMOE_SUM_SELECT(kSelSmall);
+#undef SEMMOE_SUM_SELECT
+  return true;
 }
 
 // logits[tok][e] = sum over the parts of K, in ascending order, + b_g[e] + class_bias[token_class[tok]][e]
@@ -1042,21 +1070,8 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
       float* lg = c.take<float>(size_t(cfg->T) * cfg->E);
       if (!c.ok) return SEMMOE_EWORKSPACE;
       st = launch_ksplit_gemm(X, W_r, cfg->T, cfg->E, cfg->d, big_parts, part, s);
-      const int form = select_form(*cfg);
-      if (st == SEMMOE_OK && form == kSel16 && cfg->E <= kSumSelectMaxE) {  // more than 128 experts: the 16-slot form
-        const dim3 grid(cdiv(cfg->T, 4 * kRowTokens)), block(256);
-        const bool sig = cfg->score == SEMMOE_SIGMOID;
-#define SEMMOE_SUM_SELECT(FORM_)                                                                                    \
-  do {                                                                                                              \
-    if (sig)                                                                                                        \
-      hipLaunchKernelGGL((route_sum_select_kernel<FORM_, true>), grid, block, 0, s, *cfg, big_parts, part, b_g,     \
-                         token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                          \
-    else                                                                                                            \
-      hipLaunchKernelGGL((route_sum_select_kernel<FORM_, false>), grid, block, 0, s, *cfg, big_parts, part, b_g,    \
-                         token_class, class_bias, sel_bias, logits_out, topk_ids, topk_w);                          \
-  } while (0)
-        SEMMOE_SUM_SELECT(kSel16);
-#undef SEMMOE_SUM_SELECT
+      if (st == SEMMOE_OK && launch_sum_select(cfg, s, big_parts, part, b_g, token_class, class_bias, sel_bias,
+                                               logits_out, topk_ids, topk_w)) {
         SEMMOE_LAUNCH_CHECK();
         return SEMMOE_OK;
       }
@@ -1138,6 +1153,8 @@ extern "C" int32_t semmoe_route(const semmoe_config* cfg, void* stream, const vo
 #undef SEMMOE_ROUTE_LAUNCH
     SEMMOE_LAUNCH_CHECK();
     if (n_parts > 1) {
+      // (route_sum_select_kernel in place of these two was measured on the decode shape: 22.5 against 21.0 us;
+      // with so few tokens its eight-token waves are too few to hide the latency of the partial sums)
       const size_t n = size_t(cfg->T) * cfg->E;
       hipLaunchKernelGGL(route_reduce_kernel, dim3(unsigned((n + 255) / 256)), dim3(256), 0, s, *cfg, n_parts, partial,
                          b_g, token_class, class_bias, logits_ws, logits_out);
