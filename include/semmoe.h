@@ -97,10 +97,11 @@ int32_t semmoe_workspace_bytes(const semmoe_config* cfg, size_t* bytes_out /*hos
  *     unit) or 6 (one)
  *   SEMMOE_TUNE_ROUTE_SPLIT: bf16 router with at most 512 tokens: parts the K dimension is split into over workgroups
  *     (partial sums added in order by a second kernel, then the selection kernel); 0 = always the fused kernel,
- *     default: as many parts as fill the chip, at most 16.  With more than 128 experts and enough tokens to fill the
- *     chip with tiles of 256 tokens the logits come from the 256 x 256 tile of the grouped GEMM with K in up to 8
- *     parts, followed by the same two kernels; 100 + n forces that form with n parts at any token count (d must be
- *     n parts of whole 64-element slices, at least two each), 0 switches it off too
+ *     default: as many parts as fill the chip, at most 16.  With more than 128 experts, where tiles of 256 tokens
+ *     times up to 8 parts of K (at least 8 slices each) fill three quarters of the compute units, the logits come from
+ *     the 256 x 256 tile of the grouped GEMM, followed by one kernel that adds the parts and selects; 100 + n forces
+ *     that form with n parts at any token count (d must be n parts of whole 64-element slices, at least two each),
+ *     0 switches it off too
  *   SEMMOE_TUNE_GRID_CAP: most workgroups a grouped GEMM launches (default: compute units x blocks per CU)
  *   SEMMOE_TUNE_INDEX_PATH: which implementation of the index kernels runs (default: single workgroup for
  *     T <= 2048; above, two launches per call in which every workgroup derives its prefixes from the table of

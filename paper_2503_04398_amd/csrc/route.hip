@@ -969,6 +969,7 @@ static int route_big_parts(const semmoe_config* cfg, int ncu) {
   if (parts < 1) parts = 1;
   if (parts > 8) parts = 8;
   while (parts > 1 && (nk % parts != 0 || nk / parts < 8)) --parts;
+  if (tiles * parts * 4 < (long long)ncu * 3) return 0;  // K too short to cut into enough parts: the fused kernel fills the chip
   return nk / parts >= 2 ? parts : 0;
 }
 

@@ -86,14 +86,16 @@ def test_route_from_logits_sigmoid_group_limited(E, k, T, ng, tg, scale, bias):
     ("bf16", 257, 1032, 256, 8, 0), ("bf16", 100, 4096, 128, 8, 5), ("bf16", 40, 512, 384, 6, 3),
     ("bf16", 700, 256, 64, 4, -1), ("bf16", 512, 2048, 128, 8, 16), ("bf16", 16400, 136, 64, 4, -1),
     ("bf16", 16390, 72, 256, 8, -1), ("bf16", 32800, 72, 128, 8, -1),
-    ("bf16", 8200, 1024, 256, 8, -1), ("bf16", 8200, 1024, 256, 8, 0), ("bf16", 700, 1536, 256, 8, 103),
+    ("bf16", 12300, 2560, 256, 8, -1), ("bf16", 8200, 1024, 256, 8, 102), ("bf16", 700, 1536, 256, 8, 103),
     ("bf16", 300, 512, 384, 6, 102), ("bf16", 520, 256, 132, 4, 101), ("bf16", 1000, 1024, 192, 4, 108)])
 def test_route_gemm_and_selection(dtype, T, d, E, k, split):
     """router GEMM + selection; split: the few-token router's parts of K (-1 the library's choice, 0 the fused
     kernel, n forced; T = 700 is above the few-token limit and always fused).  From 16384 tokens on a workgroup
     takes 64 tokens, from 32768 on (up to 128 experts) 128: three cases with ragged last tiles.  With more than 128
     experts and at least 32 tiles of 256 tokens the logits come from the 256 x 256 GEMM tile with K in parts
-    (T = 8200: 33 token tiles, the last with 8 tokens; the library takes 2 parts of 8 slices); 100 + n forces that form with n
+    (T = 12300, d = 2560: 49 token tiles, the last with 12 tokens, and the library takes 5 parts of 8 slices = 245
+    workgroups; where tiles x parts would fill less than three quarters of the compute units it stays with the fused
+    kernel); 100 + n forces that form with n
     parts: ragged token tiles, a second expert tile half filled (E = 384), E not a multiple of 32, two slices a part"""
     _say("route", dtype, T, d, E, k, "split", split)
     w = WL.small(T=T, d=d, E=E, k=k, D=1, C=4, dtype=dtype)
