@@ -92,7 +92,7 @@ def test_route_gemm_and_selection(dtype, T, d, E, k, split):
     """router GEMM + selection; split: the few-token router's parts of K (-1 the library's choice, 0 the fused
     kernel, n forced; T = 700 is above the few-token limit and always fused).  From 16384 tokens on a workgroup
     takes 64 tokens, from 32768 on (up to 128 experts) 128: three cases with ragged last tiles.  With more than 128
-    experts and at least 32 tiles of 256 tokens the logits come from the 256 x 256 GEMM tile with K in parts
+    experts and enough tokens the logits come from the 256 x 256 GEMM tile with K in parts
     (T = 12300, d = 2560: 49 token tiles, the last with 12 tokens, and the library takes 5 parts of 8 slices = 245
     workgroups; where tiles x parts would fill less than three quarters of the compute units it stays with the fused
     kernel); 100 + n forces that form with n
