@@ -855,7 +855,7 @@ __global__ __launch_bounds__(256) void route_sum_select_kernel(semmoe_config cfg
                                                                float* __restrict__ topk_w) {
   __shared__ __attribute__((aligned(16))) float lg_all[4 * kSumSelectTokens * (kSumSelectMaxE + 4)];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int base = (blockIdx.x * int(blockDim.x >> 6) + wave) * kSumSelectTokens;  // one to four waves per workgroup
+  const int base = (blockIdx.x * int(blockDim.x >> 6) + wave) * kSumSelectTokens;  // up to four waves per workgroup
   if (base >= cfg.T) return;  // whole wave leaves together (no workgroup barrier below)
   const int E = cfg.E, e4 = E / 4, ld = E + 4;
   float* lg = lg_all + wave * kSumSelectTokens * (kSumSelectMaxE + 4);
