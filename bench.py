@@ -403,6 +403,32 @@ def run_config(name, args, traffic_tab):
     ro = rank_offsets.cpu().numpy()
     eo = expert_offsets.cpu().numpy()
     rows_ffn = int(ro[D] - ro[0]) if args.all_ranks else int(ro[1] - ro[0])
+    # the vendor library's dense GEMMs (torch.matmul) on the flops of the timed FFN launch, as if all its rows went to
+    # one expert: [rows, d] x [d, 2F], then [rows, F] x [F, d].  No ragged groups, no SwiGLU, no tile left over at a
+    # group's end: a reference from above for a grouped kernel on the same chip and data, not part of the path
+    vendor = None
+    if w.dtype == "bf16" and rows_ffn >= 256 and not args.step_only:
+        e_ref = int(inv[0].item())
+        A1, B1 = X_perm[:rows_ffn], W_gu[e_ref].t()
+        C1 = torch.empty(rows_ffn, 2 * F, dtype=adt, device=dev)
+        A2, B2 = C1[:, :F], W_down[e_ref].t()
+        C2 = torch.empty(rows_ffn, d, dtype=adt, device=dev)
+        def dense():
+            torch.matmul(A1, B1, out=C1)
+            torch.matmul(A2, B2, out=C2)
+        for _ in range(3):
+            dense()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dense()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_dense = e0.elapsed_time(e1) / 10
+        vendor = {"ms": round(ms_dense, 4), "TFLOP/s": round(6.0 * d * F * rows_ffn / (ms_dense * 1e-3) / 1e12, 1),
+                  "what": "torch.matmul [rows,d]x[d,2F] + [rows,F]x[F,d] on the launch's rows, one expert's weights"}
+        del C1, C2
     q_hi = E if args.all_ranks else w.m
     active = int((np.diff(eo[:q_hi + 1]) > 0).sum())       # experts of the FFN launch that hold at least one row
     remote = int(remote_pairs.item())
@@ -690,6 +716,7 @@ def run_config(name, args, traffic_tab):
                                                (MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS), 4),
                                  "weights": "numpy generator" if len(host_experts) == E else
                                             "rank 0 numpy generator, other ranks drawn on the device"},
+        "vendor_dense_gemms_same_flops": vendor,
         "ms_per_step_with_stage_events": round(ms_evented, 4),
         "ms_per_step_graph_replay": None if ms_graph is None else round(ms_graph, 4),
         "remote_pair_fraction": {"vanilla_placement_home_ranks": round(int(rp2.item()) / P, 4),
