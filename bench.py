@@ -821,6 +821,14 @@ def main():
     out["device"] = torch.cuda.get_device_name(0)
     if not (args.no_peaks or args.step_only):
         out["achievable"] = achievable_peaks(m, torch, "cuda:0")
+        # each MFMA-bound FFN stage against what this chip, in this run, gave the K loop of its own tile with every
+        # load hitting in L2 (no ragged groups, no epilogue, no tail): the share of the loop's rate that survives them
+        loop = out["achievable"].get("tile_loop_TFLOPs")
+        for r in [out] + list(out.get("configs", {}).values()):
+            for nm in ("expert_ffn", "shared_ffn"):
+                st = r.get("stages", {}).get(nm)
+                if st and st.get("bound") == "mfma" and st.get("unit") == "TFLOP/s" and r.get("dtype") == "bf16" and loop:
+                    st["frac_of_measured_tile_loop"] = round(st["achieved"] / loop, 4)
     if cpu is not None:
         out["cpu_baseline"] = cpu
     print(json.dumps(out))
