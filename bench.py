@@ -407,7 +407,8 @@ def run_config(name, args, traffic_tab):
     # one expert: [rows, d] x [d, 2F], then [rows, F] x [F, d].  No ragged groups, no SwiGLU, no tile left over at a
     # group's end: a reference from above for a grouped kernel on the same chip and data, not part of the path
     vendor = None
-    if w.dtype == "bf16" and rows_ffn >= 256 and not args.step_only:
+    if w.dtype == "bf16" and rows_ffn >= 128 * w.m and not args.step_only:   # not for decode shapes: one expert's weights
+                                                                              # stay in cache, the launch streams them all
         e_ref = int(inv[0].item())
         A1, B1 = X_perm[:rows_ffn], W_gu[e_ref].t()
         C1 = torch.empty(rows_ffn, 2 * F, dtype=adt, device=dev)
