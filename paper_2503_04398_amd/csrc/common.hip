@@ -72,8 +72,12 @@ int32_t validate_config(const semmoe_config* cfg, bool need_T, bool need_rows, b
 size_t ws_route(const semmoe_config* cfg) {
   const size_t logits = align_up(size_t(cfg->T) * cfg->E * 4, 256);
   // few tokens: the router splits K over workgroups and keeps up to 16 partial sums per logit
-  // many tokens and more than 128 experts: K split of the 256 x 256 tile, up to 8 parts
-  return (cfg->T <= 512 ? 17 * logits : (cfg->E > 128 ? 9 * logits : logits)) + 512;
+  if (cfg->T <= 512) return 17 * logits + 512;
+  // more than 128 experts: K split of the 256 x 256 tile over as many parts as fill the chip, at most 8 and (a bound
+  // that needs no device: no chip has 1024 compute units) at most 1024 / tiles
+  const long long tiles = (long long)cdiv(cfg->T, 256) * cdiv(cfg->E, 256);
+  const long long parts = tiles >= 1024 ? 1 : (1024 / tiles < 8 ? 1024 / tiles : 8);
+  return (cfg->E > 128 ? size_t(parts + 1) * logits : logits) + 512;
 }
 
 }  // namespace semmoe

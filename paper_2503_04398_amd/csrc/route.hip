@@ -958,16 +958,17 @@ static int route_big_parts(const semmoe_config* cfg, int ncu) {
   const int tune = tuning_value(SEMMOE_TUNE_ROUTE_SPLIT);
   if (cfg->dtype != SEMMOE_BF16 || tune == 0 || cfg->E <= 128 || cfg->E % 4 != 0 || cfg->d % 64 != 0) return 0;
   const int nk = cfg->d / 64;
+  const long long tiles = (long long)cdiv(cfg->T, 256) * cdiv(cfg->E, 256);
+  const int cap = tiles >= 1024 ? 1 : int(1024 / tiles < 8 ? 1024 / tiles : 8);  // what the workspace is sized for
   if (tune >= 100) {
     const int parts = tune - 100;
-    return (parts >= 1 && parts <= 8 && nk % parts == 0 && nk / parts >= 2) ? parts : 0;
+    return (parts >= 1 && parts <= cap && nk % parts == 0 && nk / parts >= 2) ? parts : 0;
   }
   if (tune > 0) return 0;  // a forced split of the fused kernel
-  const long long tiles = (long long)cdiv(cfg->T, 256) * cdiv(cfg->E, 256);
   if (tiles * 8 < ncu) return 0;  // too few tokens to fill the chip with 256-token tiles and K parts of useful depth
   int parts = int(ncu / tiles);
   if (parts < 1) parts = 1;
-  if (parts > 8) parts = 8;
+  if (parts > cap) parts = cap;
   while (parts > 1 && (nk % parts != 0 || nk / parts < 8)) --parts;
   if (tiles * parts * 4 < (long long)ncu * 3) return 0;  // K too short to cut into enough parts: the fused kernel fills the chip
   return nk / parts >= 2 ? parts : 0;
